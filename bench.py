@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Benchmark of the K-hop precompute on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2]
+
+One step = one gp_propagate call: the whole hot path (slot-0 copy, K hops of
+gather/scale/accumulate over all edge blocks, completion of cut rows) on one
+synthetic workload whose inputs already sit in HBM.  Prints ONE JSON line:
+throughput in giga edge-feature updates per second (nnz * d * K / t / 1e9), the
+HBM roofline of the dominant kernel (algorithmic bytes per launch over the
+kernel's mean duration, timed with HIP events on the launch stream), and the CPU
+oracle timed beside it on the host cores as a baseline.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc
+# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); the
+# summaries are in profiles/.  None until measured for that workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+WORKLOAD_NAMES = {
+    1: "config1: G(n,M) 10k nodes / 210k nnz, d=128 fp32, sym, K=2, 4 edge blocks",
+    2: "config2: Chung-Lu 169,343 nodes / ~2.5M nnz, d=128 fp32, sym, K=3",
+    3: "config3: Chung-Lu 2.45M nodes / ~123M nnz, d=100 fp32, mean, K=3, 8M-edge blocks",
+    4: "config4: SBM 233k nodes / ~114M nnz, d=602 fp32, sum, K=2",
+}
+
+
+def algorithmic_bytes_per_hop(n: int, nnz: int, d: int, elem: int) -> int:
+    """Compulsory traffic of one hop: column ids (4 B per non-zero), the int64 row
+    pointers, one fp32 normalisation vector, X_{k-1} read once, X_k written once."""
+    return 4 * nnz + 8 * (n + 1) + 4 * n + 2 * n * d * elem
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=2, choices=sorted(WORKLOAD_NAMES))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        return 2
+
+    import torch
+    import gp_synth
+    import paper_2207_12000_amd as gp
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    t0 = time.time()
+    w = gp_synth.make_workload(args.workload)
+    t_gen = time.time() - t0
+    budget = w.block_budget_edges
+    if budget is None:
+        budget = -(-gp_synth.stored_nonzeros_upper_bound(w.n, w.m, w.flags) // w.n_blocks)
+    t0 = time.time()
+    plan = gp.gp_plan_blocks(w.src, w.dst, w.n, budget, w.flags)
+    t_plan = time.time() - t0
+    n, nnz, d, K = w.n, plan.nnz, w.d, w.K
+    elem = 4 if w.dtype == gp.GP_F32 else 2
+    tdt = torch.float32 if w.dtype == gp.GP_F32 else torch.bfloat16
+
+    X = torch.from_numpy(w.X).to(dev) if w.dtype == gp.GP_F32 else \
+        torch.from_numpy(w.X.view(np.int16)).view(torch.bfloat16).to(dev)
+    out = torch.empty((K + 1, n, d), dtype=tdt, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step():
+        gp.gp_propagate(plan, X.data_ptr(), d, d, w.dtype, w.agg, K, out.data_ptr(), d, stream)
+
+    for _ in range(max(args.warmup, 1)):     # the first call also uploads the plan
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    efu = nnz * d * K
+    value = efu / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: per-launch duration from HIP events around each launch
+    gp.gp_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    launches, hop_ms = gp.gp_profile_read("gp_hop_segments")
+    fix_launches, fix_ms = gp.gp_profile_read("gp_fixup_rows")
+    _, copy_ms = gp.gp_profile_read("gp_copy_rows")
+    gp.gp_profile_enable(False)
+    avg_launch_s = hop_ms * 1e-3 / max(launches, 1)
+    bytes_per_launch = algorithmic_bytes_per_hop(n, nnz, d, elem)
+    achieved = bytes_per_launch / avg_launch_s / 1e9
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
+
+    rec = {
+        "metric": "edge-feature updates/s (GEFU/s) for K-hop A^k X precompute",
+        "value": round(value, 3),
+        "unit": "GEFU/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.dtype == gp.GP_F32 else "bf16 storage, f32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.workload], "n": n, "nnz": nnz, "d": d, "K": K,
+                   "edge_blocks": plan.num_blocks, "agg": ["sym", "mean", "sum"][w.agg],
+                   "segments": int(plan.segments.size), "partial_rows": plan.num_partial_rows},
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "kernel": "gp_hop_segments", "launches": launches,
+                     "avg_launch_us": round(avg_launch_s * 1e6, 3), "algorithmic_bytes_per_launch": bytes_per_launch},
+        "other_kernels_ms_per_step": {"gp_fixup_rows": round(fix_ms / args.steps, 5),
+                                      "gp_copy_rows": round(copy_ms / args.steps, 5)},
+        "host_s": {"generate": round(t_gen, 2), "gp_plan_blocks": round(t_plan, 3), "timed_wall": round(wall, 3)},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        cores = min(16, os.cpu_count() or 1)
+        op = oracle.plan_blocks(w.src, w.dst, n, budget, w.flags)
+        Xw = (w.X if w.dtype == gp.GP_F32 else gp_synth.bf16_bits_to_f32(w.X)).astype(np.float64)
+        # bounded sample: whole hops of the same workload until ~10 s of CPU work
+        hops, t_cpu = 0, 0.0
+        cur = Xw
+        while hops < K and t_cpu < 10.0:
+            t0 = time.perf_counter()
+            cur = oracle.hop(op, cur, w.agg, threads=cores)
+            t_cpu += time.perf_counter() - t0
+            hops += 1
+        rec["cpu_baseline"] = {"value": round(nnz * d * hops / t_cpu / 1e9, 4), "unit": "GEFU/s", "cores": cores,
+                               "kind": "oracle", "sample": f"{hops} of {K} hops of the same workload, fp64, "
+                                                            f"{t_cpu:.2f} s"}
+    print(json.dumps(rec))
+    plan.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,172 @@
+/* gp.h -- C boundary of the K-hop graph feature precompute for MI355X (gfx950).
+ *
+ * The library computes the hop stack [X, A^ X, ..., A^^K X] that a
+ * precomputation-based / linear-convolution GNN trains on (paper Section 3.2,
+ * Algorithm 1 "Block-wise feature aggregation"; the k = 0 term is the one the
+ * Appendix A model consumes), where A^ is a constant linear aggregation
+ * operator over the graph's adjacency list:
+ *
+ *   GP_AGG_SYM   A^ = D~^-1/2 A~ D~^-1/2      (Eq. 1, the normalised adjacency;
+ *                                             D~ = row sums of the listed 0/1 matrix)
+ *   GP_AGG_MEAN  A^ = D^-1 A                   (row-normalised mean)
+ *   GP_AGG_SUM   A^ = A                        (plain sum; diagonal as listed)
+ *
+ * The adjacency list is first decomposed into disjoint, balanced edge blocks
+ * whose union is the whole list (Section 3.2, "Precomputation on GPU": the sets
+ * E^(1..a) and the identity S = sum_l D~^-1/2 A~^(l) D~^-1/2); every hop is run
+ * block by block and rows cut by a block boundary are completed by a fixed-order
+ * sum of partial rows (Algorithm 1, the accumulation over j).
+ *
+ * All entry points are plain C.  Every pointer argument says whether it is a
+ * HOST or a DEVICE pointer.  No call aborts or throws; each returns a gp_status
+ * and leaves a message for gp_last_error().  One GPU; the current HIP device at
+ * the time of the first gp_propagate on a plan is the plan's device.
+ */
+#ifndef GP_H
+#define GP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct gp_plan gp_plan; /* opaque; owned by the library */
+
+typedef enum {
+    GP_OK = 0,
+    GP_ERR_INVALID_ARG = 1,  /* null pointer, negative size, ld < d, unknown enum/flag, pageable host memory */
+    GP_ERR_INDEX_RANGE = 2,  /* a node id outside [0, n) */
+    GP_ERR_OVERFLOW = 3,     /* a count does not fit the type the layout stores it in */
+    GP_ERR_OOM_HOST = 4,
+    GP_ERR_OOM_DEVICE = 5,
+    GP_ERR_DEVICE = 6,       /* a HIP call failed, or no usable device */
+    GP_ERR_UNSUPPORTED = 7
+} gp_status;
+
+typedef enum { GP_AGG_SYM = 0, GP_AGG_MEAN = 1, GP_AGG_SUM = 2 } gp_agg;
+typedef enum { GP_F32 = 0, GP_BF16 = 1 } gp_dtype;
+
+/* plan flags */
+enum { GP_SYMMETRISE = 1u, GP_ADD_SELF_LOOPS = 2u };
+
+/* ---------------------------------------------------------------------------
+ * gp_plan_blocks -- edge decomposition and normalisation vectors.
+ * (Section 3.2: decomposition of the edge set into disjoint balanced sets;
+ *  Eq. 1 / the block-sum identity for the degree vectors; Eq. 11 for the block
+ *  count, which has one free parameter and is the smallest count within budget.)
+ *
+ *  src, dst  HOST, m int32 each.  Pair (src = j, dst = i) means "i aggregates
+ *            from j": non-zero (row i, col j).  Read only during the call.
+ *  m         number of input pairs, >= 0.
+ *  n         number of nodes, 1 .. 2^31-1.
+ *  block_budget_edges  largest number of non-zeros one block may hold, > 0.
+ *  flags     GP_SYMMETRISE also inserts (row j, col i); GP_ADD_SELF_LOOPS
+ *            inserts (i, i) for every i.
+ *  out_plan  HOST; receives the plan (NULL on error).  Free with gp_plan_destroy.
+ *
+ * The non-zeros form a SET: duplicate pairs collapse, input pairs with
+ * src == dst are dropped (the diagonal is exactly the self-loop flag).  They
+ * are listed in ascending (row, col) order; with nnz of them,
+ * b = max(1, ceil(nnz / budget)) and block p is the contiguous range
+ * [p*q + min(p,r), (p+1)*q + min(p+1,r)), q = nnz div b, r = nnz mod b, so
+ * block sizes differ by at most one.  deg[i] = number of non-zeros in row i.
+ * dinv_sqrt[i] = (float)(1/sqrt((double)deg)), dinv[i] = (float)(1/(double)deg),
+ * both 0 where deg = 0.  Runs on the host only (no GPU needed).
+ * Errors: INVALID_ARG, INDEX_RANGE, OVERFLOW, OOM_HOST.
+ */
+gp_status gp_plan_blocks(const int32_t *src, const int32_t *dst, int64_t m, int64_t n,
+                         int64_t block_budget_edges, uint32_t flags, gp_plan **out_plan);
+
+void gp_plan_destroy(gp_plan *plan); /* NULL is allowed; frees host and device memory of the plan */
+
+/* Accessors.  Returned HOST pointers stay valid until gp_plan_destroy.  A NULL
+ * plan gives 0 / NULL. */
+int64_t gp_plan_num_nodes(const gp_plan *plan);
+int64_t gp_plan_nnz(const gp_plan *plan);
+int32_t gp_plan_num_blocks(const gp_plan *plan);
+const int64_t *gp_plan_block_offsets(const gp_plan *plan); /* b+1: block p = [off[p], off[p+1]) */
+const int32_t *gp_plan_block_row_lo(const gp_plan *plan);  /* b: row of the block's first non-zero (0 if empty) */
+const int32_t *gp_plan_block_row_hi(const gp_plan *plan);  /* b: row of its last non-zero (-1 if empty) */
+const int64_t *gp_plan_rowptr(const gp_plan *plan);        /* n+1 */
+const int32_t *gp_plan_col(const gp_plan *plan);           /* nnz, ascending (row, col) */
+const int32_t *gp_plan_degree(const gp_plan *plan);        /* n */
+const float *gp_plan_dinv_sqrt(const gp_plan *plan);       /* n */
+const float *gp_plan_dinv(const gp_plan *plan);            /* n */
+
+/* Kernel schedule of the plan (library's own work decomposition, exposed so host
+ * logic can be checked without a GPU).  Every block is cut into segments: runs
+ * of consecutive non-zeros of one row, at most "segment_edges" long, never
+ * crossing a block boundary; a row without non-zeros has one segment of length
+ * 0.  A row made of one segment is written directly; a row cut into several has
+ * consecutive partial-row slots, in list order, that are summed afterwards.
+ * Segment record, 16 bytes: { uint32 start_lo; uint16 start_hi; uint16 len;
+ * int32 row; int32 slot (-1 = whole row) }, start = start_hi << 32 | start_lo. */
+int64_t gp_plan_num_segments(const gp_plan *plan);
+const void *gp_plan_segments(const gp_plan *plan);            /* num_segments records, grouped by block */
+const int64_t *gp_plan_segment_offsets(const gp_plan *plan);  /* b+1: block p owns [off[p], off[p+1]) */
+int64_t gp_plan_num_partial_rows(const gp_plan *plan);        /* number of slots */
+
+/* ---------------------------------------------------------------------------
+ * gp_propagate -- the hop stack (Algorithm 1's SX_list plus slot 0 = X).
+ *
+ *  plan      from gp_plan_blocks.
+ *  X         n x d row-major, leading dimension ldx elements (ldx >= d), of
+ *            `dtype`.  DEVICE pointer, or PINNED HOST pointer (then out_stack
+ *            must be pinned host too and the streamed schedule is used).
+ *  d         feature columns, >= 1.
+ *  dtype     GP_F32, or GP_BF16 storage (accumulation is always fp32; a stored
+ *            bf16 value is the fp32 accumulator rounded to nearest even).
+ *  agg       the operator, see above.
+ *  K         hops, >= 0 (0 writes slot 0 only).
+ *  out_stack K+1 slabs of n x d, leading dimension ldo (>= d); slab k starts at
+ *            element k*n*ldo and receives A^^k X.  Same memory kind as X.  X may
+ *            be exactly slab 0 (then ldx must equal ldo and no copy is made);
+ *            any other overlap is an error the library does not detect.
+ *  hip_stream  a hipStream_t, or NULL for the default stream.
+ *
+ * Device-resident operands: the call enqueues all work on hip_stream and
+ * returns; the caller synchronises.  Pinned-host operands: blocks and column
+ * slabs are streamed through HBM on library-owned side streams and the call
+ * returns after the last slab has reached out_stack.  The first call on a plan
+ * uploads the plan to the current device and allocates scratch (partial-row
+ * buffer); later calls with the same d reuse both.  Results are deterministic:
+ * the same inputs give the same bits on every call.
+ * Errors: INVALID_ARG, OOM_DEVICE, DEVICE, UNSUPPORTED.
+ */
+gp_status gp_propagate(const gp_plan *plan, const void *X, int64_t ldx, int32_t d, gp_dtype dtype,
+                       gp_agg agg, int32_t K, void *out_stack, int64_t ldo, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
+ * Library-wide knobs (process global; set them before planning / propagating).
+ */
+
+/* Upper limit of HBM bytes the streamed schedule may use for its staging buffers
+ * (the memory budget B_GPU of Eq. 12).  0 = choose from the device's free memory. */
+gp_status gp_set_hbm_budget_bytes(int64_t bytes);
+
+/* Named integer options; unknown names give INVALID_ARG.
+ *   "segment_edges"   longest run of non-zeros one lane group walks before the row
+ *                     is split into partial rows (8 .. 32768; default 256).  Read
+ *                     by gp_plan_blocks.
+ *   "column_tile"     feature columns per pass of the kernel, 0 = automatic.
+ */
+gp_status gp_set_option(const char *name, int64_t value);
+int64_t gp_get_option(const char *name); /* -1 for an unknown name */
+
+/* ---------------------------------------------------------------------------
+ * Kernel timing for benchmarks: while enabled, every kernel launch made by
+ * gp_propagate is bracketed by HIP events on the launch stream.
+ * gp_profile_read synchronises those events and reports, for kernels whose name
+ * starts with `prefix` ("" = all), the launch count and the summed duration.
+ */
+gp_status gp_profile_enable(int32_t on); /* also clears what was recorded */
+gp_status gp_profile_read(const char *prefix, int64_t *launches, double *total_ms);
+
+const char *gp_status_string(gp_status s);
+const char *gp_last_error(void); /* thread-local text of the calling thread's last failure */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GP_H */

@@ -1,0 +1,258 @@
+"""Python binding of libgp.so: the same calls as include/gp.h, argument
+marshalling only.  Every step of the path runs inside the library's HIP
+kernels / host C++; there is no Python or CPU fallback, and a missing library is
+an error (build it with `python -m paper_2207_12000_amd.build`).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+GP_OK = 0
+GP_ERR_INVALID_ARG, GP_ERR_INDEX_RANGE, GP_ERR_OVERFLOW = 1, 2, 3
+GP_ERR_OOM_HOST, GP_ERR_OOM_DEVICE, GP_ERR_DEVICE, GP_ERR_UNSUPPORTED = 4, 5, 6, 7
+GP_AGG_SYM, GP_AGG_MEAN, GP_AGG_SUM = 0, 1, 2
+GP_F32, GP_BF16 = 0, 1
+GP_SYMMETRISE, GP_ADD_SELF_LOOPS = 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgp.so")
+
+# every symbol include/gp.h declares: (restype, argtypes)
+_c = ctypes
+_SIGNATURES = {
+    "gp_plan_blocks": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_uint32,
+                                  _c.POINTER(_c.c_void_p)]),
+    "gp_plan_destroy": (None, [_c.c_void_p]),
+    "gp_plan_num_nodes": (_c.c_int64, [_c.c_void_p]),
+    "gp_plan_nnz": (_c.c_int64, [_c.c_void_p]),
+    "gp_plan_num_blocks": (_c.c_int32, [_c.c_void_p]),
+    "gp_plan_block_offsets": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_block_row_lo": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_block_row_hi": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_rowptr": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_col": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_degree": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_dinv_sqrt": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_dinv": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_num_segments": (_c.c_int64, [_c.c_void_p]),
+    "gp_plan_segments": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_segment_offsets": (_c.c_void_p, [_c.c_void_p]),
+    "gp_plan_num_partial_rows": (_c.c_int64, [_c.c_void_p]),
+    "gp_propagate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
+                                _c.c_void_p, _c.c_int64, _c.c_void_p]),
+    "gp_set_hbm_budget_bytes": (_c.c_int, [_c.c_int64]),
+    "gp_set_option": (_c.c_int, [_c.c_char_p, _c.c_int64]),
+    "gp_get_option": (_c.c_int64, [_c.c_char_p]),
+    "gp_profile_enable": (_c.c_int, [_c.c_int32]),
+    "gp_profile_read": (_c.c_int, [_c.c_char_p, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_double)]),
+    "gp_status_string": (_c.c_char_p, [_c.c_int]),
+    "gp_last_error": (_c.c_char_p, []),
+}
+EXPORTED_SYMBOLS = tuple(_SIGNATURES)
+
+_lib = None
+
+
+class GpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        l = lib()
+        self.status = status
+        self.status_name = l.gp_status_string(status).decode()
+        super().__init__(f"{where}: {self.status_name}: {l.gp_last_error().decode()}")
+
+
+def lib():
+    """Loads libgp.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2207_12000_amd.build`")
+        l = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(l, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = l
+    return _lib
+
+
+def _check(status: int, where: str):
+    if status != GP_OK:
+        raise GpError(status, where)
+
+
+def _view(ptr, ctype, count, dtype):
+    if not ptr or count == 0:
+        return np.empty(0, dtype=dtype)
+    return np.ctypeslib.as_array(ctypes.cast(ptr, ctypes.POINTER(ctype)), shape=(count,))
+
+
+class Plan:
+    """Owns a gp_plan*.  The array properties are views of library-owned host
+    memory, valid until close()."""
+
+    def __init__(self, handle: int):
+        self._h = handle
+
+    @property
+    def handle(self) -> int:
+        if not self._h:
+            raise ValueError("plan is closed")
+        return self._h
+
+    def close(self):
+        if self._h:
+            lib().gp_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    @property
+    def n(self) -> int:
+        return lib().gp_plan_num_nodes(self.handle)
+
+    @property
+    def nnz(self) -> int:
+        return lib().gp_plan_nnz(self.handle)
+
+    @property
+    def num_blocks(self) -> int:
+        return lib().gp_plan_num_blocks(self.handle)
+
+    @property
+    def block_off(self):
+        return _view(lib().gp_plan_block_offsets(self.handle), ctypes.c_int64, self.num_blocks + 1, np.int64)
+
+    @property
+    def block_row_lo(self):
+        return _view(lib().gp_plan_block_row_lo(self.handle), ctypes.c_int32, self.num_blocks, np.int32)
+
+    @property
+    def block_row_hi(self):
+        return _view(lib().gp_plan_block_row_hi(self.handle), ctypes.c_int32, self.num_blocks, np.int32)
+
+    @property
+    def rowptr(self):
+        return _view(lib().gp_plan_rowptr(self.handle), ctypes.c_int64, self.n + 1, np.int64)
+
+    @property
+    def col(self):
+        return _view(lib().gp_plan_col(self.handle), ctypes.c_int32, self.nnz, np.int32)
+
+    @property
+    def deg(self):
+        return _view(lib().gp_plan_degree(self.handle), ctypes.c_int32, self.n, np.int32)
+
+    @property
+    def dinv_sqrt(self):
+        return _view(lib().gp_plan_dinv_sqrt(self.handle), ctypes.c_float, self.n, np.float32)
+
+    @property
+    def dinv(self):
+        return _view(lib().gp_plan_dinv(self.handle), ctypes.c_float, self.n, np.float32)
+
+
+    SEGMENT_DTYPE = np.dtype([("start_lo", "<u4"), ("start_hi", "<u2"), ("len", "<u2"), ("row", "<i4"),
+                              ("slot", "<i4")])
+
+    @property
+    def segments(self):
+        """Structured view of the schedule's 16-byte segment records."""
+        cnt = lib().gp_plan_num_segments(self.handle)
+        raw = _view(lib().gp_plan_segments(self.handle), ctypes.c_uint8, cnt * 16, np.uint8)
+        return raw.view(self.SEGMENT_DTYPE)
+
+    @property
+    def segment_off(self):
+        return _view(lib().gp_plan_segment_offsets(self.handle), ctypes.c_int64, self.num_blocks + 1, np.int64)
+
+    @property
+    def num_partial_rows(self) -> int:
+        return lib().gp_plan_num_partial_rows(self.handle)
+
+
+def gp_plan_blocks(src, dst, n: int, block_budget_edges: int, flags: int) -> Plan:
+    """src/dst: int32 host arrays (numpy) of equal length."""
+    src = np.ascontiguousarray(src, dtype=np.int32)
+    dst = np.ascontiguousarray(dst, dtype=np.int32)
+    if src.shape != dst.shape or src.ndim != 1:
+        raise ValueError("src and dst must be 1-D and equally long")
+    out = ctypes.c_void_p()
+    st = lib().gp_plan_blocks(src.ctypes.data if src.size else None, dst.ctypes.data if dst.size else None,
+                              src.size, n, block_budget_edges, flags, ctypes.byref(out))
+    _check(st, "gp_plan_blocks")
+    return Plan(out.value)
+
+
+def gp_propagate(plan: Plan, X_ptr: int, ldx: int, d: int, dtype: int, agg: int, K: int, out_ptr: int, ldo: int,
+                 stream: Optional[int] = None):
+    """Raw-pointer form: X_ptr / out_ptr are device (or pinned host) addresses."""
+    st = lib().gp_propagate(plan.handle, X_ptr, ldx, d, dtype, agg, K, out_ptr, ldo, stream or None)
+    _check(st, "gp_propagate")
+
+
+def propagate_tensors(plan: Plan, X, agg: int, K: int, out=None, stream=None):
+    """Convenience for torch tensors (memory and streams only): X is an (n, d)
+    float32 or bfloat16 tensor on the GPU (or pinned host memory); returns the
+    (K+1, n, d) stack.  Enqueued on torch's current stream unless given."""
+    import torch
+    if X.dim() != 2 or X.stride(1) != 1:
+        raise ValueError("X must be 2-D with unit column stride")
+    n, d = X.shape
+    if n != plan.n:
+        raise ValueError("X has the wrong number of rows")
+    dtype = {torch.float32: GP_F32, torch.bfloat16: GP_BF16}[X.dtype]
+    if out is None:
+        out = torch.empty((K + 1, n, d), dtype=X.dtype, device=X.device,
+                          pin_memory=(X.device.type == "cpu"))
+    if out.shape != (K + 1, n, d) or out.dtype != X.dtype or not out.is_contiguous():
+        raise ValueError("out must be a contiguous (K+1, n, d) tensor of X's dtype")
+    if stream is None and X.is_cuda:
+        stream = torch.cuda.current_stream(X.device).cuda_stream
+    gp_propagate(plan, X.data_ptr(), X.stride(0), d, dtype, agg, K, out.data_ptr(), d, stream)
+    return out
+
+
+def gp_set_hbm_budget_bytes(nbytes: int):
+    _check(lib().gp_set_hbm_budget_bytes(nbytes), "gp_set_hbm_budget_bytes")
+
+
+def gp_set_option(name: str, value: int):
+    _check(lib().gp_set_option(name.encode(), value), "gp_set_option")
+
+
+def gp_get_option(name: str) -> int:
+    return lib().gp_get_option(name.encode())
+
+
+def gp_profile_enable(on: bool):
+    _check(lib().gp_profile_enable(1 if on else 0), "gp_profile_enable")
+
+
+def gp_profile_read(prefix: str = ""):
+    n = ctypes.c_int64()
+    ms = ctypes.c_double()
+    _check(lib().gp_profile_read(prefix.encode(), ctypes.byref(n), ctypes.byref(ms)), "gp_profile_read")
+    return n.value, ms.value
+
+
+def gp_status_string(status: int) -> str:
+    return lib().gp_status_string(status).decode()
+
+
+def gp_last_error() -> str:
+    return lib().gp_last_error().decode()

@@ -1,0 +1,178 @@
+// C boundary glue: error text, options, accessors, kernel-timing hooks.
+#include <cstdio>
+#include <cstring>
+#include <functional>
+
+#include "gp_internal.h"
+
+namespace gp {
+
+static thread_local char g_err[512] = "";
+
+gp_status fail(gp_status s, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+Options& options()
+{
+    static Options o;
+    return o;
+}
+
+// ---- profiling ------------------------------------------------------------
+namespace {
+struct Timed {
+    std::string name;
+    hipEvent_t a, b;
+};
+std::mutex g_prof_mu;
+bool g_prof_on = false;
+std::vector<Timed> g_prof;
+hipEvent_t g_open = nullptr;
+std::string g_open_name;
+
+void clear_profile()
+{
+    for (auto& t : g_prof) {
+        (void)hipEventDestroy(t.a);
+        (void)hipEventDestroy(t.b);
+    }
+    g_prof.clear();
+}
+}  // namespace
+
+bool profiling_on() { return g_prof_on; }
+
+void profile_begin(const char* name, hipStream_t stream)
+{
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (hipEventCreate(&g_open) != hipSuccess) {
+        g_open = nullptr;
+        return;
+    }
+    g_open_name = name;
+    (void)hipEventRecord(g_open, stream);
+}
+
+void profile_end(hipStream_t stream)
+{
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (!g_open) return;
+    hipEvent_t b;
+    if (hipEventCreate(&b) != hipSuccess) {
+        (void)hipEventDestroy(g_open);
+        g_open = nullptr;
+        return;
+    }
+    (void)hipEventRecord(b, stream);
+    g_prof.push_back(Timed{g_open_name, g_open, b});
+    g_open = nullptr;
+}
+
+}  // namespace gp
+
+using namespace gp;
+
+extern "C" {
+
+const char* gp_status_string(gp_status s)
+{
+    switch (s) {
+    case GP_OK: return "GP_OK";
+    case GP_ERR_INVALID_ARG: return "GP_ERR_INVALID_ARG";
+    case GP_ERR_INDEX_RANGE: return "GP_ERR_INDEX_RANGE";
+    case GP_ERR_OVERFLOW: return "GP_ERR_OVERFLOW";
+    case GP_ERR_OOM_HOST: return "GP_ERR_OOM_HOST";
+    case GP_ERR_OOM_DEVICE: return "GP_ERR_OOM_DEVICE";
+    case GP_ERR_DEVICE: return "GP_ERR_DEVICE";
+    case GP_ERR_UNSUPPORTED: return "GP_ERR_UNSUPPORTED";
+    }
+    return "GP_ERR_UNKNOWN";
+}
+
+const char* gp_last_error(void) { return g_err; }
+
+gp_status gp_set_hbm_budget_bytes(int64_t bytes)
+{
+    if (bytes < 0) return fail(GP_ERR_INVALID_ARG, "HBM budget %lld is negative", (long long)bytes);
+    options().hbm_budget_bytes = bytes;
+    return GP_OK;
+}
+
+gp_status gp_set_option(const char* name, int64_t value)
+{
+    if (!name) return fail(GP_ERR_INVALID_ARG, "option name is NULL");
+    if (!strcmp(name, "segment_edges")) {
+        if (value < 8 || value > 32768) return fail(GP_ERR_INVALID_ARG, "segment_edges must be 8 .. 32768");
+        options().segment_edges = value;
+        return GP_OK;
+    }
+    if (!strcmp(name, "column_tile")) {
+        if (value < 0) return fail(GP_ERR_INVALID_ARG, "column_tile must be >= 0");
+        options().column_tile = value;
+        return GP_OK;
+    }
+    return fail(GP_ERR_INVALID_ARG, "unknown option '%s'", name);
+}
+
+int64_t gp_get_option(const char* name)
+{
+    if (!name) return -1;
+    if (!strcmp(name, "segment_edges")) return options().segment_edges;
+    if (!strcmp(name, "column_tile")) return options().column_tile;
+    if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
+    return -1;
+}
+
+gp_status gp_profile_enable(int32_t on)
+{
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    clear_profile();
+    g_prof_on = on != 0;
+    return GP_OK;
+}
+
+gp_status gp_profile_read(const char* prefix, int64_t* launches, double* total_ms)
+{
+    if (!launches || !total_ms) return fail(GP_ERR_INVALID_ARG, "output pointer is NULL");
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    const size_t plen = prefix ? strlen(prefix) : 0;
+    int64_t cnt = 0;
+    double ms = 0.0;
+    for (auto& t : g_prof) {
+        if (plen && t.name.compare(0, plen, prefix) != 0) continue;
+        GP_HIP(hipEventSynchronize(t.b));
+        float e = 0.f;
+        GP_HIP(hipEventElapsedTime(&e, t.a, t.b));
+        ms += e;
+        ++cnt;
+    }
+    *launches = cnt;
+    *total_ms = ms;
+    return GP_OK;
+}
+
+int64_t gp_plan_num_nodes(const gp_plan* p) { return p ? p->n : 0; }
+int64_t gp_plan_nnz(const gp_plan* p) { return p ? p->nnz : 0; }
+int32_t gp_plan_num_blocks(const gp_plan* p) { return p ? p->num_blocks : 0; }
+const int64_t* gp_plan_block_offsets(const gp_plan* p) { return p ? p->block_off.data() : nullptr; }
+const int32_t* gp_plan_block_row_lo(const gp_plan* p) { return p ? p->block_row_lo.data() : nullptr; }
+const int32_t* gp_plan_block_row_hi(const gp_plan* p) { return p ? p->block_row_hi.data() : nullptr; }
+const int64_t* gp_plan_rowptr(const gp_plan* p) { return p ? p->rowptr.data() : nullptr; }
+const int32_t* gp_plan_col(const gp_plan* p) { return p ? p->col.data() : nullptr; }
+const int32_t* gp_plan_degree(const gp_plan* p) { return p ? p->deg.data() : nullptr; }
+const float* gp_plan_dinv_sqrt(const gp_plan* p) { return p ? p->dinv_sqrt.data() : nullptr; }
+const float* gp_plan_dinv(const gp_plan* p) { return p ? p->dinv.data() : nullptr; }
+int64_t gp_plan_num_segments(const gp_plan* p) { return p ? (int64_t)p->segs.size() : 0; }
+const void* gp_plan_segments(const gp_plan* p) { return p ? p->segs.data() : nullptr; }
+const int64_t* gp_plan_segment_offsets(const gp_plan* p) { return p ? p->seg_off.data() : nullptr; }
+int64_t gp_plan_num_partial_rows(const gp_plan* p) { return p ? p->num_slots : 0; }
+
+}  // extern "C"

@@ -1,0 +1,150 @@
+// Internal declarations shared by the library's translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdint>
+#include <functional>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "gp.h"
+
+namespace gp {
+
+// ---- error text ---------------------------------------------------------
+gp_status fail(gp_status s, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+#define GP_HIP(call)                                                                      \
+    do {                                                                                  \
+        hipError_t e_ = (call);                                                           \
+        if (e_ != hipSuccess)                                                             \
+            return gp::fail(e_ == hipErrorOutOfMemory ? GP_ERR_OOM_DEVICE : GP_ERR_DEVICE, \
+                            "%s failed: %s", #call, hipGetErrorString(e_));               \
+    } while (0)
+
+// ---- options ------------------------------------------------------------
+struct Options {
+    int64_t segment_edges = 256;
+    int64_t column_tile = 0;
+    int64_t hbm_budget_bytes = 0;
+};
+Options& options();
+
+int host_threads();
+// Runs fn(t, nthreads) on nthreads host threads (t = 0 .. nthreads-1) and joins.
+void parallel_run(int nthreads, const std::function<void(int, int)>& fn);
+
+// ---- the schedule the kernels walk ----------------------------------------
+// One run of consecutive non-zeros of one row, inside one edge block.
+struct alignas(16) Segment {
+    uint32_t start_lo;  // first non-zero (index into the sorted list), low 32 bits
+    uint16_t start_hi;  // bits 32..47
+    uint16_t len;       // number of non-zeros, 0 for a row without any
+    int32_t row;        // destination row
+    int32_t slot;       // -1: the run is the whole row, result goes to the output row
+                        // >=0: partial row, result goes to this row of the carry buffer
+};
+static_assert(sizeof(Segment) == 16, "Segment must be 16 bytes");
+
+// A row that was cut (by a block boundary or by the segment length): its
+// partial rows are carry slots [first_slot, first_slot + count) in list order.
+struct SplitRow {
+    int32_t row;
+    int32_t count;
+    int64_t first_slot;
+};
+
+struct DevicePlan {
+    int device = -1;
+    int32_t* col = nullptr;
+    float* dinv_sqrt = nullptr;
+    float* dinv = nullptr;
+    Segment* segs = nullptr;
+    SplitRow* split = nullptr;
+    float* carry = nullptr;     // num_slots x carry_ld fp32
+    int64_t carry_ld = 0;
+};
+
+}  // namespace gp
+
+struct gp_plan {
+    int64_t n = 0, nnz = 0;
+    uint32_t flags = 0;
+    int32_t num_blocks = 0;
+    std::vector<int64_t> block_off;
+    std::vector<int32_t> block_row_lo, block_row_hi;
+    std::vector<int64_t> rowptr;
+    std::vector<int32_t> col;
+    std::vector<int32_t> deg;
+    std::vector<float> dinv_sqrt, dinv;
+
+    // kernel schedule (library's own; not part of the checked plan)
+    int64_t segment_edges = 0;
+    std::vector<gp::Segment> segs;       // grouped by block, longest first inside a block
+    std::vector<int64_t> seg_off;        // b+1: block p owns segs [seg_off[p], seg_off[p+1])
+    std::vector<gp::SplitRow> split;     // ascending row
+    int64_t num_slots = 0;
+
+    mutable std::mutex mu;
+    mutable gp::DevicePlan dev;
+};
+
+namespace gp {
+
+gp_status build_schedule(gp_plan* plan);
+
+// resident schedule: everything already in HBM
+gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,
+                             gp_agg agg, int32_t K, void* out, int64_t ldo, hipStream_t stream);
+// streamed schedule: operands in pinned host memory
+gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,
+                             gp_agg agg, int32_t K, void* out, int64_t ldo);
+
+// ---- kernel launchers (gp_kernels.hip) -------------------------------------
+struct HopArgs {
+    const Segment* segs;    // DEVICE
+    int64_t num_segs;
+    const int32_t* col;     // DEVICE; entry e of the sorted list is col[e - col_base]
+    int64_t col_base;
+    const float* edge_w;    // DEVICE n-vector gathered by column id, or nullptr (weight 1)
+    const float* row_scale; // DEVICE n-vector applied once per finished row, or nullptr
+    const void* xin;        // DEVICE n x d, leading dimension ldin
+    int64_t ldin;
+    void* xout;             // DEVICE n x d, leading dimension ldout
+    int64_t ldout;
+    float* carry;           // DEVICE num_slots x carry_ld
+    int64_t carry_ld;
+    int32_t d;
+    gp_dtype dtype;
+};
+gp_status launch_hop(const HopArgs& a, hipStream_t stream);
+
+struct FixupArgs {
+    const SplitRow* split;  // DEVICE
+    int64_t num_split;
+    const float* carry;
+    int64_t carry_ld;
+    const float* row_scale;
+    void* xout;
+    int64_t ldout;
+    int32_t d;
+    gp_dtype dtype;
+};
+gp_status launch_fixup(const FixupArgs& a, hipStream_t stream);
+
+gp_status launch_copy_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t n, int32_t d,
+                           gp_dtype dtype, hipStream_t stream);
+
+// widest vector (in elements) every row start of both operands is aligned for
+int vector_width(gp_dtype dtype, int32_t d, int64_t ld_a, int64_t ld_b, const void* pa, const void* pb);
+// most feature columns one kernel pass covers with vectors of `vec` elements
+int max_columns_per_pass(int vec);
+
+// ---- profiling --------------------------------------------------------------
+bool profiling_on();
+void profile_begin(const char* name, hipStream_t stream);
+void profile_end(hipStream_t stream);
+
+}  // namespace gp

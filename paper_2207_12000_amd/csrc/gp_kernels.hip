@@ -1,0 +1,389 @@
+// HIP kernels for gfx950: the gather / scale / accumulate of one hop
+// (Algorithm 1, the product S^(j) X^(i) and the accumulation over j), the
+// fixed-order completion of rows that were cut, and the slot-0 copy.
+//
+// Work shape.  A wavefront (64 lanes) is divided into lane groups of G lanes.
+// One group owns one segment: a run of at most a few hundred consecutive
+// non-zeros of one destination row.  The lanes of a group span the feature
+// columns, each lane holding VPL vectors of VEC consecutive elements, so a
+// gathered feature row is read by one coalesced 16-byte-per-lane load.  The
+// group reads its column ids G at a time with one coalesced load (each lane a
+// different id, plus that id's normalisation weight), then hands them round with
+// in-group shuffles; four gathers are kept in flight per group, each with its
+// own accumulator (also what keeps the fp32 sum short-chained).  No cross-lane
+// reduction is needed: lanes own columns, not edges.
+#include <hip/hip_bfloat16.h>
+#include <hip/hip_runtime.h>
+
+#include "gp_internal.h"
+
+namespace gp {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+
+template <int N>
+struct alignas(4 * N) FVec {
+    float v[N];
+};
+template <int N>
+struct alignas(2 * N) HVec {
+    uint16_t v[N];
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// round to nearest even; NaN stays NaN (quiet), infinities pass through
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T, int VEC>
+struct Row;
+
+template <int VEC>
+struct Row<float, VEC> {
+    __device__ static __forceinline__ void load(const float* p, float (&x)[VEC])
+    {
+        const FVec<VEC> t = *reinterpret_cast<const FVec<VEC>*>(p);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) x[i] = t.v[i];
+    }
+    __device__ static __forceinline__ void store(float* p, const float (&x)[VEC])
+    {
+        FVec<VEC> t;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) t.v[i] = x[i];
+        *reinterpret_cast<FVec<VEC>*>(p) = t;
+    }
+};
+
+template <int VEC>
+struct Row<uint16_t, VEC> {
+    __device__ static __forceinline__ void load(const uint16_t* p, float (&x)[VEC])
+    {
+        const HVec<VEC> t = *reinterpret_cast<const HVec<VEC>*>(p);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(t.v[i]);
+    }
+    __device__ static __forceinline__ void store(uint16_t* p, const float (&x)[VEC])
+    {
+        HVec<VEC> t;
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) t.v[i] = f32_to_bf16(x[i]);
+        *reinterpret_cast<HVec<VEC>*>(p) = t;
+    }
+};
+
+// ---------------------------------------------------------------------------
+// one hop over a list of segments
+// ---------------------------------------------------------------------------
+template <typename T, int VEC, int G, int VPL, bool EDGE_W>
+__global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __restrict__ segs, int64_t num_segs,
+                                                            const int32_t* __restrict__ col, int64_t col_base,
+                                                            const float* __restrict__ edge_w,
+                                                            const float* __restrict__ row_scale,
+                                                            const T* __restrict__ xin, int64_t ldin,
+                                                            T* __restrict__ xout, int64_t ldout,
+                                                            float* __restrict__ carry, int64_t carry_ld, int d)
+{
+    constexpr int GPB = kThreads / G;
+    const int lane = threadIdx.x % G;
+    const int64_t sid = (int64_t)blockIdx.x * GPB + threadIdx.x / G;
+    if (sid >= num_segs) return;
+
+    const Segment sg = segs[sid];
+    const int64_t e0 = (((int64_t)sg.start_hi << 32) | (int64_t)sg.start_lo) - col_base;
+    const int len = sg.len;
+
+    // column offsets of this lane's vectors; a vector is live if it starts inside d
+    bool live[VPL];
+    int coff[VPL];
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+        coff[v] = (v * G + lane) * VEC;
+        live[v] = coff[v] < d;
+    }
+
+    float acc[kUnroll][VPL][VEC];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+        for (int v = 0; v < VPL; ++v)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[u][v][i] = 0.0f;
+
+    for (int base = 0; base < len; base += G) {
+        const int cnt = min(G, len - base);
+        int my_col = 0;
+        float my_w = 0.0f;
+        if (lane < cnt) {
+            my_col = col[e0 + base + lane];
+            if (EDGE_W) my_w = edge_w[my_col];
+        }
+        for (int t = 0; t < cnt; t += kUnroll) {
+            float x[kUnroll][VPL][VEC];
+            float w[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                // lanes past cnt hold column 0 / weight 0; their rows are not read
+                const int c = __shfl(my_col, t + u, G);
+                w[u] = EDGE_W ? __shfl(my_w, t + u, G) : 1.0f;
+                const bool on = t + u < cnt;
+                const T* src = xin + (int64_t)c * ldin;
+#pragma unroll
+                for (int v = 0; v < VPL; ++v) {
+                    if (on && live[v]) {
+                        Row<T, VEC>::load(src + coff[v], x[u][v]);
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i) x[u][v][i] = 0.0f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+                for (int v = 0; v < VPL; ++v)
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i)
+                        acc[u][v][i] = EDGE_W ? fmaf(w[u], x[u][v][i], acc[u][v][i]) : acc[u][v][i] + x[u][v][i];
+        }
+    }
+
+    const bool partial = sg.slot >= 0;
+    const float rs = (!partial && row_scale) ? row_scale[sg.row] : 1.0f;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+        if (!live[v]) continue;
+        float r[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) r[i] = ((acc[0][v][i] + acc[1][v][i]) + (acc[2][v][i] + acc[3][v][i])) * rs;
+        if (partial)
+            Row<float, VEC>::store(carry + (int64_t)sg.slot * carry_ld + coff[v], r);
+        else
+            Row<T, VEC>::store(xout + (int64_t)sg.row * ldout + coff[v], r);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// rows that were cut: add their partial rows in list order, scale, store
+// ---------------------------------------------------------------------------
+template <typename T, int VEC, int G, int VPL>
+__global__ __launch_bounds__(kThreads) void gp_fixup_rows(const SplitRow* __restrict__ split, int64_t num_split,
+                                                          const float* __restrict__ carry, int64_t carry_ld,
+                                                          const float* __restrict__ row_scale, T* __restrict__ xout,
+                                                          int64_t ldout, int d)
+{
+    constexpr int GPB = kThreads / G;
+    const int lane = threadIdx.x % G;
+    const int64_t rid = (int64_t)blockIdx.x * GPB + threadIdx.x / G;
+    if (rid >= num_split) return;
+    const SplitRow sr = split[rid];
+    const float rs = row_scale ? row_scale[sr.row] : 1.0f;
+#pragma unroll
+    for (int v = 0; v < VPL; ++v) {
+        const int c0 = (v * G + lane) * VEC;
+        if (c0 >= d) continue;
+        float acc[kUnroll][VEC];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) acc[u][i] = 0.0f;
+        const float* p = carry + sr.first_slot * carry_ld + c0;
+        for (int s = 0; s < sr.count; s += kUnroll) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                if (s + u < sr.count) {
+                    float x[VEC];
+                    Row<float, VEC>::load(p + (int64_t)(s + u) * carry_ld, x);
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) acc[u][i] += x[i];
+                }
+            }
+        }
+        float r[VEC];
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) r[i] = ((acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i])) * rs;
+        Row<T, VEC>::store(xout + (int64_t)sr.row * ldout + c0, r);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// slot 0: out[0] = X (the k = 0 term of the stack)
+// ---------------------------------------------------------------------------
+template <typename U>
+__global__ __launch_bounds__(kThreads) void gp_copy_rows(const U* __restrict__ src, int64_t lds, U* __restrict__ dst,
+                                                         int64_t ldd, int64_t n, int64_t w)
+{
+    const int64_t total = n * w;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+        const int64_t r = i / w, c = i - r * w;
+        dst[r * ldd + c] = src[r * lds + c];
+    }
+}
+
+// ---- dispatch ---------------------------------------------------------------
+
+}  // namespace
+
+int vector_width(gp_dtype dtype, int32_t d, int64_t ld_a, int64_t ld_b, const void* pa, const void* pb)
+{
+    const int es = dtype == GP_F32 ? 4 : 2;
+    int vec = 16 / es;  // 16-byte vectors when everything is aligned for them
+    while (vec > 1) {
+        const int64_t bytes = (int64_t)vec * es;
+        const bool ok = d % vec == 0 && (ld_a * es) % bytes == 0 && (ld_b * es) % bytes == 0 &&
+                        ((uintptr_t)pa % bytes) == 0 && ((uintptr_t)pb % bytes) == 0;
+        if (ok) break;
+        vec /= 2;
+    }
+    return vec;
+}
+
+namespace {
+
+template <typename T, int VEC, int G, int VPL>
+gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
+{
+    constexpr int GPB = kThreads / G;
+    const int64_t blocks = (a.num_segs + GPB - 1) / GPB;
+    if (blocks == 0) return GP_OK;
+    if (blocks > INT32_MAX) return fail(GP_ERR_UNSUPPORTED, "%lld workgroups exceed the grid limit", (long long)blocks);
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    if (a.edge_w)
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, true>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
+                           a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
+                           a.carry_ld, a.d);
+    else
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, false>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
+                           a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
+                           a.carry_ld, a.d);
+    GP_HIP(hipGetLastError());
+    return GP_OK;
+}
+
+template <typename T, int VEC, int G, int VPL>
+gp_status launch_fixup_t(const FixupArgs& a, hipStream_t stream)
+{
+    constexpr int GPB = kThreads / G;
+    const int64_t blocks = (a.num_split + GPB - 1) / GPB;
+    if (blocks == 0) return GP_OK;
+    if (blocks > INT32_MAX) return fail(GP_ERR_UNSUPPORTED, "%lld workgroups exceed the grid limit", (long long)blocks);
+    hipLaunchKernelGGL((gp_fixup_rows<T, VEC, G, VPL>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a.split,
+                       a.num_split, a.carry, a.carry_ld, a.row_scale, (T*)a.xout, a.ldout, a.d);
+    GP_HIP(hipGetLastError());
+    return GP_OK;
+}
+
+// Shape of the lane groups for a row of `d` elements in vectors of `vec`:
+// the smallest power-of-two group (8..64 lanes) that covers the row with one
+// vector per lane, else 64 lanes with several vectors per lane (at most kMaxVpl).
+constexpr int kMaxVpl = 8;
+inline int max_vpl(int vec) { return std::min(kMaxVpl, 16 / vec); }
+inline void group_shape(int32_t d, int vec, int& G, int& vpl)
+{
+    const int nvec = (d + vec - 1) / vec;
+    G = 8;
+    while (G < 64 && G < nvec) G *= 2;
+    vpl = (nvec + G - 1) / G;
+}
+
+#define GP_SHAPE_CASES(FN, T, VEC)                                                  \
+    if (G == 8 && vpl == 1) return FN<T, VEC, 8, 1>(a, stream);                     \
+    if (G == 16 && vpl == 1) return FN<T, VEC, 16, 1>(a, stream);                   \
+    if (G == 32 && vpl == 1) return FN<T, VEC, 32, 1>(a, stream);                   \
+    if (G == 64 && vpl == 1) return FN<T, VEC, 64, 1>(a, stream);                   \
+    if (G == 64 && vpl == 2) return FN<T, VEC, 64, 2>(a, stream);                   \
+    if (G == 64 && vpl == 3) return FN<T, VEC, 64, 3>(a, stream);                   \
+    if (G == 64 && vpl == 4) return FN<T, VEC, 64, 4>(a, stream);                   \
+    if (G == 64 && vpl == 5) return FN<T, VEC, 64, 5>(a, stream);                   \
+    if (G == 64 && vpl == 6) return FN<T, VEC, 64, 6>(a, stream);                   \
+    if (G == 64 && vpl == 7) return FN<T, VEC, 64, 7>(a, stream);                   \
+    if (G == 64 && vpl == 8) return FN<T, VEC, 64, 8>(a, stream);
+
+#define GP_VEC_CASES(FN, T, MAXVEC)                                                 \
+    if (vec == 1) { GP_SHAPE_CASES(FN, T, 1) }                                      \
+    if (vec == 2) { GP_SHAPE_CASES(FN, T, 2) }                                      \
+    if (vec == 4) { GP_SHAPE_CASES(FN, T, 4) }                                      \
+    if (MAXVEC == 8 && vec == 8) { GP_SHAPE_CASES(FN, T, (MAXVEC == 8 ? 8 : 4)) }
+
+}  // namespace
+
+int max_columns_per_pass(int vec) { return 64 * max_vpl(vec) * vec; }
+
+gp_status launch_hop(const HopArgs& a, hipStream_t stream)
+{
+    // carry rows are fp32 and 16-byte aligned by construction (carry_ld % 4 == 0)
+    const int vec = vector_width(a.dtype, a.d, a.ldin, a.ldout, a.xin, a.xout);
+    int G, vpl;
+    group_shape(a.d, vec, G, vpl);
+    if (vpl > max_vpl(vec)) return fail(GP_ERR_UNSUPPORTED, "d = %d needs column tiling (vec = %d)", a.d, vec);
+    if (a.dtype == GP_F32) {
+        GP_VEC_CASES(launch_hop_t, float, 4)
+    } else {
+        GP_VEC_CASES(launch_hop_t, uint16_t, 8)
+    }
+    return fail(GP_ERR_UNSUPPORTED, "no kernel for d = %d, vec = %d", a.d, vec);
+}
+
+gp_status launch_fixup(const FixupArgs& a, hipStream_t stream)
+{
+    // the fix-up reads fp32 carry rows and writes T rows: use the vector width both allow
+    int vec = vector_width(a.dtype, a.d, a.ldout, a.ldout, a.xout, a.xout);
+    if (vec > 4) vec = 4;
+    while (vec > 1 && (a.carry_ld % vec != 0)) vec /= 2;
+    int G, vpl;
+    group_shape(a.d, vec, G, vpl);
+    if (vpl > max_vpl(vec)) return fail(GP_ERR_UNSUPPORTED, "d = %d needs column tiling (vec = %d)", a.d, vec);
+    if (a.dtype == GP_F32) {
+        GP_VEC_CASES(launch_fixup_t, float, 4)
+    } else {
+        GP_VEC_CASES(launch_fixup_t, uint16_t, 4)
+    }
+    return fail(GP_ERR_UNSUPPORTED, "no fix-up kernel for d = %d, vec = %d", a.d, vec);
+}
+
+gp_status launch_copy_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t n, int32_t d, gp_dtype dtype,
+                           hipStream_t stream)
+{
+    if (n == 0) return GP_OK;
+    const int es = dtype == GP_F32 ? 4 : 2;
+    const int64_t row_bytes = (int64_t)d * es;
+    // widest unit (16, 8, 4, 2 bytes) that divides the row, both strides and both bases
+    int unit = 16;
+    while (unit > es) {
+        if (row_bytes % unit == 0 && (lds * es) % unit == 0 && (ldd * es) % unit == 0 && (uintptr_t)src % unit == 0 &&
+            (uintptr_t)dst % unit == 0)
+            break;
+        unit /= 2;
+    }
+    const int64_t w = row_bytes / unit, total = n * w;
+    const int64_t blocks = std::min<int64_t>((total + kThreads - 1) / kThreads, 256 * 32);
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    const int64_t s = lds * es / unit, t = ldd * es / unit;
+    switch (unit) {
+    case 16:
+        hipLaunchKernelGGL(gp_copy_rows<uint4>, grid, block, 0, stream, (const uint4*)src, s, (uint4*)dst, t, n, w);
+        break;
+    case 8:
+        hipLaunchKernelGGL(gp_copy_rows<uint2>, grid, block, 0, stream, (const uint2*)src, s, (uint2*)dst, t, n, w);
+        break;
+    case 4:
+        hipLaunchKernelGGL(gp_copy_rows<uint32_t>, grid, block, 0, stream, (const uint32_t*)src, s, (uint32_t*)dst, t, n, w);
+        break;
+    default:
+        hipLaunchKernelGGL(gp_copy_rows<uint16_t>, grid, block, 0, stream, (const uint16_t*)src, s, (uint16_t*)dst, t, n, w);
+        break;
+    }
+    GP_HIP(hipGetLastError());
+    return GP_OK;
+}
+
+}  // namespace gp

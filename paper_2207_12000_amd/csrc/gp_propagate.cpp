@@ -1,0 +1,194 @@
+// gp_propagate: the hop loop of Algorithm 1 (k = 1..K, every edge block, then
+// the rows cut between blocks) for operands that live in HBM, and plan upload.
+#include <algorithm>
+#include <functional>
+
+#include "gp_internal.h"
+
+namespace gp {
+
+namespace {
+
+template <class T>
+gp_status upload(T*& dptr, const std::vector<T>& h, hipStream_t stream)
+{
+    dptr = nullptr;
+    if (h.empty()) return GP_OK;
+    GP_HIP(hipMalloc((void**)&dptr, h.size() * sizeof(T)));
+    GP_HIP(hipMemcpyAsync(dptr, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice, stream));
+    return GP_OK;
+}
+
+void release(DevicePlan& D)
+{
+    (void)hipFree(D.col);
+    (void)hipFree(D.dinv_sqrt);
+    (void)hipFree(D.dinv);
+    (void)hipFree(D.segs);
+    (void)hipFree(D.split);
+    (void)hipFree(D.carry);
+    D = DevicePlan();
+}
+
+// Uploads the plan once per plan (to the device that is current at that time)
+// and (re)sizes the partial-row buffer for d columns.
+gp_status ensure_device(const gp_plan* plan, int32_t d, hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lk(plan->mu);
+    DevicePlan& D = plan->dev;
+    int cur = -1;
+    GP_HIP(hipGetDevice(&cur));
+    if (D.device >= 0 && D.device != cur)
+        return fail(GP_ERR_INVALID_ARG, "plan lives on device %d but device %d is current", D.device, cur);
+    if (D.device < 0) {
+        gp_status st;
+        if ((st = upload(D.col, plan->col, stream)) != GP_OK || (st = upload(D.dinv_sqrt, plan->dinv_sqrt, stream)) != GP_OK ||
+            (st = upload(D.dinv, plan->dinv, stream)) != GP_OK || (st = upload(D.segs, plan->segs, stream)) != GP_OK ||
+            (st = upload(D.split, plan->split, stream)) != GP_OK) {
+            release(D);
+            return st;
+        }
+        // pageable sources: the copies above are staged, but finish them before returning
+        // so the host vectors may be touched freely afterwards
+        GP_HIP(hipStreamSynchronize(stream));
+        D.device = cur;
+    }
+    const int64_t need_ld = ((int64_t)d + 3) / 4 * 4;
+    if (plan->num_slots > 0 && need_ld > D.carry_ld) {
+        // a running kernel on another stream could still be using the old buffer
+        GP_HIP(hipDeviceSynchronize());
+        (void)hipFree(D.carry);
+        D.carry = nullptr;
+        D.carry_ld = 0;
+        GP_HIP(hipMalloc((void**)&D.carry, (size_t)plan->num_slots * need_ld * sizeof(float)));
+        D.carry_ld = need_ld;
+    }
+    return GP_OK;
+}
+
+}  // namespace
+
+gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg,
+                             int32_t K, void* out, int64_t ldo, hipStream_t stream)
+{
+    gp_status st = ensure_device(plan, d, stream);
+    if (st != GP_OK) return st;
+    const DevicePlan& D = plan->dev;
+    const int64_t n = plan->n;
+    const int es = dtype == GP_F32 ? 4 : 2;
+    char* base = (char*)out;
+    const int64_t slab = n * ldo * es;
+
+    // slot 0 = X
+    if (X != out) {
+        profile_begin("gp_copy_rows", stream);
+        st = launch_copy_rows(X, ldx, out, ldo, n, d, dtype, stream);
+        profile_end(stream);
+        if (st != GP_OK) return st;
+    }
+
+    const float* edge_w = agg == GP_AGG_SYM ? D.dinv_sqrt : nullptr;
+    const float* row_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : agg == GP_AGG_MEAN ? D.dinv : nullptr;
+
+    // column tile: all columns in one pass unless the row is wider than the kernels hold
+    int64_t tile = options().column_tile;
+    {
+        // a tile is a multiple of 16 bytes, so every tile keeps the alignment of the first
+        const int64_t unit = 16 / es;
+        const int64_t cap = max_columns_per_pass(vector_width(dtype, d, ldo, ldo, out, out));
+        if (tile <= 0 || tile > cap) tile = d <= cap ? d : cap;
+        if (tile < d) tile = std::max<int64_t>(unit, tile / unit * unit);
+    }
+
+    for (int32_t k = 1; k <= K; ++k) {
+        const char* xin = base + (int64_t)(k - 1) * slab;
+        char* xout = base + (int64_t)k * slab;
+        for (int64_t c0 = 0; c0 < d; c0 += tile) {
+            const int32_t w = (int32_t)std::min<int64_t>(tile, d - c0);
+            HopArgs a;
+            a.segs = D.segs;
+            a.num_segs = (int64_t)plan->segs.size();
+            a.col = D.col;
+            a.col_base = 0;
+            a.edge_w = edge_w;
+            a.row_scale = row_scale;
+            a.xin = xin + c0 * es;
+            a.ldin = ldo;
+            a.xout = xout + c0 * es;
+            a.ldout = ldo;
+            a.carry = D.carry ? D.carry + c0 : nullptr;
+            a.carry_ld = D.carry_ld;
+            a.d = w;
+            a.dtype = dtype;
+            profile_begin("gp_hop_segments", stream);
+            st = launch_hop(a, stream);
+            profile_end(stream);
+            if (st != GP_OK) return st;
+            if (!plan->split.empty()) {
+                FixupArgs f;
+                f.split = D.split;
+                f.num_split = (int64_t)plan->split.size();
+                f.carry = D.carry + c0;
+                f.carry_ld = D.carry_ld;
+                f.row_scale = row_scale;
+                f.xout = xout + c0 * es;
+                f.ldout = ldo;
+                f.d = w;
+                f.dtype = dtype;
+                profile_begin("gp_fixup_rows", stream);
+                st = launch_fixup(f, stream);
+                profile_end(stream);
+                if (st != GP_OK) return st;
+            }
+        }
+    }
+    return GP_OK;
+}
+
+}  // namespace gp
+
+using namespace gp;
+
+extern "C" void gp_plan_destroy(gp_plan* plan)
+{
+    if (!plan) return;
+    if (plan->dev.device >= 0) {
+        int cur = -1;
+        if (hipGetDevice(&cur) == hipSuccess) {
+            if (cur != plan->dev.device) (void)hipSetDevice(plan->dev.device);
+            (void)hipDeviceSynchronize();
+            release(plan->dev);
+            if (cur != plan->dev.device && cur >= 0) (void)hipSetDevice(cur);
+        }
+    }
+    delete plan;
+}
+
+extern "C" gp_status gp_propagate(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,
+                                  gp_agg agg, int32_t K, void* out_stack, int64_t ldo, void* hip_stream)
+{
+    if (!plan) return fail(GP_ERR_INVALID_ARG, "plan is NULL");
+    if (!X || !out_stack) return fail(GP_ERR_INVALID_ARG, "X or out_stack is NULL");
+    if (d <= 0) return fail(GP_ERR_INVALID_ARG, "d = %d must be positive", d);
+    if (K < 0) return fail(GP_ERR_INVALID_ARG, "K = %d is negative", K);
+    if (ldx < d || ldo < d) return fail(GP_ERR_INVALID_ARG, "leading dimension smaller than d (ldx %lld, ldo %lld, d %d)",
+                                        (long long)ldx, (long long)ldo, d);
+    if (dtype != GP_F32 && dtype != GP_BF16) return fail(GP_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    if (agg != GP_AGG_SYM && agg != GP_AGG_MEAN && agg != GP_AGG_SUM)
+        return fail(GP_ERR_INVALID_ARG, "unknown aggregation %d", (int)agg);
+    if (X == out_stack && ldx != ldo) return fail(GP_ERR_INVALID_ARG, "X aliases slot 0 but ldx != ldo");
+    const int es = dtype == GP_F32 ? 4 : 2;
+    if (((uintptr_t)X % es) || ((uintptr_t)out_stack % es))
+        return fail(GP_ERR_INVALID_ARG, "X / out_stack not aligned to the element size");
+
+    hipPointerAttribute_t ax, ao;
+    if (hipPointerGetAttributes(&ax, X) != hipSuccess || hipPointerGetAttributes(&ao, out_stack) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(GP_ERR_INVALID_ARG, "X / out_stack is neither device memory nor pinned host memory");
+    }
+    const bool xdev = ax.type == hipMemoryTypeDevice, odev = ao.type == hipMemoryTypeDevice;
+    const bool xhost = ax.type == hipMemoryTypeHost, ohost = ao.type == hipMemoryTypeHost;
+    if (xdev && odev) return propagate_resident(plan, X, ldx, d, dtype, agg, K, out_stack, ldo, (hipStream_t)hip_stream);
+    if (xhost && ohost) return propagate_streamed(plan, X, ldx, d, dtype, agg, K, out_stack, ldo);
+    return fail(GP_ERR_INVALID_ARG, "X and out_stack must both be device memory or both be pinned host memory");
+}

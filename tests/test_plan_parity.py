@@ -1,0 +1,173 @@
+"""gp_plan_blocks (library, host C++) against the oracle's planner, bit for bit,
+plus the invariants of the library's own kernel schedule.  No GPU needed: the
+planner is host code."""
+import ctypes
+import re
+import os
+
+import numpy as np
+import pytest
+
+import gp_synth
+import oracle
+import paper_2207_12000_amd as gp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def assert_same_plan(lp: gp.Plan, op: oracle.OraclePlan):
+    assert lp.n == op.n and lp.nnz == op.nnz and lp.num_blocks == op.num_blocks
+    for name in ("block_off", "block_row_lo", "block_row_hi", "rowptr", "col", "deg"):
+        a, b = getattr(lp, name), getattr(op, name)
+        assert a.dtype == b.dtype, name
+        assert np.array_equal(a, b), name
+    # floats compared as bit patterns
+    assert np.array_equal(lp.dinv_sqrt.view(np.uint32), op.dinv_sqrt.view(np.uint32))
+    assert np.array_equal(lp.dinv.view(np.uint32), op.dinv.view(np.uint32))
+
+
+def check_schedule(lp: gp.Plan, L: int):
+    """Segments: cover every list position once, stay inside one row and one
+    block, are at most L long, longest first per block; every row is either one
+    whole-row segment or a run of consecutive slots in list order."""
+    seg = lp.segments
+    soff = lp.segment_off
+    boff = lp.block_off
+    rowptr = lp.rowptr
+    n, nnz, b = lp.n, lp.nnz, lp.num_blocks
+    start = seg["start_lo"].astype(np.int64) | (seg["start_hi"].astype(np.int64) << 32)
+    ln = seg["len"].astype(np.int64)
+    row = seg["row"].astype(np.int64)
+    slot = seg["slot"].astype(np.int64)
+    assert soff[0] == 0 and soff[-1] == seg.size
+    assert ln.max(initial=0) <= L
+    cover = np.zeros(nnz + 1, dtype=np.int64)
+    np.add.at(cover, start, 1)
+    np.add.at(cover, start + ln, -1)
+    assert np.all(np.cumsum(cover)[:nnz] == 1)                 # each position exactly once
+    assert np.all(start >= rowptr[row]) and np.all(start + ln <= rowptr[row + 1])
+    for p in range(b):
+        s, e = soff[p], soff[p + 1]
+        nz = ln[s:e] > 0
+        assert np.all(start[s:e][nz] >= boff[p]) and np.all((start + ln)[s:e][nz] <= boff[p + 1])
+        assert np.all(np.diff(ln[s:e]) <= 0)                   # longest first
+    per_row = np.bincount(row, minlength=n)
+    assert np.all(per_row >= 1)                                # empty rows still owe a zero row
+    whole = slot < 0
+    assert np.all(per_row[row[whole]] == 1)
+    assert np.all(ln[whole] == (rowptr[row[whole] + 1] - rowptr[row[whole]]))
+    part = ~whole
+    assert np.all(per_row[row[part]] > 1)
+    assert lp.num_partial_rows == int(part.sum())
+    if part.any():
+        order = np.lexsort((start[part], row[part]))
+        assert np.array_equal(slot[part][order], np.arange(part.sum()))   # slots follow (row, list order)
+
+
+CASES = [
+    ([], [], 4, 3), ([2], [0], 3, 10), ([0, 1], [1, 2], 3, 4), ([0, 0, 1, 2, 2, 1], [1, 1, 0, 2, 2, 1], 3, 100),
+    ([0], [0], 1, 1),
+]
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+@pytest.mark.parametrize("case", CASES)
+def test_tiny_cases_bit_exact(case, flags):
+    src, dst, n, budget = case
+    op = oracle.plan_blocks(src, dst, n, budget, flags)
+    with gp.gp_plan_blocks(src, dst, n, budget, flags) as lp:
+        assert_same_plan(lp, op)
+        check_schedule(lp, gp.gp_get_option("segment_edges"))
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+@pytest.mark.parametrize("seed", range(6))
+def test_random_graphs_bit_exact(seed, flags):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(1, 300))
+    m = int(rng.integers(0, 3000))
+    src = rng.integers(0, n, m)
+    dst = rng.integers(0, n, m)
+    for budget in (1, 5, 64, 10**7):
+        op = oracle.plan_blocks(src, dst, n, budget, flags)
+        with gp.gp_plan_blocks(src, dst, n, budget, flags) as lp:
+            assert_same_plan(lp, op)
+            check_schedule(lp, gp.gp_get_option("segment_edges"))
+
+
+@pytest.mark.parametrize("config,scale", [(1, 1.0), (2, 0.25), (3, 0.01), (4, 0.002), (5, 0.0002)])
+def test_workloads_bit_exact_threaded(config, scale):
+    w = gp_synth.make_workload(config, scale=scale, with_features=False)
+    budget = w.block_budget_edges or 10**9
+    op = oracle.plan_blocks(w.src, w.dst, w.n, budget, w.flags)
+    if w.n_blocks:
+        budget = -(-op.nnz // w.n_blocks)
+        op = oracle.plan_blocks(w.src, w.dst, w.n, budget, w.flags)
+        assert op.num_blocks == w.n_blocks
+    for L in (256, 8):
+        gp.gp_set_option("segment_edges", L)
+        try:
+            with gp.gp_plan_blocks(w.src, w.dst, w.n, budget, w.flags) as lp:
+                assert_same_plan(lp, op)
+                check_schedule(lp, L)
+                if L == 8:
+                    assert lp.num_partial_rows > 0            # hubs and block cuts were exercised
+        finally:
+            gp.gp_set_option("segment_edges", 256)
+
+
+def test_hub_row_split_across_many_blocks():
+    n = 50
+    src = list(range(1, n)) * 1
+    dst = [0] * (n - 1)                                        # row 0 has 49 (+1) entries
+    for flags in (0, 3):
+        op = oracle.plan_blocks(src, dst, n, 7, flags)
+        with gp.gp_plan_blocks(src, dst, n, 7, flags) as lp:
+            assert_same_plan(lp, op)
+            check_schedule(lp, 256)
+            assert lp.num_partial_rows >= 7
+
+
+def test_error_codes_match_oracle_kinds():
+    kinds = {"INVALID_ARG": gp.GP_ERR_INVALID_ARG, "INDEX_RANGE": gp.GP_ERR_INDEX_RANGE}
+    bad = [([0], [3], 3, 1, 0), ([-1], [0], 3, 1, 0), ([0], [1], 0, 1, 0), ([0], [1], 3, 0, 0), ([0], [1], 3, 1, 4),
+           ([0], [1], 2**31, 1, 0)]
+    for src, dst, n, budget, flags in bad:
+        with pytest.raises(oracle.OracleError) as oe:
+            oracle.plan_blocks(src, dst, n, budget, flags)
+        with pytest.raises(gp.GpError) as ge:
+            gp.gp_plan_blocks(src, dst, n, budget, flags)
+        assert ge.value.status == kinds[oe.value.kind]
+        assert gp.gp_last_error()
+    # NULL arguments straight through the C ABI
+    l = gp.lib()
+    out = ctypes.c_void_p(123)
+    assert l.gp_plan_blocks(None, None, 5, 3, 1, 0, ctypes.byref(out)) == gp.GP_ERR_INVALID_ARG
+    assert out.value is None
+    assert l.gp_plan_blocks(None, None, -1, 3, 1, 0, ctypes.byref(out)) == gp.GP_ERR_INVALID_ARG
+    assert l.gp_plan_blocks(None, None, 0, 3, 1, 0, None) == gp.GP_ERR_INVALID_ARG
+    l.gp_plan_destroy(None)
+    assert l.gp_plan_nnz(None) == 0 and l.gp_plan_col(None) is None
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "gp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(gp_[a-z0-9_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    l = gp.lib()
+    for name in sorted(declared):
+        assert hasattr(l, name), f"{name} declared in gp.h but not exported"
+    assert declared == set(gp.EXPORTED_SYMBOLS)
+
+
+def test_options_and_status_strings():
+    assert gp.gp_status_string(0) == "GP_OK" and gp.gp_status_string(2) == "GP_ERR_INDEX_RANGE"
+    with pytest.raises(gp.GpError):
+        gp.gp_set_option("segment_edges", 4)
+    with pytest.raises(gp.GpError):
+        gp.gp_set_option("no_such_option", 1)
+    assert gp.gp_get_option("no_such_option") == -1
+    with pytest.raises(gp.GpError):
+        gp.gp_set_hbm_budget_bytes(-1)
+    gp.gp_set_hbm_budget_bytes(0)
