@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, choices=sorted(WORKLOAD_NAMES))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="library option (gp_set_option), e.g. column_tile=32")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -66,6 +68,10 @@ def main() -> int:
         return 2
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    for kv in args.option:
+        name, val = kv.split("=")
+        gp.gp_set_option(name, int(val))
 
     t0 = time.time()
     w = gp_synth.make_workload(args.workload)
@@ -132,7 +138,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": WORKLOAD_NAMES[args.workload], "n": n, "nnz": nnz, "d": d, "K": K,
                    "edge_blocks": plan.num_blocks, "agg": ["sym", "mean", "sum"][w.agg],
-                   "segments": int(plan.segments.size), "partial_rows": plan.num_partial_rows},
+                   "segments": int(plan.segments.size), "partial_rows": plan.num_partial_rows,
+                   "options": {k: gp.gp_get_option(k) for k in ("segment_edges", "column_tile", "column_slices")}},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "kernel": "gp_hop_segments", "launches": launches,

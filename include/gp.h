@@ -147,9 +147,11 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
 
 /* Named integer options; unknown names give INVALID_ARG.
  *   "segment_edges"   longest run of non-zeros one lane group walks before the row
- *                     is split into partial rows (8 .. 32768; default 256).  Read
+ *                     is split into partial rows (8 .. 32768; default 64).  Read
  *                     by gp_plan_blocks.
  *   "column_tile"     feature columns per pass of the kernel, 0 = automatic.
+ *   "column_slices"   column slices one pass is divided into, one slice per XCD
+ *                     (1, 2, 4, 8; 0 = automatic).
  */
 gp_status gp_set_option(const char *name, int64_t value);
 int64_t gp_get_option(const char *name); /* -1 for an unknown name */

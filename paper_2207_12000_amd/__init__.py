@@ -19,7 +19,8 @@ GP_F32, GP_BF16 = 0, 1
 GP_SYMMETRISE, GP_ADD_SELF_LOOPS = 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libgp.so")
+# GP_LIB names another build of the same library (tuning variants); default: the in-tree one
+LIB_PATH = os.environ.get("GP_LIB") or os.path.join(_HERE, "libgp.so")
 
 # every symbol include/gp.h declares: (restype, argtypes)
 _c = ctypes

@@ -119,6 +119,12 @@ gp_status gp_set_option(const char* name, int64_t value)
         options().column_tile = value;
         return GP_OK;
     }
+    if (!strcmp(name, "column_slices")) {
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+            return fail(GP_ERR_INVALID_ARG, "column_slices must be 0 (automatic), 1, 2, 4 or 8");
+        options().column_slices = value;
+        return GP_OK;
+    }
     return fail(GP_ERR_INVALID_ARG, "unknown option '%s'", name);
 }
 
@@ -127,6 +133,7 @@ int64_t gp_get_option(const char* name)
     if (!name) return -1;
     if (!strcmp(name, "segment_edges")) return options().segment_edges;
     if (!strcmp(name, "column_tile")) return options().column_tile;
+    if (!strcmp(name, "column_slices")) return options().column_slices;
     if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
     return -1;
 }

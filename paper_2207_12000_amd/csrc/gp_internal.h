@@ -26,8 +26,9 @@ gp_status fail(gp_status s, const char* fmt, ...) __attribute__((format(printf, 
 
 // ---- options ------------------------------------------------------------
 struct Options {
-    int64_t segment_edges = 256;
+    int64_t segment_edges = 64;
     int64_t column_tile = 0;
+    int64_t column_slices = 0;
     int64_t hbm_budget_bytes = 0;
 };
 Options& options();
@@ -118,6 +119,8 @@ struct HopArgs {
     int64_t carry_ld;
     int32_t d;
     gp_dtype dtype;
+    int num_slices = 1;     // chosen by launch_hop
+    int slice_elems = 0;
 };
 gp_status launch_hop(const HopArgs& a, hipStream_t stream);
 

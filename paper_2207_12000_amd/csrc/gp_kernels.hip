@@ -24,13 +24,13 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
 
-template <int N>
-struct alignas(4 * N) FVec {
-    float v[N];
+template <typename E, int N>
+struct VecOf {
+    typedef E type __attribute__((ext_vector_type(N)));
 };
-template <int N>
-struct alignas(2 * N) HVec {
-    uint16_t v[N];
+template <typename E>
+struct VecOf<E, 1> {
+    typedef E type;
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
@@ -44,40 +44,75 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
     return (uint16_t)(u >> 16);
 }
 
+template <typename V, int N>
+__device__ __forceinline__ auto elem(const V& v, int i)
+{
+    if constexpr (N == 1)
+        return v;
+    else
+        return v[i];
+}
+
+// Row<T, VEC>: one aligned VEC-element vector of a feature row, widened to fp32.
+// NT = true marks the access non-temporal (streamed once: do not keep it in cache).
 template <typename T, int VEC>
 struct Row;
 
 template <int VEC>
 struct Row<float, VEC> {
+    using V = typename VecOf<float, VEC>::type;
+    template <bool NT = false>
     __device__ static __forceinline__ void load(const float* p, float (&x)[VEC])
     {
-        const FVec<VEC> t = *reinterpret_cast<const FVec<VEC>*>(p);
+        const V* q = reinterpret_cast<const V*>(p);
+        const V t = NT ? __builtin_nontemporal_load(q) : *q;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) x[i] = t.v[i];
+        for (int i = 0; i < VEC; ++i) x[i] = elem<V, VEC>(t, i);
     }
+    template <bool NT = false>
     __device__ static __forceinline__ void store(float* p, const float (&x)[VEC])
     {
-        FVec<VEC> t;
+        V t;
+        if constexpr (VEC == 1) {
+            t = x[0];
+        } else {
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) t.v[i] = x[i];
-        *reinterpret_cast<FVec<VEC>*>(p) = t;
+            for (int i = 0; i < VEC; ++i) t[i] = x[i];
+        }
+        V* q = reinterpret_cast<V*>(p);
+        if (NT)
+            __builtin_nontemporal_store(t, q);
+        else
+            *q = t;
     }
 };
 
 template <int VEC>
 struct Row<uint16_t, VEC> {
+    using V = typename VecOf<uint16_t, VEC>::type;
+    template <bool NT = false>
     __device__ static __forceinline__ void load(const uint16_t* p, float (&x)[VEC])
     {
-        const HVec<VEC> t = *reinterpret_cast<const HVec<VEC>*>(p);
+        const V* q = reinterpret_cast<const V*>(p);
+        const V t = NT ? __builtin_nontemporal_load(q) : *q;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(t.v[i]);
+        for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(elem<V, VEC>(t, i));
     }
+    template <bool NT = false>
     __device__ static __forceinline__ void store(uint16_t* p, const float (&x)[VEC])
     {
-        HVec<VEC> t;
+        V t;
+        if constexpr (VEC == 1) {
+            t = f32_to_bf16(x[0]);
+        } else {
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) t.v[i] = f32_to_bf16(x[i]);
-        *reinterpret_cast<HVec<VEC>*>(p) = t;
+            for (int i = 0; i < VEC; ++i) t[i] = f32_to_bf16(x[i]);
+        }
+        V* q = reinterpret_cast<V*>(p);
+        if (NT)
+            __builtin_nontemporal_store(t, q);
+        else
+            *q = t;
     }
 };
 
@@ -91,14 +126,34 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
                                                             const float* __restrict__ row_scale,
                                                             const T* __restrict__ xin, int64_t ldin,
                                                             T* __restrict__ xout, int64_t ldout,
-                                                            float* __restrict__ carry, int64_t carry_ld, int d)
+                                                            float* __restrict__ carry, int64_t carry_ld, int d,
+                                                            int num_slices, int slice_elems)
 {
     constexpr int GPB = kThreads / G;
     const int lane = threadIdx.x % G;
-    const int64_t sid = (int64_t)blockIdx.x * GPB + threadIdx.x / G;
+    // Workgroups are handed to the 8 XCDs round-robin by id.  Each XCD works on one
+    // column slice of X only (slice = xcd mod num_slices), so its private L2 caches
+    // num_slices times more distinct rows; the XCDs that share a slice split the
+    // segment list between them.  num_slices is 1, 2, 4 or 8.
+    const int xcd = blockIdx.x & 7;
+    const int slice = xcd & (num_slices - 1);
+    const int64_t chunk = (int64_t)(blockIdx.x >> 3) * (8 / num_slices) + xcd / num_slices;
+    const int64_t sid = chunk * GPB + threadIdx.x / G;
     if (sid >= num_segs) return;
+    const int cbase = slice * slice_elems;
+    const int cend = min(d, cbase + slice_elems);
 
-    const Segment sg = segs[sid];
+    Segment sg;
+    {
+        typedef int v4i __attribute__((ext_vector_type(4)));
+        const v4i* sp = reinterpret_cast<const v4i*>(segs + sid);
+        const v4i raw = *sp;
+        sg.start_lo = (uint32_t)raw[0];
+        sg.start_hi = (uint16_t)((uint32_t)raw[1] & 0xFFFFu);
+        sg.len = (uint16_t)((uint32_t)raw[1] >> 16);
+        sg.row = raw[2];
+        sg.slot = raw[3];
+    }
     const int64_t e0 = (((int64_t)sg.start_hi << 32) | (int64_t)sg.start_lo) - col_base;
     const int len = sg.len;
 
@@ -107,8 +162,8 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     int coff[VPL];
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
-        coff[v] = (v * G + lane) * VEC;
-        live[v] = coff[v] < d;
+        coff[v] = cbase + (v * G + lane) * VEC;
+        live[v] = coff[v] < cend;
     }
 
     float acc[kUnroll][VPL][VEC];
@@ -253,18 +308,20 @@ template <typename T, int VEC, int G, int VPL>
 gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
 {
     constexpr int GPB = kThreads / G;
-    const int64_t blocks = (a.num_segs + GPB - 1) / GPB;
-    if (blocks == 0) return GP_OK;
+    const int64_t chunks = (a.num_segs + GPB - 1) / GPB;
+    if (chunks == 0) return GP_OK;
+    const int reps = 8 / a.num_slices;  // XCDs that share one slice
+    const int64_t blocks = 8 * ((chunks + reps - 1) / reps);
     if (blocks > INT32_MAX) return fail(GP_ERR_UNSUPPORTED, "%lld workgroups exceed the grid limit", (long long)blocks);
     const dim3 grid((unsigned)blocks), block(kThreads);
     if (a.edge_w)
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, true>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems);
     else
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, false>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems);
     GP_HIP(hipGetLastError());
     return GP_OK;
 }
@@ -318,12 +375,24 @@ inline void group_shape(int32_t d, int vec, int& G, int& vpl)
 
 int max_columns_per_pass(int vec) { return 64 * max_vpl(vec) * vec; }
 
-gp_status launch_hop(const HopArgs& a, hipStream_t stream)
+gp_status launch_hop(const HopArgs& a_in, hipStream_t stream)
 {
+    HopArgs a = a_in;
     // carry rows are fp32 and 16-byte aligned by construction (carry_ld % 4 == 0)
     const int vec = vector_width(a.dtype, a.d, a.ldin, a.ldout, a.xin, a.xout);
+    const int es = a.dtype == GP_F32 ? 4 : 2;
+    const int nvec = (a.d + vec - 1) / vec;
+    // column slices: as many (1, 2, 4, 8) as keep a slice at least 256 bytes wide
+    int S = (int)options().column_slices;
+    if (S != 1 && S != 2 && S != 4 && S != 8) {
+        S = 1;
+        while (S < 8 && (int64_t)a.d * es / (2 * S) >= 256) S *= 2;
+    }
+    while (S > 1 && nvec < S) S /= 2;
+    a.num_slices = S;
+    a.slice_elems = (nvec + S - 1) / S * vec;
     int G, vpl;
-    group_shape(a.d, vec, G, vpl);
+    group_shape(a.slice_elems, vec, G, vpl);
     if (vpl > max_vpl(vec)) return fail(GP_ERR_UNSUPPORTED, "d = %d needs column tiling (vec = %d)", a.d, vec);
     if (a.dtype == GP_F32) {
         GP_VEC_CASES(launch_hop_t, float, 4)

@@ -9,6 +9,8 @@ import gp_synth
 import oracle
 import paper_2207_12000_amd as gp
 
+DEFAULT_SEGMENT_EDGES = 64
+
 pytestmark = pytest.mark.gpu
 
 TOL = {gp.GP_F32: 1e-5, gp.GP_BF16: 1e-2}
@@ -152,7 +154,7 @@ def test_hub_rows_and_block_cuts_small_segments():
         for budget in (10**9, 1000, 37):
             parity_case(w, K=2, budget=budget, agg=gp.GP_AGG_SYM)
     finally:
-        gp.gp_set_option("segment_edges", 256)
+        gp.gp_set_option("segment_edges", DEFAULT_SEGMENT_EDGES)
 
 
 def test_star_graph_one_row_spans_every_block():

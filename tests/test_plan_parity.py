@@ -12,6 +12,8 @@ import gp_synth
 import oracle
 import paper_2207_12000_amd as gp
 
+DEFAULT_SEGMENT_EDGES = 64
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
@@ -104,7 +106,7 @@ def test_workloads_bit_exact_threaded(config, scale):
         budget = -(-op.nnz // w.n_blocks)
         op = oracle.plan_blocks(w.src, w.dst, w.n, budget, w.flags)
         assert op.num_blocks == w.n_blocks
-    for L in (256, 8):
+    for L in (DEFAULT_SEGMENT_EDGES, 256, 8):
         gp.gp_set_option("segment_edges", L)
         try:
             with gp.gp_plan_blocks(w.src, w.dst, w.n, budget, w.flags) as lp:
@@ -113,7 +115,7 @@ def test_workloads_bit_exact_threaded(config, scale):
                 if L == 8:
                     assert lp.num_partial_rows > 0            # hubs and block cuts were exercised
         finally:
-            gp.gp_set_option("segment_edges", 256)
+            gp.gp_set_option("segment_edges", DEFAULT_SEGMENT_EDGES)
 
 
 def test_hub_row_split_across_many_blocks():
@@ -124,7 +126,7 @@ def test_hub_row_split_across_many_blocks():
         op = oracle.plan_blocks(src, dst, n, 7, flags)
         with gp.gp_plan_blocks(src, dst, n, 7, flags) as lp:
             assert_same_plan(lp, op)
-            check_schedule(lp, 256)
+            check_schedule(lp, DEFAULT_SEGMENT_EDGES)
             assert lp.num_partial_rows >= 7
 
 
