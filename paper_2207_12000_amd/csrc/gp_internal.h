@@ -90,6 +90,9 @@ struct gp_plan {
 
     mutable std::mutex mu;
     mutable gp::DevicePlan dev;
+    // pinned host mirrors of col / segs for the streamed schedule (made on first use)
+    mutable int32_t* pinned_col = nullptr;
+    mutable gp::Segment* pinned_segs = nullptr;
 };
 
 namespace gp {
@@ -139,6 +142,13 @@ gp_status launch_fixup(const FixupArgs& a, hipStream_t stream);
 
 gp_status launch_copy_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t n, int32_t d,
                            gp_dtype dtype, hipStream_t stream);
+
+void release_pinned(gp_plan* plan);
+
+// all column passes of one hop kernel / of the fix-up, with the partial-row buffer
+// offset pass by pass
+gp_status hop_passes(const HopArgs& a, hipStream_t stream);
+gp_status fixup_passes(const FixupArgs& f, hipStream_t stream);
 
 // widest vector (in elements) every row start of both operands is aligned for
 int vector_width(gp_dtype dtype, int32_t d, int64_t ld_a, int64_t ld_b, const void* pa, const void* pb);

@@ -66,7 +66,56 @@ gp_status ensure_device(const gp_plan* plan, int32_t d, hipStream_t stream)
     return GP_OK;
 }
 
+// width of one kernel pass over the columns: everything at once unless the row is
+// wider than the kernels hold; a pass is a multiple of 16 bytes so every pass keeps
+// the alignment of the first
+int64_t pass_width(gp_dtype dtype, int32_t d, int64_t lda, int64_t ldb, const void* pa, const void* pb)
+{
+    const int es = dtype == GP_F32 ? 4 : 2;
+    const int64_t unit = 16 / es;
+    const int64_t cap = max_columns_per_pass(vector_width(dtype, d, lda, ldb, pa, pb));
+    int64_t tile = options().column_tile;
+    if (tile <= 0 || tile > cap) tile = d <= cap ? d : cap;
+    if (tile < d) tile = std::max<int64_t>(unit, tile / unit * unit);
+    return tile;
+}
+
 }  // namespace
+
+gp_status hop_passes(const HopArgs& a0, hipStream_t stream)
+{
+    const int es = a0.dtype == GP_F32 ? 4 : 2;
+    const int64_t tile = pass_width(a0.dtype, a0.d, a0.ldin, a0.ldout, a0.xin, a0.xout);
+    for (int64_t c0 = 0; c0 < a0.d; c0 += tile) {
+        HopArgs a = a0;
+        a.d = (int32_t)std::min<int64_t>(tile, a0.d - c0);
+        a.xin = (const char*)a0.xin + c0 * es;
+        a.xout = (char*)a0.xout + c0 * es;
+        a.carry = a0.carry ? a0.carry + c0 : nullptr;
+        profile_begin("gp_hop_segments", stream);
+        gp_status st = launch_hop(a, stream);
+        profile_end(stream);
+        if (st != GP_OK) return st;
+    }
+    return GP_OK;
+}
+
+gp_status fixup_passes(const FixupArgs& f0, hipStream_t stream)
+{
+    const int es = f0.dtype == GP_F32 ? 4 : 2;
+    const int64_t tile = pass_width(f0.dtype, f0.d, f0.ldout, f0.ldout, f0.xout, f0.xout);
+    for (int64_t c0 = 0; c0 < f0.d; c0 += tile) {
+        FixupArgs f = f0;
+        f.d = (int32_t)std::min<int64_t>(tile, f0.d - c0);
+        f.xout = (char*)f0.xout + c0 * es;
+        f.carry = f0.carry + c0;
+        profile_begin("gp_fixup_rows", stream);
+        gp_status st = launch_fixup(f, stream);
+        profile_end(stream);
+        if (st != GP_OK) return st;
+    }
+    return GP_OK;
+}
 
 gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg,
                              int32_t K, void* out, int64_t ldo, hipStream_t stream)
@@ -90,56 +139,35 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
     const float* edge_w = agg == GP_AGG_SYM ? D.dinv_sqrt : nullptr;
     const float* row_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : agg == GP_AGG_MEAN ? D.dinv : nullptr;
 
-    // column tile: all columns in one pass unless the row is wider than the kernels hold
-    int64_t tile = options().column_tile;
-    {
-        // a tile is a multiple of 16 bytes, so every tile keeps the alignment of the first
-        const int64_t unit = 16 / es;
-        const int64_t cap = max_columns_per_pass(vector_width(dtype, d, ldo, ldo, out, out));
-        if (tile <= 0 || tile > cap) tile = d <= cap ? d : cap;
-        if (tile < d) tile = std::max<int64_t>(unit, tile / unit * unit);
-    }
-
     for (int32_t k = 1; k <= K; ++k) {
-        const char* xin = base + (int64_t)(k - 1) * slab;
-        char* xout = base + (int64_t)k * slab;
-        for (int64_t c0 = 0; c0 < d; c0 += tile) {
-            const int32_t w = (int32_t)std::min<int64_t>(tile, d - c0);
-            HopArgs a;
-            a.segs = D.segs;
-            a.num_segs = (int64_t)plan->segs.size();
-            a.col = D.col;
-            a.col_base = 0;
-            a.edge_w = edge_w;
-            a.row_scale = row_scale;
-            a.xin = xin + c0 * es;
-            a.ldin = ldo;
-            a.xout = xout + c0 * es;
-            a.ldout = ldo;
-            a.carry = D.carry ? D.carry + c0 : nullptr;
-            a.carry_ld = D.carry_ld;
-            a.d = w;
-            a.dtype = dtype;
-            profile_begin("gp_hop_segments", stream);
-            st = launch_hop(a, stream);
-            profile_end(stream);
-            if (st != GP_OK) return st;
-            if (!plan->split.empty()) {
-                FixupArgs f;
-                f.split = D.split;
-                f.num_split = (int64_t)plan->split.size();
-                f.carry = D.carry + c0;
-                f.carry_ld = D.carry_ld;
-                f.row_scale = row_scale;
-                f.xout = xout + c0 * es;
-                f.ldout = ldo;
-                f.d = w;
-                f.dtype = dtype;
-                profile_begin("gp_fixup_rows", stream);
-                st = launch_fixup(f, stream);
-                profile_end(stream);
-                if (st != GP_OK) return st;
-            }
+        HopArgs a;
+        a.segs = D.segs;
+        a.num_segs = (int64_t)plan->segs.size();
+        a.col = D.col;
+        a.col_base = 0;
+        a.edge_w = edge_w;
+        a.row_scale = row_scale;
+        a.xin = base + (int64_t)(k - 1) * slab;
+        a.ldin = ldo;
+        a.xout = base + (int64_t)k * slab;
+        a.ldout = ldo;
+        a.carry = D.carry;
+        a.carry_ld = D.carry_ld;
+        a.d = d;
+        a.dtype = dtype;
+        if ((st = hop_passes(a, stream)) != GP_OK) return st;
+        if (!plan->split.empty()) {
+            FixupArgs f;
+            f.split = D.split;
+            f.num_split = (int64_t)plan->split.size();
+            f.carry = D.carry;
+            f.carry_ld = D.carry_ld;
+            f.row_scale = row_scale;
+            f.xout = a.xout;
+            f.ldout = ldo;
+            f.d = d;
+            f.dtype = dtype;
+            if ((st = fixup_passes(f, stream)) != GP_OK) return st;
         }
     }
     return GP_OK;
@@ -161,6 +189,7 @@ extern "C" void gp_plan_destroy(gp_plan* plan)
             if (cur != plan->dev.device && cur >= 0) (void)hipSetDevice(cur);
         }
     }
+    release_pinned(plan);
     delete plan;
 }
 

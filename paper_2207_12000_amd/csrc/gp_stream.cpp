@@ -1,11 +1,239 @@
-// Streamed schedule (operands in pinned host memory): not built yet.
+// Streamed schedule: X and the hop stack live in pinned host memory and only a
+// bounded part of the problem is in HBM at any time (the situation Section 3.2
+// is written for: the edge list and the features do not fit on the GPU, Eq. 12).
+//
+// What stays on the device for the whole call: the two normalisation vectors,
+// the list of cut rows, the partial-row buffer, two column slabs of the feature
+// matrix (n x w) and two edge-block buffers.  The block count b is fixed by the
+// plan; the slab width w (the paper's column blocks, c = ceil(d / w)) is the
+// largest that fits the HBM budget.  Unlike Algorithm 1, which re-uploads every
+// edge block for every column block of every hop AND moves every slab in and out
+// once per hop, a slab here stays in HBM across all K hops (the hops of one
+// column slab do not depend on the other slabs), so features cross the host link
+// once in and K (+1) times out, and only the edge blocks are re-sent, c*K times,
+// double-buffered on a side stream while the previous block is being computed.
+#include <algorithm>
+#include <cstring>
+
 #include "gp_internal.h"
 
 namespace gp {
 
-gp_status propagate_streamed(const gp_plan*, const void*, int64_t, int32_t, gp_dtype, gp_agg, int32_t, void*, int64_t)
+namespace {
+
+struct Streams {
+    hipStream_t in = nullptr, cmp = nullptr, out = nullptr;
+    hipEvent_t blk_ready[2] = {nullptr, nullptr}, blk_free[2] = {nullptr, nullptr};
+    hipEvent_t slab_in = nullptr, hop_done = nullptr, out_done[2] = {nullptr, nullptr};
+    std::vector<void*> dev;
+
+    ~Streams()
+    {
+        if (in) (void)hipStreamSynchronize(in);
+        if (cmp) (void)hipStreamSynchronize(cmp);
+        if (out) (void)hipStreamSynchronize(out);
+        for (void* p : dev) (void)hipFree(p);
+        for (hipEvent_t e : {blk_ready[0], blk_ready[1], blk_free[0], blk_free[1], slab_in, hop_done, out_done[0], out_done[1]})
+            if (e) (void)hipEventDestroy(e);
+        if (in) (void)hipStreamDestroy(in);
+        if (cmp) (void)hipStreamDestroy(cmp);
+        if (out) (void)hipStreamDestroy(out);
+    }
+    gp_status init()
+    {
+        // default priority on purpose: all three streams are peers
+        GP_HIP(hipStreamCreateWithFlags(&in, hipStreamNonBlocking));
+        GP_HIP(hipStreamCreateWithFlags(&cmp, hipStreamNonBlocking));
+        GP_HIP(hipStreamCreateWithFlags(&out, hipStreamNonBlocking));
+        for (hipEvent_t* e : {&blk_ready[0], &blk_ready[1], &blk_free[0], &blk_free[1], &slab_in, &hop_done, &out_done[0], &out_done[1]})
+            GP_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
+        return GP_OK;
+    }
+    template <class T>
+    gp_status alloc(T*& p, size_t bytes)
+    {
+        p = nullptr;
+        if (bytes == 0) return GP_OK;
+        void* q = nullptr;
+        GP_HIP(hipMalloc(&q, bytes));
+        dev.push_back(q);
+        p = (T*)q;
+        return GP_OK;
+    }
+};
+
+// pinned mirrors of the two arrays that are streamed block by block
+gp_status ensure_pinned(const gp_plan* plan)
 {
-    return fail(GP_ERR_UNSUPPORTED, "pinned-host operands (streamed schedule) are not supported yet");
+    std::lock_guard<std::mutex> lk(plan->mu);
+    if (!plan->pinned_col && !plan->col.empty()) {
+        void* p = nullptr;
+        hipError_t e = hipHostMalloc(&p, plan->col.size() * sizeof(int32_t), hipHostMallocDefault);
+        if (e != hipSuccess) return fail(GP_ERR_OOM_HOST, "pinned copy of the column list: %s", hipGetErrorString(e));
+        std::memcpy(p, plan->col.data(), plan->col.size() * sizeof(int32_t));
+        plan->pinned_col = (int32_t*)p;
+    }
+    if (!plan->pinned_segs && !plan->segs.empty()) {
+        void* p = nullptr;
+        hipError_t e = hipHostMalloc(&p, plan->segs.size() * sizeof(Segment), hipHostMallocDefault);
+        if (e != hipSuccess) return fail(GP_ERR_OOM_HOST, "pinned copy of the segment list: %s", hipGetErrorString(e));
+        std::memcpy(p, plan->segs.data(), plan->segs.size() * sizeof(Segment));
+        plan->pinned_segs = (Segment*)p;
+    }
+    return GP_OK;
+}
+
+}  // namespace
+
+void release_pinned(gp_plan* plan)
+{
+    if (plan->pinned_col) (void)hipHostFree(plan->pinned_col);
+    if (plan->pinned_segs) (void)hipHostFree(plan->pinned_segs);
+    plan->pinned_col = nullptr;
+    plan->pinned_segs = nullptr;
+}
+
+gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg,
+                             int32_t K, void* out, int64_t ldo)
+{
+    const int64_t n = plan->n;
+    const int32_t b = plan->num_blocks;
+    const int es = dtype == GP_F32 ? 4 : 2;
+    const int64_t unit = 16 / es;  // slabs are whole 16-byte vectors wide
+
+    gp_status st = ensure_pinned(plan);
+    if (st != GP_OK) return st;
+
+    // ---- HBM budget -> slab width (Eq. 12 with b fixed by the plan) ----------------
+    int64_t max_edges = 0, max_segs = 0;
+    for (int32_t p = 0; p < b; ++p) {
+        max_edges = std::max(max_edges, plan->block_off[p + 1] - plan->block_off[p]);
+        max_segs = std::max(max_segs, plan->seg_off[p + 1] - plan->seg_off[p]);
+    }
+    int64_t budget = options().hbm_budget_bytes;
+    if (budget <= 0) {
+        size_t free_b = 0, total_b = 0;
+        GP_HIP(hipMemGetInfo(&free_b, &total_b));
+        budget = (int64_t)(free_b / 10 * 8);
+    }
+    const int64_t fixed = 2 * (max_edges * 4 + max_segs * (int64_t)sizeof(Segment)) + 2 * n * 4 +
+                          (int64_t)plan->split.size() * (int64_t)sizeof(SplitRow) + 4096;
+    const int64_t per_col = 2 * n * es + plan->num_slots * 4;
+    int64_t w = (budget - fixed) / per_col;
+    if (w >= d)
+        w = d;
+    else
+        w = w / unit * unit;
+    if (w < std::min<int64_t>(unit, d))
+        return fail(GP_ERR_OOM_DEVICE,
+                    "HBM budget of %lld bytes cannot hold two edge blocks (%lld bytes) plus two column slabs of %lld columns; "
+                    "plan with a smaller block budget or raise the HBM budget",
+                    (long long)budget, (long long)fixed, (long long)unit);
+    const int64_t wpad = (w + 3) / 4 * 4;  // carry rows stay 16-byte aligned
+
+    Streams S;
+    if ((st = S.init()) != GP_OK) return st;
+    float *d_dinv_sqrt, *d_dinv, *d_carry;
+    SplitRow* d_split;
+    char* d_slab[2];
+    int32_t* d_col[2];
+    Segment* d_segs[2];
+    if ((st = S.alloc(d_dinv_sqrt, (size_t)n * 4)) != GP_OK || (st = S.alloc(d_dinv, (size_t)n * 4)) != GP_OK ||
+        (st = S.alloc(d_split, plan->split.size() * sizeof(SplitRow))) != GP_OK ||
+        (st = S.alloc(d_carry, (size_t)plan->num_slots * wpad * 4)) != GP_OK ||
+        (st = S.alloc(d_slab[0], (size_t)n * w * es)) != GP_OK || (st = S.alloc(d_slab[1], (size_t)n * w * es)) != GP_OK ||
+        (st = S.alloc(d_col[0], (size_t)max_edges * 4)) != GP_OK || (st = S.alloc(d_col[1], (size_t)max_edges * 4)) != GP_OK ||
+        (st = S.alloc(d_segs[0], (size_t)max_segs * sizeof(Segment))) != GP_OK ||
+        (st = S.alloc(d_segs[1], (size_t)max_segs * sizeof(Segment))) != GP_OK)
+        return st;
+    // small vectors: pageable sources, so these two copies are synchronous in effect
+    GP_HIP(hipMemcpyAsync(d_dinv_sqrt, plan->dinv_sqrt.data(), (size_t)n * 4, hipMemcpyHostToDevice, S.cmp));
+    GP_HIP(hipMemcpyAsync(d_dinv, plan->dinv.data(), (size_t)n * 4, hipMemcpyHostToDevice, S.cmp));
+    if (!plan->split.empty())
+        GP_HIP(hipMemcpyAsync(d_split, plan->split.data(), plan->split.size() * sizeof(SplitRow), hipMemcpyHostToDevice, S.cmp));
+    GP_HIP(hipStreamSynchronize(S.cmp));
+
+    const float* edge_w = agg == GP_AGG_SYM ? d_dinv_sqrt : nullptr;
+    const float* row_scale = agg == GP_AGG_SYM ? d_dinv_sqrt : agg == GP_AGG_MEAN ? d_dinv : nullptr;
+    const int64_t out_slab = n * ldo * es;  // bytes between two hop slabs in the host stack
+    bool blk_used[2] = {false, false}, out_used[2] = {false, false};
+    int64_t blk_seq = 0;  // running count of block uploads: buffer = blk_seq & 1
+
+    for (int64_t c0 = 0; c0 < d; c0 += w) {
+        const int32_t wc = (int32_t)std::min<int64_t>(w, d - c0);
+        // X[:, c0 : c0+wc] -> slab 0 (its previous content must have left first)
+        if (out_used[0]) GP_HIP(hipStreamWaitEvent(S.cmp, S.out_done[0], 0));
+        GP_HIP(hipMemcpy2DAsync(d_slab[0], (size_t)w * es, (const char*)X + c0 * es, (size_t)ldx * es, (size_t)wc * es,
+                                (size_t)n, hipMemcpyHostToDevice, S.cmp));
+        GP_HIP(hipEventRecord(S.hop_done, S.cmp));
+        if ((const void*)X != (const void*)out) {  // slot 0 = X, sent back from the slab
+            GP_HIP(hipStreamWaitEvent(S.out, S.hop_done, 0));
+            GP_HIP(hipMemcpy2DAsync((char*)out + c0 * es, (size_t)ldo * es, d_slab[0], (size_t)w * es, (size_t)wc * es,
+                                    (size_t)n, hipMemcpyDeviceToHost, S.out));
+        }
+        GP_HIP(hipEventRecord(S.out_done[0], S.out));
+        out_used[0] = true;
+
+        for (int32_t k = 1; k <= K; ++k) {
+            const int src = (k - 1) & 1, dst = k & 1;
+            // the slab about to be overwritten may still be on its way to the host
+            if (out_used[dst]) GP_HIP(hipStreamWaitEvent(S.cmp, S.out_done[dst], 0));
+            for (int32_t p = 0; p < b; ++p, ++blk_seq) {
+                const int buf = (int)(blk_seq & 1);
+                const int64_t e_lo = plan->block_off[p], e_cnt = plan->block_off[p + 1] - e_lo;
+                const int64_t s_lo = plan->seg_off[p], s_cnt = plan->seg_off[p + 1] - s_lo;
+                if (blk_used[buf]) GP_HIP(hipStreamWaitEvent(S.in, S.blk_free[buf], 0));
+                if (e_cnt)
+                    GP_HIP(hipMemcpyAsync(d_col[buf], plan->pinned_col + e_lo, (size_t)e_cnt * 4, hipMemcpyHostToDevice, S.in));
+                if (s_cnt)
+                    GP_HIP(hipMemcpyAsync(d_segs[buf], plan->pinned_segs + s_lo, (size_t)s_cnt * sizeof(Segment),
+                                          hipMemcpyHostToDevice, S.in));
+                GP_HIP(hipEventRecord(S.blk_ready[buf], S.in));
+                GP_HIP(hipStreamWaitEvent(S.cmp, S.blk_ready[buf], 0));
+                HopArgs a;
+                a.segs = d_segs[buf];
+                a.num_segs = s_cnt;
+                a.col = d_col[buf];
+                a.col_base = e_lo;
+                a.edge_w = edge_w;
+                a.row_scale = row_scale;
+                a.xin = d_slab[src];
+                a.ldin = w;
+                a.xout = d_slab[dst];
+                a.ldout = w;
+                a.carry = d_carry;
+                a.carry_ld = wpad;
+                a.d = wc;
+                a.dtype = dtype;
+                if ((st = hop_passes(a, S.cmp)) != GP_OK) return st;
+                GP_HIP(hipEventRecord(S.blk_free[buf], S.cmp));
+                blk_used[buf] = true;
+            }
+            if (!plan->split.empty()) {
+                FixupArgs f;
+                f.split = d_split;
+                f.num_split = (int64_t)plan->split.size();
+                f.carry = d_carry;
+                f.carry_ld = wpad;
+                f.row_scale = row_scale;
+                f.xout = d_slab[dst];
+                f.ldout = w;
+                f.d = wc;
+                f.dtype = dtype;
+                if ((st = fixup_passes(f, S.cmp)) != GP_OK) return st;
+            }
+            GP_HIP(hipEventRecord(S.hop_done, S.cmp));
+            GP_HIP(hipStreamWaitEvent(S.out, S.hop_done, 0));
+            GP_HIP(hipMemcpy2DAsync((char*)out + (int64_t)k * out_slab + c0 * es, (size_t)ldo * es, d_slab[dst], (size_t)w * es,
+                                    (size_t)wc * es, (size_t)n, hipMemcpyDeviceToHost, S.out));
+            GP_HIP(hipEventRecord(S.out_done[dst], S.out));
+            out_used[dst] = true;
+        }
+    }
+    GP_HIP(hipStreamSynchronize(S.in));
+    GP_HIP(hipStreamSynchronize(S.cmp));
+    GP_HIP(hipStreamSynchronize(S.out));
+    return GP_OK;
 }
 
 }  // namespace gp

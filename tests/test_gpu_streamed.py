@@ -1,0 +1,110 @@
+"""Streamed schedule (operands in pinned host memory, bounded HBM budget):
+same results as the oracle, and as the resident schedule, when the budget
+forces several column slabs and every edge block is re-sent per slab and hop."""
+import numpy as np
+import pytest
+
+import gp_synth
+import oracle
+import paper_2207_12000_amd as gp
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu(gpu_or_skip):
+    yield
+    gp.gp_set_hbm_budget_bytes(0)
+
+
+def pinned(X_np, dtype):
+    import torch
+    if dtype == gp.GP_F32:
+        t = torch.from_numpy(np.ascontiguousarray(X_np))
+    else:
+        t = torch.from_numpy(np.ascontiguousarray(X_np).view(np.int16)).view(torch.bfloat16)
+    return t.pin_memory()
+
+
+def run_streamed(plan, X_np, dtype, agg, K, budget, alias=False):
+    import torch
+    n, d = X_np.shape
+    tdt = torch.float32 if dtype == gp.GP_F32 else torch.bfloat16
+    out = torch.full((K + 1, n, d), float("nan"), dtype=tdt).pin_memory()
+    x = pinned(X_np, dtype)
+    if alias:
+        out[0] = x
+        x = out
+    gp.gp_set_hbm_budget_bytes(budget)
+    gp.gp_profile_enable(True)
+    try:
+        gp.gp_propagate(plan, x.data_ptr(), d, d, dtype, agg, K, out.data_ptr(), d, None)
+        launches, _ = gp.gp_profile_read("gp_hop_segments")
+    finally:
+        gp.gp_profile_enable(False)
+        gp.gp_set_hbm_budget_bytes(0)
+    return out.float().numpy().astype(np.float64), launches
+
+
+def oracle_stacks(w, op, X, dtype, agg, K):
+    Xw = (X if dtype == gp.GP_F32 else gp_synth.bf16_bits_to_f32(X)).astype(np.float64)
+    return Xw, oracle.propagate(op, Xw, agg, K, 4), oracle.bound_stack(op, Xw, agg, K, 4)
+
+
+@pytest.mark.parametrize("config,scale,dtype,budget,min_tiles", [
+    (1, 0.2, gp.GP_F32, 800_000, 3),        # 4 blocks, d = 128 in slabs of a few dozen columns
+    (5, 0.0002, gp.GP_BF16, 6_000_000, 2),  # the out-of-core workload's shape, bf16 storage
+    (3, 0.004, gp.GP_F32, 10**9, 1),        # budget large enough: one slab, blocks still streamed
+])
+def test_streamed_matches_oracle(config, scale, dtype, budget, min_tiles):
+    w = gp_synth.make_workload(config, scale=scale)
+    X = w.X
+    if dtype == gp.GP_BF16 and X.dtype != np.uint16:
+        X = gp_synth.f32_to_bf16_bits(X)
+    blocks = 4
+    nnz_ub = gp_synth.stored_nonzeros_upper_bound(w.n, w.m, w.flags)
+    plan_budget = -(-nnz_ub // blocks)
+    op = oracle.plan_blocks(w.src, w.dst, w.n, plan_budget, w.flags)
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, plan_budget, w.flags) as lp:
+        got, launches = run_streamed(lp, X, dtype, w.agg, w.K, budget)
+        assert launches >= min_tiles * w.K * lp.num_blocks, f"only {launches} hop launches: budget did not tile"
+    Xw, want, bound = oracle_stacks(w, op, X, dtype, w.agg, w.K)
+    tol = 1e-5 if dtype == gp.GP_F32 else 1e-2
+    assert np.array_equal(got[0], Xw)
+    for k in range(1, w.K + 1):
+        assert np.all(np.abs(got[k] - want[k]) <= tol * bound[k] + 1e-30), f"hop {k}"
+
+
+def test_streamed_equals_resident_bit_for_bit_and_alias():
+    """Slab width is a multiple of 16 bytes, so the per-row summation order is
+    the one of the resident schedule: identical bits."""
+    import torch
+    w = gp_synth.make_workload(2, scale=0.02, d=96)
+    budget_edges = 3000
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, budget_edges, w.flags) as lp:
+        a, launches = run_streamed(lp, w.X, gp.GP_F32, w.agg, 2, 700_000)
+        assert launches > 2 * lp.num_blocks
+        b, _ = run_streamed(lp, w.X, gp.GP_F32, w.agg, 2, 700_000, alias=True)
+        res = gp.propagate_tensors(lp, torch.from_numpy(w.X).cuda(), w.agg, 2)
+        torch.cuda.synchronize()
+        c = res.cpu().numpy().astype(np.float64)
+    assert np.array_equal(a, b) and np.array_equal(a, c)
+
+
+def test_budget_too_small_is_an_error_not_a_crash():
+    w = gp_synth.make_workload(1, scale=0.2)
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, 10**9, w.flags) as lp:
+        with pytest.raises(gp.GpError) as e:
+            run_streamed(lp, w.X, gp.GP_F32, w.agg, 1, 10_000)
+        assert e.value.status == gp.GP_ERR_OOM_DEVICE
+
+
+def test_mixed_memory_kinds_rejected():
+    import torch
+    w = gp_synth.make_workload(1, scale=0.05)
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, 10**9, w.flags) as lp:
+        xh = torch.from_numpy(w.X).pin_memory()
+        od = torch.empty((2, w.n, w.d), device="cuda:0")
+        with pytest.raises(gp.GpError) as e:
+            gp.gp_propagate(lp, xh.data_ptr(), w.d, w.d, gp.GP_F32, w.agg, 1, od.data_ptr(), w.d, None)
+        assert e.value.status == gp.GP_ERR_INVALID_ARG
