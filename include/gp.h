@@ -106,6 +106,7 @@ int64_t gp_plan_num_segments(const gp_plan *plan);
 const void *gp_plan_segments(const gp_plan *plan);            /* num_segments records, grouped by block */
 const int64_t *gp_plan_segment_offsets(const gp_plan *plan);  /* b+1: block p owns [off[p], off[p+1]) */
 int64_t gp_plan_num_partial_rows(const gp_plan *plan);        /* number of slots */
+int64_t gp_plan_segment_edges(const gp_plan *plan);           /* the segment length limit this plan used */
 
 /* ---------------------------------------------------------------------------
  * gp_propagate -- the hop stack (Algorithm 1's SX_list plus slot 0 = X).
@@ -147,9 +148,11 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
 
 /* Named integer options; unknown names give INVALID_ARG.
  *   "segment_edges"   longest run of non-zeros one lane group walks before the row
- *                     is split into partial rows (8 .. 32768; default 64).  Read
+ *                     is split into partial rows (8 .. 32768), or 0 (default):
+ *                     chosen per plan as about nnz / 65536 within 64 .. 1024.  Read
  *                     by gp_plan_blocks.
  *   "column_tile"     feature columns per pass of the kernel, 0 = automatic.
+ *   "persistent_blocks"  workgroups of the hop kernel (0 = as many as stay resident).
  *   "column_slices"   column slices one pass is divided into, one slice per XCD
  *                     (1, 2, 4, 8; 0 = automatic).
  */

@@ -43,6 +43,7 @@ _SIGNATURES = {
     "gp_plan_segments": (_c.c_void_p, [_c.c_void_p]),
     "gp_plan_segment_offsets": (_c.c_void_p, [_c.c_void_p]),
     "gp_plan_num_partial_rows": (_c.c_int64, [_c.c_void_p]),
+    "gp_plan_segment_edges": (_c.c_int64, [_c.c_void_p]),
     "gp_propagate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                 _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_set_hbm_budget_bytes": (_c.c_int, [_c.c_int64]),
@@ -184,6 +185,10 @@ class Plan:
     @property
     def num_partial_rows(self) -> int:
         return lib().gp_plan_num_partial_rows(self.handle)
+
+    @property
+    def segment_edges(self) -> int:
+        return lib().gp_plan_segment_edges(self.handle)
 
 
 def gp_plan_blocks(src, dst, n: int, block_budget_edges: int, flags: int) -> Plan:

@@ -110,7 +110,8 @@ gp_status gp_set_option(const char* name, int64_t value)
 {
     if (!name) return fail(GP_ERR_INVALID_ARG, "option name is NULL");
     if (!strcmp(name, "segment_edges")) {
-        if (value < 8 || value > 32768) return fail(GP_ERR_INVALID_ARG, "segment_edges must be 8 .. 32768");
+        if (value != 0 && (value < 8 || value > 32768))
+            return fail(GP_ERR_INVALID_ARG, "segment_edges must be 0 (automatic) or 8 .. 32768");
         options().segment_edges = value;
         return GP_OK;
     }
@@ -125,6 +126,11 @@ gp_status gp_set_option(const char* name, int64_t value)
         options().column_slices = value;
         return GP_OK;
     }
+    if (!strcmp(name, "persistent_blocks")) {
+        if (value < 0 || value > (1 << 20)) return fail(GP_ERR_INVALID_ARG, "persistent_blocks must be 0 .. 2^20");
+        options().persistent_blocks = value;
+        return GP_OK;
+    }
     return fail(GP_ERR_INVALID_ARG, "unknown option '%s'", name);
 }
 
@@ -134,6 +140,7 @@ int64_t gp_get_option(const char* name)
     if (!strcmp(name, "segment_edges")) return options().segment_edges;
     if (!strcmp(name, "column_tile")) return options().column_tile;
     if (!strcmp(name, "column_slices")) return options().column_slices;
+    if (!strcmp(name, "persistent_blocks")) return options().persistent_blocks;
     if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
     return -1;
 }
@@ -181,5 +188,6 @@ int64_t gp_plan_num_segments(const gp_plan* p) { return p ? (int64_t)p->segs.siz
 const void* gp_plan_segments(const gp_plan* p) { return p ? p->segs.data() : nullptr; }
 const int64_t* gp_plan_segment_offsets(const gp_plan* p) { return p ? p->seg_off.data() : nullptr; }
 int64_t gp_plan_num_partial_rows(const gp_plan* p) { return p ? p->num_slots : 0; }
+int64_t gp_plan_segment_edges(const gp_plan* p) { return p ? p->segment_edges : 0; }
 
 }  // extern "C"

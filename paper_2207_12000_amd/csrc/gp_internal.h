@@ -26,9 +26,10 @@ gp_status fail(gp_status s, const char* fmt, ...) __attribute__((format(printf, 
 
 // ---- options ------------------------------------------------------------
 struct Options {
-    int64_t segment_edges = 64;
+    int64_t segment_edges = 0;  // 0 = chosen per plan from the non-zero count
     int64_t column_tile = 0;
     int64_t column_slices = 0;
+    int64_t persistent_blocks = 0;
     int64_t hbm_budget_bytes = 0;
 };
 Options& options();

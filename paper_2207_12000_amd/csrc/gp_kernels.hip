@@ -119,6 +119,28 @@ struct Row<uint16_t, VEC> {
 // ---------------------------------------------------------------------------
 // one hop over a list of segments
 // ---------------------------------------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+struct SegRegs {
+    int64_t e0;  // first non-zero, relative to the column buffer
+    int len, row, slot;
+};
+
+__device__ __forceinline__ SegRegs unpack_segment(const v4i raw, int64_t col_base)
+{
+    SegRegs s;
+    s.e0 = (((int64_t)((uint32_t)raw[1] & 0xFFFFu) << 32) | (int64_t)(uint32_t)raw[0]) - col_base;
+    s.len = (int)((uint32_t)raw[1] >> 16);
+    s.row = raw[2];
+    s.slot = raw[3];
+    return s;
+}
+
+// Lane groups are persistent: group q of a slice walks segments q, q + stride,
+// q + 2*stride, ... of the (longest-first) list.  The index stream is software
+// pipelined in registers so that the only memory round trip a segment waits for
+// is its row gathers: the record of segment i+2 and the first WIN column ids of
+// segment i+1 are requested while segment i is gathered.
 template <typename T, int VEC, int G, int VPL, bool EDGE_W>
 __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __restrict__ segs, int64_t num_segs,
                                                             const int32_t* __restrict__ col, int64_t col_base,
@@ -130,6 +152,9 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
                                                             int num_slices, int slice_elems)
 {
     constexpr int GPB = kThreads / G;
+    constexpr int PF = G >= 32 ? 1 : 32 / G;  // column ids each lane prefetches per segment
+    constexpr int WIN = PF * G;               // edges of a segment covered by the prefetch
+    constexpr int U = VPL * VEC <= 4 ? 8 : 4; // row gathers in flight per group
     const int lane = threadIdx.x % G;
     // Workgroups are handed to the 8 XCDs round-robin by id.  Each XCD works on one
     // column slice of X only (slice = xcd mod num_slices), so its private L2 caches
@@ -137,27 +162,14 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     // segment list between them.  num_slices is 1, 2, 4 or 8.
     const int xcd = blockIdx.x & 7;
     const int slice = xcd & (num_slices - 1);
-    const int64_t chunk = (int64_t)(blockIdx.x >> 3) * (8 / num_slices) + xcd / num_slices;
-    const int64_t sid = chunk * GPB + threadIdx.x / G;
-    if (sid >= num_segs) return;
+    const int reps = 8 / num_slices;
+    const int64_t q = ((int64_t)(blockIdx.x >> 3) * reps + xcd / num_slices) * GPB + threadIdx.x / G;
+    const int64_t stride = (int64_t)(gridDim.x >> 3) * reps * GPB;
+    if (q >= num_segs) return;
     const int cbase = slice * slice_elems;
     const int cend = min(d, cbase + slice_elems);
 
-    Segment sg;
-    {
-        typedef int v4i __attribute__((ext_vector_type(4)));
-        const v4i* sp = reinterpret_cast<const v4i*>(segs + sid);
-        const v4i raw = *sp;
-        sg.start_lo = (uint32_t)raw[0];
-        sg.start_hi = (uint16_t)((uint32_t)raw[1] & 0xFFFFu);
-        sg.len = (uint16_t)((uint32_t)raw[1] >> 16);
-        sg.row = raw[2];
-        sg.slot = raw[3];
-    }
-    const int64_t e0 = (((int64_t)sg.start_hi << 32) | (int64_t)sg.start_lo) - col_base;
-    const int len = sg.len;
-
-    // column offsets of this lane's vectors; a vector is live if it starts inside d
+    // column offsets of this lane's vectors; a vector is live if it starts inside the slice
     bool live[VPL];
     int coff[VPL];
 #pragma unroll
@@ -166,64 +178,103 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         live[v] = coff[v] < cend;
     }
 
-    float acc[kUnroll][VPL][VEC];
+    const v4i* sp = reinterpret_cast<const v4i*>(segs);
+    const v4i none = {0, 0, 0, -1};  // length 0: nothing to fetch
+    SegRegs s0 = unpack_segment(sp[q], col_base);
+    v4i raw1 = q + stride < num_segs ? sp[q + stride] : none;
+    int c0[PF];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-        for (int v = 0; v < VPL; ++v)
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) acc[u][v][i] = 0.0f;
+    for (int j = 0; j < PF; ++j) c0[j] = j * G + lane < s0.len ? col[s0.e0 + j * G + lane] : 0;
 
-    for (int base = 0; base < len; base += G) {
-        const int cnt = min(G, len - base);
-        int my_col = 0;
-        float my_w = 0.0f;
-        if (lane < cnt) {
-            my_col = col[e0 + base + lane];
-            if (EDGE_W) my_w = edge_w[my_col];
-        }
-        for (int t = 0; t < cnt; t += kUnroll) {
-            float x[kUnroll][VPL][VEC];
-            float w[kUnroll];
+    for (int64_t s = q; s < num_segs; s += stride) {
+        // ---- requests for the segments to come -----------------------------------
+        const SegRegs s1 = unpack_segment(raw1, col_base);
+        const v4i raw2 = s + 2 * stride < num_segs ? sp[s + 2 * stride] : none;
+        int c1[PF];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                // lanes past cnt hold column 0 / weight 0; their rows are not read
-                const int c = __shfl(my_col, t + u, G);
-                w[u] = EDGE_W ? __shfl(my_w, t + u, G) : 1.0f;
-                const bool on = t + u < cnt;
-                const T* src = xin + (int64_t)c * ldin;
+        for (int j = 0; j < PF; ++j) c1[j] = j * G + lane < s1.len ? col[s1.e0 + j * G + lane] : 0;
+
+        // ---- this segment ----------------------------------------------------------
+        float acc[4][VPL][VEC];
 #pragma unroll
-                for (int v = 0; v < VPL; ++v) {
-                    if (on && live[v]) {
-                        Row<T, VEC>::load(src + coff[v], x[u][v]);
-                    } else {
+        for (int u = 0; u < 4; ++u)
 #pragma unroll
-                        for (int i = 0; i < VEC; ++i) x[u][v][i] = 0.0f;
+            for (int v = 0; v < VPL; ++v)
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc[u][v][i] = 0.0f;
+
+        // gathers rows for the `cnt` (<= G) edges whose ids sit one per lane in (ids, wts)
+        auto gather_batch = [&](int ids, float wts, int cnt) {
+            for (int t = 0; t < cnt; t += U) {
+                float x[U][VPL][VEC];
+                float w[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    // lanes past cnt hold id 0 / weight 0; their rows are not read
+                    const int c = __shfl(ids, t + u, G);
+                    w[u] = EDGE_W ? __shfl(wts, t + u, G) : 1.0f;
+                    const bool on = t + u < cnt;
+                    const T* src = xin + (int64_t)c * ldin;
+#pragma unroll
+                    for (int v = 0; v < VPL; ++v) {
+                        if (on && live[v]) {
+                            Row<T, VEC>::load(src + coff[v], x[u][v]);
+                        } else {
+#pragma unroll
+                            for (int i = 0; i < VEC; ++i) x[u][v][i] = 0.0f;
+                        }
                     }
                 }
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int v = 0; v < VPL; ++v)
+#pragma unroll
+                        for (int i = 0; i < VEC; ++i)
+                            acc[u & 3][v][i] =
+                                EDGE_W ? fmaf(w[u], x[u][v][i], acc[u & 3][v][i]) : acc[u & 3][v][i] + x[u][v][i];
             }
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-#pragma unroll
-                for (int v = 0; v < VPL; ++v)
-#pragma unroll
-                    for (int i = 0; i < VEC; ++i)
-                        acc[u][v][i] = EDGE_W ? fmaf(w[u], x[u][v][i], acc[u][v][i]) : acc[u][v][i] + x[u][v][i];
-        }
-    }
+        };
 
-    const bool partial = sg.slot >= 0;
-    const float rs = (!partial && row_scale) ? row_scale[sg.row] : 1.0f;
+        const int len = s0.len;
 #pragma unroll
-    for (int v = 0; v < VPL; ++v) {
-        if (!live[v]) continue;
-        float r[VEC];
+        for (int j = 0; j < PF; ++j) {
+            const int cnt = min(G, len - j * G);
+            if (cnt > 0) {
+                float wj = 0.0f;
+                if (EDGE_W && lane < cnt) wj = edge_w[c0[j]];
+                gather_batch(c0[j], wj, cnt);
+            }
+        }
+        for (int base = WIN; base < len; base += G) {  // the part of a long segment past the prefetch
+            const int cnt = min(G, len - base);
+            int id = 0;
+            float wj = 0.0f;
+            if (lane < cnt) {
+                id = col[s0.e0 + base + lane];
+                if (EDGE_W) wj = edge_w[id];
+            }
+            gather_batch(id, wj, cnt);
+        }
+
+        const bool partial = s0.slot >= 0;
+        const float rs = (!partial && row_scale) ? row_scale[s0.row] : 1.0f;
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) r[i] = ((acc[0][v][i] + acc[1][v][i]) + (acc[2][v][i] + acc[3][v][i])) * rs;
-        if (partial)
-            Row<float, VEC>::store(carry + (int64_t)sg.slot * carry_ld + coff[v], r);
-        else
-            Row<T, VEC>::store(xout + (int64_t)sg.row * ldout + coff[v], r);
+        for (int v = 0; v < VPL; ++v) {
+            if (!live[v]) continue;
+            float r[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) r[i] = ((acc[0][v][i] + acc[1][v][i]) + (acc[2][v][i] + acc[3][v][i])) * rs;
+            if (partial)
+                Row<float, VEC>::store(carry + (int64_t)s0.slot * carry_ld + coff[v], r);
+            else
+                Row<T, VEC>::store(xout + (int64_t)s0.row * ldout + coff[v], r);
+        }
+
+        s0 = s1;
+        raw1 = raw2;
+#pragma unroll
+        for (int j = 0; j < PF; ++j) c0[j] = c1[j];
     }
 }
 
@@ -311,8 +362,19 @@ gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
     const int64_t chunks = (a.num_segs + GPB - 1) / GPB;
     if (chunks == 0) return GP_OK;
     const int reps = 8 / a.num_slices;  // XCDs that share one slice
-    const int64_t blocks = 8 * ((chunks + reps - 1) / reps);
-    if (blocks > INT32_MAX) return fail(GP_ERR_UNSUPPORTED, "%lld workgroups exceed the grid limit", (long long)blocks);
+    // persistent lane groups: as many workgroups as stay resident, fewer if the list is short
+    static const int resident = [] {
+        int per_cu = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gp_hop_segments<T, VEC, G, VPL, true>, kThreads, 0) !=
+                hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess || per_cu <= 0)
+            return 2048;
+        return per_cu * prop.multiProcessorCount;
+    }();
+    int64_t persist = options().persistent_blocks > 0 ? options().persistent_blocks : resident;
+    persist = (persist + 7) / 8 * 8;
+    const int64_t blocks = std::min<int64_t>(persist, 8 * ((chunks + reps - 1) / reps));
     const dim3 grid((unsigned)blocks), block(kThreads);
     if (a.edge_w)
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, true>), grid, block, 0, stream, a.segs, a.num_segs, a.col,

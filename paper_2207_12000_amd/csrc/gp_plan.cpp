@@ -205,7 +205,16 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
             plan->block_row_hi[p] = row_of(hi - 1);
         }
 
-        plan->segment_edges = options().segment_edges;
+        // Longest run one lane group walks alone.  A run is a serial chain of gathers,
+        // so it must stay short against the whole hop: about nnz / 65536, kept within
+        // 64 .. 1024 (small graphs: split hubs finely; large graphs: split rarely, so
+        // few rows need partial sums).
+        int64_t L = options().segment_edges;
+        if (L <= 0) {
+            L = 64;
+            while (L < 1024 && L * 2 <= nnz / 65536) L *= 2;
+        }
+        plan->segment_edges = L;
         gp_status st = build_schedule(plan);
         if (st != GP_OK) {
             delete plan;

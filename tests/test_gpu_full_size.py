@@ -1,0 +1,87 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times (device-resident fp32 stack, default options).
+
+Config 2: the whole stack against the oracle, element by element.
+Configs 3 and 4: the plan bit for bit, then every hop on sampled destination
+rows the oracle computes one by one (plus the highest-degree rows and the rows cut
+by block boundaries) from the library's own stored X_{k-1}.  A hop that meets
+|gpu_k - A^ gpu_{k-1}| <= (1e-5 / K) * A^|gpu_{k-1}| on every row would meet the
+end-to-end bound 1e-5 * A^^k|X| (errors pass through the non-negative operator
+and add up over K hops), so the per-hop bar is the stricter one.
+"""
+import numpy as np
+import pytest
+
+import gp_synth
+import oracle
+import paper_2207_12000_amd as gp
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu(gpu_or_skip):
+    yield
+
+
+def same_plan(lp, op):
+    for name in ("block_off", "block_row_lo", "block_row_hi", "rowptr", "col", "deg"):
+        assert np.array_equal(getattr(lp, name), getattr(op, name)), name
+    assert np.array_equal(lp.dinv_sqrt.view(np.uint32), op.dinv_sqrt.view(np.uint32))
+    assert np.array_equal(lp.dinv.view(np.uint32), op.dinv.view(np.uint32))
+
+
+def test_config2_full_stack_elementwise():
+    import torch
+    w = gp_synth.make_workload(2)
+    op = oracle.plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags)
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) as lp:
+        same_plan(lp, op)
+        out = gp.propagate_tensors(lp, torch.from_numpy(w.X).cuda(), w.agg, w.K)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+    Xw = w.X.astype(np.float64)
+    want = oracle.propagate(op, Xw, w.agg, w.K, threads=8)
+    bound = oracle.bound_stack(op, Xw, w.agg, w.K, threads=8)
+    assert np.array_equal(got[0], Xw)
+    for k in range(1, w.K + 1):
+        err = np.abs(got[k] - want[k])
+        assert np.all(err <= 1e-5 * bound[k] + 1e-30), f"hop {k}: worst ratio {np.max(err / (bound[k] + 1e-300)):.3g}"
+
+
+def sampled_rows(op, count, seed):
+    rng = np.random.default_rng(seed)
+    rows = set(rng.integers(0, op.n, count).tolist())
+    rows.update(np.argsort(op.deg)[-8:].tolist())                    # hubs: split into many partial rows
+    rows.update(np.flatnonzero(op.deg == 0)[:8].tolist())            # empty rows owe zeros
+    rows.update(op.block_row_lo.tolist())                            # rows cut by block boundaries
+    rows.update(op.block_row_hi[op.block_row_hi >= 0].tolist())
+    return np.array(sorted(rows), dtype=np.int64)
+
+
+@pytest.mark.parametrize("config,samples", [(3, 1500), (4, 400)])
+def test_full_size_sampled_rows_every_hop(config, samples):
+    import torch
+    w = gp_synth.make_workload(config)
+    op = oracle.plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags)
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) as lp:
+        same_plan(lp, op)
+        out = gp.propagate_tensors(lp, torch.from_numpy(w.X).cuda(), w.agg, w.K)
+        torch.cuda.synchronize()
+        rows = sampled_rows(op, samples, 1000 + config)
+        prev = w.X
+        assert torch.equal(out[0].cpu(), torch.from_numpy(w.X))
+        tol = 1e-5 / w.K
+        for k in range(1, w.K + 1):
+            cur = out[k].cpu().numpy()
+            want, bound = oracle.hop_rows(op, prev, w.agg, rows)
+            err = np.abs(cur[rows].astype(np.float64) - want)
+            assert np.all(err <= tol * bound + 1e-30), \
+                f"config {config} hop {k}: worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {tol:.2g})"
+            assert np.all(cur[rows][bound == 0] == 0)
+            prev = cur
+        # sum aggregation of an all-ones matrix gives the degree exactly, at full size
+        if config == 4:
+            ones = torch.ones((w.n, 8), device="cuda:0")
+            deg = gp.propagate_tensors(lp, ones, gp.GP_AGG_SUM, 1)[1, :, 0].cpu().numpy()
+            assert np.array_equal(deg, op.deg.astype(np.float32))

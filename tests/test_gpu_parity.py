@@ -9,7 +9,7 @@ import gp_synth
 import oracle
 import paper_2207_12000_amd as gp
 
-DEFAULT_SEGMENT_EDGES = 64
+DEFAULT_SEGMENT_EDGES = 0   # automatic
 
 pytestmark = pytest.mark.gpu
 

@@ -12,7 +12,7 @@ import gp_synth
 import oracle
 import paper_2207_12000_amd as gp
 
-DEFAULT_SEGMENT_EDGES = 64
+DEFAULT_SEGMENT_EDGES = 0   # automatic
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -79,7 +79,7 @@ def test_tiny_cases_bit_exact(case, flags):
     op = oracle.plan_blocks(src, dst, n, budget, flags)
     with gp.gp_plan_blocks(src, dst, n, budget, flags) as lp:
         assert_same_plan(lp, op)
-        check_schedule(lp, gp.gp_get_option("segment_edges"))
+        check_schedule(lp, lp.segment_edges)
 
 
 @pytest.mark.parametrize("flags", [0, 1, 2, 3])
@@ -94,7 +94,7 @@ def test_random_graphs_bit_exact(seed, flags):
         op = oracle.plan_blocks(src, dst, n, budget, flags)
         with gp.gp_plan_blocks(src, dst, n, budget, flags) as lp:
             assert_same_plan(lp, op)
-            check_schedule(lp, gp.gp_get_option("segment_edges"))
+            check_schedule(lp, lp.segment_edges)
 
 
 @pytest.mark.parametrize("config,scale", [(1, 1.0), (2, 0.25), (3, 0.01), (4, 0.002), (5, 0.0002)])
@@ -106,7 +106,7 @@ def test_workloads_bit_exact_threaded(config, scale):
         budget = -(-op.nnz // w.n_blocks)
         op = oracle.plan_blocks(w.src, w.dst, w.n, budget, w.flags)
         assert op.num_blocks == w.n_blocks
-    for L in (DEFAULT_SEGMENT_EDGES, 256, 8):
+    for L in (64, 256, 8):
         gp.gp_set_option("segment_edges", L)
         try:
             with gp.gp_plan_blocks(w.src, w.dst, w.n, budget, w.flags) as lp:
@@ -126,7 +126,7 @@ def test_hub_row_split_across_many_blocks():
         op = oracle.plan_blocks(src, dst, n, 7, flags)
         with gp.gp_plan_blocks(src, dst, n, 7, flags) as lp:
             assert_same_plan(lp, op)
-            check_schedule(lp, DEFAULT_SEGMENT_EDGES)
+            check_schedule(lp, lp.segment_edges)
             assert lp.num_partial_rows >= 7
 
 
