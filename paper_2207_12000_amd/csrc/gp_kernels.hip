@@ -444,11 +444,14 @@ gp_status launch_hop(const HopArgs& a_in, hipStream_t stream)
     const int vec = vector_width(a.dtype, a.d, a.ldin, a.ldout, a.xin, a.xout);
     const int es = a.dtype == GP_F32 ? 4 : 2;
     const int nvec = (a.d + vec - 1) / vec;
-    // column slices: as many (1, 2, 4, 8) as keep a slice at least 256 bytes wide
+    // column slices: measured on MI355X, two slices pay for rows of 512 .. 1023 bytes
+    // (each XCD's L2 then keeps twice as many distinct rows and a slice is still
+    // >= 256 contiguous bytes); narrower slices lose more to the smaller requests
+    // than they gain in hits, and wider rows are best gathered whole.
     int S = (int)options().column_slices;
     if (S != 1 && S != 2 && S != 4 && S != 8) {
-        S = 1;
-        while (S < 8 && (int64_t)a.d * es / (2 * S) >= 256) S *= 2;
+        const int64_t row_bytes = (int64_t)a.d * es;
+        S = (row_bytes >= 512 && row_bytes < 1024) ? 2 : 1;
     }
     while (S > 1 && nvec < S) S /= 2;
     a.num_slices = S;
