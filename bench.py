@@ -54,6 +54,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="library option (gp_set_option), e.g. column_tile=32")
+    ap.add_argument("--contiguous-ids", action="store_true",
+                    help="workload 4 only: community-contiguous node ids (locality given) instead of permuted ids")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -74,7 +76,7 @@ def main() -> int:
         gp.gp_set_option(name, int(val))
 
     t0 = time.time()
-    w = gp_synth.make_workload(args.workload)
+    w = gp_synth.make_workload(args.workload, contiguous_ids=args.contiguous_ids)
     t_gen = time.time() - t0
     budget = w.block_budget_edges
     if budget is None:
@@ -136,7 +138,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32" if w.dtype == gp.GP_F32 else "bf16 storage, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": WORKLOAD_NAMES[args.workload], "n": n, "nnz": nnz, "d": d, "K": K,
+        "config": {"workload": WORKLOAD_NAMES[args.workload] + (" [community-contiguous ids]" if args.contiguous_ids else ""), "n": n, "nnz": nnz, "d": d, "K": K,
                    "edge_blocks": plan.num_blocks, "agg": ["sym", "mean", "sum"][w.agg],
                    "segments": int(plan.segments.size), "partial_rows": plan.num_partial_rows,
                    "options": {k: gp.gp_get_option(k) for k in ("segment_edges", "column_tile", "column_slices")}},

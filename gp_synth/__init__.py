@@ -203,9 +203,11 @@ def _scaled(x: int, scale: float, lo: int = 1) -> int:
 
 
 def make_workload(config: int, scale: float = 1.0, d: Optional[int] = None,
-                  with_features: bool = True) -> Workload:
+                  with_features: bool = True, contiguous_ids: bool = False) -> Workload:
     """Workload `config` (1..5).  scale < 1 shrinks node and pair counts
-    together (mean degree kept) for tests; scale = 1 is the full size."""
+    together (mean degree kept) for tests; scale = 1 is the full size.
+    contiguous_ids (config 4 only) keeps every community's nodes on consecutive
+    ids instead of permuting them: the same graph with its locality given."""
     seed = BASE_SEED + config
     g = rng_for(seed, 0)
     xr = rng_for(seed, 1)
@@ -233,7 +235,7 @@ def make_workload(config: int, scale: float = 1.0, d: Optional[int] = None,
         n = comm * n_comm
         M = min(_scaled(57_000_000, scale), n * (comm - 1) // 4)
         dd, K = d or 602, 2
-        src, dst = sbm_pairs(n_comm, comm, M, 0.9, g)
+        src, dst = sbm_pairs(n_comm, comm, M, 0.9, g, contiguous_ids=contiguous_ids)
         w = Workload("sbm_dense_sum", n, dd, K, AGG_SUM, F32, SYMMETRISE | ADD_SELF_LOOPS,
                      _scaled(8_000_000, scale, 16), None, src, dst, None)
         dist = "uniform"

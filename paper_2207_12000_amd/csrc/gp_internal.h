@@ -65,6 +65,7 @@ struct DevicePlan {
     float* dinv = nullptr;
     Segment* segs = nullptr;
     SplitRow* split = nullptr;
+    float* edge_ws = nullptr;   // nnz: dinv_sqrt[col[e]], built on first use of the sym operator
     float* carry = nullptr;     // num_slots x carry_ld fp32
     int64_t carry_ld = 0;
 };
@@ -113,7 +114,9 @@ struct HopArgs {
     int64_t num_segs;
     const int32_t* col;     // DEVICE; entry e of the sorted list is col[e - col_base]
     int64_t col_base;
-    const float* edge_w;    // DEVICE n-vector gathered by column id, or nullptr (weight 1)
+    const float* edge_w;    // DEVICE: nullptr (weight 1), or an n-vector gathered by column id,
+                            // or (edge_w_per_edge) one weight per non-zero, indexed like col
+    bool edge_w_per_edge = false;
     const float* row_scale; // DEVICE n-vector applied once per finished row, or nullptr
     const void* xin;        // DEVICE n x d, leading dimension ldin
     int64_t ldin;
@@ -141,6 +144,7 @@ struct FixupArgs {
 };
 gp_status launch_fixup(const FixupArgs& a, hipStream_t stream);
 
+gp_status launch_fill_edge_weights(const int32_t* col, const float* by_col, float* w, int64_t nnz, hipStream_t stream);
 gp_status launch_copy_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t n, int32_t d,
                            gp_dtype dtype, hipStream_t stream);
 

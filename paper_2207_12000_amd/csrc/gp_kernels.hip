@@ -61,6 +61,23 @@ struct Row;
 template <int VEC>
 struct Row<float, VEC> {
     using V = typename VecOf<float, VEC>::type;
+    __device__ static __forceinline__ V load_raw(const float* p) { return *reinterpret_cast<const V*>(p); }
+    __device__ static __forceinline__ V zero_raw()
+    {
+        V z;
+        if constexpr (VEC == 1) {
+            z = 0.0f;
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) z[i] = 0.0f;
+        }
+        return z;
+    }
+    __device__ static __forceinline__ void widen(const V& t, float (&x)[VEC])
+    {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) x[i] = elem<V, VEC>(t, i);
+    }
     template <bool NT = false>
     __device__ static __forceinline__ void load(const float* p, float (&x)[VEC])
     {
@@ -90,6 +107,23 @@ struct Row<float, VEC> {
 template <int VEC>
 struct Row<uint16_t, VEC> {
     using V = typename VecOf<uint16_t, VEC>::type;
+    __device__ static __forceinline__ V load_raw(const uint16_t* p) { return *reinterpret_cast<const V*>(p); }
+    __device__ static __forceinline__ V zero_raw()
+    {
+        V z;
+        if constexpr (VEC == 1) {
+            z = 0;
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) z[i] = 0;
+        }
+        return z;
+    }
+    __device__ static __forceinline__ void widen(const V& t, float (&x)[VEC])
+    {
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(elem<V, VEC>(t, i));
+    }
     template <bool NT = false>
     __device__ static __forceinline__ void load(const uint16_t* p, float (&x)[VEC])
     {
@@ -141,7 +175,9 @@ __device__ __forceinline__ SegRegs unpack_segment(const v4i raw, int64_t col_bas
 // pipelined in registers so that the only memory round trip a segment waits for
 // is its row gathers: the record of segment i+2 and the first WIN column ids of
 // segment i+1 are requested while segment i is gathered.
-template <typename T, int VEC, int G, int VPL, bool EDGE_W>
+// EDGE_W: 0 = every weight is 1; 1 = weight gathered from an n-vector by column id;
+// 2 = weight read from a per-edge array laid out like the column list.
+template <typename T, int VEC, int G, int VPL, int EDGE_W>
 __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __restrict__ segs, int64_t num_segs,
                                                             const int32_t* __restrict__ col, int64_t col_base,
                                                             const float* __restrict__ edge_w,
@@ -154,7 +190,10 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     constexpr int GPB = kThreads / G;
     constexpr int PF = G >= 32 ? 1 : 32 / G;  // column ids each lane prefetches per segment
     constexpr int WIN = PF * G;               // edges of a segment covered by the prefetch
-    constexpr int U = VPL * VEC <= 4 ? 8 : 4; // row gathers in flight per group
+        constexpr int U = VPL * VEC * (int)sizeof(T) <= 16 ? 8 : 4;  // row gathers in flight per group
+    // interleaved fp32 accumulators per column (short summation chains); bf16 storage
+    // tolerates longer chains and its 8-element vectors are register hungry
+    constexpr int NACC = sizeof(T) == 2 ? 2 : 4;
     const int lane = threadIdx.x % G;
     // Workgroups are handed to the 8 XCDs round-robin by id.  Each XCD works on one
     // column slice of X only (slice = xcd mod num_slices), so its private L2 caches
@@ -183,21 +222,31 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     SegRegs s0 = unpack_segment(sp[q], col_base);
     v4i raw1 = q + stride < num_segs ? sp[q + stride] : none;
     int c0[PF];
+    float w0[PF];
 #pragma unroll
-    for (int j = 0; j < PF; ++j) c0[j] = j * G + lane < s0.len ? col[s0.e0 + j * G + lane] : 0;
+    for (int j = 0; j < PF; ++j) {
+        const bool in = j * G + lane < s0.len;
+        c0[j] = in ? col[s0.e0 + j * G + lane] : 0;
+        w0[j] = (EDGE_W == 2 && in) ? edge_w[s0.e0 + j * G + lane] : 0.0f;
+    }
 
     for (int64_t s = q; s < num_segs; s += stride) {
         // ---- requests for the segments to come -----------------------------------
         const SegRegs s1 = unpack_segment(raw1, col_base);
         const v4i raw2 = s + 2 * stride < num_segs ? sp[s + 2 * stride] : none;
         int c1[PF];
+        float w1[PF];
 #pragma unroll
-        for (int j = 0; j < PF; ++j) c1[j] = j * G + lane < s1.len ? col[s1.e0 + j * G + lane] : 0;
+        for (int j = 0; j < PF; ++j) {
+            const bool in = j * G + lane < s1.len;
+            c1[j] = in ? col[s1.e0 + j * G + lane] : 0;
+            w1[j] = (EDGE_W == 2 && in) ? edge_w[s1.e0 + j * G + lane] : 0.0f;
+        }
 
         // ---- this segment ----------------------------------------------------------
-        float acc[4][VPL][VEC];
+        float acc[NACC][VPL][VEC];
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < NACC; ++u)
 #pragma unroll
             for (int v = 0; v < VPL; ++v)
 #pragma unroll
@@ -206,7 +255,7 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         // gathers rows for the `cnt` (<= G) edges whose ids sit one per lane in (ids, wts)
         auto gather_batch = [&](int ids, float wts, int cnt) {
             for (int t = 0; t < cnt; t += U) {
-                float x[U][VPL][VEC];
+                typename Row<T, VEC>::V x[U][VPL];  // rows stay in their stored form while in flight
                 float w[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
@@ -217,22 +266,20 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
                     const T* src = xin + (int64_t)c * ldin;
 #pragma unroll
                     for (int v = 0; v < VPL; ++v) {
-                        if (on && live[v]) {
-                            Row<T, VEC>::load(src + coff[v], x[u][v]);
-                        } else {
-#pragma unroll
-                            for (int i = 0; i < VEC; ++i) x[u][v][i] = 0.0f;
-                        }
+                        x[u][v] = (on && live[v]) ? Row<T, VEC>::load_raw(src + coff[v]) : Row<T, VEC>::zero_raw();
                     }
                 }
 #pragma unroll
                 for (int u = 0; u < U; ++u)
 #pragma unroll
-                    for (int v = 0; v < VPL; ++v)
+                    for (int v = 0; v < VPL; ++v) {
+                        float xf[VEC];
+                        Row<T, VEC>::widen(x[u][v], xf);
 #pragma unroll
                         for (int i = 0; i < VEC; ++i)
-                            acc[u & 3][v][i] =
-                                EDGE_W ? fmaf(w[u], x[u][v][i], acc[u & 3][v][i]) : acc[u & 3][v][i] + x[u][v][i];
+                            acc[u % NACC][v][i] =
+                                EDGE_W ? fmaf(w[u], xf[i], acc[u % NACC][v][i]) : acc[u % NACC][v][i] + xf[i];
+                    }
             }
         };
 
@@ -241,8 +288,8 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         for (int j = 0; j < PF; ++j) {
             const int cnt = min(G, len - j * G);
             if (cnt > 0) {
-                float wj = 0.0f;
-                if (EDGE_W && lane < cnt) wj = edge_w[c0[j]];
+                float wj = w0[j];
+                if (EDGE_W == 1 && lane < cnt) wj = edge_w[c0[j]];
                 gather_batch(c0[j], wj, cnt);
             }
         }
@@ -252,7 +299,8 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
             float wj = 0.0f;
             if (lane < cnt) {
                 id = col[s0.e0 + base + lane];
-                if (EDGE_W) wj = edge_w[id];
+                if (EDGE_W == 1) wj = edge_w[id];
+                if (EDGE_W == 2) wj = edge_w[s0.e0 + base + lane];
             }
             gather_batch(id, wj, cnt);
         }
@@ -264,7 +312,12 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
             if (!live[v]) continue;
             float r[VEC];
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) r[i] = ((acc[0][v][i] + acc[1][v][i]) + (acc[2][v][i] + acc[3][v][i])) * rs;
+            for (int i = 0; i < VEC; ++i) {
+                float t = acc[0][v][i];
+                if constexpr (NACC == 2) t += acc[1][v][i];
+                if constexpr (NACC == 4) t = (t + acc[1][v][i]) + (acc[2][v][i] + acc[3][v][i]);
+                r[i] = t * rs;
+            }
             if (partial)
                 Row<float, VEC>::store(carry + (int64_t)s0.slot * carry_ld + coff[v], r);
             else
@@ -274,8 +327,20 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         s0 = s1;
         raw1 = raw2;
 #pragma unroll
-        for (int j = 0; j < PF; ++j) c0[j] = c1[j];
+        for (int j = 0; j < PF; ++j) {
+            c0[j] = c1[j];
+            w0[j] = w1[j];
+        }
     }
+}
+
+// per-edge weights for the sym operator: w[e] = dinv_sqrt[col[e]] (built once per plan)
+__global__ __launch_bounds__(kThreads) void gp_fill_edge_weights(const int32_t* __restrict__ col,
+                                                                 const float* __restrict__ by_col, float* __restrict__ w,
+                                                                 int64_t nnz)
+{
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < nnz; e += (int64_t)gridDim.x * kThreads)
+        w[e] = by_col[col[e]];
 }
 
 // ---------------------------------------------------------------------------
@@ -366,7 +431,7 @@ gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
     static const int resident = [] {
         int per_cu = 0, dev = 0;
         hipDeviceProp_t prop;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gp_hop_segments<T, VEC, G, VPL, true>, kThreads, 0) !=
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gp_hop_segments<T, VEC, G, VPL, 2>, kThreads, 0) !=
                 hipSuccess ||
             hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess || per_cu <= 0)
             return 2048;
@@ -376,12 +441,16 @@ gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
     persist = (persist + 7) / 8 * 8;
     const int64_t blocks = std::min<int64_t>(persist, 8 * ((chunks + reps - 1) / reps));
     const dim3 grid((unsigned)blocks), block(kThreads);
-    if (a.edge_w)
-        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, true>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
+    if (a.edge_w && a.edge_w_per_edge)
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 2>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
+                           a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems);
+    else if (a.edge_w)
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 1>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
                            a.carry_ld, a.d, a.num_slices, a.slice_elems);
     else
-        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, false>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 0>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
                            a.carry_ld, a.d, a.num_slices, a.slice_elems);
     GP_HIP(hipGetLastError());
@@ -482,6 +551,15 @@ gp_status launch_fixup(const FixupArgs& a, hipStream_t stream)
         GP_VEC_CASES(launch_fixup_t, uint16_t, 4)
     }
     return fail(GP_ERR_UNSUPPORTED, "no fix-up kernel for d = %d, vec = %d", a.d, vec);
+}
+
+gp_status launch_fill_edge_weights(const int32_t* col, const float* by_col, float* w, int64_t nnz, hipStream_t stream)
+{
+    if (nnz == 0) return GP_OK;
+    const int64_t blocks = std::min<int64_t>((nnz + kThreads - 1) / kThreads, 256 * 32);
+    hipLaunchKernelGGL(gp_fill_edge_weights, dim3((unsigned)blocks), dim3(kThreads), 0, stream, col, by_col, w, nnz);
+    GP_HIP(hipGetLastError());
+    return GP_OK;
 }
 
 gp_status launch_copy_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t n, int32_t d, gp_dtype dtype,

@@ -27,12 +27,13 @@ void release(DevicePlan& D)
     (void)hipFree(D.segs);
     (void)hipFree(D.split);
     (void)hipFree(D.carry);
+    (void)hipFree(D.edge_ws);
     D = DevicePlan();
 }
 
 // Uploads the plan once per plan (to the device that is current at that time)
 // and (re)sizes the partial-row buffer for d columns.
-gp_status ensure_device(const gp_plan* plan, int32_t d, hipStream_t stream)
+gp_status ensure_device(const gp_plan* plan, int32_t d, bool want_edge_weights, hipStream_t stream)
 {
     std::lock_guard<std::mutex> lk(plan->mu);
     DevicePlan& D = plan->dev;
@@ -52,6 +53,13 @@ gp_status ensure_device(const gp_plan* plan, int32_t d, hipStream_t stream)
         // so the host vectors may be touched freely afterwards
         GP_HIP(hipStreamSynchronize(stream));
         D.device = cur;
+    }
+    if (want_edge_weights && !D.edge_ws && plan->nnz > 0) {
+        // one coalesced fp32 per non-zero instead of one random 4-byte gather per non-zero and hop
+        GP_HIP(hipMalloc((void**)&D.edge_ws, (size_t)plan->nnz * sizeof(float)));
+        gp_status st = launch_fill_edge_weights(D.col, D.dinv_sqrt, D.edge_ws, plan->nnz, stream);
+        if (st != GP_OK) return st;
+        GP_HIP(hipStreamSynchronize(stream));  // once per plan: later calls may come on other streams
     }
     const int64_t need_ld = ((int64_t)d + 3) / 4 * 4;
     if (plan->num_slots > 0 && need_ld > D.carry_ld) {
@@ -120,7 +128,7 @@ gp_status fixup_passes(const FixupArgs& f0, hipStream_t stream)
 gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg,
                              int32_t K, void* out, int64_t ldo, hipStream_t stream)
 {
-    gp_status st = ensure_device(plan, d, stream);
+    gp_status st = ensure_device(plan, d, agg == GP_AGG_SYM, stream);
     if (st != GP_OK) return st;
     const DevicePlan& D = plan->dev;
     const int64_t n = plan->n;
@@ -136,7 +144,7 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
         if (st != GP_OK) return st;
     }
 
-    const float* edge_w = agg == GP_AGG_SYM ? D.dinv_sqrt : nullptr;
+    const float* edge_w = agg == GP_AGG_SYM ? D.edge_ws : nullptr;
     const float* row_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : agg == GP_AGG_MEAN ? D.dinv : nullptr;
 
     for (int32_t k = 1; k <= K; ++k) {
@@ -146,6 +154,7 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
         a.col = D.col;
         a.col_base = 0;
         a.edge_w = edge_w;
+        a.edge_w_per_edge = true;
         a.row_scale = row_scale;
         a.xin = base + (int64_t)(k - 1) * slab;
         a.ldin = ldo;
