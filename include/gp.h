@@ -139,6 +139,28 @@ gp_status gp_propagate(const gp_plan *plan, const void *X, int64_t ldx, int32_t 
                        gp_agg agg, int32_t K, void *out_stack, int64_t ldo, void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * Optimal graph decomposition (Section 3.2, Eq. 11 and Eq. 12): block counts
+ * from byte volumes, the available GPU volume and the environment's coefficients
+ * (all in the same unit, e.g. bytes or GB; coefficients are measured by watching
+ * memory use on small graphs).  Host only.
+ *
+ * gp_solve_normalisation_blocks: the smallest natural a with
+ *     (alpha_A*B_A + alpha_S*B_S) / a + alpha_D*B_D <= B_GPU.
+ * gp_solve_aggregation_blocks: naturals (b, c), c <= max_c (a feature matrix has
+ * only so many columns), minimising b*c subject to
+ *     beta_S*B_S / b + beta_X*B_X / c <= B_GPU,
+ * by exhaustive search; among equal products the pair with the smaller c wins
+ * (the paper does not say; fewer column blocks means fewer re-sends of every
+ * edge block).  Errors: INVALID_ARG (non-positive volume, negative coefficient,
+ * NULL output), UNSUPPORTED when no block count can satisfy the constraint (the
+ * fixed term alone exceeds B_GPU, or max_c is too small).
+ */
+gp_status gp_solve_normalisation_blocks(double B_A, double B_S, double B_D, double B_GPU, double alpha_A,
+                                        double alpha_S, double alpha_D, int64_t *a);
+gp_status gp_solve_aggregation_blocks(double B_S, double B_X, double B_GPU, double beta_S, double beta_X,
+                                      int64_t max_c, int64_t *b, int64_t *c);
+
+/* ---------------------------------------------------------------------------
  * Library-wide knobs (process global; set them before planning / propagating).
  */
 

@@ -46,6 +46,9 @@ _SIGNATURES = {
     "gp_plan_segment_edges": (_c.c_int64, [_c.c_void_p]),
     "gp_propagate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                 _c.c_void_p, _c.c_int64, _c.c_void_p]),
+    "gp_solve_normalisation_blocks": (_c.c_int, [_c.c_double] * 7 + [_c.POINTER(_c.c_int64)]),
+    "gp_solve_aggregation_blocks": (_c.c_int, [_c.c_double] * 5 + [_c.c_int64, _c.POINTER(_c.c_int64),
+                                                                  _c.POINTER(_c.c_int64)]),
     "gp_set_hbm_budget_bytes": (_c.c_int, [_c.c_int64]),
     "gp_set_option": (_c.c_int, [_c.c_char_p, _c.c_int64]),
     "gp_get_option": (_c.c_int64, [_c.c_char_p]),
@@ -231,6 +234,20 @@ def propagate_tensors(plan: Plan, X, agg: int, K: int, out=None, stream=None):
         stream = torch.cuda.current_stream(X.device).cuda_stream
     gp_propagate(plan, X.data_ptr(), X.stride(0), d, dtype, agg, K, out.data_ptr(), d, stream)
     return out
+
+
+def gp_solve_normalisation_blocks(B_A, B_S, B_D, B_GPU, alpha_A=1.0, alpha_S=1.0, alpha_D=1.0) -> int:
+    a = ctypes.c_int64()
+    _check(lib().gp_solve_normalisation_blocks(B_A, B_S, B_D, B_GPU, alpha_A, alpha_S, alpha_D, ctypes.byref(a)),
+           "gp_solve_normalisation_blocks")
+    return a.value
+
+
+def gp_solve_aggregation_blocks(B_S, B_X, B_GPU, beta_S=1.0, beta_X=1.0, max_c=1 << 20):
+    b, c = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().gp_solve_aggregation_blocks(B_S, B_X, B_GPU, beta_S, beta_X, max_c, ctypes.byref(b), ctypes.byref(c)),
+           "gp_solve_aggregation_blocks")
+    return b.value, c.value
 
 
 def gp_set_hbm_budget_bytes(nbytes: int):
