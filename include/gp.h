@@ -139,6 +139,28 @@ gp_status gp_propagate(const gp_plan *plan, const void *X, int64_t ldx, int32_t 
                        gp_agg agg, int32_t K, void *out_stack, int64_t ldo, void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * gp_propagate_combine -- a constant polynomial graph filter without the stack:
+ *     out = sum_{k=0..K} coeff[k] * A^^k X.
+ * (Appendix A, Eq. 13: the generalized-PageRank propagation sum_k gamma_k S^k H
+ *  with constant gamma; with coeff[k] = alpha (1-alpha)^k for k < K and
+ *  (1-alpha)^K for k = K it is the K-step Personalized-PageRank diffusion that the
+ *  Limitation paragraph of Section 3.1 names as another precomputable filter.)
+ *
+ *  coeff  HOST, K+1 floats, read during the call.
+ *  out    DEVICE, n x d of `dtype`, leading dimension ldo; must not overlap X.
+ *  X      DEVICE (pinned-host operands: GP_ERR_UNSUPPORTED).
+ * Hops are chained as in gp_propagate (each hop consumes the previous hop as
+ * stored in `dtype`); every term is added in fp32 from the fp32 accumulator of
+ * its hop, and bf16 output is rounded once at the end.  Two n x d slabs (and,
+ * for bf16, an n x d fp32 accumulator) are allocated on first use and kept with
+ * the plan.  Enqueued on hip_stream; deterministic.  Other arguments and errors
+ * as gp_propagate.
+ */
+gp_status gp_propagate_combine(const gp_plan *plan, const void *X, int64_t ldx, int32_t d, gp_dtype dtype,
+                               gp_agg agg, int32_t K, const float *coeff, void *out, int64_t ldo,
+                               void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * Optimal graph decomposition (Section 3.2, Eq. 11 and Eq. 12): block counts
  * from byte volumes, the available GPU volume and the environment's coefficients
  * (all in the same unit, e.g. bytes or GB; coefficients are measured by watching

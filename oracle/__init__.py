@@ -127,3 +127,26 @@ def hop_rows(plan: OraclePlan, Xprev: np.ndarray, agg: int, rows) -> np.ndarray:
         Y[t] = (w[:, None] * xs).sum(axis=0)
         B[t] = (w[:, None] * np.abs(xs)).sum(axis=0)
     return Y, B
+
+
+def combine(plan: OraclePlan, X: np.ndarray, agg: int, coeff, threads: int = 1):
+    """sum_k coeff[k] * A^^k X in fp64, term by term from the hop stack (Appendix A,
+    Eq. 13 with constant coefficients).  Returns (value, bound) with
+    bound = sum_k |coeff[k]| * A^^k |X|."""
+    coeff = [float(c) for c in coeff]
+    K = len(coeff) - 1
+    Y = propagate(plan, X, agg, K, threads)
+    B = bound_stack(plan, X, agg, K, threads)
+    val = np.zeros_like(Y[0])
+    bnd = np.zeros_like(Y[0])
+    for k in range(K + 1):
+        val += coeff[k] * Y[k]
+        bnd += abs(coeff[k]) * B[k]
+    return val, bnd
+
+
+def ppr_coefficients(alpha: float, K: int):
+    """K-step Personalized-PageRank diffusion written as a polynomial in A^:
+    Z_0 = X, Z_{t+1} = (1 - alpha) A^ Z_t + alpha X  gives
+    Z_K = sum_{k<K} alpha (1-alpha)^k A^^k X + (1-alpha)^K A^^K X."""
+    return [alpha * (1 - alpha) ** k for k in range(K)] + [(1 - alpha) ** K]

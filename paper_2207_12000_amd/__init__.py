@@ -46,6 +46,8 @@ _SIGNATURES = {
     "gp_plan_segment_edges": (_c.c_int64, [_c.c_void_p]),
     "gp_propagate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                 _c.c_void_p, _c.c_int64, _c.c_void_p]),
+    "gp_propagate_combine": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
+                                        _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_solve_normalisation_blocks": (_c.c_int, [_c.c_double] * 7 + [_c.POINTER(_c.c_int64)]),
     "gp_solve_aggregation_blocks": (_c.c_int, [_c.c_double] * 5 + [_c.c_int64, _c.POINTER(_c.c_int64),
                                                                   _c.POINTER(_c.c_int64)]),
@@ -212,6 +214,16 @@ def gp_propagate(plan: Plan, X_ptr: int, ldx: int, d: int, dtype: int, agg: int,
     """Raw-pointer form: X_ptr / out_ptr are device (or pinned host) addresses."""
     st = lib().gp_propagate(plan.handle, X_ptr, ldx, d, dtype, agg, K, out_ptr, ldo, stream or None)
     _check(st, "gp_propagate")
+
+
+def gp_propagate_combine(plan: Plan, X_ptr: int, ldx: int, d: int, dtype: int, agg: int, K: int, coeff, out_ptr: int,
+                         ldo: int, stream: Optional[int] = None):
+    """coeff: K+1 host floats.  X_ptr / out_ptr: device addresses."""
+    c = np.ascontiguousarray(coeff, dtype=np.float32)
+    if c.shape != (K + 1,):
+        raise ValueError("coeff must hold K+1 values")
+    st = lib().gp_propagate_combine(plan.handle, X_ptr, ldx, d, dtype, agg, K, c.ctypes.data, out_ptr, ldo, stream or None)
+    _check(st, "gp_propagate_combine")
 
 
 def propagate_tensors(plan: Plan, X, agg: int, K: int, out=None, stream=None):

@@ -68,6 +68,10 @@ struct DevicePlan {
     float* edge_ws = nullptr;   // nnz: dinv_sqrt[col[e]], built on first use of the sym operator
     float* carry = nullptr;     // num_slots x carry_ld fp32
     int64_t carry_ld = 0;
+    // scratch of gp_propagate_combine: two hop slabs and (bf16 storage) an fp32 accumulator
+    void* ping[2] = {nullptr, nullptr};
+    float* comb = nullptr;
+    int64_t ping_bytes = 0, comb_elems = 0;
 };
 
 }  // namespace gp
@@ -128,6 +132,11 @@ struct HopArgs {
     gp_dtype dtype;
     int num_slices = 1;     // chosen by launch_hop
     int slice_elems = 0;
+    // optional running combination: comb[row] += gamma * result row (fp32, leading dimension ldc);
+    // xout may then be nullptr (result row not stored)
+    float* comb = nullptr;
+    int64_t ldc = 0;
+    float gamma = 0.0f;
 };
 gp_status launch_hop(const HopArgs& a, hipStream_t stream);
 
@@ -141,9 +150,14 @@ struct FixupArgs {
     int64_t ldout;
     int32_t d;
     gp_dtype dtype;
+    float* comb = nullptr;  // as in HopArgs
+    int64_t ldc = 0;
+    float gamma = 0.0f;
 };
 gp_status launch_fixup(const FixupArgs& a, hipStream_t stream);
 
+gp_status launch_scale_convert(const void* src, int64_t lds, gp_dtype src_type, void* dst, int64_t ldd, gp_dtype dst_type,
+                               int64_t n, int32_t d, float gamma, hipStream_t stream);
 gp_status launch_fill_edge_weights(const int32_t* col, const float* by_col, float* w, int64_t nnz, hipStream_t stream);
 gp_status launch_copy_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t n, int32_t d,
                            gp_dtype dtype, hipStream_t stream);

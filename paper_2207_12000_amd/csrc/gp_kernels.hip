@@ -185,7 +185,8 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
                                                             const T* __restrict__ xin, int64_t ldin,
                                                             T* __restrict__ xout, int64_t ldout,
                                                             float* __restrict__ carry, int64_t carry_ld, int d,
-                                                            int num_slices, int slice_elems)
+                                                            int num_slices, int slice_elems, float* __restrict__ comb,
+                                                            int64_t ldc, float gamma)
 {
     constexpr int GPB = kThreads / G;
     constexpr int PF = G >= 32 ? 1 : 32 / G;  // column ids each lane prefetches per segment
@@ -318,10 +319,19 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
                 if constexpr (NACC == 4) t = (t + acc[1][v][i]) + (acc[2][v][i] + acc[3][v][i]);
                 r[i] = t * rs;
             }
-            if (partial)
+            if (partial) {
                 Row<float, VEC>::store(carry + (int64_t)s0.slot * carry_ld + coff[v], r);
-            else
-                Row<T, VEC>::store(xout + (int64_t)s0.row * ldout + coff[v], r);
+            } else {
+                if (xout) Row<T, VEC>::store(xout + (int64_t)s0.row * ldout + coff[v], r);
+                if (comb) {  // running filter output: comb[row] += gamma * (A^^k X)[row]
+                    float* cp = comb + (int64_t)s0.row * ldc + coff[v];
+                    float c[VEC];
+                    Row<float, VEC>::load(cp, c);
+#pragma unroll
+                    for (int i = 0; i < VEC; ++i) c[i] = fmaf(gamma, r[i], c[i]);
+                    Row<float, VEC>::store(cp, c);
+                }
+            }
         }
 
         s0 = s1;
@@ -350,7 +360,8 @@ template <typename T, int VEC, int G, int VPL>
 __global__ __launch_bounds__(kThreads) void gp_fixup_rows(const SplitRow* __restrict__ split, int64_t num_split,
                                                           const float* __restrict__ carry, int64_t carry_ld,
                                                           const float* __restrict__ row_scale, T* __restrict__ xout,
-                                                          int64_t ldout, int d)
+                                                          int64_t ldout, int d, float* __restrict__ comb, int64_t ldc,
+                                                          float gamma)
 {
     constexpr int GPB = kThreads / G;
     const int lane = threadIdx.x % G;
@@ -382,7 +393,30 @@ __global__ __launch_bounds__(kThreads) void gp_fixup_rows(const SplitRow* __rest
         float r[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) r[i] = ((acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i])) * rs;
-        Row<T, VEC>::store(xout + (int64_t)sr.row * ldout + c0, r);
+        if (xout) Row<T, VEC>::store(xout + (int64_t)sr.row * ldout + c0, r);
+        if (comb) {
+            float* cp = comb + (int64_t)sr.row * ldc + c0;
+            float c[VEC];
+            Row<float, VEC>::load(cp, c);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) c[i] = fmaf(gamma, r[i], c[i]);
+            Row<float, VEC>::store(cp, c);
+        }
+    }
+}
+
+// comb = gamma * X (fp32 accumulator of the filter output), or out = bf16(comb)
+template <typename TI, typename TO>
+__global__ __launch_bounds__(kThreads) void gp_scale_convert(const TI* __restrict__ src, int64_t lds, TO* __restrict__ dst,
+                                                             int64_t ldd, int64_t n, int d, float gamma)
+{
+    const int64_t total = n * d;
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+        const int64_t r = i / d, c = i - r * d;
+        float x[1];
+        Row<TI, 1>::load(src + r * lds + c, x);
+        x[0] *= gamma;
+        Row<TO, 1>::store(dst + r * ldd + c, x);
     }
 }
 
@@ -444,15 +478,15 @@ gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
     if (a.edge_w && a.edge_w_per_edge)
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 2>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d, a.num_slices, a.slice_elems);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
     else if (a.edge_w)
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 1>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d, a.num_slices, a.slice_elems);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
     else
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 0>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d, a.num_slices, a.slice_elems);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
     GP_HIP(hipGetLastError());
     return GP_OK;
 }
@@ -465,7 +499,7 @@ gp_status launch_fixup_t(const FixupArgs& a, hipStream_t stream)
     if (blocks == 0) return GP_OK;
     if (blocks > INT32_MAX) return fail(GP_ERR_UNSUPPORTED, "%lld workgroups exceed the grid limit", (long long)blocks);
     hipLaunchKernelGGL((gp_fixup_rows<T, VEC, G, VPL>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, a.split,
-                       a.num_split, a.carry, a.carry_ld, a.row_scale, (T*)a.xout, a.ldout, a.d);
+                       a.num_split, a.carry, a.carry_ld, a.row_scale, (T*)a.xout, a.ldout, a.d, a.comb, a.ldc, a.gamma);
     GP_HIP(hipGetLastError());
     return GP_OK;
 }
@@ -510,7 +544,8 @@ gp_status launch_hop(const HopArgs& a_in, hipStream_t stream)
 {
     HopArgs a = a_in;
     // carry rows are fp32 and 16-byte aligned by construction (carry_ld % 4 == 0)
-    const int vec = vector_width(a.dtype, a.d, a.ldin, a.ldout, a.xin, a.xout);
+    int vec = vector_width(a.dtype, a.d, a.ldin, a.xout ? a.ldout : a.ldin, a.xin, a.xout ? a.xout : a.xin);
+    if (a.comb) vec = std::min(vec, vector_width(GP_F32, a.d, a.ldc, a.ldc, a.comb, a.comb));
     const int es = a.dtype == GP_F32 ? 4 : 2;
     const int nvec = (a.d + vec - 1) / vec;
     // column slices: measured on MI355X, two slices pay for rows of 512 .. 1023 bytes
@@ -539,7 +574,8 @@ gp_status launch_hop(const HopArgs& a_in, hipStream_t stream)
 gp_status launch_fixup(const FixupArgs& a, hipStream_t stream)
 {
     // the fix-up reads fp32 carry rows and writes T rows: use the vector width both allow
-    int vec = vector_width(a.dtype, a.d, a.ldout, a.ldout, a.xout, a.xout);
+    int vec = a.xout ? vector_width(a.dtype, a.d, a.ldout, a.ldout, a.xout, a.xout) : 4;
+    if (a.comb) vec = std::min(vec, vector_width(GP_F32, a.d, a.ldc, a.ldc, a.comb, a.comb));
     if (vec > 4) vec = 4;
     while (vec > 1 && (a.carry_ld % vec != 0)) vec /= 2;
     int G, vpl;
@@ -551,6 +587,24 @@ gp_status launch_fixup(const FixupArgs& a, hipStream_t stream)
         GP_VEC_CASES(launch_fixup_t, uint16_t, 4)
     }
     return fail(GP_ERR_UNSUPPORTED, "no fix-up kernel for d = %d, vec = %d", a.d, vec);
+}
+
+gp_status launch_scale_convert(const void* src, int64_t lds, gp_dtype src_type, void* dst, int64_t ldd, gp_dtype dst_type,
+                               int64_t n, int32_t d, float gamma, hipStream_t stream)
+{
+    if (n == 0) return GP_OK;
+    const int64_t blocks = std::min<int64_t>((n * d + kThreads - 1) / kThreads, 256 * 32);
+    const dim3 grid((unsigned)blocks), block(kThreads);
+    if (src_type == GP_F32 && dst_type == GP_F32)
+        hipLaunchKernelGGL((gp_scale_convert<float, float>), grid, block, 0, stream, (const float*)src, lds, (float*)dst, ldd, n, d, gamma);
+    else if (src_type == GP_BF16 && dst_type == GP_F32)
+        hipLaunchKernelGGL((gp_scale_convert<uint16_t, float>), grid, block, 0, stream, (const uint16_t*)src, lds, (float*)dst, ldd, n, d, gamma);
+    else if (src_type == GP_F32 && dst_type == GP_BF16)
+        hipLaunchKernelGGL((gp_scale_convert<float, uint16_t>), grid, block, 0, stream, (const float*)src, lds, (uint16_t*)dst, ldd, n, d, gamma);
+    else
+        return fail(GP_ERR_UNSUPPORTED, "scale/convert between these types is not needed");
+    GP_HIP(hipGetLastError());
+    return GP_OK;
 }
 
 gp_status launch_fill_edge_weights(const int32_t* col, const float* by_col, float* w, int64_t nnz, hipStream_t stream)

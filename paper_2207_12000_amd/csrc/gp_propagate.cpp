@@ -28,6 +28,9 @@ void release(DevicePlan& D)
     (void)hipFree(D.split);
     (void)hipFree(D.carry);
     (void)hipFree(D.edge_ws);
+    (void)hipFree(D.ping[0]);
+    (void)hipFree(D.ping[1]);
+    (void)hipFree(D.comb);
     D = DevicePlan();
 }
 
@@ -93,13 +96,15 @@ int64_t pass_width(gp_dtype dtype, int32_t d, int64_t lda, int64_t ldb, const vo
 gp_status hop_passes(const HopArgs& a0, hipStream_t stream)
 {
     const int es = a0.dtype == GP_F32 ? 4 : 2;
-    const int64_t tile = pass_width(a0.dtype, a0.d, a0.ldin, a0.ldout, a0.xin, a0.xout);
+    const int64_t tile = pass_width(a0.dtype, a0.d, a0.ldin, a0.xout ? a0.ldout : a0.ldin, a0.xin, a0.xout ? a0.xout : a0.xin);
     for (int64_t c0 = 0; c0 < a0.d; c0 += tile) {
         HopArgs a = a0;
         a.d = (int32_t)std::min<int64_t>(tile, a0.d - c0);
         a.xin = (const char*)a0.xin + c0 * es;
         a.xout = (char*)a0.xout + c0 * es;
         a.carry = a0.carry ? a0.carry + c0 : nullptr;
+        a.xout = a0.xout ? (char*)a0.xout + c0 * es : nullptr;
+        a.comb = a0.comb ? a0.comb + c0 : nullptr;
         profile_begin("gp_hop_segments", stream);
         gp_status st = launch_hop(a, stream);
         profile_end(stream);
@@ -111,12 +116,15 @@ gp_status hop_passes(const HopArgs& a0, hipStream_t stream)
 gp_status fixup_passes(const FixupArgs& f0, hipStream_t stream)
 {
     const int es = f0.dtype == GP_F32 ? 4 : 2;
-    const int64_t tile = pass_width(f0.dtype, f0.d, f0.ldout, f0.ldout, f0.xout, f0.xout);
+    const int64_t tile = f0.xout ? pass_width(f0.dtype, f0.d, f0.ldout, f0.ldout, f0.xout, f0.xout)
+                                 : pass_width(GP_F32, f0.d, f0.ldc, f0.ldc, f0.comb, f0.comb);
     for (int64_t c0 = 0; c0 < f0.d; c0 += tile) {
         FixupArgs f = f0;
         f.d = (int32_t)std::min<int64_t>(tile, f0.d - c0);
         f.xout = (char*)f0.xout + c0 * es;
         f.carry = f0.carry + c0;
+        f.xout = f0.xout ? (char*)f0.xout + c0 * es : nullptr;
+        f.comb = f0.comb ? f0.comb + c0 : nullptr;
         profile_begin("gp_fixup_rows", stream);
         gp_status st = launch_fixup(f, stream);
         profile_end(stream);
@@ -182,6 +190,99 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
     return GP_OK;
 }
 
+// out = sum_k coeff[k] * A^^k X without the stack: hop k reads slab (k-1)&1 (X for k = 1),
+// writes slab k&1 (nothing for k = K) and adds coeff[k] times its fp32 rows into the
+// accumulator, which is `out` itself for fp32 and an fp32 scratch for bf16 storage.
+gp_status propagate_combine(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg,
+                            int32_t K, const float* coeff, void* out, int64_t ldo, hipStream_t stream)
+{
+    gp_status st = ensure_device(plan, d, agg == GP_AGG_SYM, stream);
+    if (st != GP_OK) return st;
+    DevicePlan& D = plan->dev;
+    const int64_t n = plan->n;
+    const int es = dtype == GP_F32 ? 4 : 2;
+    const int64_t ldp = ((int64_t)d + 16 / es - 1) / (16 / es) * (16 / es);  // slab rows start on 16 bytes
+    const int64_t ldc_scratch = ((int64_t)d + 3) / 4 * 4;
+    {
+        std::lock_guard<std::mutex> lk(plan->mu);
+        const int64_t need = n * ldp * es;
+        if (K >= 2 && need > D.ping_bytes) {
+            GP_HIP(hipDeviceSynchronize());
+            (void)hipFree(D.ping[0]);
+            (void)hipFree(D.ping[1]);
+            D.ping[0] = D.ping[1] = nullptr;
+            D.ping_bytes = 0;
+            GP_HIP(hipMalloc(&D.ping[0], (size_t)need));
+            GP_HIP(hipMalloc(&D.ping[1], (size_t)need));
+            D.ping_bytes = need;
+        }
+        if (dtype == GP_BF16 && n * ldc_scratch > D.comb_elems) {
+            GP_HIP(hipDeviceSynchronize());
+            (void)hipFree(D.comb);
+            D.comb = nullptr;
+            D.comb_elems = 0;
+            GP_HIP(hipMalloc((void**)&D.comb, (size_t)(n * ldc_scratch) * sizeof(float)));
+            D.comb_elems = n * ldc_scratch;
+        }
+    }
+    float* comb = dtype == GP_F32 ? (float*)out : D.comb;
+    const int64_t ldc = dtype == GP_F32 ? ldo : ldc_scratch;
+
+    // k = 0 term
+    profile_begin("gp_scale_convert", stream);
+    st = launch_scale_convert(X, ldx, dtype, comb, ldc, GP_F32, n, d, coeff[0], stream);
+    profile_end(stream);
+    if (st != GP_OK) return st;
+
+    const float* edge_w = agg == GP_AGG_SYM ? D.edge_ws : nullptr;
+    const float* row_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : agg == GP_AGG_MEAN ? D.dinv : nullptr;
+    for (int32_t k = 1; k <= K; ++k) {
+        HopArgs a;
+        a.segs = D.segs;
+        a.num_segs = (int64_t)plan->segs.size();
+        a.col = D.col;
+        a.col_base = 0;
+        a.edge_w = edge_w;
+        a.edge_w_per_edge = true;
+        a.row_scale = row_scale;
+        a.xin = k == 1 ? X : D.ping[(k - 1) & 1];
+        a.ldin = k == 1 ? ldx : ldp;
+        a.xout = k == K ? nullptr : D.ping[k & 1];
+        a.ldout = ldp;
+        a.carry = D.carry;
+        a.carry_ld = D.carry_ld;
+        a.d = d;
+        a.dtype = dtype;
+        a.comb = comb;
+        a.ldc = ldc;
+        a.gamma = coeff[k];
+        if ((st = hop_passes(a, stream)) != GP_OK) return st;
+        if (!plan->split.empty()) {
+            FixupArgs f;
+            f.split = D.split;
+            f.num_split = (int64_t)plan->split.size();
+            f.carry = D.carry;
+            f.carry_ld = D.carry_ld;
+            f.row_scale = row_scale;
+            f.xout = a.xout;
+            f.ldout = ldp;
+            f.d = d;
+            f.dtype = dtype;
+            f.comb = comb;
+            f.ldc = ldc;
+            f.gamma = coeff[k];
+            if ((st = fixup_passes(f, stream)) != GP_OK) return st;
+        }
+    }
+    if (dtype == GP_BF16) {
+        profile_begin("gp_scale_convert", stream);
+        st = launch_scale_convert(comb, ldc, GP_F32, out, ldo, GP_BF16, n, d, 1.0f, stream);
+        profile_end(stream);
+        if (st != GP_OK) return st;
+    }
+    return GP_OK;
+}
+
 }  // namespace gp
 
 using namespace gp;
@@ -200,6 +301,31 @@ extern "C" void gp_plan_destroy(gp_plan* plan)
     }
     release_pinned(plan);
     delete plan;
+}
+
+extern "C" gp_status gp_propagate_combine(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,
+                                          gp_agg agg, int32_t K, const float* coeff, void* out, int64_t ldo,
+                                          void* hip_stream)
+{
+    if (!plan) return fail(GP_ERR_INVALID_ARG, "plan is NULL");
+    if (!X || !out || !coeff) return fail(GP_ERR_INVALID_ARG, "X, out or coeff is NULL");
+    if (d <= 0) return fail(GP_ERR_INVALID_ARG, "d = %d must be positive", d);
+    if (K < 0) return fail(GP_ERR_INVALID_ARG, "K = %d is negative", K);
+    if (ldx < d || ldo < d) return fail(GP_ERR_INVALID_ARG, "leading dimension smaller than d");
+    if (dtype != GP_F32 && dtype != GP_BF16) return fail(GP_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    if (agg != GP_AGG_SYM && agg != GP_AGG_MEAN && agg != GP_AGG_SUM)
+        return fail(GP_ERR_INVALID_ARG, "unknown aggregation %d", (int)agg);
+    if (X == out) return fail(GP_ERR_INVALID_ARG, "X and out must not overlap");
+    const int es = dtype == GP_F32 ? 4 : 2;
+    if (((uintptr_t)X % es) || ((uintptr_t)out % es)) return fail(GP_ERR_INVALID_ARG, "X / out not aligned to the element size");
+    hipPointerAttribute_t ax, ao;
+    if (hipPointerGetAttributes(&ax, X) != hipSuccess || hipPointerGetAttributes(&ao, out) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(GP_ERR_INVALID_ARG, "X / out is not device memory");
+    }
+    if (ax.type != hipMemoryTypeDevice || ao.type != hipMemoryTypeDevice)
+        return fail(GP_ERR_UNSUPPORTED, "gp_propagate_combine takes device-resident operands only");
+    return propagate_combine(plan, X, ldx, d, dtype, agg, K, coeff, out, ldo, (hipStream_t)hip_stream);
 }
 
 extern "C" gp_status gp_propagate(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,

@@ -93,6 +93,26 @@ void release_pinned(gp_plan* plan)
     plan->pinned_segs = nullptr;
 }
 
+namespace {
+
+// n rows of wc elements between a pinned host matrix and a device slab.  A run that
+// is contiguous on both sides is one DMA copy; a strided one (a column slab of a
+// wider matrix) is moved by the row-copy kernel reading / writing the pinned host
+// memory directly, which keeps the link busy with full-row bursts where a pitched
+// DMA copy crawls.
+gp_status move_rows(void* dst, int64_t ldd, const void* src, int64_t lds, int64_t n, int32_t wc, gp_dtype dtype,
+                    hipMemcpyKind kind, hipStream_t stream)
+{
+    const int es = dtype == GP_F32 ? 4 : 2;
+    if (ldd == wc && lds == wc) {
+        GP_HIP(hipMemcpyAsync(dst, src, (size_t)n * wc * es, kind, stream));
+        return GP_OK;
+    }
+    return launch_copy_rows(src, lds, dst, ldd, n, wc, dtype, stream);
+}
+
+}  // namespace
+
 gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg,
                              int32_t K, void* out, int64_t ldo)
 {
@@ -163,13 +183,13 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
         const int32_t wc = (int32_t)std::min<int64_t>(w, d - c0);
         // X[:, c0 : c0+wc] -> slab 0 (its previous content must have left first)
         if (out_used[0]) GP_HIP(hipStreamWaitEvent(S.cmp, S.out_done[0], 0));
-        GP_HIP(hipMemcpy2DAsync(d_slab[0], (size_t)w * es, (const char*)X + c0 * es, (size_t)ldx * es, (size_t)wc * es,
-                                (size_t)n, hipMemcpyHostToDevice, S.cmp));
+        if ((st = move_rows(d_slab[0], w, (const char*)X + c0 * es, ldx, n, wc, dtype, hipMemcpyHostToDevice, S.cmp)) != GP_OK)
+            return st;
         GP_HIP(hipEventRecord(S.hop_done, S.cmp));
         if ((const void*)X != (const void*)out) {  // slot 0 = X, sent back from the slab
             GP_HIP(hipStreamWaitEvent(S.out, S.hop_done, 0));
-            GP_HIP(hipMemcpy2DAsync((char*)out + c0 * es, (size_t)ldo * es, d_slab[0], (size_t)w * es, (size_t)wc * es,
-                                    (size_t)n, hipMemcpyDeviceToHost, S.out));
+            if ((st = move_rows((char*)out + c0 * es, ldo, d_slab[0], w, n, wc, dtype, hipMemcpyDeviceToHost, S.out)) != GP_OK)
+                return st;
         }
         GP_HIP(hipEventRecord(S.out_done[0], S.out));
         out_used[0] = true;
@@ -224,8 +244,9 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
             }
             GP_HIP(hipEventRecord(S.hop_done, S.cmp));
             GP_HIP(hipStreamWaitEvent(S.out, S.hop_done, 0));
-            GP_HIP(hipMemcpy2DAsync((char*)out + (int64_t)k * out_slab + c0 * es, (size_t)ldo * es, d_slab[dst], (size_t)w * es,
-                                    (size_t)wc * es, (size_t)n, hipMemcpyDeviceToHost, S.out));
+            if ((st = move_rows((char*)out + (int64_t)k * out_slab + c0 * es, ldo, d_slab[dst], w, n, wc, dtype,
+                                hipMemcpyDeviceToHost, S.out)) != GP_OK)
+                return st;
             GP_HIP(hipEventRecord(S.out_done[dst], S.out));
             out_used[dst] = true;
         }
