@@ -36,6 +36,7 @@ WORKLOAD_NAMES = {
     2: "config2: Chung-Lu 169,343 nodes / ~2.5M nnz, d=128 fp32, sym, K=3",
     3: "config3: Chung-Lu 2.45M nodes / ~123M nnz, d=100 fp32, mean, K=3, 8M-edge blocks",
     4: "config4: SBM 233k nodes / ~114M nnz, d=602 fp32, sum, K=2",
+    5: "config5: Chung-Lu 111M nodes / ~3.3B nnz, d=128 bf16 storage, sym, K=3, out-of-core",
 }
 
 
@@ -51,6 +52,12 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", type=int, default=2, choices=sorted(WORKLOAD_NAMES))
+    ap.add_argument("--scale", type=float, default=1.0,
+                    help="shrink node and pair counts together (workload 5 is only practical below 1)")
+    ap.add_argument("--memory", choices=["device", "pinned"], default=None,
+                    help="where X and the stack live: device (resident schedule) or pinned host memory "
+                         "(streamed schedule; the default for workload 5)")
+    ap.add_argument("--hbm-budget-gb", type=float, default=0.0, help="streamed schedule: HBM budget (0 = automatic)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="library option (gp_set_option), e.g. column_tile=32")
@@ -76,7 +83,10 @@ def main() -> int:
         gp.gp_set_option(name, int(val))
 
     t0 = time.time()
-    w = gp_synth.make_workload(args.workload, contiguous_ids=args.contiguous_ids)
+    w = gp_synth.make_workload(args.workload, scale=args.scale, contiguous_ids=args.contiguous_ids)
+    memory = args.memory or ("pinned" if w.streamed else "device")
+    if args.hbm_budget_gb > 0:
+        gp.gp_set_hbm_budget_bytes(int(args.hbm_budget_gb * 2**30))
     t_gen = time.time() - t0
     budget = w.block_budget_edges
     if budget is None:
@@ -88,10 +98,15 @@ def main() -> int:
     elem = 4 if w.dtype == gp.GP_F32 else 2
     tdt = torch.float32 if w.dtype == gp.GP_F32 else torch.bfloat16
 
-    X = torch.from_numpy(w.X).to(dev) if w.dtype == gp.GP_F32 else \
-        torch.from_numpy(w.X.view(np.int16)).view(torch.bfloat16).to(dev)
-    out = torch.empty((K + 1, n, d), dtype=tdt, device=dev)
-    stream = torch.cuda.current_stream().cuda_stream
+    X = torch.from_numpy(w.X) if w.dtype == gp.GP_F32 else torch.from_numpy(w.X.view(np.int16)).view(torch.bfloat16)
+    if memory == "device":
+        X = X.to(dev)
+        out = torch.empty((K + 1, n, d), dtype=tdt, device=dev)
+        stream = torch.cuda.current_stream().cuda_stream
+    else:                                    # streamed schedule: the call returns when the stack is on the host
+        X = X.pin_memory()
+        out = torch.empty((K + 1, n, d), dtype=tdt).pin_memory()
+        stream = None
 
     def step():
         gp.gp_propagate(plan, X.data_ptr(), d, d, w.dtype, w.agg, K, out.data_ptr(), d, stream)
@@ -107,7 +122,9 @@ def main() -> int:
     e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    ms_per_step = e0.elapsed_time(e1) / args.steps
+    # device operands: HIP events on the launch stream; pinned operands: the call is
+    # synchronous and works on its own streams, so the host clock is the measure
+    ms_per_step = e0.elapsed_time(e1) / args.steps if memory == "device" else wall * 1e3 / args.steps
     efu = nnz * d * K
     value = efu / (ms_per_step * 1e-3) / 1e9
 
@@ -121,9 +138,12 @@ def main() -> int:
     _, copy_ms = gp.gp_profile_read("gp_copy_rows")
     gp.gp_profile_enable(False)
     avg_launch_s = hop_ms * 1e-3 / max(launches, 1)
-    bytes_per_launch = algorithmic_bytes_per_hop(n, nnz, d, elem)
+    # one launch covers a whole hop on device operands; the streamed schedule launches
+    # once per edge block and column slab, each launch doing its share of the hop
+    launches_per_hop = max(1, round(launches / max(args.steps * K, 1)))
+    bytes_per_launch = algorithmic_bytes_per_hop(n, nnz, d, elem) // launches_per_hop
     achieved = bytes_per_launch / avg_launch_s / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload)
+    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if (args.scale == 1.0 and memory == "device") else None
 
     rec = {
         "metric": "edge-feature updates/s (GEFU/s) for K-hop A^k X precompute",
@@ -138,19 +158,27 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32" if w.dtype == gp.GP_F32 else "bf16 storage, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": WORKLOAD_NAMES[args.workload] + (" [community-contiguous ids]" if args.contiguous_ids else ""), "n": n, "nnz": nnz, "d": d, "K": K,
+        "config": {"workload": WORKLOAD_NAMES[args.workload] + (" [community-contiguous ids]" if args.contiguous_ids else "")
+                   + (f" [scale {args.scale}]" if args.scale != 1.0 else ""), "memory": memory, "n": n, "nnz": nnz, "d": d, "K": K,
                    "edge_blocks": plan.num_blocks, "agg": ["sym", "mean", "sum"][w.agg],
                    "segments": int(plan.segments.size), "partial_rows": plan.num_partial_rows,
                    "options": {k: gp.gp_get_option(k) for k in ("segment_edges", "column_tile", "column_slices")}},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-                     "kernel": "gp_hop_segments", "launches": launches,
+                     "kernel": "gp_hop_segments", "launches": launches, "launches_per_hop": launches_per_hop,
                      "avg_launch_us": round(avg_launch_s * 1e6, 3), "algorithmic_bytes_per_launch": bytes_per_launch},
         "other_kernels_ms_per_step": {"gp_fixup_rows": round(fix_ms / args.steps, 5),
                                       "gp_copy_rows": round(copy_ms / args.steps, 5)},
         "host_s": {"generate": round(t_gen, 2), "gp_plan_blocks": round(t_plan, 3), "timed_wall": round(wall, 3)},
     }
 
+    if memory == "pinned":
+        # bytes that crossed the host link per step: X in, K+1 slabs out (slab 0 is X sent
+        # back), and every edge block once per hop and column slab
+        slabs = max(1, launches // max(args.steps * K * plan.num_blocks, 1))
+        link_bytes = n * d * elem * (K + 2) + slabs * K * (4 * nnz + 16 * int(plan.segments.size))
+        rec["host_link"] = {"bytes_per_step": link_bytes, "GB/s": round(link_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+                            "column_slabs": slabs}
     if not args.no_cpu_baseline:
         import oracle
         cores = min(16, os.cpu_count() or 1)
