@@ -48,7 +48,7 @@ typedef enum { GP_AGG_SYM = 0, GP_AGG_MEAN = 1, GP_AGG_SUM = 2 } gp_agg;
 typedef enum { GP_F32 = 0, GP_BF16 = 1 } gp_dtype;
 
 /* plan flags */
-enum { GP_SYMMETRISE = 1u, GP_ADD_SELF_LOOPS = 2u };
+enum { GP_SYMMETRISE = 1u, GP_ADD_SELF_LOOPS = 2u, GP_PLAN_ON_DEVICE = 4u };
 
 /* ---------------------------------------------------------------------------
  * gp_plan_blocks -- edge decomposition and normalisation vectors.
@@ -62,7 +62,10 @@ enum { GP_SYMMETRISE = 1u, GP_ADD_SELF_LOOPS = 2u };
  *  n         number of nodes, 1 .. 2^31-1.
  *  block_budget_edges  largest number of non-zeros one block may hold, > 0.
  *  flags     GP_SYMMETRISE also inserts (row j, col i); GP_ADD_SELF_LOOPS
- *            inserts (i, i) for every i.
+ *            inserts (i, i) for every i.  GP_PLAN_ON_DEVICE sorts and de-duplicates
+ *            the non-zeros on the current GPU instead of on the host threads
+ *            (same plan, bit for bit; needs a GPU; at most 2^31 - 1 candidate
+ *            entries, else GP_ERR_UNSUPPORTED).
  *  out_plan  HOST; receives the plan (NULL on error).  Free with gp_plan_destroy.
  *
  * The non-zeros form a SET: duplicate pairs collapse, input pairs with
@@ -72,7 +75,8 @@ enum { GP_SYMMETRISE = 1u, GP_ADD_SELF_LOOPS = 2u };
  * [p*q + min(p,r), (p+1)*q + min(p+1,r)), q = nnz div b, r = nnz mod b, so
  * block sizes differ by at most one.  deg[i] = number of non-zeros in row i.
  * dinv_sqrt[i] = (float)(1/sqrt((double)deg)), dinv[i] = (float)(1/(double)deg),
- * both 0 where deg = 0.  Runs on the host only (no GPU needed).
+ * both 0 where deg = 0.  Runs on the host only (no GPU needed) unless
+ * GP_PLAN_ON_DEVICE is set.
  * Errors: INVALID_ARG, INDEX_RANGE, OVERFLOW, OOM_HOST.
  */
 gp_status gp_plan_blocks(const int32_t *src, const int32_t *dst, int64_t m, int64_t n,

@@ -16,7 +16,7 @@ GP_ERR_INVALID_ARG, GP_ERR_INDEX_RANGE, GP_ERR_OVERFLOW = 1, 2, 3
 GP_ERR_OOM_HOST, GP_ERR_OOM_DEVICE, GP_ERR_DEVICE, GP_ERR_UNSUPPORTED = 4, 5, 6, 7
 GP_AGG_SYM, GP_AGG_MEAN, GP_AGG_SUM = 0, 1, 2
 GP_F32, GP_BF16 = 0, 1
-GP_SYMMETRISE, GP_ADD_SELF_LOOPS = 1, 2
+GP_SYMMETRISE, GP_ADD_SELF_LOOPS, GP_PLAN_ON_DEVICE = 1, 2, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 # GP_LIB names another build of the same library (tuning variants); default: the in-tree one

@@ -104,6 +104,8 @@ struct gp_plan {
 namespace gp {
 
 gp_status build_schedule(gp_plan* plan);
+// fills plan->nnz, rowptr, col, deg from validated input pairs, on the current GPU
+gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64_t n, bool sym, bool loops, gp_plan* plan);
 
 // resident schedule: everything already in HBM
 gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,

@@ -57,7 +57,7 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
     if (m > 0 && (!src || !dst)) return fail(GP_ERR_INVALID_ARG, "src/dst is NULL with m > 0");
     if (n <= 0 || n > INT32_MAX) return fail(GP_ERR_INVALID_ARG, "n = %lld outside 1 .. 2^31-1", (long long)n);
     if (block_budget_edges <= 0) return fail(GP_ERR_INVALID_ARG, "block budget must be positive");
-    if (flags & ~(uint32_t)(GP_SYMMETRISE | GP_ADD_SELF_LOOPS))
+    if (flags & ~(uint32_t)(GP_SYMMETRISE | GP_ADD_SELF_LOOPS | GP_PLAN_ON_DEVICE))
         return fail(GP_ERR_INVALID_ARG, "unknown plan flag 0x%x", flags);
     const bool sym = flags & GP_SYMMETRISE, loops = flags & GP_ADD_SELF_LOOPS;
     // every candidate count must stay far inside int64 and the 48-bit segment start
@@ -91,81 +91,92 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
                         src[e], dst[e], (long long)n);
         }
 
-        // 2. candidates per row (before duplicates collapse)
-        std::vector<int64_t> cand_ptr((size_t)n + 1, 0);
-        {
-            int64_t* cnt = cand_ptr.data() + 1;
-            if (loops)
-                for (int64_t i = 0; i < n; ++i) cnt[i] = 1;
-            parallel_run(nt, [&](int t, int k) {
-                int64_t lo, hi;
-                chunk_of(m, t, k, lo, hi);
-                for (int64_t e = lo; e < hi; ++e) {
-                    const int32_t s = src[e], d = dst[e];
-                    if (s == d) continue;
-                    __atomic_fetch_add(&cnt[d], 1, __ATOMIC_RELAXED);
-                    if (sym) __atomic_fetch_add(&cnt[s], 1, __ATOMIC_RELAXED);
-                }
-            });
-            for (int64_t i = 0; i < n; ++i) cand_ptr[i + 1] += cand_ptr[i];
-        }
-        const int64_t ncand = cand_ptr[n];
-
-        // 3. bucket the column ids by row
-        std::vector<int32_t> cand((size_t)ncand);
-        {
-            std::vector<int64_t> cursor(cand_ptr.begin(), cand_ptr.end() - 1);
-            if (loops)
-                for (int64_t i = 0; i < n; ++i) cand[cursor[i]++] = (int32_t)i;
-            parallel_run(nt, [&](int t, int k) {
-                int64_t lo, hi;
-                chunk_of(m, t, k, lo, hi);
-                for (int64_t e = lo; e < hi; ++e) {
-                    const int32_t s = src[e], d = dst[e];
-                    if (s == d) continue;
-                    cand[__atomic_fetch_add(&cursor[d], 1, __ATOMIC_RELAXED)] = s;
-                    if (sym) cand[__atomic_fetch_add(&cursor[s], 1, __ATOMIC_RELAXED)] = d;
-                }
-            });
-        }
-
-        // 4. sort + unique inside each row; threads own row ranges of similar candidate count
-        plan->deg.assign((size_t)n, 0);
-        std::vector<int64_t> row_cut((size_t)nt + 1);
-        for (int t = 0; t <= nt; ++t) {
-            const int64_t target = ncand / nt * t + std::min<int64_t>(t, ncand % nt);
-            row_cut[t] = std::lower_bound(cand_ptr.begin(), cand_ptr.end(), target) - cand_ptr.begin();
-            if (row_cut[t] > n) row_cut[t] = n;
-        }
-        row_cut[0] = 0;
-        row_cut[nt] = n;
-        parallel_run(nt, [&](int t, int) {
-            for (int64_t i = row_cut[t]; i < row_cut[t + 1]; ++i) {
-                int32_t* b = cand.data() + cand_ptr[i];
-                int32_t* e = cand.data() + cand_ptr[i + 1];
-                std::sort(b, e);
-                plan->deg[i] = (int32_t)(std::unique(b, e) - b);
+        if (flags & GP_PLAN_ON_DEVICE) {
+            // sort / unique / row pointers on the current GPU; same arrays, bit for bit
+            gp_status st = csr_on_device(src, dst, m, n, sym, loops, plan);
+            if (st != GP_OK) {
+                delete plan;
+                return st;
             }
-        });
+        } else {
+            // 2. candidates per row (before duplicates collapse)
+            std::vector<int64_t> cand_ptr((size_t)n + 1, 0);
+            {
+                int64_t* cnt = cand_ptr.data() + 1;
+                if (loops)
+                    for (int64_t i = 0; i < n; ++i) cnt[i] = 1;
+                parallel_run(nt, [&](int t, int k) {
+                    int64_t lo, hi;
+                    chunk_of(m, t, k, lo, hi);
+                    for (int64_t e = lo; e < hi; ++e) {
+                        const int32_t s = src[e], d = dst[e];
+                        if (s == d) continue;
+                        __atomic_fetch_add(&cnt[d], 1, __ATOMIC_RELAXED);
+                        if (sym) __atomic_fetch_add(&cnt[s], 1, __ATOMIC_RELAXED);
+                    }
+                });
+                for (int64_t i = 0; i < n; ++i) cand_ptr[i + 1] += cand_ptr[i];
+            }
+            const int64_t ncand = cand_ptr[n];
 
-        // 5. rowptr and the compacted column list
-        plan->rowptr.assign((size_t)n + 1, 0);
-        for (int64_t i = 0; i < n; ++i) plan->rowptr[i + 1] = plan->rowptr[i] + plan->deg[i];
-        const int64_t nnz = plan->rowptr[n];
-        if (nnz >= (INT64_C(1) << 47)) {
-            delete plan;
-            return fail(GP_ERR_OVERFLOW, "non-zero count %lld exceeds the 47-bit list index", (long long)nnz);
+            // 3. bucket the column ids by row
+            std::vector<int32_t> cand((size_t)ncand);
+            {
+                std::vector<int64_t> cursor(cand_ptr.begin(), cand_ptr.end() - 1);
+                if (loops)
+                    for (int64_t i = 0; i < n; ++i) cand[cursor[i]++] = (int32_t)i;
+                parallel_run(nt, [&](int t, int k) {
+                    int64_t lo, hi;
+                    chunk_of(m, t, k, lo, hi);
+                    for (int64_t e = lo; e < hi; ++e) {
+                        const int32_t s = src[e], d = dst[e];
+                        if (s == d) continue;
+                        cand[__atomic_fetch_add(&cursor[d], 1, __ATOMIC_RELAXED)] = s;
+                        if (sym) cand[__atomic_fetch_add(&cursor[s], 1, __ATOMIC_RELAXED)] = d;
+                    }
+                });
+            }
+
+            // 4. sort + unique inside each row; threads own row ranges of similar candidate count
+            plan->deg.assign((size_t)n, 0);
+            std::vector<int64_t> row_cut((size_t)nt + 1);
+            for (int t = 0; t <= nt; ++t) {
+                const int64_t target = ncand / nt * t + std::min<int64_t>(t, ncand % nt);
+                row_cut[t] = std::lower_bound(cand_ptr.begin(), cand_ptr.end(), target) - cand_ptr.begin();
+                if (row_cut[t] > n) row_cut[t] = n;
+            }
+            row_cut[0] = 0;
+            row_cut[nt] = n;
+            parallel_run(nt, [&](int t, int) {
+                for (int64_t i = row_cut[t]; i < row_cut[t + 1]; ++i) {
+                    int32_t* b = cand.data() + cand_ptr[i];
+                    int32_t* e = cand.data() + cand_ptr[i + 1];
+                    std::sort(b, e);
+                    plan->deg[i] = (int32_t)(std::unique(b, e) - b);
+                }
+            });
+
+            // 5. rowptr and the compacted column list
+            plan->rowptr.assign((size_t)n + 1, 0);
+            for (int64_t i = 0; i < n; ++i) plan->rowptr[i + 1] = plan->rowptr[i] + plan->deg[i];
+            const int64_t nnz = plan->rowptr[n];
+            if (nnz >= (INT64_C(1) << 47)) {
+                delete plan;
+                return fail(GP_ERR_OVERFLOW, "non-zero count %lld exceeds the 47-bit list index", (long long)nnz);
+            }
+            plan->nnz = nnz;
+            plan->col.resize((size_t)nnz);
+            parallel_run(nt, [&](int t, int) {
+                for (int64_t i = row_cut[t]; i < row_cut[t + 1]; ++i)
+                    if (plan->deg[i])
+                        std::memcpy(plan->col.data() + plan->rowptr[i], cand.data() + cand_ptr[i],
+                                    sizeof(int32_t) * (size_t)plan->deg[i]);
+            });
+            std::vector<int32_t>().swap(cand);
+            std::vector<int64_t>().swap(cand_ptr);
+
         }
-        plan->nnz = nnz;
-        plan->col.resize((size_t)nnz);
-        parallel_run(nt, [&](int t, int) {
-            for (int64_t i = row_cut[t]; i < row_cut[t + 1]; ++i)
-                if (plan->deg[i])
-                    std::memcpy(plan->col.data() + plan->rowptr[i], cand.data() + cand_ptr[i],
-                                sizeof(int32_t) * (size_t)plan->deg[i]);
-        });
-        std::vector<int32_t>().swap(cand);
-        std::vector<int64_t>().swap(cand_ptr);
+        const int64_t nnz = plan->nnz;
 
         // 6. normalisation vectors: one correctly rounded recipe, fp64 then narrowed once
         plan->dinv_sqrt.resize((size_t)n);

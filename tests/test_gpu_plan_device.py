@@ -1,0 +1,82 @@
+"""gp_plan_blocks with GP_PLAN_ON_DEVICE (sort / unique / row pointers on the
+GPU) against the oracle's planner, bit for bit, and against the host planner."""
+import time
+
+import numpy as np
+import pytest
+
+import gp_synth
+import oracle
+import paper_2207_12000_amd as gp
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu(gpu_or_skip):
+    yield
+
+
+def same(lp, op):
+    assert lp.n == op.n and lp.nnz == op.nnz and lp.num_blocks == op.num_blocks
+    for name in ("block_off", "block_row_lo", "block_row_hi", "rowptr", "col", "deg"):
+        assert np.array_equal(getattr(lp, name), getattr(op, name)), name
+    assert np.array_equal(lp.dinv_sqrt.view(np.uint32), op.dinv_sqrt.view(np.uint32))
+    assert np.array_equal(lp.dinv.view(np.uint32), op.dinv.view(np.uint32))
+
+
+CASES = [([], [], 4, 3), ([2], [0], 3, 10), ([0, 1], [1, 2], 3, 4), ([0, 0, 1, 2, 2, 1], [1, 1, 0, 2, 2, 1], 3, 100),
+         ([0], [0], 1, 1), ([1, 1, 1], [1, 1, 1], 5, 2)]
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+@pytest.mark.parametrize("case", CASES)
+def test_tiny_cases(case, flags):
+    src, dst, n, budget = case
+    op = oracle.plan_blocks(src, dst, n, budget, flags)
+    with gp.gp_plan_blocks(src, dst, n, budget, flags | gp.GP_PLAN_ON_DEVICE) as lp:
+        same(lp, op)
+
+
+@pytest.mark.parametrize("flags", [0, 1, 2, 3])
+@pytest.mark.parametrize("seed", range(4))
+def test_random_graphs(seed, flags):
+    rng = np.random.default_rng(500 + seed)
+    n = int(rng.integers(1, 400))
+    m = int(rng.integers(0, 5000))
+    src, dst = rng.integers(0, n, m), rng.integers(0, n, m)
+    op = oracle.plan_blocks(src, dst, n, 97, flags)
+    with gp.gp_plan_blocks(src, dst, n, 97, flags | gp.GP_PLAN_ON_DEVICE) as lp:
+        same(lp, op)
+
+
+@pytest.mark.parametrize("config,scale", [(1, 1.0), (2, 1.0), (3, 0.05), (4, 0.02), (5, 0.002)])
+def test_workloads_and_propagate_from_a_device_plan(config, scale):
+    import torch
+    w = gp_synth.make_workload(config, scale=scale, d=16)
+    budget = w.block_budget_edges or 60000
+    op = oracle.plan_blocks(w.src, w.dst, w.n, budget, w.flags)
+    t0 = time.perf_counter()
+    lp = gp.gp_plan_blocks(w.src, w.dst, w.n, budget, w.flags | gp.GP_PLAN_ON_DEVICE)
+    t_dev = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    hp = gp.gp_plan_blocks(w.src, w.dst, w.n, budget, w.flags)
+    t_host = time.perf_counter() - t0
+    print(f"config {config} scale {scale}: nnz {lp.nnz}, plan on device {t_dev:.3f} s, on host {t_host:.3f} s")
+    with lp, hp:
+        same(lp, op)
+        assert np.array_equal(lp.segments, hp.segments)          # same schedule either way
+        x = torch.from_numpy(w.X if w.X.dtype == np.float32 else gp_synth.bf16_bits_to_f32(w.X)).cuda()
+        a = gp.propagate_tensors(lp, x, w.agg, 1)
+        b = gp.propagate_tensors(hp, x, w.agg, 1)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
+
+
+def test_errors_keep_their_codes():
+    with pytest.raises(gp.GpError) as e:
+        gp.gp_plan_blocks([0], [7], 3, 1, gp.GP_PLAN_ON_DEVICE)
+    assert e.value.status == gp.GP_ERR_INDEX_RANGE
+    with pytest.raises(gp.GpError) as e:
+        gp.gp_plan_blocks([0], [1], 3, 1, 8)
+    assert e.value.status == gp.GP_ERR_INVALID_ARG

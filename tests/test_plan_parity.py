@@ -132,7 +132,7 @@ def test_hub_row_split_across_many_blocks():
 
 def test_error_codes_match_oracle_kinds():
     kinds = {"INVALID_ARG": gp.GP_ERR_INVALID_ARG, "INDEX_RANGE": gp.GP_ERR_INDEX_RANGE}
-    bad = [([0], [3], 3, 1, 0), ([-1], [0], 3, 1, 0), ([0], [1], 0, 1, 0), ([0], [1], 3, 0, 0), ([0], [1], 3, 1, 4),
+    bad = [([0], [3], 3, 1, 0), ([-1], [0], 3, 1, 0), ([0], [1], 0, 1, 0), ([0], [1], 3, 0, 0), ([0], [1], 3, 1, 8),
            ([0], [1], 2**31, 1, 0)]
     for src, dst, n, budget, flags in bad:
         with pytest.raises(oracle.OracleError) as oe:
