@@ -161,8 +161,10 @@ gp_status launch_fixup(const FixupArgs& a, hipStream_t stream);
 gp_status launch_scale_convert(const void* src, int64_t lds, gp_dtype src_type, void* dst, int64_t ldd, gp_dtype dst_type,
                                int64_t n, int32_t d, float gamma, hipStream_t stream);
 gp_status launch_fill_edge_weights(const int32_t* col, const float* by_col, float* w, int64_t nnz, hipStream_t stream);
+// max_blocks > 0 caps the grid (copies over the host link need few workgroups and
+// must leave the compute units to the kernels running beside them)
 gp_status launch_copy_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t n, int32_t d,
-                           gp_dtype dtype, hipStream_t stream);
+                           gp_dtype dtype, hipStream_t stream, int max_blocks = 0);
 
 void release_pinned(gp_plan* plan);
 

@@ -617,7 +617,7 @@ gp_status launch_fill_edge_weights(const int32_t* col, const float* by_col, floa
 }
 
 gp_status launch_copy_rows(const void* src, int64_t lds, void* dst, int64_t ldd, int64_t n, int32_t d, gp_dtype dtype,
-                           hipStream_t stream)
+                           hipStream_t stream, int max_blocks)
 {
     if (n == 0) return GP_OK;
     const int es = dtype == GP_F32 ? 4 : 2;
@@ -631,7 +631,7 @@ gp_status launch_copy_rows(const void* src, int64_t lds, void* dst, int64_t ldd,
         unit /= 2;
     }
     const int64_t w = row_bytes / unit, total = n * w;
-    const int64_t blocks = std::min<int64_t>((total + kThreads - 1) / kThreads, 256 * 32);
+    const int64_t blocks = std::min<int64_t>((total + kThreads - 1) / kThreads, max_blocks > 0 ? max_blocks : 256 * 32);
     const dim3 grid((unsigned)blocks), block(kThreads);
     const int64_t s = lds * es / unit, t = ldd * es / unit;
     switch (unit) {

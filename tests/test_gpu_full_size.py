@@ -85,3 +85,50 @@ def test_full_size_sampled_rows_every_hop(config, samples):
             ones = torch.ones((w.n, 8), device="cuda:0")
             deg = gp.propagate_tensors(lp, ones, gp.GP_AGG_SUM, 1)[1, :, 0].cpu().numpy()
             assert np.array_equal(deg, op.deg.astype(np.float32))
+
+
+def test_config5_streamed_sampled_rows_every_hop():
+    """The out-of-core workload (bf16 storage, sym, K = 3) through the streamed
+    schedule from pinned host memory, at a scale the oracle's planner still handles
+    (GP_TEST_CONFIG5_SCALE, default 0.05 = 5.55 M nodes / 161 M non-zeros).  Each hop
+    is checked on sampled rows against the oracle applied to the library's own stored
+    previous hop: one RNE store plus fp32 accumulation, |err| <= 2^-8 * A^|X_{k-1}|,
+    which implies the end-to-end 1e-2 bound for K = 3."""
+    import os
+
+    import torch
+    scale = float(os.environ.get("GP_TEST_CONFIG5_SCALE", "0.05"))
+    w = gp_synth.make_workload(5, scale=scale)
+    op = oracle.plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags)
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) as lp:
+        same_plan(lp, op)
+        x = torch.from_numpy(w.X.view(np.int16)).view(torch.bfloat16).pin_memory()
+        out = torch.empty((w.K + 1, w.n, w.d), dtype=torch.bfloat16).pin_memory()
+        # a budget that forces two column slabs and streams every edge block per hop and slab
+        per_col = 2 * w.n * 2 + lp.num_partial_rows * 4
+        fixed = 2 * (int(np.diff(lp.block_off).max()) * 4 + int(np.diff(lp.segment_off).max()) * 16) + 8 * w.n \
+            + 16 * lp.num_partial_rows + 4096
+        gp.gp_set_hbm_budget_bytes(fixed + per_col * 72)
+        try:
+            gp.gp_propagate(lp, x.data_ptr(), w.d, w.d, gp.GP_BF16, w.agg, w.K, out.data_ptr(), w.d, None)
+        finally:
+            gp.gp_set_hbm_budget_bytes(0)
+    assert torch.equal(out[0].view(torch.int16), x.view(torch.int16))
+    rows = sampled_rows(op, 600, 5005)
+    stack = out.view(torch.int16).numpy().view(np.uint16)
+    class Widened:
+        """bf16 bit patterns that widen exactly on row access (what the oracle's
+        row-by-row evaluation indexes)."""
+
+        def __init__(self, bits):
+            self.bits, self.shape = bits, bits.shape
+
+        def __getitem__(self, idx):
+            return gp_synth.bf16_bits_to_f32(self.bits[idx])
+
+    for k in range(1, w.K + 1):
+        want, bound = oracle.hop_rows(op, Widened(stack[k - 1]), w.agg, rows)
+        got = gp_synth.bf16_bits_to_f32(stack[k][rows]).astype(np.float64)
+        err = np.abs(got - want)
+        assert np.all(err <= 2.0 ** -8 * bound + 1e-30), \
+            f"hop {k}: worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {2.0 ** -8:.3g})"
