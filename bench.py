@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc
 # (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); the
 # summaries are in profiles/gp_hop_segments_<workload>.md.  Per launch, default options.
-MEASURED_TRAFFIC_BYTES = {1: 29_419_394, 2: 1_065_586_671, 3: 60_530_361_013, 4: 286_150_624_139}
+MEASURED_TRAFFIC_BYTES = {1: 32_612_875, 2: 1_072_032_400, 3: 60_522_738_707, 4: 285_626_792_016}
 
 WORKLOAD_NAMES = {
     1: "config1: G(n,M) 10k nodes / 210k nnz, d=128 fp32, sym, K=2, 4 edge blocks",
