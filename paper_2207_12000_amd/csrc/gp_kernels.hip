@@ -267,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
                     const T* src = xin + (int64_t)c * ldin;
 #pragma unroll
                     for (int v = 0; v < VPL; ++v) {
-                        x[u][v] = (on && live[v]) ? Row<T, VEC>::load_raw(src + coff[v]) : Row<T, VEC>::zero_raw();
+x[u][v] = (on && live[v]) ? Row<T, VEC>::load_raw(src + coff[v]) : Row<T, VEC>::zero_raw();
                     }
                 }
 #pragma unroll
