@@ -135,8 +135,9 @@ int64_t gp_plan_segment_edges(const gp_plan *plan);           /* the segment len
  * slabs are streamed through HBM on library-owned side streams and the call
  * returns after the last slab has reached out_stack.  The first call on a plan
  * uploads the plan to the current device and allocates scratch (partial-row
- * buffer); later calls with the same d reuse both.  Results are deterministic:
- * the same inputs give the same bits on every call.
+ * buffer); later calls with the same d reuse both.  Calls on ONE plan must not
+ * overlap in time (they share that scratch); different plans are independent.
+ * Results are deterministic: the same inputs give the same bits on every call.
  * Errors: INVALID_ARG, OOM_DEVICE, DEVICE, UNSUPPORTED.
  */
 gp_status gp_propagate(const gp_plan *plan, const void *X, int64_t ldx, int32_t d, gp_dtype dtype,

@@ -12,7 +12,6 @@
 // in-group shuffles; four gathers are kept in flight per group, each with its
 // own accumulator (also what keeps the fp32 sum short-chained).  No cross-lane
 // reduction is needed: lanes own columns, not edges.
-#include <hip/hip_bfloat16.h>
 #include <hip/hip_runtime.h>
 
 #include "gp_internal.h"
@@ -54,7 +53,6 @@ __device__ __forceinline__ auto elem(const V& v, int i)
 }
 
 // Row<T, VEC>: one aligned VEC-element vector of a feature row, widened to fp32.
-// NT = true marks the access non-temporal (streamed once: do not keep it in cache).
 template <typename T, int VEC>
 struct Row;
 
@@ -78,15 +76,13 @@ struct Row<float, VEC> {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) x[i] = elem<V, VEC>(t, i);
     }
-    template <bool NT = false>
     __device__ static __forceinline__ void load(const float* p, float (&x)[VEC])
     {
         const V* q = reinterpret_cast<const V*>(p);
-        const V t = NT ? __builtin_nontemporal_load(q) : *q;
+        const V t = *q;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) x[i] = elem<V, VEC>(t, i);
     }
-    template <bool NT = false>
     __device__ static __forceinline__ void store(float* p, const float (&x)[VEC])
     {
         V t;
@@ -96,11 +92,7 @@ struct Row<float, VEC> {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) t[i] = x[i];
         }
-        V* q = reinterpret_cast<V*>(p);
-        if (NT)
-            __builtin_nontemporal_store(t, q);
-        else
-            *q = t;
+        *reinterpret_cast<V*>(p) = t;
     }
 };
 
@@ -124,15 +116,13 @@ struct Row<uint16_t, VEC> {
 #pragma unroll
         for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(elem<V, VEC>(t, i));
     }
-    template <bool NT = false>
     __device__ static __forceinline__ void load(const uint16_t* p, float (&x)[VEC])
     {
         const V* q = reinterpret_cast<const V*>(p);
-        const V t = NT ? __builtin_nontemporal_load(q) : *q;
+        const V t = *q;
 #pragma unroll
         for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(elem<V, VEC>(t, i));
     }
-    template <bool NT = false>
     __device__ static __forceinline__ void store(uint16_t* p, const float (&x)[VEC])
     {
         V t;
@@ -142,11 +132,7 @@ struct Row<uint16_t, VEC> {
 #pragma unroll
             for (int i = 0; i < VEC; ++i) t[i] = f32_to_bf16(x[i]);
         }
-        V* q = reinterpret_cast<V*>(p);
-        if (NT)
-            __builtin_nontemporal_store(t, q);
-        else
-            *q = t;
+        *reinterpret_cast<V*>(p) = t;
     }
 };
 

@@ -251,3 +251,20 @@ def test_bad_arguments_return_status():
             with pytest.raises(gp.GpError) as e:
                 gp.gp_propagate(lp, *args)
             assert e.value.status == gp.GP_ERR_INVALID_ARG
+
+
+def test_many_hops_and_repeated_calls_on_one_plan():
+    """K = 6 (error grows at most linearly with K against the bound), then the same
+    plan reused with another width, dtype and operator: the scratch is resized."""
+    w = gp_synth.make_workload(2, scale=0.02, d=48)
+    lp, op = plan_pair(w.src, w.dst, w.n, 3000, w.flags)
+    with lp:
+        for d, dtype, agg, K in [(48, gp.GP_F32, gp.GP_AGG_SYM, 6), (16, gp.GP_BF16, gp.GP_AGG_MEAN, 2),
+                                 (48, gp.GP_F32, gp.GP_AGG_SUM, 1), (40, gp.GP_BF16, gp.GP_AGG_SYM, 3)]:
+            X = w.X[:, :d]
+            if dtype == gp.GP_BF16:
+                X = gp_synth.f32_to_bf16_bits(X)
+            got = run_library(lp, X, dtype, agg, K)
+            Xw = widen(X, dtype)
+            check(got, oracle.propagate(op, Xw, agg, K, 4), oracle.bound_stack(op, Xw, agg, K, 4), TOL[dtype],
+                  f"d={d} dtype={dtype} agg={agg} K={K}")
