@@ -173,6 +173,16 @@ def features(n: int, d: int, dist: str, rng: np.random.Generator) -> np.ndarray:
     raise ValueError(dist)
 
 
+def fill_features(out: np.ndarray, dist: str, rng: np.random.Generator, chunk_rows: int = 1 << 18) -> None:
+    """Draws features() row chunk by row chunk into `out` (float32, or uint16 for
+    bf16 bit patterns), so that a matrix too large to hold twice can be generated
+    in place (e.g. into pinned host memory).  Same stream, same numbers."""
+    n, d = out.shape
+    for r0 in range(0, n, chunk_rows):
+        x = features(min(chunk_rows, n - r0), d, dist, rng)
+        out[r0:r0 + x.shape[0]] = f32_to_bf16_bits(x) if out.dtype == np.uint16 else x
+
+
 # --------------------------------------------------------------------------
 # the five workloads
 # --------------------------------------------------------------------------

@@ -236,3 +236,24 @@ def test_bf16_helpers_round_to_nearest_even():
     bits = gp_synth.f32_to_bf16_bits(x)
     back = gp_synth.bf16_bits_to_f32(bits)
     assert back.tolist() == [1.0, 1.0, 1.015625, -2.5, 0.0, 3.140625]
+
+
+@pytest.mark.parametrize("flags", [0, SYMMETRISE, ADD_SELF_LOOPS, BOTH])
+def test_sampled_row_oracle_agrees_with_the_full_one(flags):
+    """The pair-list scan used at sizes the full planner cannot hold must give the
+    same neighbour sets, degrees and rows as the planner-based oracle."""
+    from oracle import sampled
+    w = gp_synth.make_workload(3, scale=0.002, d=6)
+    plan = oracle.plan_blocks(w.src, w.dst, w.n, 10**9, flags)
+    rng = np.random.default_rng(8)
+    rows = np.concatenate([rng.integers(0, w.n, 40), np.argsort(plan.deg)[-3:], np.argsort(plan.deg)[:3]])
+    cols, deg = sampled.neighbourhoods(w.src, w.dst, w.n, flags, rows, chunk=5000)
+    for t, i in enumerate(rows):
+        assert np.array_equal(cols[t], plan.col[plan.rowptr[i]:plan.rowptr[i + 1]])
+    for node, g in deg.items():
+        assert g == plan.deg[node]
+    X = w.X.astype(np.float64)
+    for agg in (AGG_SYM, AGG_MEAN, AGG_SUM):
+        y, b = sampled.hop_rows(cols, deg, rows, X, agg)
+        y2, b2 = oracle.hop_rows(plan, X, agg, rows)
+        assert np.allclose(y, y2, rtol=1e-13, atol=1e-300) and np.allclose(b, b2, rtol=1e-13, atol=1e-300)
