@@ -106,15 +106,16 @@ def test_config5_streamed_sampled_rows_every_hop():
     rows against the oracle applied to the library's own stored previous hop: one RNE
     store plus fp32 accumulation, |err| <= 2^-8 * A^|X_{k-1}|, which implies the
     end-to-end 1e-2 bound for K = 3.  Up to scale 0.3 the oracle's planner is built in
-    full (and the plan compared bit for bit); above it the sampled rows' neighbour sets
-    and degrees come from a scan of the pair list (oracle.sampled)."""
+    full (and the plan compared bit for bit); above it, or with
+    GP_TEST_CONFIG5_ORACLE=sampled, the sampled rows' neighbour sets and degrees come
+    from a scan of the pair list (oracle.sampled)."""
     import os
     import time
 
     import torch
     from oracle import sampled
     scale = float(os.environ.get("GP_TEST_CONFIG5_SCALE", "0.05"))
-    full_oracle = scale <= 0.3
+    full_oracle = scale <= 0.3 and os.environ.get("GP_TEST_CONFIG5_ORACLE", "full") != "sampled"
     t0 = time.time()
     w = gp_synth.make_workload(5, scale=scale, with_features=False)
     x = torch.empty((w.n, w.d), dtype=torch.bfloat16, pin_memory=True)
