@@ -73,7 +73,8 @@ def hop_rows(cols, deg, rows, Xprev, agg: int):
         di = float(deg[int(i)])
         if agg == 0:
             dj = np.array([deg[int(j)] for j in cs], dtype=np.float64)
-            w = np.where((di > 0) & (dj > 0), 1.0 / np.sqrt(di * dj), 0.0)
+            with np.errstate(divide="ignore"):
+                w = np.where((di > 0) & (dj > 0), 1.0 / np.sqrt(di * dj), 0.0)
         elif agg == 1:
             w = np.full(cs.size, 1.0 / di if di > 0 else 0.0)
         else:
