@@ -10,10 +10,13 @@
 // edge block for every column block of every hop AND moves every slab in and out
 // once per hop, a slab here stays in HBM across all K hops (the hops of one
 // column slab do not depend on the other slabs), so features cross the host link
-// once in and K (+1) times out, and only the edge blocks are re-sent, c*K times,
-// double-buffered on a side stream while the previous block is being computed.
+// once in and K times out (slab 0 = X is a host-to-host copy done by host threads
+// meanwhile), and only the edge blocks are re-sent, c*K times, double-buffered on a
+// side stream while the previous block is being computed -- or sent just once and
+// kept, when the budget has room for all of them.
 #include <algorithm>
 #include <cstring>
+#include <thread>
 
 #include "gp_internal.h"
 
@@ -23,8 +26,8 @@ namespace {
 
 struct Streams {
     hipStream_t in = nullptr, cmp = nullptr, out = nullptr;
-    hipEvent_t blk_ready[2] = {nullptr, nullptr}, blk_free[2] = {nullptr, nullptr};
-    hipEvent_t slab_in = nullptr, hop_done = nullptr, out_done[2] = {nullptr, nullptr};
+    std::vector<hipEvent_t> blk_ready, blk_free;  // one pair per edge-block buffer
+    hipEvent_t hop_done = nullptr, out_done[2] = {nullptr, nullptr};
     std::vector<void*> dev;
 
     ~Streams()
@@ -33,20 +36,28 @@ struct Streams {
         if (cmp) (void)hipStreamSynchronize(cmp);
         if (out) (void)hipStreamSynchronize(out);
         for (void* p : dev) (void)hipFree(p);
-        for (hipEvent_t e : {blk_ready[0], blk_ready[1], blk_free[0], blk_free[1], slab_in, hop_done, out_done[0], out_done[1]})
+        for (hipEvent_t e : blk_ready) (void)hipEventDestroy(e);
+        for (hipEvent_t e : blk_free) (void)hipEventDestroy(e);
+        for (hipEvent_t e : {hop_done, out_done[0], out_done[1]})
             if (e) (void)hipEventDestroy(e);
         if (in) (void)hipStreamDestroy(in);
         if (cmp) (void)hipStreamDestroy(cmp);
         if (out) (void)hipStreamDestroy(out);
     }
-    gp_status init()
+    gp_status init(int block_buffers)
     {
         // default priority on purpose: all three streams are peers
         GP_HIP(hipStreamCreateWithFlags(&in, hipStreamNonBlocking));
         GP_HIP(hipStreamCreateWithFlags(&cmp, hipStreamNonBlocking));
         GP_HIP(hipStreamCreateWithFlags(&out, hipStreamNonBlocking));
-        for (hipEvent_t* e : {&blk_ready[0], &blk_ready[1], &blk_free[0], &blk_free[1], &slab_in, &hop_done, &out_done[0], &out_done[1]})
-            GP_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
+        for (hipEvent_t* e : {&hop_done, &out_done[0], &out_done[1]}) GP_HIP(hipEventCreateWithFlags(e, hipEventDisableTiming));
+        for (int i = 0; i < block_buffers; ++i) {
+            hipEvent_t a = nullptr, b = nullptr;
+            GP_HIP(hipEventCreateWithFlags(&a, hipEventDisableTiming));
+            blk_ready.push_back(a);
+            GP_HIP(hipEventCreateWithFlags(&b, hipEventDisableTiming));
+            blk_free.push_back(b);
+        }
         return GP_OK;
     }
     template <class T>
@@ -156,22 +167,31 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
                     "plan with a smaller block budget or raise the HBM budget",
                     (long long)budget, (long long)fixed, (long long)unit);
     const int64_t wpad = (w + 3) / 4 * 4;  // carry rows stay 16-byte aligned
+    // Edge-block buffers: two for double buffering; if the budget has room for all b
+    // blocks they are uploaded once and stay (on a 288 GB device only what does not fit
+    // has to be streamed again every hop).
+    const int64_t block_bytes = max_edges * 4 + max_segs * (int64_t)sizeof(Segment);
+    int64_t nbuf = 2;
+    if (block_bytes > 0) nbuf = std::min<int64_t>(b, 2 + (budget - fixed - per_col * w) / block_bytes);
+    if (nbuf < b) nbuf = std::min<int64_t>(b, 2);
+    const bool blocks_stay = nbuf >= b;
 
     Streams S;
-    if ((st = S.init()) != GP_OK) return st;
+    if ((st = S.init((int)nbuf)) != GP_OK) return st;
     float *d_dinv_sqrt, *d_dinv, *d_carry;
     SplitRow* d_split;
     char* d_slab[2];
-    int32_t* d_col[2];
-    Segment* d_segs[2];
+    std::vector<int32_t*> d_col((size_t)nbuf, nullptr);
+    std::vector<Segment*> d_segs((size_t)nbuf, nullptr);
     if ((st = S.alloc(d_dinv_sqrt, (size_t)n * 4)) != GP_OK || (st = S.alloc(d_dinv, (size_t)n * 4)) != GP_OK ||
         (st = S.alloc(d_split, plan->split.size() * sizeof(SplitRow))) != GP_OK ||
         (st = S.alloc(d_carry, (size_t)plan->num_slots * wpad * 4)) != GP_OK ||
-        (st = S.alloc(d_slab[0], (size_t)n * w * es)) != GP_OK || (st = S.alloc(d_slab[1], (size_t)n * w * es)) != GP_OK ||
-        (st = S.alloc(d_col[0], (size_t)max_edges * 4)) != GP_OK || (st = S.alloc(d_col[1], (size_t)max_edges * 4)) != GP_OK ||
-        (st = S.alloc(d_segs[0], (size_t)max_segs * sizeof(Segment))) != GP_OK ||
-        (st = S.alloc(d_segs[1], (size_t)max_segs * sizeof(Segment))) != GP_OK)
+        (st = S.alloc(d_slab[0], (size_t)n * w * es)) != GP_OK || (st = S.alloc(d_slab[1], (size_t)n * w * es)) != GP_OK)
         return st;
+    for (int64_t i = 0; i < nbuf; ++i)
+        if ((st = S.alloc(d_col[i], (size_t)max_edges * 4)) != GP_OK ||
+            (st = S.alloc(d_segs[i], (size_t)max_segs * sizeof(Segment))) != GP_OK)
+            return st;
     // small vectors: pageable sources, so these two copies are synchronous in effect
     GP_HIP(hipMemcpyAsync(d_dinv_sqrt, plan->dinv_sqrt.data(), (size_t)n * 4, hipMemcpyHostToDevice, S.cmp));
     GP_HIP(hipMemcpyAsync(d_dinv, plan->dinv.data(), (size_t)n * 4, hipMemcpyHostToDevice, S.cmp));
@@ -182,8 +202,33 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
     const float* edge_w = agg == GP_AGG_SYM ? d_dinv_sqrt : nullptr;
     const float* row_scale = agg == GP_AGG_SYM ? d_dinv_sqrt : agg == GP_AGG_MEAN ? d_dinv : nullptr;
     const int64_t out_slab = n * ldo * es;  // bytes between two hop slabs in the host stack
-    bool blk_used[2] = {false, false}, out_used[2] = {false, false};
-    int64_t blk_seq = 0;  // running count of block uploads: buffer = blk_seq & 1
+    std::vector<char> blk_used((size_t)nbuf, 0);
+    bool out_used[2] = {false, false};
+    int64_t blk_seq = 0;  // running count of block visits: ring position when blocks do not stay
+
+    // slot 0 = X never needs the device: host threads copy it while the GPU works
+    std::vector<std::thread> copiers;
+    if ((const void*)X != (const void*)out) {
+        const int nthreads = (int64_t)n * d * es < (1 << 22) ? 1 : 4;
+        for (int t = 0; t < nthreads; ++t)
+            copiers.emplace_back([=] {
+                const int64_t r0 = n * t / nthreads, r1 = n * (t + 1) / nthreads;
+                if (ldx == d && ldo == d) {
+                    std::memcpy((char*)out + r0 * d * es, (const char*)X + r0 * d * es, (size_t)(r1 - r0) * d * es);
+                } else {
+                    for (int64_t r = r0; r < r1; ++r)
+                        std::memcpy((char*)out + r * ldo * es, (const char*)X + r * ldx * es, (size_t)d * es);
+                }
+            });
+    }
+    struct Joiner {
+        std::vector<std::thread>& v;
+        ~Joiner()
+        {
+            for (auto& t : v)
+                if (t.joinable()) t.join();
+        }
+    } joiner{copiers};
 
     for (int64_t c0 = 0; c0 < d; c0 += w) {
         const int32_t wc = (int32_t)std::min<int64_t>(w, d - c0);
@@ -191,30 +236,25 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
         if (out_used[0]) GP_HIP(hipStreamWaitEvent(S.cmp, S.out_done[0], 0));
         if ((st = move_rows(d_slab[0], w, (const char*)X + c0 * es, ldx, n, wc, dtype, hipMemcpyHostToDevice, S.cmp)) != GP_OK)
             return st;
-        GP_HIP(hipEventRecord(S.hop_done, S.cmp));
-        if ((const void*)X != (const void*)out) {  // slot 0 = X, sent back from the slab
-            GP_HIP(hipStreamWaitEvent(S.out, S.hop_done, 0));
-            if ((st = move_rows((char*)out + c0 * es, ldo, d_slab[0], w, n, wc, dtype, hipMemcpyDeviceToHost, S.out)) != GP_OK)
-                return st;
-        }
-        GP_HIP(hipEventRecord(S.out_done[0], S.out));
-        out_used[0] = true;
+        out_used[0] = false;  // nothing leaves from the slab that holds X
 
         for (int32_t k = 1; k <= K; ++k) {
             const int src = (k - 1) & 1, dst = k & 1;
             // the slab about to be overwritten may still be on its way to the host
             if (out_used[dst]) GP_HIP(hipStreamWaitEvent(S.cmp, S.out_done[dst], 0));
             for (int32_t p = 0; p < b; ++p, ++blk_seq) {
-                const int buf = (int)(blk_seq & 1);
+                const int buf = blocks_stay ? p : (int)(blk_seq % nbuf);
                 const int64_t e_lo = plan->block_off[p], e_cnt = plan->block_off[p + 1] - e_lo;
                 const int64_t s_lo = plan->seg_off[p], s_cnt = plan->seg_off[p + 1] - s_lo;
-                if (blk_used[buf]) GP_HIP(hipStreamWaitEvent(S.in, S.blk_free[buf], 0));
-                if (e_cnt)
-                    GP_HIP(hipMemcpyAsync(d_col[buf], plan->pinned_col + e_lo, (size_t)e_cnt * 4, hipMemcpyHostToDevice, S.in));
-                if (s_cnt)
-                    GP_HIP(hipMemcpyAsync(d_segs[buf], plan->pinned_segs + s_lo, (size_t)s_cnt * sizeof(Segment),
-                                          hipMemcpyHostToDevice, S.in));
-                GP_HIP(hipEventRecord(S.blk_ready[buf], S.in));
+                if (!(blocks_stay && blk_used[buf])) {  // a block that stays is sent once
+                    if (blk_used[buf]) GP_HIP(hipStreamWaitEvent(S.in, S.blk_free[buf], 0));
+                    if (e_cnt)
+                        GP_HIP(hipMemcpyAsync(d_col[buf], plan->pinned_col + e_lo, (size_t)e_cnt * 4, hipMemcpyHostToDevice, S.in));
+                    if (s_cnt)
+                        GP_HIP(hipMemcpyAsync(d_segs[buf], plan->pinned_segs + s_lo, (size_t)s_cnt * sizeof(Segment),
+                                              hipMemcpyHostToDevice, S.in));
+                    GP_HIP(hipEventRecord(S.blk_ready[buf], S.in));
+                }
                 GP_HIP(hipStreamWaitEvent(S.cmp, S.blk_ready[buf], 0));
                 HopArgs a;
                 a.segs = d_segs[buf];
@@ -233,7 +273,7 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
                 a.dtype = dtype;
                 if ((st = hop_passes(a, S.cmp)) != GP_OK) return st;
                 GP_HIP(hipEventRecord(S.blk_free[buf], S.cmp));
-                blk_used[buf] = true;
+                blk_used[buf] = 1;
             }
             if (!plan->split.empty()) {
                 FixupArgs f;
@@ -260,6 +300,7 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
     GP_HIP(hipStreamSynchronize(S.in));
     GP_HIP(hipStreamSynchronize(S.cmp));
     GP_HIP(hipStreamSynchronize(S.out));
+    for (auto& t : copiers) t.join();
     return GP_OK;
 }
 
