@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     constexpr int GPB = kThreads / G;
     constexpr int PF = G >= 32 ? 1 : 32 / G;  // column ids each lane prefetches per segment
     constexpr int WIN = PF * G;               // edges of a segment covered by the prefetch
-        constexpr int U = VPL * VEC * (int)sizeof(T) <= 16 ? 8 : 4;  // row gathers in flight per group
+    constexpr int U = VPL * VEC * (int)sizeof(T) <= 16 ? 8 : 4;  // row gathers in flight per group
     // interleaved fp32 accumulators per column (short summation chains); bf16 storage
     // tolerates longer chains and its 8-element vectors are register hungry
     constexpr int NACC = sizeof(T) == 2 ? 2 : 4;
@@ -253,7 +253,7 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
                     const T* src = xin + (int64_t)c * ldin;
 #pragma unroll
                     for (int v = 0; v < VPL; ++v) {
-x[u][v] = (on && live[v]) ? Row<T, VEC>::load_raw(src + coff[v]) : Row<T, VEC>::zero_raw();
+                        x[u][v] = (on && live[v]) ? Row<T, VEC>::load_raw(src + coff[v]) : Row<T, VEC>::zero_raw();
                     }
                 }
 #pragma unroll
