@@ -11,6 +11,7 @@
 #include <atomic>
 #include <cmath>
 #include <cstring>
+#include <exception>
 #include <functional>
 #include <new>
 #include <thread>
@@ -32,10 +33,21 @@ void parallel_run(int nthreads, const std::function<void(int, int)>& fn)
         fn(0, 1);
         return;
     }
+    // an exception inside a worker (e.g. bad_alloc) must reach the caller, not terminate the process
     std::vector<std::thread> th;
+    std::vector<std::exception_ptr> err((size_t)nthreads);
     th.reserve(nthreads);
-    for (int t = 0; t < nthreads; ++t) th.emplace_back(fn, t, nthreads);
+    for (int t = 0; t < nthreads; ++t)
+        th.emplace_back([&fn, &err, t, nthreads] {
+            try {
+                fn(t, nthreads);
+            } catch (...) {
+                err[(size_t)t] = std::current_exception();
+            }
+        });
     for (auto& x : th) x.join();
+    for (auto& e : err)
+        if (e) std::rethrow_exception(e);
 }
 
 static inline void chunk_of(int64_t total, int t, int nt, int64_t& lo, int64_t& hi)
@@ -235,6 +247,9 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
         delete plan;
         return fail(GP_ERR_OOM_HOST, "host allocation failed while planning (m = %lld, n = %lld)", (long long)m,
                     (long long)n);
+    } catch (const std::exception& e) {  // e.g. no more threads: a host resource ran out
+        delete plan;
+        return fail(GP_ERR_OOM_HOST, "planning failed: %s", e.what());
     }
     *out_plan = plan;
     return GP_OK;

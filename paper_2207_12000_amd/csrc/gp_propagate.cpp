@@ -1,6 +1,7 @@
 // gp_propagate: the hop loop of Algorithm 1 (k = 1..K, every edge block, then
 // the rows cut between blocks) for operands that live in HBM, and plan upload.
 #include <algorithm>
+#include <exception>
 #include <functional>
 
 #include "gp_internal.h"
@@ -325,7 +326,11 @@ extern "C" gp_status gp_propagate_combine(const gp_plan* plan, const void* X, in
     }
     if (ax.type != hipMemoryTypeDevice || ao.type != hipMemoryTypeDevice)
         return fail(GP_ERR_UNSUPPORTED, "gp_propagate_combine takes device-resident operands only");
-    return propagate_combine(plan, X, ldx, d, dtype, agg, K, coeff, out, ldo, (hipStream_t)hip_stream);
+    try {
+        return propagate_combine(plan, X, ldx, d, dtype, agg, K, coeff, out, ldo, (hipStream_t)hip_stream);
+    } catch (const std::exception& e) {
+        return fail(GP_ERR_OOM_HOST, "gp_propagate_combine: %s", e.what());
+    }
 }
 
 extern "C" gp_status gp_propagate(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,
@@ -352,7 +357,11 @@ extern "C" gp_status gp_propagate(const gp_plan* plan, const void* X, int64_t ld
     }
     const bool xdev = ax.type == hipMemoryTypeDevice, odev = ao.type == hipMemoryTypeDevice;
     const bool xhost = ax.type == hipMemoryTypeHost, ohost = ao.type == hipMemoryTypeHost;
-    if (xdev && odev) return propagate_resident(plan, X, ldx, d, dtype, agg, K, out_stack, ldo, (hipStream_t)hip_stream);
-    if (xhost && ohost) return propagate_streamed(plan, X, ldx, d, dtype, agg, K, out_stack, ldo);
+    try {  // nothing may leave the C boundary as an exception
+        if (xdev && odev) return propagate_resident(plan, X, ldx, d, dtype, agg, K, out_stack, ldo, (hipStream_t)hip_stream);
+        if (xhost && ohost) return propagate_streamed(plan, X, ldx, d, dtype, agg, K, out_stack, ldo);
+    } catch (const std::exception& e) {
+        return fail(GP_ERR_OOM_HOST, "gp_propagate: %s", e.what());
+    }
     return fail(GP_ERR_INVALID_ARG, "X and out_stack must both be device memory or both be pinned host memory");
 }
