@@ -71,6 +71,9 @@ def main() -> int:
     import torch
     import gp_synth
     import paper_2207_12000_amd as gp
+    if not os.path.exists(gp.LIB_PATH):      # load what is built; build only if nothing is
+        from paper_2207_12000_amd import build as libbuild
+        libbuild.build()
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

@@ -10,6 +10,11 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # load what is built; build only if nothing is (hipcc cross-compiles without a GPU)
+    import paper_2207_12000_amd as gp
+    if not os.path.exists(gp.LIB_PATH):
+        from paper_2207_12000_amd import build as libbuild
+        libbuild.build()
 
 
 def has_gpu() -> bool:
