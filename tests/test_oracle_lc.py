@@ -1,0 +1,118 @@
+"""Pins of the LC-forward oracle (Appendix A, LC version of GPRGNN) against things
+other than itself: a hand-worked example, scalar brute force from the formula,
+the collapse to one matrix product when no ReLU is active, the ReLU that kills
+everything, the T = 1 identity-weight case that must equal the pinned polynomial
+filter of the hop oracle, and the symmetries of the formula."""
+import numpy as np
+
+import oracle
+from oracle import lc
+
+
+def test_hand_worked_example():
+    # two hops, one batch row each worked by hand:
+    #  hop 0 row [2, 1]:  [2, 1] W1 = [2.5, 0]   -> relu [2.5, 0] -> . [2, 3] = 5
+    #  hop 1 row [-1, 1]: [-1, 1] W1 = [-0.5, 3] -> relu [0, 3]   -> . [2, 3] = 9
+    #  H = 0.5 * 5 + 2 * 9 = 20.5
+    stack = np.array([[[2.0, 1.0]], [[-1.0, 1.0]]])
+    W1 = np.array([[1.0, -1.0], [0.5, 2.0]])
+    W2 = np.array([[2.0], [3.0]])
+    H = lc.lc_forward(stack, [0], [0.5, 2.0], [W1, W2])
+    assert H.shape == (1, 1) and H[0, 0] == 20.5
+
+
+def _brute(stack, ids, gamma, Ws):
+    out = []
+    for i in ids:
+        acc = [0.0] * Ws[-1].shape[1]
+        for k, g in enumerate(gamma):
+            z = [float(v) for v in stack[k][i]]
+            for t, W in enumerate(Ws):
+                nz = []
+                for c in range(W.shape[1]):
+                    s = 0.0
+                    for r in range(W.shape[0]):
+                        s += z[r] * float(W[r, c])
+                    if t < len(Ws) - 1 and s < 0.0:
+                        s = 0.0
+                    nz.append(s)
+                z = nz
+            for c in range(len(acc)):
+                acc[c] += g * z[c]
+        out.append(acc)
+    return np.array(out)
+
+
+def test_scalar_brute_force():
+    rng = np.random.default_rng(11)
+    for T in (1, 2, 3, 4):
+        dims = [5] + [6, 4, 7][:T - 1] + [3]
+        stack = rng.normal(size=(3, 9, 5))
+        Ws = [rng.normal(size=(dims[t], dims[t + 1])) for t in range(T)]
+        ids = [8, 0, 3, 3]
+        gamma = rng.normal(size=3)
+        got = lc.lc_forward(stack, ids, gamma, Ws)
+        assert np.allclose(got, _brute(stack, ids, gamma, Ws), rtol=1e-12, atol=1e-12)
+
+
+def test_no_active_relu_collapses_to_one_product():
+    rng = np.random.default_rng(12)
+    stack = rng.uniform(0, 1, size=(4, 20, 6))
+    Ws = [rng.uniform(0, 1, size=s) for s in ((6, 8), (8, 8), (8, 5))]
+    gamma = np.array([0.4, 0.3, 0.2, 0.1])
+    ids = np.arange(20)[::-1]
+    P = Ws[0] @ (Ws[1] @ Ws[2])                       # right-to-left association
+    want = np.tensordot(gamma, stack[:, ids, :], axes=1) @ P
+    assert np.allclose(lc.lc_forward(stack, ids, gamma, Ws), want, rtol=1e-12)
+
+
+def test_relu_kills_negative_first_layer():
+    rng = np.random.default_rng(13)
+    stack = rng.uniform(0, 1, size=(2, 5, 4))
+    Ws = [-rng.uniform(0.1, 1, size=(4, 6)), rng.normal(size=(6, 3))]
+    assert np.all(lc.lc_forward(stack, [0, 1, 2], [1.0, 1.0], Ws) == 0.0)
+    # without a hidden layer nothing is clipped
+    assert np.all(lc.lc_forward(stack, [0, 1, 2], [1.0, 1.0], Ws[:1]) < 0.0)
+
+
+def test_identity_weight_equals_polynomial_filter():
+    rng = np.random.default_rng(14)
+    n, d, K = 40, 6, 3
+    src = rng.integers(0, n, 150).astype(np.int32)
+    dst = rng.integers(0, n, 150).astype(np.int32)
+    plan = oracle.plan_blocks(src, dst, n, 60, oracle.SYMMETRISE | oracle.ADD_SELF_LOOPS)
+    X = rng.normal(size=(n, d))
+    stack = oracle.propagate(plan, X, oracle.AGG_SYM, K)
+    gamma = oracle.ppr_coefficients(0.15, K)
+    ids = rng.permutation(n)[:17]
+    H = lc.lc_forward(stack, ids, gamma, [np.eye(d)])
+    assert np.allclose(H, oracle.combine(plan, X, oracle.AGG_SYM, gamma)[0][ids], rtol=1e-12, atol=1e-14)
+
+
+def test_single_branch_is_the_gcn_form():
+    rng = np.random.default_rng(15)
+    stack = rng.normal(size=(3, 12, 4))
+    Ws = [rng.normal(size=(4, 5)), rng.normal(size=(5, 2))]
+    H = lc.lc_forward(stack, np.arange(12), [0.0, 0.0, 1.0], Ws)
+    assert np.allclose(H, np.maximum(stack[2] @ Ws[0], 0) @ Ws[1], rtol=1e-13)
+
+
+def test_symmetries():
+    rng = np.random.default_rng(16)
+    stack = rng.normal(size=(3, 30, 7))
+    Ws = [rng.normal(size=s) for s in ((7, 9), (9, 6), (6, 4))]
+    gamma = rng.normal(size=3)
+    ids = rng.integers(0, 30, 11)
+    H = lc.lc_forward(stack, ids, gamma, Ws)
+    # batch rows are independent: permuting the batch permutes the output rows
+    p = rng.permutation(11)
+    assert np.array_equal(lc.lc_forward(stack, ids[p], gamma, Ws), H[p])
+    # relabelling hidden units (columns of W_l, rows of W_{l+1}) changes nothing
+    q1, q2 = rng.permutation(9), rng.permutation(6)
+    Wp = [Ws[0][:, q1], Ws[1][q1][:, q2], Ws[2][q2]]
+    assert np.allclose(lc.lc_forward(stack, ids, gamma, Wp), H, rtol=1e-12, atol=1e-13)
+    # linear in gamma, positively homogeneous in each weight matrix
+    assert np.allclose(lc.lc_forward(stack, ids, 2 * gamma, Ws), 2 * H, rtol=1e-13)
+    assert np.allclose(lc.lc_forward(stack, ids, gamma, [3 * Ws[0], Ws[1], 0.5 * Ws[2]]), 1.5 * H, rtol=1e-12)
+    # the bound dominates
+    assert np.all(np.abs(H) <= lc.lc_bound(stack, ids, gamma, Ws) * (1 + 1e-12))
