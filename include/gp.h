@@ -166,6 +166,38 @@ gp_status gp_propagate_combine(const gp_plan *plan, const void *X, int64_t ldx, 
                                void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * gp_lc_forward -- forward pass of an LC-version model over a mini-batch of the
+ * hop stack (Appendix A, the LC version of GPRGNN:
+ *     H[i] = sum_{k=0..K} gamma[k] * MLP(X_k[batch[i]]),
+ *     MLP(Z) = relu(... relu(Z W_1) ... W_{T-1}) W_T,
+ *  the T weight matrices shared by all hops, no bias terms; with gamma = e_K it is
+ *  the single-branch H^LC of Section 3.1, the LC version of a GCN).  The softmax
+ *  the paper puts on top is left to the consumer.
+ *
+ *  stack   DEVICE, K+1 slabs of n x d as gp_propagate writes them: slab k starts at
+ *          element k*n*ld, rows ld elements apart (ld >= d), of `dtype` (bf16 is
+ *          widened exactly; all arithmetic is fp32 on the matrix cores).
+ *  batch   DEVICE, B row numbers; NULL means rows 0 .. B-1 (then B <= n).  A row
+ *          number outside [0, n) is not an error: that output row is computed
+ *          from a row of zeros.
+ *  gamma   HOST, K+1 floats, read during the call.  0 <= K <= 15.
+ *  T       layers, 1 .. 8.  W: HOST array of T DEVICE pointers; W[t] is dense
+ *          row-major in_t x width[t], in_0 = d, in_t = width[t-1].  width: HOST,
+ *          T ints, each 1 .. 256 (others: GP_ERR_UNSUPPORTED).
+ *  out     DEVICE, B x width[T-1] fp32, rows ldo floats apart; must not overlap
+ *          the inputs.
+ *
+ * Enqueued on hip_stream; deterministic.  With K >= 1 the per-hop results pass
+ * through a library-owned buffer per device (at most 256 MiB, grown on demand),
+ * so calls on one device must not overlap in time.
+ * Errors: INVALID_ARG, UNSUPPORTED, OOM_DEVICE, DEVICE.
+ */
+gp_status gp_lc_forward(const void *stack, int64_t ld, gp_dtype dtype, int64_t n, int32_t d, int32_t K,
+                        const int32_t *batch, int64_t B, const float *gamma, int32_t T,
+                        const float *const *W, const int32_t *width, float *out, int64_t ldo,
+                        void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * Optimal graph decomposition (Section 3.2, Eq. 11 and Eq. 12): block counts
  * from byte volumes, the available GPU volume and the environment's coefficients
  * (all in the same unit, e.g. bytes or GB; coefficients are measured by watching

@@ -48,6 +48,8 @@ _SIGNATURES = {
                                 _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_propagate_combine": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                         _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
+    "gp_lc_forward": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int, _c.c_int64, _c.c_int32, _c.c_int32, _c.c_void_p, _c.c_int64,
+                                 _c.c_void_p, _c.c_int32, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_solve_normalisation_blocks": (_c.c_int, [_c.c_double] * 7 + [_c.POINTER(_c.c_int64)]),
     "gp_solve_aggregation_blocks": (_c.c_int, [_c.c_double] * 5 + [_c.c_int64, _c.POINTER(_c.c_int64),
                                                                   _c.POINTER(_c.c_int64)]),
@@ -245,6 +247,52 @@ def propagate_tensors(plan: Plan, X, agg: int, K: int, out=None, stream=None):
     if stream is None and X.is_cuda:
         stream = torch.cuda.current_stream(X.device).cuda_stream
     gp_propagate(plan, X.data_ptr(), X.stride(0), d, dtype, agg, K, out.data_ptr(), d, stream)
+    return out
+
+
+def gp_lc_forward(stack_ptr: int, ld: int, dtype: int, n: int, d: int, K: int, batch_ptr: Optional[int], B: int, gamma,
+                  weight_ptrs, widths, out_ptr: int, ldo: int, stream: Optional[int] = None):
+    """Raw-pointer form.  gamma: K+1 host floats; weight_ptrs: T device addresses;
+    widths: T output widths; batch_ptr: device address of B int32 row numbers or None."""
+    g = np.ascontiguousarray(gamma, dtype=np.float32)
+    if g.shape != (K + 1,):
+        raise ValueError("gamma must hold K+1 values")
+    T = len(weight_ptrs)
+    if len(widths) != T:
+        raise ValueError("one width per weight matrix")
+    W = (ctypes.c_void_p * max(T, 1))(*[int(p) for p in weight_ptrs])
+    wd = np.ascontiguousarray(widths, dtype=np.int32)
+    st = lib().gp_lc_forward(stack_ptr, ld, dtype, n, d, K, batch_ptr or None, B, g.ctypes.data, T,
+                             ctypes.cast(W, ctypes.c_void_p), wd.ctypes.data, out_ptr, ldo, stream or None)
+    _check(st, "gp_lc_forward")
+
+
+def lc_forward_tensors(stack, batch, gamma, weights, out=None, stream=None):
+    """Convenience for torch tensors (memory and streams only): stack is the
+    contiguous (K+1, n, d) float32 / bfloat16 GPU tensor gp_propagate filled, batch an
+    int32 GPU tensor of row numbers (or None for all rows), weights a list of
+    contiguous float32 GPU matrices.  Returns the (B, width_T) float32 result."""
+    import torch
+    if stack.dim() != 3 or not stack.is_contiguous():
+        raise ValueError("stack must be a contiguous (K+1, n, d) tensor")
+    K1, n, d = stack.shape
+    dtype = {torch.float32: GP_F32, torch.bfloat16: GP_BF16}[stack.dtype]
+    if batch is not None and (batch.dtype != torch.int32 or batch.dim() != 1 or not batch.is_contiguous()):
+        raise ValueError("batch must be a contiguous int32 vector")
+    B = n if batch is None else batch.numel()
+    inner = d
+    for W in weights:
+        if W.dtype != torch.float32 or W.dim() != 2 or not W.is_contiguous() or W.shape[0] != inner:
+            raise ValueError("weights must be contiguous float32 matrices whose shapes chain from d")
+        inner = W.shape[1]
+    if out is None:
+        out = torch.empty((B, inner), dtype=torch.float32, device=stack.device)
+    if out.shape != (B, inner) or out.dtype != torch.float32 or out.stride(1) != 1:
+        raise ValueError("out must be a (B, width_T) float32 tensor with unit column stride")
+    if stream is None:
+        stream = torch.cuda.current_stream(stack.device).cuda_stream
+    gp_lc_forward(stack.data_ptr(), d, dtype, n, d, K1 - 1, None if batch is None else batch.data_ptr(), B, gamma,
+                  [W.data_ptr() for W in weights], [W.shape[1] for W in weights], out.data_ptr(), out.stride(0), stream)
     return out
 
 

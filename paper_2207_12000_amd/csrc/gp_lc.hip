@@ -1,0 +1,384 @@
+// Forward pass of an LC-version model over the hop stack (Appendix A: the LC version
+// of GPRGNN; Section 3.1: the H^LC formula for the single-branch case):
+//
+//     H[batch] = sum_k gamma_k * MLP(X_k[batch]),   MLP(Z) = relu(..relu(Z W_1)..W_{T-1}) W_T.
+//
+// This is the one dense contraction on the path, so it runs on the matrix cores:
+// fp32 MFMA (v_mfma_f32_32x32x2_f32), all layers of one hop fused in one kernel.
+// A workgroup of four waves owns 64 batch rows.  The rows' features (later: the
+// previous layer's activations) sit in LDS as the A operand; the weights are the B
+// operand, read straight from L2 (all T matrices together are a few hundred KB and
+// stay there) one 8-row chunk ahead of the MFMAs that use them; the layer output
+// stays in accumulator registers until every wave is done with the LDS tile, then
+// replaces it (ReLU applied on the way).  Nothing but the gathered rows and the
+// final B x C result touches HBM.
+//
+// Index freedom used: MFMA sums over k and yields 32 columns per tile, but which k
+// and which column a lane supplies is the kernel's choice as long as A and B agree.
+// Lane half hh of a wave takes k = 8c + 4hh + s for step s of chunk c (one 16-byte
+// LDS read feeds four MFMA steps), and column j of a wave's tile t is output column
+// base + NT*j + t, so the NT tiles of a wave need NT consecutive weights per lane
+// (one vector load) and produce NT consecutive activations per lane (one vector
+// LDS store).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <mutex>
+
+#include "gp_internal.h"
+
+namespace gp {
+
+namespace {
+
+constexpr int kLcThreads = 256;
+constexpr int kTM = 64;          // batch rows per workgroup
+constexpr int kPanel = 256;      // widest inner dimension staged in LDS at once
+constexpr int kLd = kPanel + 4;  // LDS row stride in floats (16-byte aligned rows, banks staggered)
+constexpr int kMaxLayers = 8;
+constexpr int kMaxHops = 16;
+constexpr size_t kLdsBytes = (size_t)kTM * kLd * sizeof(float);
+constexpr int64_t kWorkspaceBytes = INT64_C(256) << 20;  // cap on the partial results of one piece
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef unsigned short v4u16 __attribute__((ext_vector_type(4)));
+
+struct LcArgs {
+    const void* stack;
+    int64_t ld, slab;  // elements: row stride, distance between hop slabs
+    int64_t n;
+    int d, hops;  // hops = K + 1
+    const int32_t* batch;
+    int64_t B;
+    float gamma[kMaxHops];
+    int T;
+    const float* W[kMaxLayers];
+    int width[kMaxLayers];
+    int wvec[kMaxLayers];  // 1: W_t rows may be read with NT-wide vector loads
+    int xvec;              // 1: stack rows may be read four elements at a time
+    float* dst;            // the result when hops = 1, else the partial results [hop][B][ldd]
+    int64_t ldd;
+};
+
+__device__ __forceinline__ float widen(float v) { return v; }
+__device__ __forceinline__ float widen(unsigned short v) { return __uint_as_float((unsigned)v << 16); }
+
+__device__ __forceinline__ v4f load4(const float* p) { return *reinterpret_cast<const v4f*>(p); }
+__device__ __forceinline__ v4f load4(const unsigned short* p)
+{
+    const v4u16 b = *reinterpret_cast<const v4u16*>(p);
+    v4f r;
+    r.x = widen(b.x), r.y = widen(b.y), r.z = widen(b.z), r.w = widen(b.w);
+    return r;
+}
+
+// 64 x kin panel of the batch rows of one slab -> LDS, widened to fp32, zero beyond
+// kin (up to the next multiple of 8), zero for rows past the batch or ids outside
+// [0, n) (those rows are never stored).
+template <typename T>
+__device__ __forceinline__ void lc_gather(float* __restrict__ tile, const T* __restrict__ slab, const LcArgs& a,
+                                          int64_t row0, int p0, int kin, int tid)
+{
+    const int nq = ((kin + 7) & ~7) >> 2;  // groups of four columns per row
+    for (int idx = tid; idx < kTM * nq; idx += kLcThreads) {
+        const int r = idx / nq, q = idx - r * nq;
+        const int64_t br = row0 + r;
+        int64_t id = -1;
+        if (br < a.B) id = a.batch ? (int64_t)a.batch[br] : br;
+        v4f v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (id >= 0 && id < a.n) {
+            const T* src = slab + id * a.ld + p0 + 4 * q;
+            if (a.xvec && 4 * q + 4 <= kin) {
+                v = load4(src);
+            } else {
+                if (4 * q + 0 < kin) v.x = widen(src[0]);
+                if (4 * q + 1 < kin) v.y = widen(src[1]);
+                if (4 * q + 2 < kin) v.z = widen(src[2]);
+                if (4 * q + 3 < kin) v.w = widen(src[3]);
+            }
+        }
+        *reinterpret_cast<v4f*>(tile + r * kLd + 4 * q) = v;
+    }
+}
+
+// weights of one 8-row chunk for this lane: rows krow .. krow+3, NT columns from colb
+template <int NT>
+__device__ __forceinline__ void lc_load_b(const float* __restrict__ W, int N, int kin, int krow, int colb, bool vec,
+                                          float (&b)[4][NT])
+{
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const bool rok = krow + s < kin;
+        const float* p = W + (int64_t)(krow + s) * N + colb;
+        if constexpr (NT == 4) {
+            if (vec) {
+                v4f v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (rok && colb < N) v = *reinterpret_cast<const v4f*>(p);
+                b[s][0] = v.x, b[s][1] = v.y, b[s][2] = v.z, b[s][3] = v.w;
+                continue;
+            }
+        }
+        if constexpr (NT == 2) {
+            if (vec) {
+                v2f v = {0.0f, 0.0f};
+                if (rok && colb < N) v = *reinterpret_cast<const v2f*>(p);
+                b[s][0] = v.x, b[s][1] = v.y;
+                continue;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) b[s][t] = (rok && colb + t < N) ? p[t] : 0.0f;
+    }
+}
+
+// acc[0..NT) += tile(64 x kin) * W(kin x N) for this wave's 32 rows and 32*NT columns
+template <int NT>
+__device__ __forceinline__ void lc_layer(const float* __restrict__ tile, int kin, const float* __restrict__ W, int N,
+                                         bool vec, int rb, int ch, int j, int hh, v16f (&acc)[4])
+{
+    const int colb = ch * 32 * NT + NT * j;
+    const float* arow = tile + (rb * 32 + j) * kLd + 4 * hh;
+    const int chunks = (kin + 7) >> 3;
+    float bc[4][NT], bn[4][NT];
+    lc_load_b<NT>(W, N, kin, 4 * hh, colb, vec, bc);
+    for (int c = 0; c < chunks; ++c) {
+        if (c + 1 < chunks) lc_load_b<NT>(W, N, kin, (c + 1) * 8 + 4 * hh, colb, vec, bn);
+        const v4f av = *reinterpret_cast<const v4f*>(arow + c * 8);
+        const float as[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[s], bc[s][t], acc[t], 0, 0, 0);
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) bc[s][t] = bn[s][t];
+    }
+}
+
+__device__ __forceinline__ void lc_layer_nt(int NT, const float* tile, int kin, const float* W, int N, bool vec, int rb,
+                                            int ch, int j, int hh, v16f (&acc)[4])
+{
+    switch (NT) {
+    case 1: lc_layer<1>(tile, kin, W, N, vec, rb, ch, j, hh, acc); break;
+    case 2: lc_layer<2>(tile, kin, W, N, vec, rb, ch, j, hh, acc); break;
+    case 3: lc_layer<3>(tile, kin, W, N, vec, rb, ch, j, hh, acc); break;
+    default: lc_layer<4>(tile, kin, W, N, vec, rb, ch, j, hh, acc); break;
+    }
+}
+
+// accumulator element r of a 32x32 tile sits in row 8*(r/4) + 4*(lane/32) + r%4
+__device__ __forceinline__ int acc_row(int r, int hh) { return 8 * (r >> 2) + 4 * hh + (r & 3); }
+
+// tile <- relu(acc) for the 64*NT columns the four waves hold; acc <- 0
+template <int NT>
+__device__ __forceinline__ void lc_store_relu(float* __restrict__ tile, int rb, int ch, int j, int hh, v16f (&acc)[4])
+{
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float* p = tile + (rb * 32 + acc_row(r, hh)) * kLd + ch * 32 * NT + NT * j;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const float x = acc[t][r];
+            p[t] = x < 0.0f ? 0.0f : x;  // NaN stays NaN
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = (v16f)(0.0f);
+}
+
+__device__ __forceinline__ void lc_store_relu_nt(int NT, float* tile, int rb, int ch, int j, int hh, v16f (&acc)[4])
+{
+    switch (NT) {
+    case 1: lc_store_relu<1>(tile, rb, ch, j, hh, acc); break;
+    case 2: lc_store_relu<2>(tile, rb, ch, j, hh, acc); break;
+    case 3: lc_store_relu<3>(tile, rb, ch, j, hh, acc); break;
+    default: lc_store_relu<4>(tile, rb, ch, j, hh, acc); break;
+    }
+}
+
+// One workgroup: 64 batch rows of one hop k; writes gamma_k * MLP(X_k[rows]) to slab k
+// of the partial results.
+template <typename T>
+__global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
+{
+    extern __shared__ __align__(16) float tile[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = lane & 31, hh = lane >> 5;
+    const int rb = wave & 1, ch = wave >> 1;
+    const int k = (int)(blockIdx.x % (unsigned)a.hops);
+    const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)a.hops) * kTM;
+    const int C = a.width[a.T - 1];
+    const int NTL = (C + 63) >> 6;
+
+    v16f acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = (v16f)(0.0f);
+
+    const T* slab = static_cast<const T*>(a.stack) + (int64_t)k * a.slab;
+    const int N1 = a.width[0];
+    const int NT1 = (N1 + 63) >> 6;
+    for (int p0 = 0; p0 < a.d; p0 += kPanel) {  // first layer, one panel of feature columns at a time
+        const int kin = min(kPanel, a.d - p0);
+        __syncthreads();
+        lc_gather<T>(tile, slab, a, row0, p0, kin, tid);
+        __syncthreads();
+        lc_layer_nt(NT1, tile, kin, a.W[0] + (int64_t)p0 * N1, N1, a.wvec[0] != 0, rb, ch, j, hh, acc);
+    }
+    for (int t = 1; t < a.T; ++t) {
+        const int Np = a.width[t - 1], N = a.width[t];
+        __syncthreads();  // every wave is done reading the tile
+        lc_store_relu_nt((Np + 63) >> 6, tile, rb, ch, j, hh, acc);
+        __syncthreads();
+        lc_layer_nt((N + 63) >> 6, tile, Np, a.W[t], N, a.wvec[t] != 0, rb, ch, j, hh, acc);
+    }
+
+    const float g = a.gamma[k];
+    float* dst = a.dst + (int64_t)k * a.B * a.ldd;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        if (t >= NTL) break;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int64_t br = row0 + rb * 32 + acc_row(r, hh);
+            const int col = ch * 32 * NTL + NTL * j + t;
+            if (br < a.B && col < C) dst[br * a.ldd + col] = g * acc[t][r];
+        }
+    }
+}
+
+// out[i][c] = sum over items, in item order, of the partial results
+__global__ __launch_bounds__(kLcThreads) void gp_lc_reduce(const float* __restrict__ part, int items, int64_t B, int C,
+                                                           float* __restrict__ out, int64_t ldo)
+{
+    const int64_t total = B * C;
+    for (int64_t i = (int64_t)blockIdx.x * kLcThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kLcThreads) {
+        float s = 0.0f;
+        for (int it = 0; it < items; ++it) s += part[(int64_t)it * total + i];
+        out[(i / C) * ldo + i % C] = s;
+    }
+}
+
+// partial results of the split schedule: one grow-only buffer per device
+struct Workspace {
+    float* p = nullptr;
+    size_t bytes = 0;
+};
+std::mutex g_ws_mu;
+Workspace g_ws[64];
+
+gp_status workspace(size_t bytes, float** out)
+{
+    int dev = 0;
+    GP_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return fail(GP_ERR_UNSUPPORTED, "device ordinal %d not supported", dev);
+    std::lock_guard<std::mutex> lk(g_ws_mu);
+    Workspace& w = g_ws[dev];
+    if (w.bytes < bytes) {
+        if (w.p) GP_HIP(hipFree(w.p));  // waits for the device: no earlier launch still uses it
+        w.p = nullptr, w.bytes = 0;
+        GP_HIP(hipMalloc((void**)&w.p, bytes));
+        w.bytes = bytes;
+    }
+    *out = w.p;
+    return GP_OK;
+}
+
+template <typename T>
+gp_status launch_mlp(const LcArgs& a, unsigned grid, hipStream_t stream)
+{
+    static std::once_flag once;
+    static hipError_t attr = hipSuccess;
+    std::call_once(once, [] {
+        attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&gp_lc_mlp<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)kLdsBytes);
+    });
+    GP_HIP(attr);
+    profile_begin("gp_lc_mlp", stream);
+    hipLaunchKernelGGL(gp_lc_mlp<T>, dim3(grid), dim3(kLcThreads), kLdsBytes, stream, a);
+    profile_end(stream);
+    GP_HIP(hipGetLastError());
+    return GP_OK;
+}
+
+}  // namespace
+
+gp_status lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, int32_t d, int32_t K, const int32_t* batch,
+                     int64_t B, const float* gamma, int32_t T, const float* const* W, const int32_t* width, float* out,
+                     int64_t ldo, hipStream_t stream)
+{
+    if (!stack || !gamma || !W || !width || !out) return fail(GP_ERR_INVALID_ARG, "NULL argument");
+    if (dtype != GP_F32 && dtype != GP_BF16) return fail(GP_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    if (n < 1 || d < 1 || ld < d) return fail(GP_ERR_INVALID_ARG, "need n >= 1, d >= 1, ld >= d");
+    if (K < 0 || K + 1 > kMaxHops) return fail(GP_ERR_UNSUPPORTED, "K = %d: 0 .. %d hops supported", K, kMaxHops - 1);
+    if (T < 1 || T > kMaxLayers) return fail(GP_ERR_UNSUPPORTED, "T = %d: 1 .. %d layers supported", T, kMaxLayers);
+    if (B < 0 || (!batch && B > n)) return fail(GP_ERR_INVALID_ARG, "B = %lld out of range", (long long)B);
+    for (int t = 0; t < T; ++t) {
+        if (!W[t]) return fail(GP_ERR_INVALID_ARG, "W[%d] is NULL", t);
+        if (width[t] < 1 || width[t] > kPanel)
+            return fail(GP_ERR_UNSUPPORTED, "layer %d is %d wide: 1 .. %d supported", t + 1, width[t], kPanel);
+    }
+    const int C = width[T - 1];
+    if (ldo < C) return fail(GP_ERR_INVALID_ARG, "ldo < output width");
+    if (B == 0) return GP_OK;
+
+    LcArgs a{};
+    a.stack = stack, a.ld = ld, a.slab = n * ld, a.n = n, a.d = d, a.hops = K + 1;
+    a.batch = batch, a.B = B, a.T = T;
+    for (int k = 0; k <= K; ++k) a.gamma[k] = gamma[k];
+    for (int t = 0; t < T; ++t) {
+        a.W[t] = W[t], a.width[t] = width[t];
+        const int nt = (width[t] + 63) / 64;
+        a.wvec[t] = (nt == 2 || nt == 4) && width[t] % nt == 0 && (uintptr_t)W[t] % (4 * nt) == 0;
+    }
+    const size_t esz = dtype == GP_F32 ? 4 : 2;
+    a.xvec = ld % 4 == 0 && (uintptr_t)stack % (4 * esz) == 0;
+
+    // One workgroup per (64-row tile, hop), so that a mini-batch of a few thousand rows
+    // still fills the chip; the hops' results are then summed in hop order.  Large
+    // batches go through in pieces that keep the partial results within a fixed size.
+    const int64_t piece = a.hops == 1 ? B : std::max<int64_t>(kTM, kWorkspaceBytes / ((int64_t)a.hops * C * 4) / kTM * kTM);
+    float* part = nullptr;
+    if (a.hops > 1) {
+        gp_status st = workspace((size_t)a.hops * std::min(piece, B) * C * sizeof(float), &part);
+        if (st != GP_OK) return st;
+    }
+    for (int64_t b0 = 0; b0 < B; b0 += piece) {
+        LcArgs p = a;
+        p.B = std::min(piece, B - b0);
+        p.batch = batch ? batch + b0 : nullptr;
+        if (!batch) p.stack = static_cast<const char*>(stack) + (size_t)b0 * ld * esz, p.n = n - b0;
+        if (a.hops > 1)
+            p.dst = part, p.ldd = C;
+        else
+            p.dst = out + b0 * ldo, p.ldd = ldo;
+        const int64_t grid = (p.B + kTM - 1) / kTM * a.hops;
+        if (grid > 0x7fffffffLL) return fail(GP_ERR_UNSUPPORTED, "batch too large for one launch");
+        gp_status st = dtype == GP_F32 ? launch_mlp<float>(p, (unsigned)grid, stream)
+                                       : launch_mlp<unsigned short>(p, (unsigned)grid, stream);
+        if (st != GP_OK) return st;
+        if (a.hops > 1) {
+            const unsigned rgrid = (unsigned)std::min<int64_t>((p.B * C + kLcThreads - 1) / kLcThreads, 256 * 8);
+            profile_begin("gp_lc_reduce", stream);
+            hipLaunchKernelGGL(gp_lc_reduce, dim3(rgrid), dim3(kLcThreads), 0, stream, part, a.hops, p.B, C, out + b0 * ldo, ldo);
+            profile_end(stream);
+            GP_HIP(hipGetLastError());
+        }
+    }
+    return GP_OK;
+}
+
+}  // namespace gp
+
+extern "C" gp_status gp_lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, int32_t d, int32_t K,
+                                   const int32_t* batch, int64_t B, const float* gamma, int32_t T, const float* const* W,
+                                   const int32_t* width, float* out, int64_t ldo, void* hip_stream)
+{
+    try {
+        return gp::lc_forward(stack, ld, dtype, n, d, K, batch, B, gamma, T, W, width, out, ldo, (hipStream_t)hip_stream);
+    } catch (const std::exception& e) {
+        return gp::fail(GP_ERR_OOM_HOST, "gp_lc_forward: %s", e.what());
+    }
+}

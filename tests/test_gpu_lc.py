@@ -1,0 +1,171 @@
+"""GPU parity of gp_lc_forward (Appendix A, LC version of GPRGNN) against the fp64
+oracle, element by element.
+
+Tolerance.  Every layer is an fp32 dot product of length in_l accumulated in some
+order, so its error is at most gamma_{in_l} = in_l * u (u = 2^-24, first order)
+times sum |a||w|; later layers pass that on through |W| (ReLU is 1-Lipschitz) and
+add their own.  With the scaling by gamma_k and the K+1-term sum the total is at most
+(sum_l in_l + T + K + 2) * u * bound, bound = sum_k |gamma_k| |X_k| |W_1| ... |W_T|;
+the tests allow 1.5 times that for the higher-order terms.
+"""
+import numpy as np
+import pytest
+
+import gp_synth
+import oracle
+from oracle import lc
+import paper_2207_12000_amd as gp
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu(gpu_or_skip):
+    yield
+
+
+def tolerance(d, widths, K):
+    return 1.5 * (d + sum(widths[:-1]) + len(widths) + K + 2) * 2.0 ** -24
+
+
+def make_weights(rng, d, widths):
+    dims = [d] + list(widths)
+    return [(rng.normal(size=(dims[t], dims[t + 1])) / np.sqrt(dims[t])).astype(np.float32) for t in range(len(widths))]
+
+
+def run(stack_np, ids, gamma, Ws, bf16=False, ldo_pad=0):
+    """stack_np: float32 (or uint16 bf16 bits) array (K+1, n, d).  Returns the GPU result."""
+    import torch
+    if bf16:
+        stack = torch.from_numpy(stack_np.view(np.int16)).view(torch.bfloat16).cuda()
+    else:
+        stack = torch.from_numpy(stack_np).cuda()
+    batch = None if ids is None else torch.from_numpy(np.asarray(ids, dtype=np.int32)).cuda()
+    Wd = [torch.from_numpy(W).cuda() for W in Ws]
+    B = stack.shape[1] if ids is None else len(ids)
+    C = Ws[-1].shape[1]
+    buf = torch.full((B, C + ldo_pad), -7.0, device="cuda")
+    out = gp.lc_forward_tensors(stack, batch, gamma, Wd, out=buf[:, :C])
+    torch.cuda.synchronize()
+    if ldo_pad:
+        assert torch.all(buf[:, C:] == -7.0)              # nothing written past the row
+    return out.cpu().numpy().astype(np.float64)
+
+
+def check(stack_np, ids, gamma, Ws, bf16=False, **kw):
+    got = run(stack_np, ids, gamma, Ws, bf16=bf16, **kw)
+    wide = gp_synth.bf16_bits_to_f32(stack_np) if bf16 else stack_np
+    rows = np.arange(wide.shape[1]) if ids is None else ids
+    want = lc.lc_forward(wide, rows, gamma, Ws)
+    bound = lc.lc_bound(wide, rows, gamma, Ws)
+    tol = tolerance(wide.shape[2], [W.shape[1] for W in Ws], len(gamma) - 1)
+    err = np.abs(got - want)
+    assert got.shape == want.shape
+    assert np.all(err <= tol * bound + 1e-30), f"worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {tol:.3g})"
+    return got
+
+
+CASES = [
+    # d, widths, K, n, B
+    (128, [256, 256, 256, 40], 3, 3000, 209),     # the paper's shape: hidden 256, four layers, 40 classes
+    (100, [256, 41], 3, 2000, 4096),              # d not a multiple of 8, duplicates in the batch
+    (602, [256, 256, 41], 2, 700, 130),           # three feature panels
+    (7, [5], 2, 50, 33),                          # one layer: a linear model on the filtered features
+    (64, [192, 172], 5, 500, 64),                 # three tiles per wave
+    (33, [37, 130, 3], 1, 300, 1),                # odd widths: scalar weight loads, a single row
+    (16, [64] * 7 + [10], 0, 200, 77),            # K = 0, eight layers
+    (256, [128, 128], 4, 400, 191),
+]
+
+
+@pytest.mark.parametrize("d,widths,K,n,B", CASES)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_parity(d, widths, K, n, B, bf16):
+    rng = np.random.default_rng(1000 + d + B)
+    stack = rng.normal(size=(K + 1, n, d)).astype(np.float32)
+    if bf16:
+        stack = gp_synth.f32_to_bf16_bits(stack)
+    ids = rng.integers(0, n, B)
+    gamma = rng.normal(size=K + 1)
+    check(stack, ids, gamma, make_weights(rng, d, widths), bf16=bf16, ldo_pad=3 if B < 100 else 0)
+
+
+def test_all_rows_and_determinism():
+    rng = np.random.default_rng(7)
+    stack = rng.normal(size=(3, 1000, 48)).astype(np.float32)
+    Ws = make_weights(rng, 48, [96, 12])
+    a = check(stack, None, [0.5, 0.3, 0.2], Ws)
+    b = run(stack, None, [0.5, 0.3, 0.2], Ws)
+    assert np.array_equal(a, b)
+
+
+def test_rows_outside_the_graph_give_zero_rows():
+    rng = np.random.default_rng(8)
+    stack = rng.normal(size=(2, 100, 20)).astype(np.float32)
+    Ws = make_weights(rng, 20, [32, 6])
+    ids = np.array([5, -1, 100, 99, 2 ** 31 - 1, 0], dtype=np.int64)
+    got = run(stack, ids, [1.0, 1.0], Ws)
+    assert np.all(got[[1, 2, 4]] == 0.0)
+    want = lc.lc_forward(stack, ids[[0, 3, 5]], [1.0, 1.0], Ws)
+    assert np.allclose(got[[0, 3, 5]], want, rtol=1e-4, atol=1e-5)
+
+
+def test_unaligned_operands():
+    """A stack whose rows are not 16-byte aligned (ld = d + 1, base off by one
+    element) takes the element-wise gather."""
+    import torch
+    rng = np.random.default_rng(9)
+    K, n, d, ld = 2, 150, 30, 31
+    flat = torch.zeros((K + 1) * n * ld + 1, device="cuda")
+    stack_np = rng.normal(size=(K + 1, n, d)).astype(np.float32)
+    view = flat[1:].view(K + 1, n, ld)
+    view[:, :, :d] = torch.from_numpy(stack_np).cuda()
+    Ws = make_weights(rng, d, [64, 8])
+    Wd = [torch.from_numpy(W).cuda() for W in Ws]
+    ids = rng.integers(0, n, 70)
+    batch = torch.from_numpy(ids.astype(np.int32)).cuda()
+    out = torch.empty((70, 8), device="cuda")
+    gamma = [0.2, 0.5, 0.3]
+    gp.gp_lc_forward(view.data_ptr(), ld, gp.GP_F32, n, d, K, batch.data_ptr(), 70, gamma,
+                     [W.data_ptr() for W in Wd], [64, 8], out.data_ptr(), 8, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = lc.lc_forward(stack_np, ids, gamma, Ws)
+    bound = lc.lc_bound(stack_np, ids, gamma, Ws)
+    assert np.all(np.abs(out.cpu().numpy() - want) <= tolerance(d, [64, 8], K) * bound + 1e-30)
+
+
+def test_large_batch_goes_through_in_pieces():
+    """16 hops x 256 output columns: the per-hop results of 40,000 rows exceed the
+    library's buffer, so the batch is processed in several pieces."""
+    rng = np.random.default_rng(10)
+    K, n, d = 15, 3000, 16
+    stack = rng.normal(size=(K + 1, n, d)).astype(np.float32)
+    Ws = make_weights(rng, d, [256])
+    ids = rng.integers(0, n, 40000)
+    check(stack, ids, rng.normal(size=K + 1), Ws)
+
+
+def test_on_the_propagated_stack_of_config_2():
+    """The consumer on the real thing: config 2's hop stack as gp_propagate leaves it
+    in HBM, one mini-batch of 4096 rows (the paper's batch size) and all rows, with
+    the paper's model shape (hidden 256, four layers, 40 classes) and PPR-initialised
+    gamma.  The oracle runs on the GPU's own stored stack."""
+    import torch
+    w = gp_synth.make_workload(2)
+    rng = np.random.default_rng(2)
+    Ws = make_weights(rng, w.d, [256, 256, 256, 40])
+    gamma = oracle.ppr_coefficients(0.1, w.K)
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) as lp:
+        stack = gp.propagate_tensors(lp, torch.from_numpy(w.X).cuda(), w.agg, w.K)
+    Wd = [torch.from_numpy(W).cuda() for W in Ws]
+    stack_np = stack.cpu().numpy()
+    tol = tolerance(w.d, [256, 256, 256, 40], w.K)
+    for ids in (rng.permutation(w.n)[:4096], None):
+        batch = None if ids is None else torch.from_numpy(ids.astype(np.int32)).cuda()
+        out = gp.lc_forward_tensors(stack, batch, gamma, Wd)
+        torch.cuda.synchronize()
+        rows = np.arange(w.n) if ids is None else ids
+        want = lc.lc_forward(stack_np, rows, gamma, Ws)
+        bound = lc.lc_bound(stack_np, rows, gamma, Ws)
+        err = np.abs(out.cpu().numpy() - want)
+        assert np.all(err <= tol * bound + 1e-30), f"worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {tol:.3g})"
