@@ -103,69 +103,113 @@ __device__ __forceinline__ void lc_gather(float* __restrict__ tile, const T* __r
     }
 }
 
-// weights of one 8-row chunk for this lane: rows krow .. krow+3, NT columns from colb
-template <int NT>
-__device__ __forceinline__ void lc_load_b(const float* __restrict__ W, int N, int kin, int krow, int colb, bool vec,
+// Weights of one full 8-row chunk for this lane: rows 4hh .. 4hh+3 of the chunk that
+// starts at Wc (= W + 8c*N, the same for the whole wave), NT columns.  Loads are
+// never predicated (a predicated load costs a branch): a lane whose columns lie
+// beyond N reads column 0 instead (coff is clamped) and its products are discarded
+// when the layer's output is stored.  roff = 4hh*N; vectors use coff[0] only.
+template <int NT, bool VEC>
+__device__ __forceinline__ void lc_load_b(const float* __restrict__ Wc, int N, int roff, const int (&coff)[NT],
                                           float (&b)[4][NT])
 {
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-        const bool rok = krow + s < kin;
-        const float* p = W + (int64_t)(krow + s) * N + colb;
-        if constexpr (NT == 4) {
-            if (vec) {
-                v4f v = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (rok && colb < N) v = *reinterpret_cast<const v4f*>(p);
-                b[s][0] = v.x, b[s][1] = v.y, b[s][2] = v.z, b[s][3] = v.w;
-                continue;
-            }
-        }
-        if constexpr (NT == 2) {
-            if (vec) {
-                v2f v = {0.0f, 0.0f};
-                if (rok && colb < N) v = *reinterpret_cast<const v2f*>(p);
-                b[s][0] = v.x, b[s][1] = v.y;
-                continue;
-            }
-        }
+        const float* p = Wc + s * N;
+        if constexpr (NT == 4 && VEC) {
+            const v4f v = *reinterpret_cast<const v4f*>(&p[roff + coff[0]]);
+            b[s][0] = v.x, b[s][1] = v.y, b[s][2] = v.z, b[s][3] = v.w;
+        } else if constexpr (NT == 2 && VEC) {
+            const v2f v = *reinterpret_cast<const v2f*>(&p[roff + coff[0]]);
+            b[s][0] = v.x, b[s][1] = v.y;
+        } else {
 #pragma unroll
-        for (int t = 0; t < NT; ++t) b[s][t] = (rok && colb + t < N) ? p[t] : 0.0f;
+            for (int t = 0; t < NT; ++t) b[s][t] = p[roff + coff[t]];
+        }
     }
 }
 
-// acc[0..NT) += tile(64 x kin) * W(kin x N) for this wave's 32 rows and 32*NT columns
+// The last, partial chunk (rows_left < 8 rows): a row beyond the matrix is read as
+// row 0 of the chunk and replaced by zero.
 template <int NT>
+__device__ __forceinline__ void lc_load_b_tail(const float* __restrict__ Wc, int N, int rows_left, int hh,
+                                               const int (&coff)[NT], float (&b)[4][NT])
+{
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int r = 4 * hh + s;
+        const bool ok = r < rows_left;
+        const int roff = ok ? r * N : 0;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const float v = Wc[roff + coff[t]];
+            b[s][t] = ok ? v : 0.0f;
+        }
+    }
+}
+
+// the 4 * NT MFMAs of one chunk: step s multiplies k = 8c + 4hh + s
+template <int NT>
+__device__ __forceinline__ void lc_mfma_chunk(const v4f av, const float (&b)[4][NT], v16f (&acc)[4])
+{
+    const float as[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[s], b[s][t], acc[t], 0, 0, 0);
+}
+
+// acc[0..NT) += tile(64 x kin) * W(kin x N) for this wave's 32 rows and 32*NT columns.
+// Operands are requested two chunks (32 * NT MFMAs) before they are used, in three
+// rotating register sets, so that one wave alone can keep its matrix core busy.  A
+// request past the last full chunk repeats that chunk (harmless, in bounds) instead
+// of being skipped, which keeps the loop free of predicated loads.
+template <int NT, bool VEC>
 __device__ __forceinline__ void lc_layer(const float* __restrict__ tile, int kin, const float* __restrict__ W, int N,
-                                         bool vec, int rb, int ch, int j, int hh, v16f (&acc)[4])
+                                         int rb, int ch, int j, int hh, v16f (&acc)[4])
 {
     const int colb = ch * 32 * NT + NT * j;
     const float* arow = tile + (rb * 32 + j) * kLd + 4 * hh;
-    const int chunks = (kin + 7) >> 3;
-    float bc[4][NT], bn[4][NT];
-    lc_load_b<NT>(W, N, kin, 4 * hh, colb, vec, bc);
-    for (int c = 0; c < chunks; ++c) {
-        if (c + 1 < chunks) lc_load_b<NT>(W, N, kin, (c + 1) * 8 + 4 * hh, colb, vec, bn);
-        const v4f av = *reinterpret_cast<const v4f*>(arow + c * 8);
-        const float as[4] = {av.x, av.y, av.z, av.w};
+    const int full = kin >> 3;
+    const int roff = 4 * hh * N;
+    int coff[NT];
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[s], bc[s][t], acc[t], 0, 0, 0);
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-            for (int t = 0; t < NT; ++t) bc[s][t] = bn[s][t];
+    for (int t = 0; t < NT; ++t) coff[t] = colb + t < N ? colb + t : 0;
+    if (full > 0) {
+        auto load_a = [&](int c) { return *reinterpret_cast<const v4f*>(arow + min(c, full - 1) * 8); };
+        auto load_b = [&](int c, float (&b)[4][NT]) { lc_load_b<NT, VEC>(W + (int64_t)min(c, full - 1) * 8 * N, N, roff, coff, b); };
+        float b0[4][NT], b1[4][NT], b2[4][NT];
+        v4f a0, a1, a2;
+        load_b(0, b0), a0 = load_a(0);
+        load_b(1, b1), a1 = load_a(1);
+        for (int c = 0; c < full; c += 3) {
+            load_b(c + 2, b2), a2 = load_a(c + 2);
+            lc_mfma_chunk<NT>(a0, b0, acc);
+            if (c + 1 >= full) break;
+            load_b(c + 3, b0), a0 = load_a(c + 3);
+            lc_mfma_chunk<NT>(a1, b1, acc);
+            if (c + 2 >= full) break;
+            load_b(c + 4, b1), a1 = load_a(c + 4);
+            lc_mfma_chunk<NT>(a2, b2, acc);
+        }
+    }
+    if (kin & 7) {
+        float bt[4][NT];
+        lc_load_b_tail<NT>(W + (int64_t)full * 8 * N, N, kin & 7, hh, coff, bt);
+        const v4f at = *reinterpret_cast<const v4f*>(arow + full * 8);  // zero beyond kin
+        lc_mfma_chunk<NT>(at, bt, acc);
     }
 }
 
 __device__ __forceinline__ void lc_layer_nt(int NT, const float* tile, int kin, const float* W, int N, bool vec, int rb,
                                             int ch, int j, int hh, v16f (&acc)[4])
 {
-    switch (NT) {
-    case 1: lc_layer<1>(tile, kin, W, N, vec, rb, ch, j, hh, acc); break;
-    case 2: lc_layer<2>(tile, kin, W, N, vec, rb, ch, j, hh, acc); break;
-    case 3: lc_layer<3>(tile, kin, W, N, vec, rb, ch, j, hh, acc); break;
-    default: lc_layer<4>(tile, kin, W, N, vec, rb, ch, j, hh, acc); break;
+    switch (NT * 2 + (vec ? 1 : 0)) {  // vec is only ever set for NT = 2 and 4
+    case 2: lc_layer<1, false>(tile, kin, W, N, rb, ch, j, hh, acc); break;
+    case 4: lc_layer<2, false>(tile, kin, W, N, rb, ch, j, hh, acc); break;
+    case 5: lc_layer<2, true>(tile, kin, W, N, rb, ch, j, hh, acc); break;
+    case 6: lc_layer<3, false>(tile, kin, W, N, rb, ch, j, hh, acc); break;
+    case 8: lc_layer<4, false>(tile, kin, W, N, rb, ch, j, hh, acc); break;
+    default: lc_layer<4, true>(tile, kin, W, N, rb, ch, j, hh, acc); break;
     }
 }
 
@@ -174,28 +218,32 @@ __device__ __forceinline__ int acc_row(int r, int hh) { return 8 * (r >> 2) + 4 
 
 // tile <- relu(acc) for the 64*NT columns the four waves hold; acc <- 0
 template <int NT>
-__device__ __forceinline__ void lc_store_relu(float* __restrict__ tile, int rb, int ch, int j, int hh, v16f (&acc)[4])
+__device__ __forceinline__ void lc_store_relu(float* __restrict__ tile, int Np, int rb, int ch, int j, int hh,
+                                              v16f (&acc)[4])
 {
+    bool keep[NT];  // columns beyond the layer's width hold products of clamped loads: store zeros
+#pragma unroll
+    for (int t = 0; t < NT; ++t) keep[t] = ch * 32 * NT + NT * j + t < Np;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         float* p = tile + (rb * 32 + acc_row(r, hh)) * kLd + ch * 32 * NT + NT * j;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const float x = acc[t][r];
-            p[t] = x < 0.0f ? 0.0f : x;  // NaN stays NaN
+            p[t] = (x < 0.0f || !keep[t]) ? 0.0f : x;  // NaN stays NaN
         }
     }
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = (v16f)(0.0f);
 }
 
-__device__ __forceinline__ void lc_store_relu_nt(int NT, float* tile, int rb, int ch, int j, int hh, v16f (&acc)[4])
+__device__ __forceinline__ void lc_store_relu_nt(int NT, float* tile, int Np, int rb, int ch, int j, int hh, v16f (&acc)[4])
 {
     switch (NT) {
-    case 1: lc_store_relu<1>(tile, rb, ch, j, hh, acc); break;
-    case 2: lc_store_relu<2>(tile, rb, ch, j, hh, acc); break;
-    case 3: lc_store_relu<3>(tile, rb, ch, j, hh, acc); break;
-    default: lc_store_relu<4>(tile, rb, ch, j, hh, acc); break;
+    case 1: lc_store_relu<1>(tile, Np, rb, ch, j, hh, acc); break;
+    case 2: lc_store_relu<2>(tile, Np, rb, ch, j, hh, acc); break;
+    case 3: lc_store_relu<3>(tile, Np, rb, ch, j, hh, acc); break;
+    default: lc_store_relu<4>(tile, Np, rb, ch, j, hh, acc); break;
     }
 }
 
@@ -230,7 +278,7 @@ __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
     for (int t = 1; t < a.T; ++t) {
         const int Np = a.width[t - 1], N = a.width[t];
         __syncthreads();  // every wave is done reading the tile
-        lc_store_relu_nt((Np + 63) >> 6, tile, rb, ch, j, hh, acc);
+        lc_store_relu_nt((Np + 63) >> 6, tile, Np, rb, ch, j, hh, acc);
         __syncthreads();
         lc_layer_nt((N + 63) >> 6, tile, Np, a.W[t], N, a.wvec[t] != 0, rb, ch, j, hh, acc);
     }
