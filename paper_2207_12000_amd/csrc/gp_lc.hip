@@ -76,31 +76,71 @@ __device__ __forceinline__ v4f load4(const unsigned short* p)
 
 // 64 x kin panel of the batch rows of one slab -> LDS, widened to fp32, zero beyond
 // kin (up to the next multiple of 8), zero for rows past the batch or ids outside
-// [0, n) (those rows are never stored).
+// [0, n) (those rows are never stored).  Eight independent requests per thread are
+// in flight before the first is written to LDS.
 template <typename T>
 __device__ __forceinline__ void lc_gather(float* __restrict__ tile, const T* __restrict__ slab, const LcArgs& a,
                                           int64_t row0, int p0, int kin, int tid)
 {
-    const int nq = ((kin + 7) & ~7) >> 2;  // groups of four columns per row
-    for (int idx = tid; idx < kTM * nq; idx += kLcThreads) {
-        const int r = idx / nq, q = idx - r * nq;
-        const int64_t br = row0 + r;
-        int64_t id = -1;
-        if (br < a.B) id = a.batch ? (int64_t)a.batch[br] : br;
-        v4f v = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (id >= 0 && id < a.n) {
-            const T* src = slab + id * a.ld + p0 + 4 * q;
-            if (a.xvec && 4 * q + 4 <= kin) {
-                v = load4(src);
-            } else {
-                if (4 * q + 0 < kin) v.x = widen(src[0]);
-                if (4 * q + 1 < kin) v.y = widen(src[1]);
-                if (4 * q + 2 < kin) v.z = widen(src[2]);
-                if (4 * q + 3 < kin) v.w = widen(src[3]);
+    constexpr int U = 8;
+    const unsigned nq = (unsigned)(((kin + 7) & ~7) >> 2);  // groups of four columns per row
+    const unsigned total = kTM * nq;
+    for (unsigned base = 0; base < total; base += U * kLcThreads) {
+        int64_t id[U];
+        unsigned r[U], q[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const unsigned idx = base + u * kLcThreads + tid;
+            r[u] = idx / nq, q[u] = idx - r[u] * nq;
+            const int64_t br = row0 + r[u];
+            id[u] = -1;
+            if (idx < total && br < a.B) id[u] = a.batch ? (int64_t)a.batch[br] : br;
+        }
+        v4f v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            v[u] = (v4f){0.0f, 0.0f, 0.0f, 0.0f};
+            if (id[u] >= 0 && id[u] < a.n) {
+                const T* src = slab + id[u] * a.ld + p0 + 4 * q[u];
+                const int c0 = 4 * (int)q[u];
+                if (a.xvec && c0 + 4 <= kin) {
+                    v[u] = load4(src);
+                } else {
+                    if (c0 + 0 < kin) v[u].x = widen(src[0]);
+                    if (c0 + 1 < kin) v[u].y = widen(src[1]);
+                    if (c0 + 2 < kin) v[u].z = widen(src[2]);
+                    if (c0 + 3 < kin) v[u].w = widen(src[3]);
+                }
             }
         }
-        *reinterpret_cast<v4f*>(tile + r * kLd + 4 * q) = v;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (base + u * kLcThreads + tid < total) *reinterpret_cast<v4f*>(tile + r[u] * kLd + 4 * q[u]) = v[u];
     }
+}
+
+// How the four waves of a workgroup split a layer with N output columns.
+//   wide   (N > 64):  wave w owns columns [w*32*NT, (w+1)*32*NT), NT = ceil(N/128), of
+//                     BOTH 32-row blocks: every weight is fetched by exactly one wave.
+//   narrow (N <= 64): wave w owns row block w & 1 and columns [(w>>1)*32, +32): all four
+//                     matrix cores stay busy on a 40- or 64-class output layer.
+// A wave whose columns all lie beyond N sits the layer out.  Tile (r, t) of a wave is
+// accumulator r*NT + t; column i of tile t is output column colbase + NT*i + t.
+struct WaveMap {
+    int rbw;      // row blocks this wave owns: 2 (wide) or 1 (narrow)
+    int nt;       // 32-column tiles per row block: 1 or 2
+    int rb0;      // first row block
+    int colbase;  // first column
+};
+__device__ __forceinline__ WaveMap wave_map(int N, int wave)
+{
+    WaveMap m;
+    if (N > 64) {
+        m.rbw = 2, m.nt = (N + 127) >> 7, m.rb0 = 0, m.colbase = wave * 32 * m.nt;
+    } else {
+        m.rbw = 1, m.nt = 1, m.rb0 = wave & 1, m.colbase = (wave >> 1) * 32;
+    }
+    return m;
 }
 
 // Weights of one full 8-row chunk for this lane: rows 4hh .. 4hh+3 of the chunk that
@@ -109,21 +149,17 @@ __device__ __forceinline__ void lc_gather(float* __restrict__ tile, const T* __r
 // beyond N reads column 0 instead (coff is clamped) and its products are discarded
 // when the layer's output is stored.  roff = 4hh*N; vectors use coff[0] only.
 template <int NT, bool VEC>
-__device__ __forceinline__ void lc_load_b(const float* __restrict__ Wc, int N, int roff, const int (&coff)[NT],
-                                          float (&b)[4][NT])
+__device__ __forceinline__ void lc_load_b(const float* Wc, int N, int roff, const int (&coff)[NT], float (&b)[4][NT])
 {
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         const float* p = Wc + s * N;
-        if constexpr (NT == 4 && VEC) {
-            const v4f v = *reinterpret_cast<const v4f*>(&p[roff + coff[0]]);
-            b[s][0] = v.x, b[s][1] = v.y, b[s][2] = v.z, b[s][3] = v.w;
-        } else if constexpr (NT == 2 && VEC) {
-            const v2f v = *reinterpret_cast<const v2f*>(&p[roff + coff[0]]);
+        if constexpr (NT == 2 && VEC) {
+            const v2f v = *reinterpret_cast<const v2f*>(p + (unsigned)(roff + coff[0]));
             b[s][0] = v.x, b[s][1] = v.y;
         } else {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) b[s][t] = p[roff + coff[t]];
+            for (int t = 0; t < NT; ++t) b[s][t] = p[(unsigned)(roff + coff[t])];
         }
     }
 }
@@ -131,8 +167,8 @@ __device__ __forceinline__ void lc_load_b(const float* __restrict__ Wc, int N, i
 // The last, partial chunk (rows_left < 8 rows): a row beyond the matrix is read as
 // row 0 of the chunk and replaced by zero.
 template <int NT>
-__device__ __forceinline__ void lc_load_b_tail(const float* __restrict__ Wc, int N, int rows_left, int hh,
-                                               const int (&coff)[NT], float (&b)[4][NT])
+__device__ __forceinline__ void lc_load_b_tail(const float* Wc, int N, int rows_left, int hh, const int (&coff)[NT],
+                                               float (&b)[4][NT])
 {
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -147,104 +183,130 @@ __device__ __forceinline__ void lc_load_b_tail(const float* __restrict__ Wc, int
     }
 }
 
-// the 4 * NT MFMAs of one chunk: step s multiplies k = 8c + 4hh + s
-template <int NT>
-__device__ __forceinline__ void lc_mfma_chunk(const v4f av, const float (&b)[4][NT], v16f (&acc)[4])
+// nothing moves across: neither in the compiler's middle end (the memory clobber) nor
+// in its instruction scheduler
+__device__ __forceinline__ void lc_fence()
 {
-    const float as[4] = {av.x, av.y, av.z, av.w};
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// the 4 * RBW * NT MFMAs of one chunk: step s multiplies k = 8c + 4hh + s
+template <int RBW, int NT>
+__device__ __forceinline__ void lc_mfma_chunk(const v4f (&av)[RBW], const float (&b)[4][NT], v16f (&acc)[4])
+{
 #pragma unroll
     for (int s = 0; s < 4; ++s)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(as[s], b[s][t], acc[t], 0, 0, 0);
+        for (int r = 0; r < RBW; ++r)
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                acc[r * NT + t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[r][s], b[s][t], acc[r * NT + t], 0, 0, 0);
 }
 
-// acc[0..NT) += tile(64 x kin) * W(kin x N) for this wave's 32 rows and 32*NT columns.
-// Operands are requested two chunks (32 * NT MFMAs) before they are used, in three
-// rotating register sets, so that one wave alone can keep its matrix core busy.  A
+// acc += tile(64 x kin) * W(kin x N) for this wave's share (see WaveMap).  Operands
+// are requested one chunk before they are used, in two alternating register sets.  A
 // request past the last full chunk repeats that chunk (harmless, in bounds) instead
 // of being skipped, which keeps the loop free of predicated loads.
-template <int NT, bool VEC>
-__device__ __forceinline__ void lc_layer(const float* __restrict__ tile, int kin, const float* __restrict__ W, int N,
-                                         int rb, int ch, int j, int hh, v16f (&acc)[4])
+template <int RBW, int NT, bool VEC>
+__device__ __forceinline__ void lc_layer(const float* tile, int kin, const float* W, int N, const WaveMap& m, int j, int hh,
+                                         v16f (&acc)[4])
 {
-    const int colb = ch * 32 * NT + NT * j;
-    const float* arow = tile + (rb * 32 + j) * kLd + 4 * hh;
+    const int colb = m.colbase + NT * j;
+    const float* arow = tile + (m.rb0 * 32 + j) * kLd + 4 * hh;
     const int full = kin >> 3;
     const int roff = 4 * hh * N;
     int coff[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) coff[t] = colb + t < N ? colb + t : 0;
     if (full > 0) {
-        auto load_a = [&](int c) { return *reinterpret_cast<const v4f*>(arow + min(c, full - 1) * 8); };
+        auto load_a = [&](int c, v4f (&av)[RBW]) {
+#pragma unroll
+            for (int r = 0; r < RBW; ++r) av[r] = *reinterpret_cast<const v4f*>(arow + r * 32 * kLd + min(c, full - 1) * 8);
+        };
         auto load_b = [&](int c, float (&b)[4][NT]) { lc_load_b<NT, VEC>(W + (int64_t)min(c, full - 1) * 8 * N, N, roff, coff, b); };
-        float b0[4][NT], b1[4][NT], b2[4][NT];
-        v4f a0, a1, a2;
-        load_b(0, b0), a0 = load_a(0);
-        load_b(1, b1), a1 = load_a(1);
-        for (int c = 0; c < full; c += 3) {
-            load_b(c + 2, b2), a2 = load_a(c + 2);
-            lc_mfma_chunk<NT>(a0, b0, acc);
-            if (c + 1 >= full) break;
-            load_b(c + 3, b0), a0 = load_a(c + 3);
-            lc_mfma_chunk<NT>(a1, b1, acc);
-            if (c + 2 >= full) break;
-            load_b(c + 4, b1), a1 = load_a(c + 4);
-            lc_mfma_chunk<NT>(a2, b2, acc);
+        float b0[4][NT], b1[4][NT];
+        v4f a0[RBW], a1[RBW];
+        // the fences keep each request group ahead of the MFMA group it is written
+        // before; left alone, the compiler sinks the loads to their first use
+        load_b(0, b0), load_a(0, a0);
+        int c = 0;
+        for (; c + 2 <= full; c += 2) {  // steady state: two chunks per trip, no exits inside
+            load_b(c + 1, b1), load_a(c + 1, a1);
+            lc_fence();
+            lc_mfma_chunk<RBW, NT>(a0, b0, acc);
+            lc_fence();
+            load_b(c + 2, b0), load_a(c + 2, a0);
+            lc_fence();
+            lc_mfma_chunk<RBW, NT>(a1, b1, acc);
+            lc_fence();
         }
+        if (c < full) lc_mfma_chunk<RBW, NT>(a0, b0, acc);  // an odd last chunk is already here
     }
     if (kin & 7) {
         float bt[4][NT];
+        v4f at[RBW];
         lc_load_b_tail<NT>(W + (int64_t)full * 8 * N, N, kin & 7, hh, coff, bt);
-        const v4f at = *reinterpret_cast<const v4f*>(arow + full * 8);  // zero beyond kin
-        lc_mfma_chunk<NT>(at, bt, acc);
+#pragma unroll
+        for (int r = 0; r < RBW; ++r) at[r] = *reinterpret_cast<const v4f*>(arow + r * 32 * kLd + full * 8);  // zero beyond kin
+        lc_mfma_chunk<RBW, NT>(at, bt, acc);
     }
 }
 
-__device__ __forceinline__ void lc_layer_nt(int NT, const float* tile, int kin, const float* W, int N, bool vec, int rb,
-                                            int ch, int j, int hh, v16f (&acc)[4])
+__device__ __forceinline__ void lc_layer_any(const float* tile, int kin, const float* W, int N, bool vec, int wave, int j,
+                                             int hh, v16f (&acc)[4])
 {
-    switch (NT * 2 + (vec ? 1 : 0)) {  // vec is only ever set for NT = 2 and 4
-    case 2: lc_layer<1, false>(tile, kin, W, N, rb, ch, j, hh, acc); break;
-    case 4: lc_layer<2, false>(tile, kin, W, N, rb, ch, j, hh, acc); break;
-    case 5: lc_layer<2, true>(tile, kin, W, N, rb, ch, j, hh, acc); break;
-    case 6: lc_layer<3, false>(tile, kin, W, N, rb, ch, j, hh, acc); break;
-    case 8: lc_layer<4, false>(tile, kin, W, N, rb, ch, j, hh, acc); break;
-    default: lc_layer<4, true>(tile, kin, W, N, rb, ch, j, hh, acc); break;
-    }
+    const WaveMap m = wave_map(N, wave);
+    if (m.colbase >= N) return;
+    if (m.rbw == 1)
+        lc_layer<1, 1, false>(tile, kin, W, N, m, j, hh, acc);
+    else if (m.nt == 1)
+        lc_layer<2, 1, false>(tile, kin, W, N, m, j, hh, acc);
+    else if (vec)
+        lc_layer<2, 2, true>(tile, kin, W, N, m, j, hh, acc);
+    else
+        lc_layer<2, 2, false>(tile, kin, W, N, m, j, hh, acc);
 }
 
-// accumulator element r of a 32x32 tile sits in row 8*(r/4) + 4*(lane/32) + r%4
-__device__ __forceinline__ int acc_row(int r, int hh) { return 8 * (r >> 2) + 4 * hh + (r & 3); }
+// accumulator element e of a 32x32 tile sits in row 8*(e/4) + 4*(lane/32) + e%4
+__device__ __forceinline__ int acc_row(int e, int hh) { return 8 * (e >> 2) + 4 * hh + (e & 3); }
 
-// tile <- relu(acc) for the 64*NT columns the four waves hold; acc <- 0
-template <int NT>
-__device__ __forceinline__ void lc_store_relu(float* __restrict__ tile, int Np, int rb, int ch, int j, int hh,
-                                              v16f (&acc)[4])
+// tile <- relu(acc) for this wave's share of a layer of width Np; columns beyond Np
+// (products of clamped loads) become zeros; acc <- 0
+template <int RBW, int NT>
+__device__ __forceinline__ void lc_store_relu(float* __restrict__ tile, int Np, const WaveMap& m, int j, int hh, v16f (&acc)[4])
 {
-    bool keep[NT];  // columns beyond the layer's width hold products of clamped loads: store zeros
+    bool keep[NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) keep[t] = ch * 32 * NT + NT * j + t < Np;
+    for (int t = 0; t < NT; ++t) keep[t] = m.colbase + NT * j + t < Np;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        float* p = tile + (rb * 32 + acc_row(r, hh)) * kLd + ch * 32 * NT + NT * j;
+    for (int r = 0; r < RBW; ++r)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const float x = acc[t][r];
-            p[t] = (x < 0.0f || !keep[t]) ? 0.0f : x;  // NaN stays NaN
+        for (int e = 0; e < 16; ++e) {
+            float* p = tile + ((m.rb0 + r) * 32 + acc_row(e, hh)) * kLd + m.colbase + NT * j;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const float x = acc[r * NT + t][e];
+                p[t] = (x < 0.0f || !keep[t]) ? 0.0f : x;  // NaN stays NaN
+            }
         }
-    }
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = (v16f)(0.0f);
+    for (int t = 0; t < 4; ++t) acc[t] = (v16f)(0.0f);
 }
 
-__device__ __forceinline__ void lc_store_relu_nt(int NT, float* tile, int Np, int rb, int ch, int j, int hh, v16f (&acc)[4])
+// Every column below the next multiple of 8 of Np must be written (the next layer
+// reads that far): a wave that sat the layer out holds zeros and stores them too
+// when its columns start below that bound.
+__device__ __forceinline__ void lc_store_relu_any(float* tile, int Np, int wave, int j, int hh, v16f (&acc)[4])
 {
-    switch (NT) {
-    case 1: lc_store_relu<1>(tile, Np, rb, ch, j, hh, acc); break;
-    case 2: lc_store_relu<2>(tile, Np, rb, ch, j, hh, acc); break;
-    case 3: lc_store_relu<3>(tile, Np, rb, ch, j, hh, acc); break;
-    default: lc_store_relu<4>(tile, Np, rb, ch, j, hh, acc); break;
-    }
+    const WaveMap m = wave_map(Np, wave);
+    if (m.colbase >= ((Np + 7) & ~7)) return;
+    if (m.rbw == 1)
+        lc_store_relu<1, 1>(tile, Np, m, j, hh, acc);
+    else if (m.nt == 1)
+        lc_store_relu<2, 1>(tile, Np, m, j, hh, acc);
+    else
+        lc_store_relu<2, 2>(tile, Np, m, j, hh, acc);
 }
 
 // One workgroup: 64 batch rows of one hop k; writes gamma_k * MLP(X_k[rows]) to slab k
@@ -255,11 +317,9 @@ __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
     extern __shared__ __align__(16) float tile[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 31, hh = lane >> 5;
-    const int rb = wave & 1, ch = wave >> 1;
     const int k = (int)(blockIdx.x % (unsigned)a.hops);
     const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)a.hops) * kTM;
     const int C = a.width[a.T - 1];
-    const int NTL = (C + 63) >> 6;
 
     v16f acc[4];
 #pragma unroll
@@ -267,32 +327,38 @@ __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
 
     const T* slab = static_cast<const T*>(a.stack) + (int64_t)k * a.slab;
     const int N1 = a.width[0];
-    const int NT1 = (N1 + 63) >> 6;
     for (int p0 = 0; p0 < a.d; p0 += kPanel) {  // first layer, one panel of feature columns at a time
         const int kin = min(kPanel, a.d - p0);
         __syncthreads();
         lc_gather<T>(tile, slab, a, row0, p0, kin, tid);
         __syncthreads();
-        lc_layer_nt(NT1, tile, kin, a.W[0] + (int64_t)p0 * N1, N1, a.wvec[0] != 0, rb, ch, j, hh, acc);
+        lc_layer_any(tile, kin, a.W[0] + (int64_t)p0 * N1, N1, a.wvec[0] != 0, wave, j, hh, acc);
     }
     for (int t = 1; t < a.T; ++t) {
         const int Np = a.width[t - 1], N = a.width[t];
         __syncthreads();  // every wave is done reading the tile
-        lc_store_relu_nt((Np + 63) >> 6, tile, Np, rb, ch, j, hh, acc);
+        lc_store_relu_any(tile, Np, wave, j, hh, acc);
         __syncthreads();
-        lc_layer_nt((N + 63) >> 6, tile, Np, a.W[t], N, a.wvec[t] != 0, rb, ch, j, hh, acc);
+        lc_layer_any(tile, Np, a.W[t], N, a.wvec[t] != 0, wave, j, hh, acc);
     }
 
     const float g = a.gamma[k];
     float* dst = a.dst + (int64_t)k * a.B * a.ldd;
+    const WaveMap m = wave_map(C, wave);
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        if (t >= NTL) break;
+    for (int r = 0; r < 2; ++r) {
+        if (r >= m.rbw) break;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t br = row0 + rb * 32 + acc_row(r, hh);
-            const int col = ch * 32 * NTL + NTL * j + t;
-            if (br < a.B && col < C) dst[br * a.ldd + col] = g * acc[t][r];
+        for (int t = 0; t < 2; ++t) {
+            if (t >= m.nt) break;
+            const int col = m.colbase + m.nt * j + t;
+            // (r, t) -> accumulator r*nt + t; nt is 1 or 2
+            const v16f& v = m.nt == 1 ? acc[r] : acc[r * 2 + t];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int64_t br = row0 + (m.rb0 + r) * 32 + acc_row(e, hh);
+                if (br < a.B && col < C) dst[br * a.ldd + col] = g * v[e];
+            }
         }
     }
 }
@@ -378,8 +444,7 @@ gp_status lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, i
     for (int k = 0; k <= K; ++k) a.gamma[k] = gamma[k];
     for (int t = 0; t < T; ++t) {
         a.W[t] = W[t], a.width[t] = width[t];
-        const int nt = (width[t] + 63) / 64;
-        a.wvec[t] = (nt == 2 || nt == 4) && width[t] % nt == 0 && (uintptr_t)W[t] % (4 * nt) == 0;
+        a.wvec[t] = width[t] > 128 && width[t] % 2 == 0 && (uintptr_t)W[t] % 8 == 0;  // two tiles per wave, pairs aligned
     }
     const size_t esz = dtype == GP_F32 ? 4 : 2;
     a.xvec = ld % 4 == 0 && (uintptr_t)stack % (4 * esz) == 0;
