@@ -46,6 +46,85 @@ def algorithmic_bytes_per_hop(n: int, nnz: int, d: int, elem: int) -> int:
     return 4 * nnz + 8 * (n + 1) + 4 * n + 2 * n * d * elem
 
 
+LC_WIDTHS = [256, 256, 256, 40]      # hidden 256 (Appendix B), four MLP layers (GPRGNN's setting), 40 classes
+MFMA_F32_PEAK_TFLOPS = 157.3
+
+
+def bench_lc(args, gp, torch, w, plan, stack, t_gen, t_plan) -> int:
+    """One step = the LC-version forward pass (Appendix A) over all n rows of the hop
+    stack gp_propagate left in HBM, in mini-batches of --lc-batch randomly permuted
+    rows (the paper trains with batches of 4096)."""
+    n, d, K = w.n, w.d, w.K
+    rng = np.random.default_rng(20220712)
+    dims = [d] + LC_WIDTHS
+    Ws_np = [(rng.normal(size=(dims[t], dims[t + 1])) / np.sqrt(dims[t])).astype(np.float32) for t in range(len(LC_WIDTHS))]
+    Ws = [torch.from_numpy(W).cuda() for W in Ws_np]
+    gamma = [0.1 * 0.9 ** k for k in range(K)] + [0.9 ** K]          # PPR-initialised hop weights
+    perm_np = rng.permutation(n).astype(np.int32)
+    perm = torch.from_numpy(perm_np).cuda()
+    B = args.lc_batch if args.lc_batch > 0 else n
+    batches = [perm[i:i + B] for i in range(0, n, B)] if B < n else [None]
+    H = torch.empty((n, LC_WIDTHS[-1]), device="cuda")
+    outs = [H[i:i + B] for i in range(0, n, B)] if B < n else [H]
+
+    def step():
+        for b, o in zip(batches, outs):
+            gp.lc_forward_tensors(stack, b, gamma, Ws, out=o)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = e0.elapsed_time(e1) / args.steps
+    gp.gp_profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    launches, mlp_ms = gp.gp_profile_read("gp_lc_mlp")
+    _, red_ms = gp.gp_profile_read("gp_lc_reduce")
+    gp.gp_profile_enable(False)
+    flops_per_row = 2 * sum(dims[t] * dims[t + 1] for t in range(len(LC_WIDTHS))) * (K + 1)
+    rows_per_launch = n / max(launches / args.steps, 1)
+    avg_launch_s = mlp_ms * 1e-3 / max(launches, 1)
+    achieved = rows_per_launch * flops_per_row / avg_launch_s / 1e12
+    rec = {
+        "metric": "LC-version forward rows/s over the K-hop stack",
+        "value": round(n / (ms_per_step * 1e-3) / 1e6, 3), "unit": "Mrows/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.workload] + "; consumer: GPRGNN_LC forward, widths "
+                               + "-".join(map(str, dims)) + f", {K + 1} hops, batch {B}", "n": n, "d": d, "K": K,
+                   "calls_per_step": len(batches)},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / MFMA_F32_PEAK_TFLOPS, 4), "traffic": None, "kernel": "gp_lc_mlp",
+                     "launches": launches, "avg_launch_us": round(avg_launch_s * 1e6, 3),
+                     "algorithmic_flops_per_launch": int(rows_per_launch * flops_per_row)},
+        "other_kernels_ms_per_step": {"gp_lc_reduce": round(red_ms / args.steps, 5)},
+        "host_s": {"generate": round(t_gen, 2), "gp_plan_blocks": round(t_plan, 3)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import lc
+        stack_np = stack.cpu().numpy()
+        rows, t_cpu = 0, 0.0
+        i = 0
+        while t_cpu < 10.0:                                # bounded sample: whole mini-batches, about 10 s
+            ids = perm_np[i:i + 4096]
+            t0 = time.perf_counter()
+            lc.lc_forward(stack_np, ids, gamma, Ws_np)
+            t_cpu += time.perf_counter() - t0
+            rows += len(ids)
+            i = (i + 4096) % max(n - 4096, 1)
+        rec["cpu_baseline"] = {"value": round(rows / t_cpu / 1e6, 4), "unit": "Mrows/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
+                               "kind": "oracle", "sample": f"{rows} rows in mini-batches of 4096, fp64 numpy, {t_cpu:.2f} s"}
+    print(json.dumps(rec))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +140,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="library option (gp_set_option), e.g. column_tile=32")
+    ap.add_argument("--lc", action="store_true",
+                    help="time the LC-version forward pass (gp_lc_forward) over the hop stack instead of the precompute")
+    ap.add_argument("--lc-batch", type=int, default=4096, help="--lc: mini-batch rows per call (0 = all rows in one call)")
     ap.add_argument("--contiguous-ids", action="store_true",
                     help="workload 4 only: community-contiguous node ids (locality given) instead of permuted ids")
     args = ap.parse_args()
@@ -113,6 +195,16 @@ def main() -> int:
 
     def step():
         gp.gp_propagate(plan, X.data_ptr(), d, d, w.dtype, w.agg, K, out.data_ptr(), d, stream)
+
+    if args.lc:
+        if memory != "device":
+            print("bench.py: --lc needs the stack in HBM (device memory)", file=sys.stderr)
+            return 2
+        step()
+        torch.cuda.synchronize()
+        rc = bench_lc(args, gp, torch, w, plan, out, t_gen, t_plan)
+        plan.close()
+        return rc
 
     for _ in range(max(args.warmup, 1)):     # the first call also uploads the plan
         step()
