@@ -234,6 +234,7 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
  *                     by gp_plan_blocks.
  *   "column_tile"     feature columns per pass of the kernel, 0 = automatic.
  *   "persistent_blocks"  workgroups of the hop kernel (0 = as many as stay resident).
+ *   "lc_tile_rows"       batch rows per work item of gp_lc_forward: 32 or 64 (0 = by batch size).
  *   "column_slices"   column slices one pass is divided into, one slice per XCD
  *                     (1, 2, 4, 8; 0 = automatic).
  */

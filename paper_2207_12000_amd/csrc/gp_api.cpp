@@ -131,6 +131,11 @@ gp_status gp_set_option(const char* name, int64_t value)
         options().persistent_blocks = value;
         return GP_OK;
     }
+    if (!strcmp(name, "lc_tile_rows")) {
+        if (value != 0 && value != 32 && value != 64) return fail(GP_ERR_INVALID_ARG, "lc_tile_rows must be 0, 32 or 64");
+        options().lc_tile_rows = value;
+        return GP_OK;
+    }
     return fail(GP_ERR_INVALID_ARG, "unknown option '%s'", name);
 }
 
@@ -141,6 +146,7 @@ int64_t gp_get_option(const char* name)
     if (!strcmp(name, "column_tile")) return options().column_tile;
     if (!strcmp(name, "column_slices")) return options().column_slices;
     if (!strcmp(name, "persistent_blocks")) return options().persistent_blocks;
+    if (!strcmp(name, "lc_tile_rows")) return options().lc_tile_rows;
     if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
     return -1;
 }

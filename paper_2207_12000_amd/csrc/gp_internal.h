@@ -30,6 +30,7 @@ struct Options {
     int64_t column_tile = 0;
     int64_t column_slices = 0;
     int64_t persistent_blocks = 0;
+    int64_t lc_tile_rows = 0;  // 0 = chosen per call from the batch size
     int64_t hbm_budget_bytes = 0;
 };
 Options& options();

@@ -32,12 +32,10 @@ namespace gp {
 namespace {
 
 constexpr int kLcThreads = 256;
-constexpr int kTM = 64;          // batch rows per workgroup
 constexpr int kPanel = 256;      // widest inner dimension staged in LDS at once
 constexpr int kLd = kPanel + 4;  // LDS row stride in floats (16-byte aligned rows, banks staggered)
 constexpr int kMaxLayers = 8;
 constexpr int kMaxHops = 16;
-constexpr size_t kLdsBytes = (size_t)kTM * kLd * sizeof(float);
 constexpr int64_t kWorkspaceBytes = INT64_C(256) << 20;  // cap on the partial results of one piece
 
 typedef float v16f __attribute__((ext_vector_type(16)));
@@ -78,13 +76,13 @@ __device__ __forceinline__ v4f load4(const unsigned short* p)
 // kin (up to the next multiple of 8), zero for rows past the batch or ids outside
 // [0, n) (those rows are never stored).  Eight independent requests per thread are
 // in flight before the first is written to LDS.
-template <typename T>
+template <typename T, int TM>
 __device__ __forceinline__ void lc_gather(float* __restrict__ tile, const T* __restrict__ slab, const LcArgs& a,
                                           int64_t row0, int p0, int kin, int tid)
 {
     constexpr int U = 8;
     const unsigned nq = (unsigned)(((kin + 7) & ~7) >> 2);  // groups of four columns per row
-    const unsigned total = kTM * nq;
+    const unsigned total = TM * nq;
     for (unsigned base = 0; base < total; base += U * kLcThreads) {
         int64_t id[U];
         unsigned r[U], q[U];
@@ -132,11 +130,12 @@ struct WaveMap {
     int rb0;      // first row block
     int colbase;  // first column
 };
+template <int RB>  // RB = 32-row blocks per work item: 2 (64 rows) or 1 (32 rows, all waves split the columns)
 __device__ __forceinline__ WaveMap wave_map(int N, int wave)
 {
     WaveMap m;
-    if (N > 64) {
-        m.rbw = 2, m.nt = (N + 127) >> 7, m.rb0 = 0, m.colbase = wave * 32 * m.nt;
+    if (RB == 1 || N > 64) {
+        m.rbw = RB, m.nt = (N + 127) >> 7, m.rb0 = 0, m.colbase = wave * 32 * m.nt;
     } else {
         m.rbw = 1, m.nt = 1, m.rb0 = wave & 1, m.colbase = (wave >> 1) * 32;
     }
@@ -253,19 +252,22 @@ __device__ __forceinline__ void lc_layer(const float* tile, int kin, const float
     }
 }
 
+template <int RB>
 __device__ __forceinline__ void lc_layer_any(const float* tile, int kin, const float* W, int N, bool vec, int wave, int j,
                                              int hh, v16f (&acc)[4])
 {
-    const WaveMap m = wave_map(N, wave);
+    const WaveMap m = wave_map<RB>(N, wave);
     if (m.colbase >= N) return;
-    if (m.rbw == 1)
+    if (m.nt == 2) {
+        if (vec)
+            lc_layer<RB, 2, true>(tile, kin, W, N, m, j, hh, acc);
+        else
+            lc_layer<RB, 2, false>(tile, kin, W, N, m, j, hh, acc);
+    } else if (RB == 2 && m.rbw == 2) {
+        lc_layer<RB, 1, false>(tile, kin, W, N, m, j, hh, acc);
+    } else {
         lc_layer<1, 1, false>(tile, kin, W, N, m, j, hh, acc);
-    else if (m.nt == 1)
-        lc_layer<2, 1, false>(tile, kin, W, N, m, j, hh, acc);
-    else if (vec)
-        lc_layer<2, 2, true>(tile, kin, W, N, m, j, hh, acc);
-    else
-        lc_layer<2, 2, false>(tile, kin, W, N, m, j, hh, acc);
+    }
 }
 
 // accumulator element e of a 32x32 tile sits in row 8*(e/4) + 4*(lane/32) + e%4
@@ -297,28 +299,30 @@ __device__ __forceinline__ void lc_store_relu(float* __restrict__ tile, int Np, 
 // Every column below the next multiple of 8 of Np must be written (the next layer
 // reads that far): a wave that sat the layer out holds zeros and stores them too
 // when its columns start below that bound.
+template <int RB>
 __device__ __forceinline__ void lc_store_relu_any(float* tile, int Np, int wave, int j, int hh, v16f (&acc)[4])
 {
-    const WaveMap m = wave_map(Np, wave);
+    const WaveMap m = wave_map<RB>(Np, wave);
     if (m.colbase >= ((Np + 7) & ~7)) return;
-    if (m.rbw == 1)
-        lc_store_relu<1, 1>(tile, Np, m, j, hh, acc);
-    else if (m.nt == 1)
-        lc_store_relu<2, 1>(tile, Np, m, j, hh, acc);
+    if (m.nt == 2)
+        lc_store_relu<RB, 2>(tile, Np, m, j, hh, acc);
+    else if (RB == 2 && m.rbw == 2)
+        lc_store_relu<RB, 1>(tile, Np, m, j, hh, acc);
     else
-        lc_store_relu<2, 2>(tile, Np, m, j, hh, acc);
+        lc_store_relu<1, 1>(tile, Np, m, j, hh, acc);
 }
 
-// One workgroup: 64 batch rows of one hop k; writes gamma_k * MLP(X_k[rows]) to slab k
+// One workgroup: 32*RB batch rows of one hop k; writes gamma_k * MLP(X_k[rows]) to slab k
 // of the partial results.
-template <typename T>
+template <typename T, int RB>
 __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
 {
+    constexpr int TM = 32 * RB;
     extern __shared__ __align__(16) float tile[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 31, hh = lane >> 5;
     const int k = (int)(blockIdx.x % (unsigned)a.hops);
-    const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)a.hops) * kTM;
+    const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)a.hops) * TM;
     const int C = a.width[a.T - 1];
 
     v16f acc[4];
@@ -330,23 +334,23 @@ __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
     for (int p0 = 0; p0 < a.d; p0 += kPanel) {  // first layer, one panel of feature columns at a time
         const int kin = min(kPanel, a.d - p0);
         __syncthreads();
-        lc_gather<T>(tile, slab, a, row0, p0, kin, tid);
+        lc_gather<T, TM>(tile, slab, a, row0, p0, kin, tid);
         __syncthreads();
-        lc_layer_any(tile, kin, a.W[0] + (int64_t)p0 * N1, N1, a.wvec[0] != 0, wave, j, hh, acc);
+        lc_layer_any<RB>(tile, kin, a.W[0] + (int64_t)p0 * N1, N1, a.wvec[0] != 0, wave, j, hh, acc);
     }
     for (int t = 1; t < a.T; ++t) {
         const int Np = a.width[t - 1], N = a.width[t];
         __syncthreads();  // every wave is done reading the tile
-        lc_store_relu_any(tile, Np, wave, j, hh, acc);
+        lc_store_relu_any<RB>(tile, Np, wave, j, hh, acc);
         __syncthreads();
-        lc_layer_any(tile, Np, a.W[t], N, a.wvec[t] != 0, wave, j, hh, acc);
+        lc_layer_any<RB>(tile, Np, a.W[t], N, a.wvec[t] != 0, wave, j, hh, acc);
     }
 
     const float g = a.gamma[k];
     float* dst = a.dst + (int64_t)k * a.B * a.ldd;
-    const WaveMap m = wave_map(C, wave);
+    const WaveMap m = wave_map<RB>(C, wave);
 #pragma unroll
-    for (int r = 0; r < 2; ++r) {
+    for (int r = 0; r < RB; ++r) {
         if (r >= m.rbw) break;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
@@ -400,18 +404,31 @@ gp_status workspace(size_t bytes, float** out)
     return GP_OK;
 }
 
-template <typename T>
+int compute_units()
+{
+    static int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1)
+            n = 256;
+        return n;
+    }();
+    return cus;
+}
+
+template <typename T, int RB>
 gp_status launch_mlp(const LcArgs& a, unsigned grid, hipStream_t stream)
 {
+    constexpr size_t lds = (size_t)32 * RB * kLd * sizeof(float);
     static std::once_flag once;
     static hipError_t attr = hipSuccess;
     std::call_once(once, [] {
-        attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&gp_lc_mlp<T>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)kLdsBytes);
+        attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&gp_lc_mlp<T, RB>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)lds);
     });
     GP_HIP(attr);
     profile_begin("gp_lc_mlp", stream);
-    hipLaunchKernelGGL(gp_lc_mlp<T>, dim3(grid), dim3(kLcThreads), kLdsBytes, stream, a);
+    hipLaunchKernelGGL((gp_lc_mlp<T, RB>), dim3(grid), dim3(kLcThreads), lds, stream, a);
     profile_end(stream);
     GP_HIP(hipGetLastError());
     return GP_OK;
@@ -449,10 +466,16 @@ gp_status lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, i
     const size_t esz = dtype == GP_F32 ? 4 : 2;
     a.xvec = ld % 4 == 0 && (uintptr_t)stack % (4 * esz) == 0;
 
-    // One workgroup per (64-row tile, hop), so that a mini-batch of a few thousand rows
-    // still fills the chip; the hops' results are then summed in hop order.  Large
-    // batches go through in pieces that keep the partial results within a fixed size.
-    const int64_t piece = a.hops == 1 ? B : std::max<int64_t>(kTM, kWorkspaceBytes / ((int64_t)a.hops * C * 4) / kTM * kTM);
+    // One workgroup per (row tile, hop), so that a mini-batch of a few thousand rows
+    // still fills the chip; the hops' results are then summed in hop order.  Tiles are
+    // 64 rows; 32 rows when even those give no more than one workgroup per CU (the
+    // call then lasts as long as one work item, and a 32-row item is the shorter one:
+    // 37 against 56 us at the paper's model shape; from two items per CU on, 64-row
+    // items win because each weight is fetched once per 64 rows).  Large batches go
+    // through in pieces that keep the partial results within a fixed size.
+    int tm = (int)options().lc_tile_rows;
+    if (tm == 0) tm = ((B + 31) / 32) * a.hops <= (int64_t)compute_units() ? 32 : 64;
+    const int64_t piece = a.hops == 1 ? B : std::max<int64_t>(64, kWorkspaceBytes / ((int64_t)a.hops * C * 4) / 64 * 64);
     float* part = nullptr;
     if (a.hops > 1) {
         gp_status st = workspace((size_t)a.hops * std::min(piece, B) * C * sizeof(float), &part);
@@ -467,10 +490,15 @@ gp_status lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, i
             p.dst = part, p.ldd = C;
         else
             p.dst = out + b0 * ldo, p.ldd = ldo;
-        const int64_t grid = (p.B + kTM - 1) / kTM * a.hops;
+        const int64_t grid = (p.B + tm - 1) / tm * a.hops;
         if (grid > 0x7fffffffLL) return fail(GP_ERR_UNSUPPORTED, "batch too large for one launch");
-        gp_status st = dtype == GP_F32 ? launch_mlp<float>(p, (unsigned)grid, stream)
-                                       : launch_mlp<unsigned short>(p, (unsigned)grid, stream);
+        gp_status st;
+        if (tm == 64)
+            st = dtype == GP_F32 ? launch_mlp<float, 2>(p, (unsigned)grid, stream)
+                                 : launch_mlp<unsigned short, 2>(p, (unsigned)grid, stream);
+        else
+            st = dtype == GP_F32 ? launch_mlp<float, 1>(p, (unsigned)grid, stream)
+                                 : launch_mlp<unsigned short, 1>(p, (unsigned)grid, stream);
         if (st != GP_OK) return st;
         if (a.hops > 1) {
             const unsigned rgrid = (unsigned)std::min<int64_t>((p.B * C + kLcThreads - 1) / kLcThreads, 256 * 8);

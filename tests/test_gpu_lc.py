@@ -80,14 +80,20 @@ CASES = [
 
 @pytest.mark.parametrize("d,widths,K,n,B", CASES)
 @pytest.mark.parametrize("bf16", [False, True])
-def test_parity(d, widths, K, n, B, bf16):
+@pytest.mark.parametrize("tile_rows", [32, 64])
+def test_parity(d, widths, K, n, B, bf16, tile_rows):
+    """Both work-item heights (the library picks 32 rows for small batches, 64 otherwise)."""
     rng = np.random.default_rng(1000 + d + B)
     stack = rng.normal(size=(K + 1, n, d)).astype(np.float32)
     if bf16:
         stack = gp_synth.f32_to_bf16_bits(stack)
     ids = rng.integers(0, n, B)
     gamma = rng.normal(size=K + 1)
-    check(stack, ids, gamma, make_weights(rng, d, widths), bf16=bf16, ldo_pad=3 if B < 100 else 0)
+    gp.gp_set_option("lc_tile_rows", tile_rows)
+    try:
+        check(stack, ids, gamma, make_weights(rng, d, widths), bf16=bf16, ldo_pad=3 if B < 100 else 0)
+    finally:
+        gp.gp_set_option("lc_tile_rows", 0)
 
 
 def test_all_rows_and_determinism():
