@@ -175,3 +175,55 @@ def test_on_the_propagated_stack_of_config_2():
         bound = lc.lc_bound(stack_np, rows, gamma, Ws)
         err = np.abs(out.cpu().numpy() - want)
         assert np.all(err <= tol * bound + 1e-30), f"worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {tol:.3g})"
+
+
+def test_random_shapes():
+    """Forty seeded random shapes: feature widths 1 .. 300 (one or two panels), one to
+    four layers of widths 1 .. 256, 1 .. 5 hops, 1 .. 300 rows, both work-item heights,
+    batch lists with out-of-range entries mixed in."""
+    rng = np.random.default_rng(4242)
+    try:
+        for case in range(40):
+            d = int(rng.integers(1, 301))
+            T = int(rng.integers(1, 5))
+            widths = [int(rng.integers(1, 257)) for _ in range(T)]
+            K = int(rng.integers(0, 5))
+            n = int(rng.integers(1, 400))
+            B = int(rng.integers(1, 301))
+            stack = rng.normal(size=(K + 1, n, d)).astype(np.float32)
+            ids = rng.integers(0, n, B)
+            gamma = rng.normal(size=K + 1)
+            Ws = make_weights(rng, d, widths)
+            gp.gp_set_option("lc_tile_rows", int(rng.choice([0, 32, 64])))
+            print(f"case {case}: d {d} widths {widths} K {K} n {n} B {B}", flush=True)
+            check(stack, ids, gamma, Ws)
+    finally:
+        gp.gp_set_option("lc_tile_rows", 0)
+
+
+def test_replays_in_a_hip_graph():
+    """After one eager call (which sizes the library's buffer) the call allocates
+    nothing and can be captured; every replay must reproduce the eager bits."""
+    import torch
+    rng = np.random.default_rng(11)
+    K, n, d = 3, 2000, 64
+    stack = torch.from_numpy(rng.normal(size=(K + 1, n, d)).astype(np.float32)).cuda()
+    Ws = [torch.from_numpy(W).cuda() for W in make_weights(rng, d, [128, 128, 16])]
+    batch = torch.from_numpy(rng.integers(0, n, 500).astype(np.int32)).cuda()
+    gamma = [0.4, 0.3, 0.2, 0.1]
+    eager = gp.lc_forward_tensors(stack, batch, gamma, Ws).clone()
+    torch.cuda.synchronize()
+    out = torch.zeros_like(eager)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(g, stream=side):                           # the binding takes torch's current stream
+        gp.lc_forward_tensors(stack, batch, gamma, Ws, out=out)
+    for _ in range(3):
+        out.fill_(-1.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
+        gp.lc_forward_tensors(stack, batch, gamma, Ws)               # eager work between the replays
+        torch.cuda.synchronize()

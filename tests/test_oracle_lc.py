@@ -116,3 +116,20 @@ def test_symmetries():
     assert np.allclose(lc.lc_forward(stack, ids, gamma, [3 * Ws[0], Ws[1], 0.5 * Ws[2]]), 1.5 * H, rtol=1e-12)
     # the bound dominates
     assert np.all(np.abs(H) <= lc.lc_bound(stack, ids, gamma, Ws) * (1 + 1e-12))
+
+
+def test_matches_an_independent_library_chain():
+    """The same formula through torch's CPU linear / relu in fp64 (another library's
+    matmul and clamp, applied hop by hop and stacked the other way round)."""
+    import torch
+    rng = np.random.default_rng(17)
+    stack = rng.normal(size=(4, 50, 12))
+    Ws = [rng.normal(size=s) for s in ((12, 20), (20, 20), (20, 20), (20, 5))]
+    gamma = rng.normal(size=4)
+    ids = rng.integers(0, 50, 23)
+    Z = torch.from_numpy(stack[:, ids, :])                      # (hops, B, d): all hops at once
+    for W in Ws[:-1]:
+        Z = torch.relu(torch.nn.functional.linear(Z, torch.from_numpy(W.T.copy())))
+    Z = torch.nn.functional.linear(Z, torch.from_numpy(Ws[-1].T.copy()))
+    want = torch.einsum("k,kbc->bc", torch.from_numpy(gamma), Z).numpy()
+    assert np.allclose(lc.lc_forward(stack, ids, gamma, Ws), want, rtol=1e-12, atol=1e-12)
