@@ -189,7 +189,9 @@ gp_status gp_propagate_combine(const gp_plan *plan, const void *X, int64_t ldx, 
  *
  * Enqueued on hip_stream; deterministic.  With K >= 1 the per-hop results pass
  * through a library-owned buffer per device (at most 256 MiB, grown on demand),
- * so calls on one device must not overlap in time.
+ * so calls on one device must not overlap in time.  Growing that buffer is the
+ * only allocation: after a call with at least as many rows and output columns,
+ * a call enqueues kernels only and may be captured in a HIP graph.
  * Errors: INVALID_ARG, UNSUPPORTED, OOM_DEVICE, DEVICE.
  */
 gp_status gp_lc_forward(const void *stack, int64_t ld, gp_dtype dtype, int64_t n, int32_t d, int32_t K,

@@ -23,6 +23,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <mutex>
 
 #include "gp_internal.h"
@@ -420,13 +421,17 @@ template <typename T, int RB>
 gp_status launch_mlp(const LcArgs& a, unsigned grid, hipStream_t stream)
 {
     constexpr size_t lds = (size_t)32 * RB * kLd * sizeof(float);
-    static std::once_flag once;
-    static hipError_t attr = hipSuccess;
-    std::call_once(once, [] {
-        attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&gp_lc_mlp<T, RB>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)lds);
-    });
-    GP_HIP(attr);
+    // the kernel's LDS tile is above the 64 KB a kernel gets by default: raise the limit
+    // once per device (the attribute belongs to the device's copy of the kernel)
+    static std::atomic<uint64_t> done{0};
+    int dev = 0;
+    GP_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return fail(GP_ERR_UNSUPPORTED, "device ordinal %d not supported", dev);
+    if (!(done.load(std::memory_order_acquire) >> dev & 1)) {
+        GP_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gp_lc_mlp<T, RB>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        done.fetch_or(UINT64_C(1) << dev, std::memory_order_release);
+    }
     profile_begin("gp_lc_mlp", stream);
     hipLaunchKernelGGL((gp_lc_mlp<T, RB>), dim3(grid), dim3(kLcThreads), lds, stream, a);
     profile_end(stream);
