@@ -5,13 +5,14 @@
 //
 // This is the one dense contraction on the path, so it runs on the matrix cores:
 // fp32 MFMA (v_mfma_f32_32x32x2_f32), all layers of one hop fused in one kernel.
-// A workgroup of four waves owns 64 batch rows.  The rows' features (later: the
+// A workgroup of four waves owns 64 batch rows (32 for very small batches) of one hop;
+// the hops' results are summed afterwards in hop order.  The rows' features (later: the
 // previous layer's activations) sit in LDS as the A operand; the weights are the B
 // operand, read straight from L2 (all T matrices together are a few hundred KB and
 // stay there) one 8-row chunk ahead of the MFMAs that use them; the layer output
 // stays in accumulator registers until every wave is done with the LDS tile, then
 // replaces it (ReLU applied on the way).  Nothing but the gathered rows and the
-// final B x C result touches HBM.
+// per-hop B x C results touches HBM.
 //
 // Index freedom used: MFMA sums over k and yields 32 columns per tile, but which k
 // and which column a lane supplies is the kernel's choice as long as A and B agree.
