@@ -133,3 +133,43 @@ def test_matches_an_independent_library_chain():
     Z = torch.nn.functional.linear(Z, torch.from_numpy(Ws[-1].T.copy()))
     want = torch.einsum("k,kbc->bc", torch.from_numpy(gamma), Z).numpy()
     assert np.allclose(lc.lc_forward(stack, ids, gamma, Ws), want, rtol=1e-12, atol=1e-12)
+
+
+def test_branches_written_out_for_two_hops():
+    """The H^LC formula of Section 3.1 for K = 2, typed out term by term:
+    branch 1 = (S X) W_1, branch 2 = relu((S^2 X) W_1) W_2."""
+    rng = np.random.default_rng(18)
+    stack = rng.normal(size=(3, 9, 4))                      # slabs X, SX, S^2 X
+    W1, W2 = rng.normal(size=(4, 5)), rng.normal(size=(5, 5))
+    ids = np.array([3, 1, 8])
+    b1 = stack[1][ids] @ W1
+    b2 = np.maximum(stack[2][ids] @ W1, 0.0) @ W2
+    g = [1.0, 1.0, 1.0]
+    for comb, want in ((lc.COMB_CONCAT, np.hstack([b1, b2])), (lc.COMB_MAX, np.maximum(b1, b2)), (lc.COMB_SUM, b1 + b2)):
+        got = lc.lc_forward_branches(stack, ids, g, [W1, W2], depth=[0, 1, 2], comb=comb)
+        assert np.allclose(got, want, rtol=1e-13, atol=1e-13)
+
+
+def test_branches_reduce_to_the_shared_depth_case_and_to_single_branches():
+    rng = np.random.default_rng(19)
+    stack = rng.normal(size=(4, 15, 6))
+    Ws = [rng.normal(size=s) for s in ((6, 7), (7, 7), (7, 7))]
+    gamma = rng.normal(size=4)
+    ids = rng.integers(0, 15, 8)
+    # equal depth + sum is the GPRGNN form
+    assert np.allclose(lc.lc_forward_branches(stack, ids, gamma, Ws, [3, 3, 3, 3], lc.COMB_SUM),
+                       lc.lc_forward(stack, ids, gamma, Ws), rtol=1e-13)
+    # every branch alone is a shared-depth call with one non-zero coefficient and a truncated weight list
+    depth = [0, 1, 2, 3]
+    singles = []
+    for k in (1, 2, 3):
+        e = np.zeros(4)
+        e[k] = gamma[k]
+        singles.append(lc.lc_forward(stack, ids, e, Ws[:depth[k]]))
+    assert np.allclose(lc.lc_forward_branches(stack, ids, gamma, Ws, depth, lc.COMB_CONCAT), np.hstack(singles), rtol=1e-13)
+    assert np.allclose(lc.lc_forward_branches(stack, ids, gamma, Ws, depth, lc.COMB_MAX), np.maximum.reduce(singles), rtol=1e-13)
+    assert np.allclose(lc.lc_forward_branches(stack, ids, gamma, Ws, depth, lc.COMB_SUM), np.add.reduce(singles), rtol=1e-13)
+    # the bound dominates under every combination
+    for comb in (lc.COMB_SUM, lc.COMB_CONCAT, lc.COMB_MAX):
+        H = lc.lc_forward_branches(stack, ids, gamma, Ws, depth, comb)
+        assert np.all(np.abs(H) <= lc.lc_bound_branches(stack, ids, gamma, Ws, depth, comb) * (1 + 1e-12))
