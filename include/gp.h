@@ -200,6 +200,29 @@ gp_status gp_lc_forward(const void *stack, int64_t ld, gp_dtype dtype, int64_t n
                         void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * gp_lc_forward_branches -- the general H^LC of Section 3.1 (the LC version of
+ * JKNet): one branch per hop, of its own depth, combined by COMB:
+ *     branch_k = relu(... relu(X_k[batch] W_1) ... W_{depth[k]-1}) W_{depth[k]},
+ *     H        = COMB_k(gamma[k] * branch_k).
+ * The paper's formula is depth[k] = k for k = 1..K (hop 0 left out) with COMB =
+ * concatenation or max pooling; depth[k] = T for every k with GP_COMB_SUM is
+ * gp_lc_forward.
+ *
+ *  depth   HOST, K+1 ints in 0 .. T; 0 leaves hop k out; at least one non-zero.
+ *  comb    GP_COMB_SUM / GP_COMB_MAX: all branches must end in the same width
+ *          (INVALID_ARG otherwise), out is B x that width;
+ *          GP_COMB_CONCAT: out is B x (sum of the branches' widths), branches side
+ *          by side in hop order.
+ * Everything else as gp_lc_forward (concatenation writes the result directly and
+ * needs no library buffer).
+ */
+typedef enum { GP_COMB_SUM = 0, GP_COMB_CONCAT = 1, GP_COMB_MAX = 2 } gp_comb;
+gp_status gp_lc_forward_branches(const void *stack, int64_t ld, gp_dtype dtype, int64_t n, int32_t d, int32_t K,
+                                 const int32_t *batch, int64_t B, const float *gamma, const int32_t *depth,
+                                 gp_comb comb, int32_t T, const float *const *W, const int32_t *width,
+                                 float *out, int64_t ldo, void *hip_stream);
+
+/* ---------------------------------------------------------------------------
  * Optimal graph decomposition (Section 3.2, Eq. 11 and Eq. 12): block counts
  * from byte volumes, the available GPU volume and the environment's coefficients
  * (all in the same unit, e.g. bytes or GB; coefficients are measured by watching

@@ -50,6 +50,9 @@ _SIGNATURES = {
                                         _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_lc_forward": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int, _c.c_int64, _c.c_int32, _c.c_int32, _c.c_void_p, _c.c_int64,
                                  _c.c_void_p, _c.c_int32, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
+    "gp_lc_forward_branches": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int, _c.c_int64, _c.c_int32, _c.c_int32, _c.c_void_p,
+                                          _c.c_int64, _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int32, _c.c_void_p,
+                                          _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_solve_normalisation_blocks": (_c.c_int, [_c.c_double] * 7 + [_c.POINTER(_c.c_int64)]),
     "gp_solve_aggregation_blocks": (_c.c_int, [_c.c_double] * 5 + [_c.c_int64, _c.POINTER(_c.c_int64),
                                                                   _c.POINTER(_c.c_int64)]),
@@ -267,11 +270,34 @@ def gp_lc_forward(stack_ptr: int, ld: int, dtype: int, n: int, d: int, K: int, b
     _check(st, "gp_lc_forward")
 
 
-def lc_forward_tensors(stack, batch, gamma, weights, out=None, stream=None):
+GP_COMB_SUM, GP_COMB_CONCAT, GP_COMB_MAX = 0, 1, 2
+
+
+def gp_lc_forward_branches(stack_ptr: int, ld: int, dtype: int, n: int, d: int, K: int, batch_ptr: Optional[int], B: int,
+                           gamma, depth, comb: int, weight_ptrs, widths, out_ptr: int, ldo: int,
+                           stream: Optional[int] = None):
+    """Raw-pointer form.  depth: K+1 host ints (layers branch k applies, 0 = hop left out);
+    comb: GP_COMB_SUM / GP_COMB_CONCAT / GP_COMB_MAX; the rest as gp_lc_forward."""
+    g = np.ascontiguousarray(gamma, dtype=np.float32)
+    dp = np.ascontiguousarray(depth, dtype=np.int32)
+    if g.shape != (K + 1,) or dp.shape != (K + 1,):
+        raise ValueError("gamma and depth must hold K+1 values")
+    T = len(weight_ptrs)
+    if len(widths) != T:
+        raise ValueError("one width per weight matrix")
+    W = (ctypes.c_void_p * max(T, 1))(*[int(p) for p in weight_ptrs])
+    wd = np.ascontiguousarray(widths, dtype=np.int32)
+    st = lib().gp_lc_forward_branches(stack_ptr, ld, dtype, n, d, K, batch_ptr or None, B, g.ctypes.data, dp.ctypes.data, comb,
+                                      T, ctypes.cast(W, ctypes.c_void_p), wd.ctypes.data, out_ptr, ldo, stream or None)
+    _check(st, "gp_lc_forward_branches")
+
+
+def lc_forward_tensors(stack, batch, gamma, weights, out=None, stream=None, depth=None, comb=GP_COMB_SUM):
     """Convenience for torch tensors (memory and streams only): stack is the
     contiguous (K+1, n, d) float32 / bfloat16 GPU tensor gp_propagate filled, batch an
     int32 GPU tensor of row numbers (or None for all rows), weights a list of
-    contiguous float32 GPU matrices.  Returns the (B, width_T) float32 result."""
+    contiguous float32 GPU matrices.  Returns the (B, width) float32 result.  With
+    `depth` (K+1 ints) the branch form gp_lc_forward_branches is called."""
     import torch
     if stack.dim() != 3 or not stack.is_contiguous():
         raise ValueError("stack must be a contiguous (K+1, n, d) tensor")
@@ -285,14 +311,24 @@ def lc_forward_tensors(stack, batch, gamma, weights, out=None, stream=None):
         if W.dtype != torch.float32 or W.dim() != 2 or not W.is_contiguous() or W.shape[0] != inner:
             raise ValueError("weights must be contiguous float32 matrices whose shapes chain from d")
         inner = W.shape[1]
+    if depth is not None:
+        ends = [weights[dk - 1].shape[1] for dk in depth if dk > 0]
+        if not ends:
+            raise ValueError("every hop is left out")
+        inner = sum(ends) if comb == GP_COMB_CONCAT else ends[0]
     if out is None:
         out = torch.empty((B, inner), dtype=torch.float32, device=stack.device)
     if out.shape != (B, inner) or out.dtype != torch.float32 or out.stride(1) != 1:
-        raise ValueError("out must be a (B, width_T) float32 tensor with unit column stride")
+        raise ValueError("out must be a (B, width) float32 tensor with unit column stride")
     if stream is None:
         stream = torch.cuda.current_stream(stack.device).cuda_stream
-    gp_lc_forward(stack.data_ptr(), d, dtype, n, d, K1 - 1, None if batch is None else batch.data_ptr(), B, gamma,
-                  [W.data_ptr() for W in weights], [W.shape[1] for W in weights], out.data_ptr(), out.stride(0), stream)
+    bp = None if batch is None else batch.data_ptr()
+    wp, ww = [W.data_ptr() for W in weights], [W.shape[1] for W in weights]
+    if depth is None:
+        gp_lc_forward(stack.data_ptr(), d, dtype, n, d, K1 - 1, bp, B, gamma, wp, ww, out.data_ptr(), out.stride(0), stream)
+    else:
+        gp_lc_forward_branches(stack.data_ptr(), d, dtype, n, d, K1 - 1, bp, B, gamma, depth, comb, wp, ww, out.data_ptr(),
+                               out.stride(0), stream)
     return out
 
 

@@ -49,7 +49,12 @@ struct LcArgs {
     const void* stack;
     int64_t ld, slab;  // elements: row stride, distance between hop slabs
     int64_t n;
-    int d, hops;  // hops = K + 1
+    int d;
+    int hops;                 // branches in use: work item = tile * hops + branch
+    int hop_of[kMaxHops];     // branch -> slab of the stack it reads
+    int depth[kMaxHops];      // branch -> number of weight matrices it applies
+    int out_off[kMaxHops];    // branch -> first output column when branches are written side by side
+    int direct;               // 1: branches write the final result (side by side, or there is just one)
     const int32_t* batch;
     int64_t B;
     float gamma[kMaxHops];
@@ -58,7 +63,7 @@ struct LcArgs {
     int width[kMaxLayers];
     int wvec[kMaxLayers];  // 1: W_t rows may be read with NT-wide vector loads
     int xvec;              // 1: stack rows may be read four elements at a time
-    float* dst;            // the result when hops = 1, else the partial results [hop][B][ldd]
+    float* dst;            // the result (direct), else the partial results [branch][B][ldd]
     int64_t ldd;
 };
 
@@ -314,8 +319,9 @@ __device__ __forceinline__ void lc_store_relu_any(float* tile, int Np, int wave,
         lc_store_relu<1, 1>(tile, Np, m, j, hh, acc);
 }
 
-// One workgroup: 32*RB batch rows of one hop k; writes gamma_k * MLP(X_k[rows]) to slab k
-// of the partial results.
+// One workgroup: 32*RB batch rows of one branch (hop k, the first depth_k layers); writes
+// gamma_k * branch_k either to its slab of the partial results or, when branches are
+// concatenated, to its columns of the result.
 template <typename T, int RB>
 __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
 {
@@ -323,9 +329,10 @@ __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
     extern __shared__ __align__(16) float tile[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = lane & 31, hh = lane >> 5;
-    const int k = (int)(blockIdx.x % (unsigned)a.hops);
+    const int br = (int)(blockIdx.x % (unsigned)a.hops);
+    const int k = a.hop_of[br], layers = a.depth[br];
     const int64_t row0 = (int64_t)(blockIdx.x / (unsigned)a.hops) * TM;
-    const int C = a.width[a.T - 1];
+    const int C = a.width[layers - 1];
 
     v16f acc[4];
 #pragma unroll
@@ -340,7 +347,7 @@ __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
         __syncthreads();
         lc_layer_any<RB>(tile, kin, a.W[0] + (int64_t)p0 * N1, N1, a.wvec[0] != 0, wave, j, hh, acc);
     }
-    for (int t = 1; t < a.T; ++t) {
+    for (int t = 1; t < layers; ++t) {
         const int Np = a.width[t - 1], N = a.width[t];
         __syncthreads();  // every wave is done reading the tile
         lc_store_relu_any<RB>(tile, Np, wave, j, hh, acc);
@@ -349,7 +356,7 @@ __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
     }
 
     const float g = a.gamma[k];
-    float* dst = a.dst + (int64_t)k * a.B * a.ldd;
+    float* dst = a.direct ? a.dst + a.out_off[br] : a.dst + (int64_t)br * a.B * a.ldd;
     const WaveMap m = wave_map<RB>(C, wave);
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
@@ -362,21 +369,24 @@ __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
             const v16f& v = m.nt == 1 ? acc[r] : acc[r * 2 + t];
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int64_t br = row0 + (m.rb0 + r) * 32 + acc_row(e, hh);
-                if (br < a.B && col < C) dst[br * a.ldd + col] = g * v[e];
+                const int64_t row = row0 + (m.rb0 + r) * 32 + acc_row(e, hh);
+                if (row < a.B && col < C) dst[row * a.ldd + col] = g * v[e];
             }
         }
     }
 }
 
-// out[i][c] = sum over items, in item order, of the partial results
-__global__ __launch_bounds__(kLcThreads) void gp_lc_reduce(const float* __restrict__ part, int items, int64_t B, int C,
-                                                           float* __restrict__ out, int64_t ldo)
+// out[i][c] = sum (or maximum) over the branches, in branch order, of the partial results
+__global__ __launch_bounds__(kLcThreads) void gp_lc_reduce(const float* __restrict__ part, int items, int take_max, int64_t B,
+                                                           int C, float* __restrict__ out, int64_t ldo)
 {
     const int64_t total = B * C;
     for (int64_t i = (int64_t)blockIdx.x * kLcThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kLcThreads) {
-        float s = 0.0f;
-        for (int it = 0; it < items; ++it) s += part[(int64_t)it * total + i];
+        float s = part[i];
+        for (int it = 1; it < items; ++it) {
+            const float v = part[(int64_t)it * total + i];
+            s = take_max ? (v > s || v != v ? v : s) : s + v;  // a NaN branch makes the maximum NaN
+        }
         out[(i / C) * ldo + i % C] = s;
     }
 }
@@ -443,11 +453,13 @@ gp_status launch_mlp(const LcArgs& a, unsigned grid, hipStream_t stream)
 }  // namespace
 
 gp_status lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, int32_t d, int32_t K, const int32_t* batch,
-                     int64_t B, const float* gamma, int32_t T, const float* const* W, const int32_t* width, float* out,
-                     int64_t ldo, hipStream_t stream)
+                     int64_t B, const float* gamma, const int32_t* depth, gp_comb comb, int32_t T, const float* const* W,
+                     const int32_t* width, float* out, int64_t ldo, hipStream_t stream)
 {
     if (!stack || !gamma || !W || !width || !out) return fail(GP_ERR_INVALID_ARG, "NULL argument");
     if (dtype != GP_F32 && dtype != GP_BF16) return fail(GP_ERR_INVALID_ARG, "unknown dtype %d", (int)dtype);
+    if (comb != GP_COMB_SUM && comb != GP_COMB_CONCAT && comb != GP_COMB_MAX)
+        return fail(GP_ERR_INVALID_ARG, "unknown combination %d", (int)comb);
     if (n < 1 || d < 1 || ld < d) return fail(GP_ERR_INVALID_ARG, "need n >= 1, d >= 1, ld >= d");
     if (K < 0 || K + 1 > kMaxHops) return fail(GP_ERR_UNSUPPORTED, "K = %d: 0 .. %d hops supported", K, kMaxHops - 1);
     if (T < 1 || T > kMaxLayers) return fail(GP_ERR_UNSUPPORTED, "T = %d: 1 .. %d layers supported", T, kMaxLayers);
@@ -457,14 +469,30 @@ gp_status lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, i
         if (width[t] < 1 || width[t] > kPanel)
             return fail(GP_ERR_UNSUPPORTED, "layer %d is %d wide: 1 .. %d supported", t + 1, width[t], kPanel);
     }
-    const int C = width[T - 1];
-    if (ldo < C) return fail(GP_ERR_INVALID_ARG, "ldo < output width");
-    if (B == 0) return GP_OK;
 
     LcArgs a{};
-    a.stack = stack, a.ld = ld, a.slab = n * ld, a.n = n, a.d = d, a.hops = K + 1;
+    a.stack = stack, a.ld = ld, a.slab = n * ld, a.n = n, a.d = d;
     a.batch = batch, a.B = B, a.T = T;
-    for (int k = 0; k <= K; ++k) a.gamma[k] = gamma[k];
+    // branches in use, their depths and where their columns go
+    int C = 0, total_width = 0;
+    for (int k = 0; k <= K; ++k) {
+        const int dk = depth ? depth[k] : T;
+        if (dk < 0 || dk > T) return fail(GP_ERR_INVALID_ARG, "depth[%d] = %d outside 0 .. T", k, dk);
+        a.gamma[k] = gamma[k];
+        if (dk == 0) continue;
+        const int wk = width[dk - 1];
+        if (comb != GP_COMB_CONCAT && a.hops > 0 && wk != C)
+            return fail(GP_ERR_INVALID_ARG, "branches of widths %d and %d cannot be summed or maximised", C, wk);
+        C = std::max(C, wk);
+        a.hop_of[a.hops] = k, a.depth[a.hops] = dk, a.out_off[a.hops] = comb == GP_COMB_CONCAT ? total_width : 0;
+        total_width += wk;
+        ++a.hops;
+    }
+    if (a.hops == 0) return fail(GP_ERR_INVALID_ARG, "every hop is left out (all depths are 0)");
+    const int out_width = comb == GP_COMB_CONCAT ? total_width : C;
+    if (ldo < out_width) return fail(GP_ERR_INVALID_ARG, "ldo < output width %d", out_width);
+    if (B == 0) return GP_OK;
+    a.direct = comb == GP_COMB_CONCAT || a.hops == 1;
     for (int t = 0; t < T; ++t) {
         a.W[t] = W[t], a.width[t] = width[t];
         a.wvec[t] = width[t] > 128 && width[t] % 2 == 0 && (uintptr_t)W[t] % 8 == 0;  // two tiles per wave, pairs aligned
@@ -472,18 +500,18 @@ gp_status lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, i
     const size_t esz = dtype == GP_F32 ? 4 : 2;
     a.xvec = ld % 4 == 0 && (uintptr_t)stack % (4 * esz) == 0;
 
-    // One workgroup per (row tile, hop), so that a mini-batch of a few thousand rows
-    // still fills the chip; the hops' results are then summed in hop order.  Tiles are
-    // 64 rows; 32 rows when even those give no more than one workgroup per CU (the
-    // call then lasts as long as one work item, and a 32-row item is the shorter one:
-    // 37 against 56 us at the paper's model shape; from two items per CU on, 64-row
+    // One workgroup per (row tile, branch), so that a mini-batch of a few thousand rows
+    // still fills the chip; the branches' results are then combined in hop order.
+    // Tiles are 64 rows; 32 rows when even those give no more than one workgroup per CU
+    // (the call then lasts as long as one work item, and a 32-row item is the shorter
+    // one: 37 against 56 us at the paper's model shape; from two items per CU on, 64-row
     // items win because each weight is fetched once per 64 rows).  Large batches go
     // through in pieces that keep the partial results within a fixed size.
     int tm = (int)options().lc_tile_rows;
     if (tm == 0) tm = ((B + 31) / 32) * a.hops <= (int64_t)compute_units() ? 32 : 64;
-    const int64_t piece = a.hops == 1 ? B : std::max<int64_t>(64, kWorkspaceBytes / ((int64_t)a.hops * C * 4) / 64 * 64);
+    const int64_t piece = a.direct ? B : std::max<int64_t>(64, kWorkspaceBytes / ((int64_t)a.hops * C * 4) / 64 * 64);
     float* part = nullptr;
-    if (a.hops > 1) {
+    if (!a.direct) {
         gp_status st = workspace((size_t)a.hops * std::min(piece, B) * C * sizeof(float), &part);
         if (st != GP_OK) return st;
     }
@@ -492,10 +520,10 @@ gp_status lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, i
         p.B = std::min(piece, B - b0);
         p.batch = batch ? batch + b0 : nullptr;
         if (!batch) p.stack = static_cast<const char*>(stack) + (size_t)b0 * ld * esz, p.n = n - b0;
-        if (a.hops > 1)
-            p.dst = part, p.ldd = C;
-        else
+        if (a.direct)
             p.dst = out + b0 * ldo, p.ldd = ldo;
+        else
+            p.dst = part, p.ldd = C;
         const int64_t grid = (p.B + tm - 1) / tm * a.hops;
         if (grid > 0x7fffffffLL) return fail(GP_ERR_UNSUPPORTED, "batch too large for one launch");
         gp_status st;
@@ -506,10 +534,11 @@ gp_status lc_forward(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, i
             st = dtype == GP_F32 ? launch_mlp<float, 1>(p, (unsigned)grid, stream)
                                  : launch_mlp<unsigned short, 1>(p, (unsigned)grid, stream);
         if (st != GP_OK) return st;
-        if (a.hops > 1) {
+        if (!a.direct) {
             const unsigned rgrid = (unsigned)std::min<int64_t>((p.B * C + kLcThreads - 1) / kLcThreads, 256 * 8);
             profile_begin("gp_lc_reduce", stream);
-            hipLaunchKernelGGL(gp_lc_reduce, dim3(rgrid), dim3(kLcThreads), 0, stream, part, a.hops, p.B, C, out + b0 * ldo, ldo);
+            hipLaunchKernelGGL(gp_lc_reduce, dim3(rgrid), dim3(kLcThreads), 0, stream, part, a.hops, comb == GP_COMB_MAX ? 1 : 0,
+                               p.B, C, out + b0 * ldo, ldo);
             profile_end(stream);
             GP_HIP(hipGetLastError());
         }
@@ -524,8 +553,23 @@ extern "C" gp_status gp_lc_forward(const void* stack, int64_t ld, gp_dtype dtype
                                    const int32_t* width, float* out, int64_t ldo, void* hip_stream)
 {
     try {
-        return gp::lc_forward(stack, ld, dtype, n, d, K, batch, B, gamma, T, W, width, out, ldo, (hipStream_t)hip_stream);
+        return gp::lc_forward(stack, ld, dtype, n, d, K, batch, B, gamma, nullptr, GP_COMB_SUM, T, W, width, out, ldo,
+                              (hipStream_t)hip_stream);
     } catch (const std::exception& e) {
         return gp::fail(GP_ERR_OOM_HOST, "gp_lc_forward: %s", e.what());
+    }
+}
+
+extern "C" gp_status gp_lc_forward_branches(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, int32_t d, int32_t K,
+                                            const int32_t* batch, int64_t B, const float* gamma, const int32_t* depth,
+                                            gp_comb comb, int32_t T, const float* const* W, const int32_t* width, float* out,
+                                            int64_t ldo, void* hip_stream)
+{
+    try {
+        if (!depth) return gp::fail(GP_ERR_INVALID_ARG, "NULL argument");
+        return gp::lc_forward(stack, ld, dtype, n, d, K, batch, B, gamma, depth, comb, T, W, width, out, ldo,
+                              (hipStream_t)hip_stream);
+    } catch (const std::exception& e) {
+        return gp::fail(GP_ERR_OOM_HOST, "gp_lc_forward_branches: %s", e.what());
     }
 }

@@ -227,3 +227,41 @@ def test_replays_in_a_hip_graph():
         assert torch.equal(out, eager)
         gp.lc_forward_tensors(stack, batch, gamma, Ws)               # eager work between the replays
         torch.cuda.synchronize()
+
+
+BRANCH_CASES = [
+    # d, widths, K, depth, comb, B
+    (128, [256, 256, 256], 3, [0, 1, 2, 3], gp.GP_COMB_CONCAT, 300),   # the paper's form: hop k runs k layers, concat pooling
+    (128, [256, 256, 256], 3, [0, 1, 2, 3], gp.GP_COMB_MAX, 300),      # max pooling
+    (64, [40, 40], 2, [1, 2, 2], gp.GP_COMB_SUM, 100),
+    (30, [17, 33, 5], 4, [3, 0, 1, 2, 3], gp.GP_COMB_CONCAT, 77),      # widths 5, 17, 33, 5 side by side
+    (20, [64], 5, [1, 0, 0, 0, 0, 1], gp.GP_COMB_MAX, 10),
+    (48, [96, 12], 2, [0, 2, 0], gp.GP_COMB_SUM, 5000),                # one branch: written directly
+]
+
+
+@pytest.mark.parametrize("d,widths,K,depth,comb,B", BRANCH_CASES)
+@pytest.mark.parametrize("bf16", [False, True])
+def test_branches_parity(d, widths, K, depth, comb, B, bf16):
+    import torch
+    rng = np.random.default_rng(2000 + d + B)
+    n = 1500
+    stack_np = rng.normal(size=(K + 1, n, d)).astype(np.float32)
+    if bf16:
+        stack_np = gp_synth.f32_to_bf16_bits(stack_np)
+        stack = torch.from_numpy(stack_np.view(np.int16)).view(torch.bfloat16).cuda()
+    else:
+        stack = torch.from_numpy(stack_np).cuda()
+    wide = gp_synth.bf16_bits_to_f32(stack_np) if bf16 else stack_np
+    ids = rng.integers(0, n, B)
+    gamma = rng.normal(size=K + 1) if comb == gp.GP_COMB_SUM else np.ones(K + 1)
+    Ws = make_weights(rng, d, widths)
+    out = gp.lc_forward_tensors(stack, torch.from_numpy(ids.astype(np.int32)).cuda(), gamma,
+                                [torch.from_numpy(W).cuda() for W in Ws], depth=depth, comb=comb)
+    torch.cuda.synchronize()
+    want = lc.lc_forward_branches(wide, ids, gamma, Ws, depth, comb)
+    bound = lc.lc_bound_branches(wide, ids, gamma, Ws, depth, comb)
+    err = np.abs(out.cpu().numpy().astype(np.float64) - want)
+    tol = tolerance(d, widths, K)
+    assert out.shape == want.shape
+    assert np.all(err <= tol * bound + 1e-30), f"worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {tol:.3g})"

@@ -43,3 +43,30 @@ def test_empty_batch_is_a_no_op():
 def test_gamma_length_is_checked_by_the_binding():
     with pytest.raises(ValueError):
         call(gamma=[1.0])
+
+
+def call_branches(**kw):
+    a = dict(stack_ptr=4096, ld=8, dtype=gp.GP_F32, n=10, d=8, K=2, batch_ptr=None, B=4, gamma=[1.0, 1.0, 1.0],
+             depth=[0, 1, 2], comb=gp.GP_COMB_CONCAT, weight_ptrs=[4096, 4096], widths=[4, 6], out_ptr=4096, ldo=10)
+    a.update(kw)
+    gp.gp_lc_forward_branches(**a)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(depth=[0, 0, 0]), gp.GP_ERR_INVALID_ARG),                       # every hop left out
+    (dict(depth=[0, 1, 3]), gp.GP_ERR_INVALID_ARG),                       # deeper than the weight list
+    (dict(depth=[0, -1, 2]), gp.GP_ERR_INVALID_ARG),
+    (dict(comb=3), gp.GP_ERR_INVALID_ARG),
+    (dict(comb=gp.GP_COMB_SUM), gp.GP_ERR_INVALID_ARG),                   # widths 4 and 6 cannot be summed
+    (dict(comb=gp.GP_COMB_MAX), gp.GP_ERR_INVALID_ARG),
+    (dict(ldo=9), gp.GP_ERR_INVALID_ARG),                                 # concatenation is 4 + 6 columns wide
+])
+def test_branches_rejected_arguments(kw, status):
+    with pytest.raises(gp.GpError) as e:
+        call_branches(**kw)
+    assert e.value.status == status
+
+
+def test_branches_empty_batch_is_a_no_op():
+    call_branches(B=0)
+    call_branches(B=0, comb=gp.GP_COMB_MAX, widths=[6, 6], ldo=6)
