@@ -342,7 +342,7 @@ __global__ __launch_bounds__(kLcThreads, 2) void gp_lc_mlp(const LcArgs a)
     const int N1 = a.width[0];
     for (int p0 = 0; p0 < a.d; p0 += kPanel) {  // first layer, one panel of feature columns at a time
         const int kin = min(kPanel, a.d - p0);
-        __syncthreads();
+        if (p0 > 0) __syncthreads();  // every wave is done with the previous panel (nothing is in the tile before the first)
         lc_gather<T, TM>(tile, slab, a, row0, p0, kin, tid);
         __syncthreads();
         lc_layer_any<RB>(tile, kin, a.W[0] + (int64_t)p0 * N1, N1, a.wvec[0] != 0, wave, j, hh, acc);
