@@ -94,6 +94,19 @@ struct Row<float, VEC> {
         }
         *reinterpret_cast<V*>(p) = t;
     }
+    // finished output rows: nothing reads them again during this launch, so they are
+    // stored with the streaming hint and leave the L2 to the gathered rows
+    __device__ static __forceinline__ void store_stream(float* p, const float (&x)[VEC])
+    {
+        V t;
+        if constexpr (VEC == 1) {
+            t = x[0];
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) t[i] = x[i];
+        }
+        __builtin_nontemporal_store(t, reinterpret_cast<V*>(p));
+    }
 };
 
 template <int VEC>
@@ -133,6 +146,17 @@ struct Row<uint16_t, VEC> {
             for (int i = 0; i < VEC; ++i) t[i] = f32_to_bf16(x[i]);
         }
         *reinterpret_cast<V*>(p) = t;
+    }
+    __device__ static __forceinline__ void store_stream(uint16_t* p, const float (&x)[VEC])
+    {
+        V t;
+        if constexpr (VEC == 1) {
+            t = f32_to_bf16(x[0]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) t[i] = f32_to_bf16(x[i]);
+        }
+        __builtin_nontemporal_store(t, reinterpret_cast<V*>(p));
     }
 };
 
@@ -308,7 +332,7 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
             if (partial) {
                 Row<float, VEC>::store(carry + (int64_t)s0.slot * carry_ld + coff[v], r);
             } else {
-                if (xout) Row<T, VEC>::store(xout + (int64_t)s0.row * ldout + coff[v], r);
+                if (xout) Row<T, VEC>::store_stream(xout + (int64_t)s0.row * ldout + coff[v], r);
                 if (comb) {  // running filter output: comb[row] += gamma * (A^^k X)[row]
                     float* cp = comb + (int64_t)s0.row * ldc + coff[v];
                     float c[VEC];
@@ -379,7 +403,7 @@ __global__ __launch_bounds__(kThreads) void gp_fixup_rows(const SplitRow* __rest
         float r[VEC];
 #pragma unroll
         for (int i = 0; i < VEC; ++i) r[i] = ((acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i])) * rs;
-        if (xout) Row<T, VEC>::store(xout + (int64_t)sr.row * ldout + c0, r);
+        if (xout) Row<T, VEC>::store_stream(xout + (int64_t)sr.row * ldout + c0, r);
         if (comb) {
             float* cp = comb + (int64_t)sr.row * ldc + c0;
             float c[VEC];
