@@ -100,6 +100,9 @@ struct gp_plan {
     // pinned host mirrors of col / segs for the streamed schedule (made on first use)
     mutable int32_t* pinned_col = nullptr;
     mutable gp::Segment* pinned_segs = nullptr;
+    // streamed schedule: after block p every row below rows_final[p] is complete, and
+    // split rows [0, split_final[p]) are the cut rows among them (filled with the pinned mirrors)
+    mutable std::vector<int64_t> rows_final, split_final;
 };
 
 namespace gp {

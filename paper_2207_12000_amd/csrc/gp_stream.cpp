@@ -91,6 +91,26 @@ gp_status ensure_pinned(const gp_plan* plan)
         std::memcpy(p, plan->segs.data(), plan->segs.size() * sizeof(Segment));
         plan->pinned_segs = (Segment*)p;
     }
+    if (plan->rows_final.empty() && plan->num_blocks > 0) {
+        // first row that a later block still writes to (through any of its segments,
+        // empty rows included): everything below it is final once block p is done
+        const int32_t b = plan->num_blocks;
+        std::vector<int64_t> first((size_t)b, plan->n);
+        for (int32_t q = 0; q < b; ++q)
+            for (int64_t s = plan->seg_off[q]; s < plan->seg_off[q + 1]; ++s)
+                first[(size_t)q] = std::min<int64_t>(first[(size_t)q], plan->segs[(size_t)s].row);
+        plan->rows_final.assign((size_t)b, plan->n);
+        plan->split_final.assign((size_t)b, (int64_t)plan->split.size());
+        int64_t later = plan->n;
+        for (int32_t q = b - 1; q >= 0; --q) {
+            plan->rows_final[(size_t)q] = later;
+            plan->split_final[(size_t)q] =
+                std::lower_bound(plan->split.begin(), plan->split.end(), later,
+                                 [](const SplitRow& r, int64_t row) { return (int64_t)r.row < row; }) -
+                plan->split.begin();
+            later = std::min(later, first[(size_t)q]);
+        }
+    }
     return GP_OK;
 }
 
@@ -117,6 +137,7 @@ namespace {
 // running beside it, 8 / 16 / 32 / 64 / 128 / 512 workgroups gave 370 / 309 / 322 /
 // 355 / 358 / 384 ms per 3-hop call (runtime copy: 439 ms).
 constexpr int kLinkCopyBlocks = 16;
+constexpr int64_t kMinRowsPerCopy = 4096;  // a finished row range smaller than this waits for the next block
 gp_status move_rows(void* dst, int64_t ldd, const void* src, int64_t lds, int64_t n, int32_t wc, gp_dtype dtype,
                     hipMemcpyKind kind, hipStream_t stream)
 {
@@ -242,6 +263,7 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
             const int src = (k - 1) & 1, dst = k & 1;
             // the slab about to be overwritten may still be on its way to the host
             if (out_used[dst]) GP_HIP(hipStreamWaitEvent(S.cmp, S.out_done[dst], 0));
+            int64_t rows_done = 0, split_done = 0;
             for (int32_t p = 0; p < b; ++p, ++blk_seq) {
                 const int buf = blocks_stay ? p : (int)(blk_seq % nbuf);
                 const int64_t e_lo = plan->block_off[p], e_cnt = plan->block_off[p + 1] - e_lo;
@@ -274,25 +296,34 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
                 if ((st = hop_passes(a, S.cmp)) != GP_OK) return st;
                 GP_HIP(hipEventRecord(S.blk_free[buf], S.cmp));
                 blk_used[buf] = 1;
+                // Rows that no later block writes to are final now: complete the cut
+                // ones among them and send the range home while the next blocks run.
+                const int64_t rows_to = plan->rows_final[(size_t)p], split_to = plan->split_final[(size_t)p];
+                if (split_to > split_done) {
+                    FixupArgs f;
+                    f.split = d_split + split_done;
+                    f.num_split = split_to - split_done;
+                    f.carry = d_carry;
+                    f.carry_ld = wpad;
+                    f.row_scale = row_scale;
+                    f.xout = d_slab[dst];
+                    f.ldout = w;
+                    f.d = wc;
+                    f.dtype = dtype;
+                    if ((st = fixup_passes(f, S.cmp)) != GP_OK) return st;
+                    split_done = split_to;
+                }
+                // (small ranges are held back and leave with the next one)
+                if (rows_to > rows_done && (rows_to - rows_done >= kMinRowsPerCopy || p == b - 1)) {
+                    GP_HIP(hipEventRecord(S.hop_done, S.cmp));
+                    GP_HIP(hipStreamWaitEvent(S.out, S.hop_done, 0));
+                    if ((st = move_rows((char*)out + (int64_t)k * out_slab + (rows_done * ldo + c0) * es, ldo,
+                                        d_slab[dst] + rows_done * w * es, w, rows_to - rows_done, wc, dtype,
+                                        hipMemcpyDeviceToHost, S.out)) != GP_OK)
+                        return st;
+                    rows_done = rows_to;
+                }
             }
-            if (!plan->split.empty()) {
-                FixupArgs f;
-                f.split = d_split;
-                f.num_split = (int64_t)plan->split.size();
-                f.carry = d_carry;
-                f.carry_ld = wpad;
-                f.row_scale = row_scale;
-                f.xout = d_slab[dst];
-                f.ldout = w;
-                f.d = wc;
-                f.dtype = dtype;
-                if ((st = fixup_passes(f, S.cmp)) != GP_OK) return st;
-            }
-            GP_HIP(hipEventRecord(S.hop_done, S.cmp));
-            GP_HIP(hipStreamWaitEvent(S.out, S.hop_done, 0));
-            if ((st = move_rows((char*)out + (int64_t)k * out_slab + c0 * es, ldo, d_slab[dst], w, n, wc, dtype,
-                                hipMemcpyDeviceToHost, S.out)) != GP_OK)
-                return st;
             GP_HIP(hipEventRecord(S.out_done[dst], S.out));
             out_used[dst] = true;
         }
