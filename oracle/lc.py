@@ -112,3 +112,12 @@ def lc_bound_branches(stack, ids, gamma, weights, depth, comb):
     if comb == COMB_CONCAT:
         return np.concatenate(parts, axis=1)
     return np.add.reduce(parts)
+
+
+def softmax_rows(H):
+    """Y = softmax(H^LC), row by row (Section 3.1: the predicted label matrix):
+    y_c = exp(h_c) / sum_c' exp(h_c'), evaluated after subtracting the row maximum,
+    which leaves the value unchanged and keeps exp in range."""
+    H = np.asarray(H, dtype=np.float64)
+    E = np.exp(H - H.max(axis=1, keepdims=True))
+    return E / E.sum(axis=1, keepdims=True)

@@ -173,3 +173,16 @@ def test_branches_reduce_to_the_shared_depth_case_and_to_single_branches():
     for comb in (lc.COMB_SUM, lc.COMB_CONCAT, lc.COMB_MAX):
         H = lc.lc_forward_branches(stack, ids, gamma, Ws, depth, comb)
         assert np.all(np.abs(H) <= lc.lc_bound_branches(stack, ids, gamma, Ws, depth, comb) * (1 + 1e-12))
+
+
+def test_softmax_rows():
+    from scipy.special import softmax
+    rng = np.random.default_rng(20)
+    H = rng.normal(size=(13, 7)) * 5
+    Y = lc.softmax_rows(H)
+    assert np.allclose(Y, softmax(H, axis=1), rtol=1e-13)                 # library routine
+    assert np.allclose(Y.sum(axis=1), 1.0, rtol=1e-14) and np.all(Y > 0)
+    assert np.allclose(lc.softmax_rows(H + 1000.0), Y, rtol=1e-10)          # shift invariance, no overflow
+    assert np.allclose(lc.softmax_rows(np.zeros((2, 4))), 0.25)            # uniform on equal scores
+    two = lc.softmax_rows(np.array([[0.0, np.log(3.0)]]))                   # closed form: 1/4, 3/4
+    assert np.allclose(two, [[0.25, 0.75]], rtol=1e-15)
