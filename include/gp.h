@@ -172,7 +172,7 @@ gp_status gp_propagate_combine(const gp_plan *plan, const void *X, int64_t ldx, 
  *     MLP(Z) = relu(... relu(Z W_1) ... W_{T-1}) W_T,
  *  the T weight matrices shared by all hops, no bias terms; with gamma = e_K it is
  *  the single-branch H^LC of Section 3.1, the LC version of a GCN).  The softmax
- *  the paper puts on top is left to the consumer.
+ *  the paper puts on top is gp_lc_softmax.
  *
  *  stack   DEVICE, K+1 slabs of n x d as gp_propagate writes them: slab k starts at
  *          element k*n*ld, rows ld elements apart (ld >= d), of `dtype` (bf16 is
@@ -221,6 +221,12 @@ gp_status gp_lc_forward_branches(const void *stack, int64_t ld, gp_dtype dtype, 
                                  const int32_t *batch, int64_t B, const float *gamma, const int32_t *depth,
                                  gp_comb comb, int32_t T, const float *const *W, const int32_t *width,
                                  float *out, int64_t ldo, void *hip_stream);
+
+/* gp_lc_softmax -- Y = softmax(H) row by row, in place (Section 3.1: the predicted
+ * label matrix Y = softmax(H^LC)).  H: DEVICE, B x C fp32, rows ld floats apart
+ * (ld >= C).  fp32 arithmetic, row maximum subtracted before exp.  Enqueued on
+ * hip_stream.  Errors: INVALID_ARG, DEVICE. */
+gp_status gp_lc_softmax(float *H, int64_t B, int32_t C, int64_t ld, void *hip_stream);
 
 /* ---------------------------------------------------------------------------
  * Optimal graph decomposition (Section 3.2, Eq. 11 and Eq. 12): block counts

@@ -53,6 +53,7 @@ _SIGNATURES = {
     "gp_lc_forward_branches": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int, _c.c_int64, _c.c_int32, _c.c_int32, _c.c_void_p,
                                           _c.c_int64, _c.c_void_p, _c.c_void_p, _c.c_int, _c.c_int32, _c.c_void_p,
                                           _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
+    "gp_lc_softmax": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int64, _c.c_void_p]),
     "gp_solve_normalisation_blocks": (_c.c_int, [_c.c_double] * 7 + [_c.POINTER(_c.c_int64)]),
     "gp_solve_aggregation_blocks": (_c.c_int, [_c.c_double] * 5 + [_c.c_int64, _c.POINTER(_c.c_int64),
                                                                   _c.POINTER(_c.c_int64)]),
@@ -271,6 +272,11 @@ def gp_lc_forward(stack_ptr: int, ld: int, dtype: int, n: int, d: int, K: int, b
 
 
 GP_COMB_SUM, GP_COMB_CONCAT, GP_COMB_MAX = 0, 1, 2
+
+
+def gp_lc_softmax(H_ptr: int, B: int, C: int, ld: int, stream: Optional[int] = None):
+    """Row softmax in place on a device matrix of B x C floats (rows ld floats apart)."""
+    _check(lib().gp_lc_softmax(H_ptr or None, B, C, ld, stream or None), "gp_lc_softmax")
 
 
 def gp_lc_forward_branches(stack_ptr: int, ld: int, dtype: int, n: int, d: int, K: int, batch_ptr: Optional[int], B: int,

@@ -391,6 +391,27 @@ __global__ __launch_bounds__(kLcThreads) void gp_lc_reduce(const float* __restri
     }
 }
 
+// Y = softmax(H) row by row, in place: one wave per row, row maximum subtracted first
+__global__ __launch_bounds__(kLcThreads) void gp_lc_softmax_rows(float* __restrict__ H, int64_t B, int C, int64_t ld)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * kLcThreads + threadIdx.x) >> 6;
+    const int64_t waves = (int64_t)gridDim.x * (kLcThreads >> 6);
+    for (int64_t r = wave; r < B; r += waves) {
+        float* row = H + r * ld;
+        float m = -INFINITY;
+        for (int c = lane; c < C; c += 64) m = fmaxf(m, row[c]);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+        float sum = 0.0f;
+        for (int c = lane; c < C; c += 64) sum += expf(row[c] - m);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+        const float inv = 1.0f / sum;
+        for (int c = lane; c < C; c += 64) row[c] = expf(row[c] - m) * inv;
+    }
+}
+
 // partial results of the split schedule: one grow-only buffer per device
 struct Workspace {
     float* p = nullptr;
@@ -558,6 +579,21 @@ extern "C" gp_status gp_lc_forward(const void* stack, int64_t ld, gp_dtype dtype
     } catch (const std::exception& e) {
         return gp::fail(GP_ERR_OOM_HOST, "gp_lc_forward: %s", e.what());
     }
+}
+
+extern "C" gp_status gp_lc_softmax(float* H, int64_t B, int32_t C, int64_t ld, void* hip_stream)
+{
+    using namespace gp;
+    if (!H) return fail(GP_ERR_INVALID_ARG, "NULL argument");
+    if (B < 0 || C < 1 || ld < C) return fail(GP_ERR_INVALID_ARG, "need B >= 0, C >= 1, ld >= C");
+    if (B == 0) return GP_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const unsigned grid = (unsigned)std::min<int64_t>((B + 3) / 4, 256 * 16);
+    profile_begin("gp_lc_softmax_rows", stream);
+    hipLaunchKernelGGL(gp_lc_softmax_rows, dim3(grid), dim3(kLcThreads), 0, stream, H, B, (int)C, ld);
+    profile_end(stream);
+    GP_HIP(hipGetLastError());
+    return GP_OK;
 }
 
 extern "C" gp_status gp_lc_forward_branches(const void* stack, int64_t ld, gp_dtype dtype, int64_t n, int32_t d, int32_t K,

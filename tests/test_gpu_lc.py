@@ -265,3 +265,22 @@ def test_branches_parity(d, widths, K, depth, comb, B, bf16):
     tol = tolerance(d, widths, K)
     assert out.shape == want.shape
     assert np.all(err <= tol * bound + 1e-30), f"worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {tol:.3g})"
+
+
+@pytest.mark.parametrize("B,C,pad", [(1, 1, 0), (5, 40, 0), (1000, 41, 3), (333, 172, 0), (64, 256, 5), (7, 1000, 0)])
+def test_softmax_rows(B, C, pad):
+    """fp32 arithmetic: the rounded difference h - max (|h - max| < 64 here) costs up to
+    64 * 2^-24 relative in exp, in the numerator and in every term of the denominator,
+    the C-term sum C * 2^-24, exp itself and the division a few ulp."""
+    import torch
+    rng = np.random.default_rng(3000 + B + C)
+    H = (rng.normal(size=(B, C)) * 6).astype(np.float32)
+    buf = torch.full((B, C + pad), 9.0, device="cuda")
+    buf[:, :C] = torch.from_numpy(H).cuda()
+    gp.gp_lc_softmax(buf.data_ptr(), B, C, C + pad, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = buf[:, :C].cpu().numpy().astype(np.float64)
+    want = lc.softmax_rows(H)
+    assert np.all(np.abs(got - want) <= (C + 160) * 2.0 ** -24 * want + 1e-37)
+    if pad:
+        assert torch.all(buf[:, C:] == 9.0)

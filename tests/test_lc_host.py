@@ -70,3 +70,14 @@ def test_branches_rejected_arguments(kw, status):
 def test_branches_empty_batch_is_a_no_op():
     call_branches(B=0)
     call_branches(B=0, comb=gp.GP_COMB_MAX, widths=[6, 6], ldo=6)
+
+
+@pytest.mark.parametrize("args", [(0, 4, 4, 4), (4096, -1, 4, 4), (4096, 4, 0, 4), (4096, 4, 5, 4)])
+def test_softmax_rejected_arguments(args):
+    with pytest.raises(gp.GpError) as e:
+        gp.gp_lc_softmax(*args)
+    assert e.value.status == gp.GP_ERR_INVALID_ARG
+
+
+def test_softmax_of_no_rows_is_a_no_op():
+    gp.gp_lc_softmax(4096, 0, 4, 4)
