@@ -437,8 +437,23 @@ template <typename U>
 __global__ __launch_bounds__(kThreads) void gp_copy_rows(const U* __restrict__ src, int64_t lds, U* __restrict__ dst,
                                                          int64_t ldd, int64_t n, int64_t w)
 {
-    const int64_t total = n * w;
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < total; i += (int64_t)gridDim.x * kThreads) {
+    // four independent elements per thread and trip: a small grid (the host-link copies
+    // run on 16 workgroups beside the hop kernel) still keeps enough bytes in flight
+    const int64_t total = n * w, step = (int64_t)gridDim.x * kThreads;
+    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    for (; i + 3 * step < total; i += 4 * step) {
+        U v[4];
+        int64_t o[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t e = i + u * step, r = e / w, c = e - r * w;
+            v[u] = src[r * lds + c];
+            o[u] = r * ldd + c;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) dst[o[u]] = v[u];
+    }
+    for (; i < total; i += step) {
         const int64_t r = i / w, c = i - r * w;
         dst[r * ldd + c] = src[r * lds + c];
     }
