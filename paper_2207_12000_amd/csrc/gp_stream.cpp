@@ -126,23 +126,25 @@ void release_pinned(gp_plan* plan)
 
 namespace {
 
-// n rows of wc elements between a pinned host matrix and a device slab.  Host to
-// device, a run that is contiguous on both sides is one DMA copy.  Everything else
-// is moved by the row-copy kernel reading / writing the pinned host memory
-// directly, on a small grid: pitched DMA copies crawl (4 - 13 GB/s here), and the
-// runtime serves large device-to-host copies with a machine-filling copy kernel
-// that stalls the hop kernel running beside it for the whole transfer.  Stores to
-// host memory queue up in the same memory pipeline the gathers use, so the grid is
-// kept just large enough to fill the link: measured on a 2.8 GB slab with the hops
-// running beside it, 8 / 16 / 32 / 64 / 128 / 512 workgroups gave 370 / 309 / 322 /
-// 355 / 358 / 384 ms per 3-hop call (runtime copy: 439 ms).
+// n rows of wc elements between a pinned host matrix and a device slab.  A run that
+// is contiguous on both sides is one runtime copy in either direction: with rows
+// leaving block by block (ranges of ~100 MB) that measured best (config-5 shape at
+// 10 % scale: 0.240 s per call against 0.259 s through the row-copy kernel).  A
+// strided run (a column slab of a wider matrix) is moved by the row-copy kernel
+// reading / writing the pinned host memory directly, on a small grid: pitched
+// runtime copies crawl (4 - 13 GB/s here).  Whatever moves the rows out, a hop
+// kernel running beside it lasts as long as the copy does (stores to host memory
+// queue up in the same memory pipeline the gathers use), so the call is bound by
+// the link's outgoing direction either way.  Grid of the kernel, measured on a
+// 2.8 GB slab sent whole with the hops beside it: 8 / 16 / 32 / 64 / 128 / 512
+// workgroups gave 370 / 309 / 322 / 355 / 358 / 384 ms per 3-hop call.
 constexpr int kLinkCopyBlocks = 16;
 constexpr int64_t kMinRowsPerCopy = 4096;  // a finished row range smaller than this waits for the next block
 gp_status move_rows(void* dst, int64_t ldd, const void* src, int64_t lds, int64_t n, int32_t wc, gp_dtype dtype,
                     hipMemcpyKind kind, hipStream_t stream)
 {
     const int es = dtype == GP_F32 ? 4 : 2;
-    if (kind == hipMemcpyHostToDevice && ldd == wc && lds == wc) {
+    if (ldd == wc && lds == wc) {
         GP_HIP(hipMemcpyAsync(dst, src, (size_t)n * wc * es, kind, stream));
         return GP_OK;
     }
