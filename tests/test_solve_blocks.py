@@ -70,3 +70,54 @@ def test_paper_block_counts_are_feasible_and_reachable():
         if (b, c) == (10, 16):
             hit = True
     assert hit, "b = 10, c = 16 is never the minimiser: the reading of Eq. 12 would be off"
+
+
+# ---- pins of the oracle itself (oracle/solve.py), by hand-worked cases ----------------
+
+def test_oracle_normalisation_boundary_is_inclusive():
+    # Eq. 11 with equality: (30 + 30)/2 + 2 = 32 fits a volume of 32; a = 1 gives 62
+    assert osolve.normalisation_blocks(30, 30, 2, 32) == 2
+    # a hair more on the divided term: 60.001/2 + 2 > 32, 60.001/3 + 2 = 22.0003 fits
+    assert osolve.normalisation_blocks(30, 30.001, 2, 32) == 3
+    # coefficients multiply their own volume only: (2*10 + 0.5*20)/a + 3*4 <= 27  <=>  30/a <= 15
+    assert osolve.normalisation_blocks(10, 20, 4, 27, 2.0, 0.5, 3.0) == 2
+    # the fixed term alone is over the volume: no a exists
+    assert osolve.normalisation_blocks(1, 1, 40, 32, limit=1000) is None
+    # nothing to divide: one block
+    assert osolve.normalisation_blocks(0, 0, 5, 5) == 1
+
+
+def test_oracle_aggregation_hand_cases():
+    # 64/b + 64/c <= 32: b = c = 4 gives exactly 32 (product 16); every pair with a smaller
+    # product fails: (2, c) needs 64/c <= 0, (3, 5) gives 34.1, (5, 3) the same
+    assert osolve.aggregation_blocks(64, 64, 32) == (4, 4)
+    # product tie: 32/b + 32/c <= 24 holds with equality at (2, 4) and (4, 2), product 8;
+    # (3, 3) has product 9, (2, 3) gives 26.7, b = 1 or c = 1 gives at least 32.  Smaller c wins.
+    assert osolve.aggregation_blocks(32, 32, 24) == (4, 2)
+    # coefficients: 2*30/b + 3*10/c <= 20: (3, 3) = 20 + 10 = 30 no; (4, 2) = 15 + 15 no;
+    # (6, 1) no (30 alone); (4, 3) = 15 + 10 = 25 no; (5, 2) = 12 + 15 no; (6, 2) = 10 + 15 no;
+    # (4, 6) = 15 + 5 = 20 fits with product 24; (6, 3) = 10 + 10 = 20 fits with product 18;
+    # (5, 3) = 12 + 10 = 22 no; (8, 2) = 7.5 + 15 no; products 13..17: (4,4) = 22.5, (5,3), (3,5) = 26, (8,2), (2,8) = 33.75 no
+    assert osolve.aggregation_blocks(30, 10, 20, 2.0, 3.0) == (6, 3)
+    # the column limit binds: 10/b + 100/c <= 32 needs c >= 4
+    assert osolve.aggregation_blocks(10, 100, 32, max_c=3) is None
+    assert osolve.aggregation_blocks(0, 10, 32) == (1, 1)
+
+
+def test_oracle_reaches_the_papers_block_counts():
+    """Section 4.2 (67 GB normalised adjacency, 57 GB features, 32 GB GPU: a = 3, b = 10, c = 16),
+    evaluated with the oracle alone.  beta = (2.0, 5.2): 134/10 + 296.4/16 = 13.4 + 18.525 = 31.925
+    fits, and no pair with a smaller product does (checked pair by pair below)."""
+    B_S, B_X, B_GPU = 67.0, 57.0, 32.0
+    assert osolve.aggregation_blocks(B_S, B_X, B_GPU, 2.0, 5.2, max_c=128) == (10, 16)
+    for b in range(1, 160):
+        for c in range(1, 160):
+            if b * c < 160:
+                assert 2.0 * B_S / b + 5.2 * B_X / c > B_GPU, (b, c)
+            if b * c == 160 and c < 16:
+                assert 2.0 * B_S / b + 5.2 * B_X / c > B_GPU, (b, c)     # so the tie-break is not what picks c = 16
+    B_A = 2 * 8 * 3_342_431_700 / 1e9          # the adjacency list as two int64 per non-zero: 53.48
+    B_D = 8 * 111_059_956 / 1e9                # 0.888
+    # alpha = (0.6, 0.6): 0.6 * (53.48 + 67) = 72.29; /2 + 0.89 = 37.0 > 32, /3 + 0.89 = 24.98 fits
+    assert osolve.normalisation_blocks(B_A, B_S, B_D, B_GPU, 0.6, 0.6, 1.0) == 3
+    assert (0.6 * B_A + 0.6 * B_S) / 2 + B_D > B_GPU >= (0.6 * B_A + 0.6 * B_S) / 3 + B_D
