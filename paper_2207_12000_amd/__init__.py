@@ -19,8 +19,7 @@ GP_F32, GP_BF16 = 0, 1
 GP_SYMMETRISE, GP_ADD_SELF_LOOPS, GP_PLAN_ON_DEVICE = 1, 2, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# GP_LIB names another build of the same library (tuning variants); default: the in-tree one
-LIB_PATH = os.environ.get("GP_LIB") or os.path.join(_HERE, "libgp.so")
+LIB_PATH = os.path.join(_HERE, "libgp.so")
 
 # every symbol include/gp.h declares: (restype, argtypes)
 _c = ctypes

@@ -37,9 +37,7 @@ def _stale(target: str, deps) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force: bool = False, verbose: bool = False, defines=(), out: str = LIB, objdir: str = OBJ) -> str:
-    """defines / out / objdir: alternative builds (e.g. tuning variants) beside the default one."""
-    OBJ, LIB = objdir, out
+def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
     headers = [os.path.join(CSRC, "gp_internal.h"), os.path.join(ROOT, "include", "gp.h")]
     hipcc = _hipcc()
@@ -48,7 +46,7 @@ def build(force: bool = False, verbose: bool = False, defines=(), out: str = LIB
         src = os.path.join(CSRC, name)
         obj = os.path.join(OBJ, name + ".o")
         if force or _stale(obj, [src] + headers):
-            cmd = [hipcc] + COMMON + DEVICE + [f"-D{d}" for d in defines] + ["-x", "hip", "-c", src, "-o", obj]
+            cmd = [hipcc] + COMMON + DEVICE + ["-x", "hip", "-c", src, "-o", obj]
             if verbose:
                 print(" ".join(cmd), flush=True)
             subprocess.check_call(cmd)
@@ -70,9 +68,5 @@ if __name__ == "__main__":
     import argparse
     ap = argparse.ArgumentParser()
     ap.add_argument("--force", action="store_true")
-    ap.add_argument("-D", dest="defines", action="append", default=[])
-    ap.add_argument("--out", default=LIB)
-    ap.add_argument("--objdir", default=OBJ)
     a = ap.parse_args()
-    print(build(force=a.force, verbose=True, defines=a.defines, out=os.path.abspath(a.out),
-                objdir=os.path.abspath(a.objdir)))
+    print(build(force=a.force, verbose=True))
