@@ -104,13 +104,44 @@ const float *gp_plan_dinv(const gp_plan *plan);            /* n */
  * crossing a block boundary; a row without non-zeros has one segment of length
  * 0.  A row made of one segment is written directly; a row cut into several has
  * consecutive partial-row slots, in list order, that are summed afterwards.
- * Segment record, 16 bytes: { uint32 start_lo; uint16 start_hi; uint16 len;
- * int32 row; int32 slot (-1 = whole row) }, start = start_hi << 32 | start_lo. */
+ * Segment record, 16 bytes: { uint32 start_lo; uint8 start_hi; uint8 slice; uint16 len;
+ * int32 row; int32 slot (-1 = whole row) }, start = start_hi << 32 | start_lo (40 bits);
+ * slice is 0 in this list and names a column slice in gp_plan_work_lists' records. */
 int64_t gp_plan_num_segments(const gp_plan *plan);
 const void *gp_plan_segments(const gp_plan *plan);            /* num_segments records, grouped by block */
 const int64_t *gp_plan_segment_offsets(const gp_plan *plan);  /* b+1: block p owns [off[p], off[p+1]) */
 int64_t gp_plan_num_partial_rows(const gp_plan *plan);        /* number of slots */
 int64_t gp_plan_segment_edges(const gp_plan *plan);           /* the segment length limit this plan used */
+
+/* Cache schedule of the device-resident hops (library's own; exposed so host logic
+ * can be checked without a GPU).  The paper's decomposition is agnostic on nodes
+ * (Section 3.2, Limitation paragraph); the order in which destination rows are
+ * processed does not change the result, only how often a gathered feature row is still
+ * in the cache of the part of the chip that asks for it.  Algorithm 1's two cuts --
+ * column blocks and edge blocks -- are re-used here as that order.
+ *
+ * gp_plan_row_clusters: rows grouped by synchronous label propagation over the
+ * non-zero pattern (every row takes the most frequent label among its sources, ties to
+ * the smallest label, until few rows change; deterministic).  label: HOST, n ints or
+ * NULL; clusters are numbered 0 .. *num_clusters-1.  *inside_fraction = share of the
+ * non-zeros whose source lies in the row's own cluster; *typical_rows = rows in the
+ * cluster of a typical non-zero.  Computed on first use and kept with the plan.
+ *
+ * gp_plan_work_lists: the explicit work lists a hop over rows of d elements of `dtype`,
+ * gathered in vectors of `vec` elements, would walk: *num_slices column slices of
+ * *slice_elems elements (the last one narrower), and for each of the GPU's 8 XCDs the
+ * records [xcd_off[x], xcd_off[x+1]) -- the plan's segments, each with the column slice
+ * it is for, listed cluster by cluster.  Every (segment, slice) pair appears exactly
+ * once over the 8 lists.  *num_slices = 0 means this plan keeps the implicit lists
+ * (XCD x takes slice x mod S of every segment): its rows do not gather mostly from
+ * their own cluster, or no slice of at least 128 bytes makes a cluster's rows fit the
+ * share of a 4 MB L2 the schedule counts on.  xcd_off: HOST, 9 entries.  records:
+ * HOST, room for `capacity` 16-byte records, or NULL to get the counts only.
+ * Errors: INVALID_ARG, OOM_HOST. */
+gp_status gp_plan_row_clusters(const gp_plan *plan, int32_t *label, int32_t *num_clusters,
+                               double *inside_fraction, double *typical_rows);
+gp_status gp_plan_work_lists(const gp_plan *plan, int32_t d, gp_dtype dtype, int32_t vec, int32_t *num_slices,
+                             int32_t *slice_elems, int64_t *xcd_off, void *records, int64_t capacity);
 
 /* ---------------------------------------------------------------------------
  * gp_propagate -- the hop stack (Algorithm 1's SX_list plus slot 0 = X).
@@ -251,7 +282,10 @@ gp_status gp_solve_aggregation_blocks(double B_S, double B_X, double B_GPU, doub
                                       int64_t max_c, int64_t *b, int64_t *c);
 
 /* ---------------------------------------------------------------------------
- * Library-wide knobs (process global; set them before planning / propagating).
+ * Library-wide knobs.  gp_set_option changes the process-wide defaults;
+ * gp_plan_blocks copies them into the plan it makes, and every later call on that
+ * plan uses the plan's copy ("lc_tile_rows" and the HBM budget, which belong to
+ * calls without a plan or to the machine, are read when the call is made).
  */
 
 /* Upper limit of HBM bytes the streamed schedule may use for its staging buffers
@@ -266,8 +300,10 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
  *   "column_tile"     feature columns per pass of the kernel, 0 = automatic.
  *   "persistent_blocks"  workgroups of the hop kernel (0 = as many as stay resident).
  *   "lc_tile_rows"       batch rows per work item of gp_lc_forward: 32 or 64 (0 = by batch size).
- *   "column_slices"   column slices one pass is divided into, one slice per XCD
- *                     (1, 2, 4, 8; 0 = automatic).
+ *   "column_slices"   column slices one pass is divided into (1 .. 16; 0 = automatic).
+ *                     Implicit work lists take 1, 2, 4 or 8 (anything else = automatic).
+ *   "cache_schedule"  0 = explicit per-XCD work lists where the plan's row clusters
+ *                     call for them (see gp_plan_work_lists), 1 = always, 2 = never.
  */
 gp_status gp_set_option(const char *name, int64_t value);
 int64_t gp_get_option(const char *name); /* -1 for an unknown name */

@@ -43,6 +43,10 @@ _SIGNATURES = {
     "gp_plan_segment_offsets": (_c.c_void_p, [_c.c_void_p]),
     "gp_plan_num_partial_rows": (_c.c_int64, [_c.c_void_p]),
     "gp_plan_segment_edges": (_c.c_int64, [_c.c_void_p]),
+    "gp_plan_row_clusters": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.POINTER(_c.c_int32), _c.POINTER(_c.c_double),
+                                        _c.POINTER(_c.c_double)]),
+    "gp_plan_work_lists": (_c.c_int, [_c.c_void_p, _c.c_int32, _c.c_int, _c.c_int32, _c.POINTER(_c.c_int32),
+                                      _c.POINTER(_c.c_int32), _c.c_void_p, _c.c_void_p, _c.c_int64]),
     "gp_propagate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                 _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_propagate_combine": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
@@ -178,8 +182,8 @@ class Plan:
         return _view(lib().gp_plan_dinv(self.handle), ctypes.c_float, self.n, np.float32)
 
 
-    SEGMENT_DTYPE = np.dtype([("start_lo", "<u4"), ("start_hi", "<u2"), ("len", "<u2"), ("row", "<i4"),
-                              ("slot", "<i4")])
+    SEGMENT_DTYPE = np.dtype([("start_lo", "<u4"), ("start_hi", "u1"), ("slice", "u1"), ("len", "<u2"),
+                              ("row", "<i4"), ("slot", "<i4")])
 
     @property
     def segments(self):
@@ -199,6 +203,27 @@ class Plan:
     @property
     def segment_edges(self) -> int:
         return lib().gp_plan_segment_edges(self.handle)
+
+    def row_clusters(self):
+        """(label[n], num_clusters, inside_fraction, typical_rows) of the cache schedule."""
+        label = np.empty(self.n, dtype=np.int32)
+        num, inside, typical = ctypes.c_int32(), ctypes.c_double(), ctypes.c_double()
+        _check(lib().gp_plan_row_clusters(self.handle, label.ctypes.data, ctypes.byref(num), ctypes.byref(inside),
+                                          ctypes.byref(typical)), "gp_plan_row_clusters")
+        return label, num.value, inside.value, typical.value
+
+    def work_lists(self, d: int, dtype: int, vec: int):
+        """(num_slices, slice_elems, xcd_off[9], records) of the explicit work lists for rows of
+        d elements, or num_slices = 0 when the plan keeps the implicit lists."""
+        S, elems = ctypes.c_int32(), ctypes.c_int32()
+        off = np.zeros(9, dtype=np.int64)
+        _check(lib().gp_plan_work_lists(self.handle, d, dtype, vec, ctypes.byref(S), ctypes.byref(elems), off.ctypes.data,
+                                        None, 0), "gp_plan_work_lists")
+        recs = np.zeros(int(off[8]), dtype=self.SEGMENT_DTYPE)
+        if S.value:
+            _check(lib().gp_plan_work_lists(self.handle, d, dtype, vec, ctypes.byref(S), ctypes.byref(elems),
+                                            off.ctypes.data, recs.ctypes.data, recs.size), "gp_plan_work_lists")
+        return S.value, elems.value, off, recs
 
 
 def gp_plan_blocks(src, dst, n: int, block_budget_edges: int, flags: int) -> Plan:

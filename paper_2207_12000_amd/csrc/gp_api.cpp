@@ -121,9 +121,13 @@ gp_status gp_set_option(const char* name, int64_t value)
         return GP_OK;
     }
     if (!strcmp(name, "column_slices")) {
-        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
-            return fail(GP_ERR_INVALID_ARG, "column_slices must be 0 (automatic), 1, 2, 4 or 8");
+        if (value < 0 || value > 16) return fail(GP_ERR_INVALID_ARG, "column_slices must be 0 (automatic) or 1 .. 16");
         options().column_slices = value;
+        return GP_OK;
+    }
+    if (!strcmp(name, "cache_schedule")) {
+        if (value < 0 || value > 2) return fail(GP_ERR_INVALID_ARG, "cache_schedule must be 0 (automatic), 1 (on) or 2 (off)");
+        options().cache_schedule = value;
         return GP_OK;
     }
     if (!strcmp(name, "persistent_blocks")) {
@@ -146,6 +150,7 @@ int64_t gp_get_option(const char* name)
     if (!strcmp(name, "column_tile")) return options().column_tile;
     if (!strcmp(name, "column_slices")) return options().column_slices;
     if (!strcmp(name, "persistent_blocks")) return options().persistent_blocks;
+    if (!strcmp(name, "cache_schedule")) return options().cache_schedule;
     if (!strcmp(name, "lc_tile_rows")) return options().lc_tile_rows;
     if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
     return -1;

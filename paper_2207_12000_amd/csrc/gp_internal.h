@@ -30,6 +30,7 @@ struct Options {
     int64_t column_tile = 0;
     int64_t column_slices = 0;
     int64_t persistent_blocks = 0;
+    int64_t cache_schedule = 0;  // 0 = decided per plan, 1 = explicit per-XCD lists always, 2 = never
     int64_t lc_tile_rows = 0;  // 0 = chosen per call from the batch size
     int64_t hbm_budget_bytes = 0;
 };
@@ -43,7 +44,8 @@ void parallel_run(int nthreads, const std::function<void(int, int)>& fn);
 // One run of consecutive non-zeros of one row, inside one edge block.
 struct alignas(16) Segment {
     uint32_t start_lo;  // first non-zero (index into the sorted list), low 32 bits
-    uint16_t start_hi;  // bits 32..47
+    uint8_t start_hi;   // bits 32..39
+    uint8_t slice;      // column slice the record is for (explicit per-XCD work lists; 0 in the plan's own list)
     uint16_t len;       // number of non-zeros, 0 for a row without any
     int32_t row;        // destination row
     int32_t slot;       // -1: the run is the whole row, result goes to the output row
@@ -59,6 +61,22 @@ struct SplitRow {
     int64_t first_slot;
 };
 
+// Row clusters of the cache schedule (gp_cluster.cpp).
+struct RowClusters {
+    bool ready = false;
+    std::vector<int32_t> label;    // n: cluster of every row, clusters numbered 0 .. num-1
+    int32_t num = 0;
+    double inside_fraction = 0.0;  // share of the non-zeros whose source lies in the row's own cluster
+    double typical_rows = 0.0;     // rows in the cluster of a typical non-zero (non-zero-weighted mean size)
+};
+
+// Explicit per-XCD work lists on the device, for one slice shape.
+struct XcdWork {
+    int num_slices = 0, slice_elems = 0;
+    Segment* recs = nullptr;  // DEVICE
+    int64_t off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+};
+
 struct DevicePlan {
     int device = -1;
     int32_t* col = nullptr;
@@ -69,10 +87,12 @@ struct DevicePlan {
     float* edge_ws = nullptr;   // nnz: dinv_sqrt[col[e]], built on first use of the sym operator
     float* carry = nullptr;     // num_slots x carry_ld fp32
     int64_t carry_ld = 0;
+    unsigned long long* ctrl = nullptr;  // kHopCtrlWords words, zero between launches
     // scratch of gp_propagate_combine: two hop slabs and (bf16 storage) an fp32 accumulator
     void* ping[2] = {nullptr, nullptr};
     float* comb = nullptr;
     int64_t ping_bytes = 0, comb_elems = 0;
+    std::vector<XcdWork> work;  // explicit work lists built so far (one per slice shape)
 };
 
 }  // namespace gp
@@ -95,7 +115,10 @@ struct gp_plan {
     std::vector<gp::SplitRow> split;     // ascending row
     int64_t num_slots = 0;
 
+    gp::Options opt;  // the library options as they stood when the plan was made
+
     mutable std::mutex mu;
+    mutable gp::RowClusters clusters;  // made on first use (under mu)
     mutable gp::DevicePlan dev;
     // pinned host mirrors of col / segs for the streamed schedule (made on first use)
     mutable int32_t* pinned_col = nullptr;
@@ -108,6 +131,12 @@ struct gp_plan {
 namespace gp {
 
 gp_status build_schedule(gp_plan* plan);
+void cluster_rows(const gp_plan& P, RowClusters& C);
+void build_xcd_lists(const gp_plan& P, const RowClusters& C, int S, int slice_elems, int d, std::vector<Segment>& recs,
+                     int64_t off[9]);
+// Slice shape of the explicit work lists for rows of d elements in vectors of `vec`
+// (element size es), or false if this plan keeps the implicit lists.
+bool choose_cache_schedule(const gp_plan* plan, int32_t d, int es, int vec, int& num_slices, int& slice_elems);
 // fills plan->nnz, rowptr, col, deg from validated input pairs, on the current GPU
 gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64_t n, bool sym, bool loops, gp_plan* plan);
 
@@ -119,6 +148,7 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
                              gp_agg agg, int32_t K, void* out, int64_t ldo);
 
 // ---- kernel launchers (gp_kernels.hip) -------------------------------------
+constexpr int kHopCtrlWords = 16;
 struct HopArgs {
     const Segment* segs;    // DEVICE
     int64_t num_segs;
@@ -136,8 +166,20 @@ struct HopArgs {
     int64_t carry_ld;
     int32_t d;
     gp_dtype dtype;
-    int num_slices = 1;     // chosen by launch_hop
+    // DEVICE, kHopCtrlWords 64-bit words, zero between launches: the work cursors of the 8 XCDs
+    // and the count of finished lane groups.  Launches that share it must not overlap in time.
+    unsigned long long* ctrl = nullptr;
+    // work lists.  xcd_off == nullptr: implicit lists over segs[0 .. num_segs), the slice count
+    // chosen by launch_hop (column_slices: 1, 2, 4, 8 or 0 = automatic).  Otherwise HOST
+    // array of 9 offsets: XCD x walks records [xcd_off[x], xcd_off[x+1]) of segs, each record
+    // naming its slice; num_slices / slice_elems are then the caller's (slice_elems a
+    // multiple of hop_vector_width()).
+    const int64_t* xcd_off = nullptr;
+    int num_slices = 1;
     int slice_elems = 0;
+    int64_t column_slices = 0;
+    int64_t persistent_blocks = 0;  // workgroups of the launch, 0 = as many as stay resident
+    int64_t column_tile = 0;        // feature columns per kernel pass, 0 = automatic
     // optional running combination: comb[row] += gamma * result row (fp32, leading dimension ldc);
     // xout may then be nullptr (result row not stored)
     float* comb = nullptr;
@@ -145,6 +187,8 @@ struct HopArgs {
     float gamma = 0.0f;
 };
 gp_status launch_hop(const HopArgs& a, hipStream_t stream);
+// widest vector (in elements) the operands of this launch are aligned for
+int hop_vector_width(const HopArgs& a);
 
 struct FixupArgs {
     const SplitRow* split;  // DEVICE
@@ -159,6 +203,7 @@ struct FixupArgs {
     float* comb = nullptr;  // as in HopArgs
     int64_t ldc = 0;
     float gamma = 0.0f;
+    int64_t column_tile = 0;
 };
 gp_status launch_fixup(const FixupArgs& a, hipStream_t stream);
 

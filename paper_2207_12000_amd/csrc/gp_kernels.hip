@@ -167,28 +167,49 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 struct SegRegs {
     int64_t e0;  // first non-zero, relative to the column buffer
-    int len, row, slot;
+    int len, row, slot, slice;
 };
 
 __device__ __forceinline__ SegRegs unpack_segment(const v4i raw, int64_t col_base)
 {
     SegRegs s;
-    s.e0 = (((int64_t)((uint32_t)raw[1] & 0xFFFFu) << 32) | (int64_t)(uint32_t)raw[0]) - col_base;
+    s.e0 = (((int64_t)((uint32_t)raw[1] & 0xFFu) << 32) | (int64_t)(uint32_t)raw[0]) - col_base;
+    s.slice = (int)(((uint32_t)raw[1] >> 8) & 0xFFu);
     s.len = (int)((uint32_t)raw[1] >> 16);
     s.row = raw[2];
     s.slot = raw[3];
     return s;
 }
 
-// Lane groups are persistent: group q of a slice walks segments q, q + stride,
-// q + 2*stride, ... of the (longest-first) list.  The index stream is software
-// pipelined in registers so that the only memory round trip a segment waits for
-// is its row gathers: the record of segment i+2 and the first WIN column ids of
-// segment i+1 are requested while segment i is gathered.
+// Lane groups are persistent.  Each of the 8 XCDs (workgroups are handed to them
+// round-robin by id) walks a work list of its own: in the implicit form XCD x takes
+// column slice x mod num_slices of every record, the XCDs that share a slice taking
+// the records interleaved; in the explicit form the host has written one list per
+// XCD (records [off[x], off[x+1]) of `segs`), each record naming its column slice, so
+// that what an XCD's private L2 must hold at any time -- the source rows its current
+// records draw from, one slice wide -- is the host's choice (Algorithm 1's cut into
+// column blocks and edge blocks, used as a cache schedule).  Group q of an XCD takes
+// positions q, q + stride, ... of that XCD's list.  The index stream is software
+// pipelined in registers so that the only memory round trip a record waits for is
+// its row gathers: the record two positions ahead and the first WIN column ids of the
+// next one are requested while the current one is gathered.
 // EDGE_W: 0 = every weight is 1; 1 = weight gathered from an n-vector by column id;
 // 2 = weight read from a per-edge array laid out like the column list.
+struct XcdLists {
+    int64_t off[9];
+    int explicit_lists;
+};
+
+// Work is handed out record by record from one cursor per XCD (ctrl[0..8)), so that all
+// lane groups of an XCD work inside a narrow window of its list whatever their speeds:
+// with fixed shares the groups drift apart and the window -- what the L2 has to hold --
+// grows to many times the intended size.  A group keeps three tickets in flight (the
+// record it gathers, the next one whose column ids it has requested, and the one after
+// whose record it has requested).  ctrl[8] counts the groups that are done; the last one
+// puts all nine words back to zero, so the buffer is zero between launches.
 template <typename T, int VEC, int G, int VPL, int EDGE_W>
 __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __restrict__ segs, int64_t num_segs,
+                                                            const XcdLists lists, unsigned long long* __restrict__ ctrl,
                                                             const int32_t* __restrict__ col, int64_t col_base,
                                                             const float* __restrict__ edge_w,
                                                             const float* __restrict__ row_scale,
@@ -206,32 +227,35 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     // tolerates longer chains and its 8-element vectors are register hungry
     constexpr int NACC = sizeof(T) == 2 ? 2 : 4;
     const int lane = threadIdx.x % G;
-    // Workgroups are handed to the 8 XCDs round-robin by id.  Each XCD works on one
-    // column slice of X only (slice = xcd mod num_slices), so its private L2 caches
-    // num_slices times more distinct rows; the XCDs that share a slice split the
-    // segment list between them.  num_slices is 1, 2, 4 or 8.
     const int xcd = blockIdx.x & 7;
-    const int slice = xcd & (num_slices - 1);
-    const int reps = 8 / num_slices;
-    const int64_t q = ((int64_t)(blockIdx.x >> 3) * reps + xcd / num_slices) * GPB + threadIdx.x / G;
-    const int64_t stride = (int64_t)(gridDim.x >> 3) * reps * GPB;
-    if (q >= num_segs) return;
-    const int cbase = slice * slice_elems;
-    const int cend = min(d, cbase + slice_elems);
-
-    // column offsets of this lane's vectors; a vector is live if it starts inside the slice
-    bool live[VPL];
-    int coff[VPL];
-#pragma unroll
-    for (int v = 0; v < VPL; ++v) {
-        coff[v] = cbase + (v * G + lane) * VEC;
-        live[v] = coff[v] < cend;
+    // this XCD's list: record of position p is segs[base + p * rstep], p < count
+    int64_t base, count;
+    int rstep, xcd_slice;
+    if (lists.explicit_lists) {
+        base = lists.off[xcd];
+        count = lists.off[xcd + 1] - base;
+        rstep = 1;
+        xcd_slice = -1;  // every record names its slice
+    } else {
+        const int reps = 8 / num_slices;  // num_slices is 1, 2, 4 or 8 here
+        base = xcd / num_slices;
+        count = num_segs > base ? (num_segs - base + reps - 1) / reps : 0;
+        rstep = reps;
+        xcd_slice = xcd & (num_slices - 1);
     }
+    // next position of this XCD's list (one atomic per group, result shared inside the group)
+    auto take = [&]() -> int64_t {
+        unsigned long long t = 0;
+        if (lane == 0) t = atomicAdd(ctrl + xcd, 1ULL);
+        const unsigned lo = __shfl((unsigned)t, 0, G), hi = __shfl((unsigned)(t >> 32), 0, G);
+        return (int64_t)(((unsigned long long)hi << 32) | lo);
+    };
 
-    const v4i* sp = reinterpret_cast<const v4i*>(segs);
+    const v4i* sp = reinterpret_cast<const v4i*>(segs) + base;
     const v4i none = {0, 0, 0, -1};  // length 0: nothing to fetch
-    SegRegs s0 = unpack_segment(sp[q], col_base);
-    v4i raw1 = q + stride < num_segs ? sp[q + stride] : none;
+    int64_t t0 = take(), t1 = take(), t2 = take();
+    SegRegs s0 = unpack_segment(t0 < count ? sp[t0 * rstep] : none, col_base);
+    v4i raw1 = t1 < count ? sp[t1 * rstep] : none;
     int c0[PF];
     float w0[PF];
 #pragma unroll
@@ -241,10 +265,11 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         w0[j] = (EDGE_W == 2 && in) ? edge_w[s0.e0 + j * G + lane] : 0.0f;
     }
 
-    for (int64_t s = q; s < num_segs; s += stride) {
+    while (t0 < count) {
         // ---- requests for the segments to come -----------------------------------
+        const int64_t t3 = take();
         const SegRegs s1 = unpack_segment(raw1, col_base);
-        const v4i raw2 = s + 2 * stride < num_segs ? sp[s + 2 * stride] : none;
+        const v4i raw2 = t2 < count ? sp[t2 * rstep] : none;
         int c1[PF];
         float w1[PF];
 #pragma unroll
@@ -255,6 +280,16 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         }
 
         // ---- this segment ----------------------------------------------------------
+        // column offsets of this lane's vectors; a vector is live if it starts inside the slice
+        const int cbase = (xcd_slice >= 0 ? xcd_slice : s0.slice) * slice_elems;
+        const int cend = min(d, cbase + slice_elems);
+        bool live[VPL];
+        int coff[VPL];
+#pragma unroll
+        for (int v = 0; v < VPL; ++v) {
+            coff[v] = cbase + (v * G + lane) * VEC;
+            live[v] = coff[v] < cend;
+        }
         float acc[NACC][VPL][VEC];
 #pragma unroll
         for (int u = 0; u < NACC; ++u)
@@ -350,6 +385,20 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         for (int j = 0; j < PF; ++j) {
             c0[j] = c1[j];
             w0[j] = w1[j];
+        }
+        t0 = t1;
+        t1 = t2;
+        t2 = t3;
+    }
+
+    // every ticket this group asked for has been answered by now; the last group to get
+    // here puts the cursors back to zero for the next launch
+    if (lane == 0) {
+        const unsigned long long groups = (unsigned long long)gridDim.x * GPB;
+        if (atomicAdd(ctrl + 8, 1ULL) == groups - 1) {
+            __threadfence();
+#pragma unroll
+            for (int i = 0; i < 9; ++i) atomicExch(ctrl + i, 0ULL);
         }
     }
 }
@@ -483,10 +532,22 @@ template <typename T, int VEC, int G, int VPL>
 gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
 {
     constexpr int GPB = kThreads / G;
-    const int64_t chunks = (a.num_segs + GPB - 1) / GPB;
+    XcdLists lists;
+    int64_t longest = 0;  // records in the longest per-XCD list
+    if (a.xcd_off) {
+        for (int x = 0; x <= 8; ++x) lists.off[x] = a.xcd_off[x];
+        for (int x = 0; x < 8; ++x) longest = std::max(longest, lists.off[x + 1] - lists.off[x]);
+        lists.explicit_lists = 1;
+    } else {
+        for (int x = 0; x <= 8; ++x) lists.off[x] = 0;
+        const int reps = 8 / a.num_slices;  // XCDs that share one slice
+        longest = (a.num_segs + reps - 1) / reps;
+        lists.explicit_lists = 0;
+    }
+    const int64_t chunks = (longest + GPB - 1) / GPB;  // workgroups per XCD that find work
     if (chunks == 0) return GP_OK;
-    const int reps = 8 / a.num_slices;  // XCDs that share one slice
-    // persistent lane groups: as many workgroups as stay resident, fewer if the list is short
+    if (!a.ctrl) return fail(GP_ERR_INVALID_ARG, "hop launch without its cursor buffer");
+    // persistent lane groups: as many workgroups as stay resident, fewer if the lists are short
     static const int resident = [] {
         int per_cu = 0, dev = 0;
         hipDeviceProp_t prop;
@@ -496,20 +557,20 @@ gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
             return 2048;
         return per_cu * prop.multiProcessorCount;
     }();
-    int64_t persist = options().persistent_blocks > 0 ? options().persistent_blocks : resident;
+    int64_t persist = a.persistent_blocks > 0 ? a.persistent_blocks : resident;
     persist = (persist + 7) / 8 * 8;
-    const int64_t blocks = std::min<int64_t>(persist, 8 * ((chunks + reps - 1) / reps));
+    const int64_t blocks = std::min<int64_t>(persist, 8 * chunks);
     const dim3 grid((unsigned)blocks), block(kThreads);
     if (a.edge_w && a.edge_w_per_edge)
-        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 2>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 2>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
                            a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
     else if (a.edge_w)
-        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 1>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 1>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
                            a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
     else
-        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 0>), grid, block, 0, stream, a.segs, a.num_segs, a.col,
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 0>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
                            a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
     GP_HIP(hipGetLastError());
@@ -565,26 +626,47 @@ inline void group_shape(int32_t d, int vec, int& G, int& vpl)
 
 int max_columns_per_pass(int vec) { return 64 * max_vpl(vec) * vec; }
 
-gp_status launch_hop(const HopArgs& a_in, hipStream_t stream)
+int hop_vector_width(const HopArgs& a)
 {
-    HopArgs a = a_in;
     // carry rows are fp32 and 16-byte aligned by construction (carry_ld % 4 == 0)
     int vec = vector_width(a.dtype, a.d, a.ldin, a.xout ? a.ldout : a.ldin, a.xin, a.xout ? a.xout : a.xin);
     if (a.comb) vec = std::min(vec, vector_width(GP_F32, a.d, a.ldc, a.ldc, a.comb, a.comb));
+    return vec;
+}
+
+// Column slices of the implicit work lists: each XCD's private L2 then sees only 1/S of
+// every row and holds S times more distinct rows.  Measured on MI355X on graphs whose
+// reuse comes from popular rows only: two slices pay for rows of 512 .. 1023 bytes (a slice
+// is still >= 256 contiguous bytes); narrower slices lose more to the smaller requests and
+// to the repeated per-record work than they gain in hits, and wider rows are best gathered whole.
+int implicit_slices(const HopArgs& a, int vec)
+{
     const int es = a.dtype == GP_F32 ? 4 : 2;
     const int nvec = (a.d + vec - 1) / vec;
-    // column slices: measured on MI355X, two slices pay for rows of 512 .. 1023 bytes
-    // (each XCD's L2 then keeps twice as many distinct rows and a slice is still
-    // >= 256 contiguous bytes); narrower slices lose more to the smaller requests
-    // than they gain in hits, and wider rows are best gathered whole.
-    int S = (int)options().column_slices;
+    int S = (int)a.column_slices;
     if (S != 1 && S != 2 && S != 4 && S != 8) {
         const int64_t row_bytes = (int64_t)a.d * es;
         S = (row_bytes >= 512 && row_bytes < 1024) ? 2 : 1;
     }
     while (S > 1 && nvec < S) S /= 2;
-    a.num_slices = S;
-    a.slice_elems = (nvec + S - 1) / S * vec;
+    return S;
+}
+
+gp_status launch_hop(const HopArgs& a_in, hipStream_t stream)
+{
+    HopArgs a = a_in;
+    const int vec = hop_vector_width(a);
+    const int nvec = (a.d + vec - 1) / vec;
+    if (a.xcd_off) {
+        // explicit lists: the caller fixed the slices when it wrote the records
+        if (a.num_slices < 1 || a.num_slices > 255 || a.slice_elems <= 0 || a.slice_elems % vec != 0 ||
+            (int64_t)a.num_slices * a.slice_elems < a.d)
+            return fail(GP_ERR_INVALID_ARG, "work lists do not fit the launch (slices %d x %d elements, d %d, vec %d)",
+                        a.num_slices, a.slice_elems, a.d, vec);
+    } else {
+        a.num_slices = implicit_slices(a, vec);
+        a.slice_elems = (nvec + a.num_slices - 1) / a.num_slices * vec;
+    }
     int G, vpl;
     group_shape(a.slice_elems, vec, G, vpl);
     if (vpl > max_vpl(vec)) return fail(GP_ERR_UNSUPPORTED, "d = %d needs column tiling (vec = %d)", a.d, vec);

@@ -72,8 +72,8 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
     if (flags & ~(uint32_t)(GP_SYMMETRISE | GP_ADD_SELF_LOOPS | GP_PLAN_ON_DEVICE))
         return fail(GP_ERR_INVALID_ARG, "unknown plan flag 0x%x", flags);
     const bool sym = flags & GP_SYMMETRISE, loops = flags & GP_ADD_SELF_LOOPS;
-    // every candidate count must stay far inside int64 and the 48-bit segment start
-    if (m > (INT64_C(1) << 46)) return fail(GP_ERR_OVERFLOW, "m = %lld is too large", (long long)m);
+    // every candidate count must stay far inside int64 and the 40-bit segment start
+    if (m > (INT64_C(1) << 38)) return fail(GP_ERR_OVERFLOW, "m = %lld is too large", (long long)m);
 
     const int nt = (m + n < (1 << 16)) ? 1 : host_threads();
     gp_plan* plan = nullptr;
@@ -81,6 +81,7 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
         plan = new gp_plan();
         plan->n = n;
         plan->flags = flags;
+        plan->opt = options();
 
         // 1. validate
         std::atomic<int64_t> bad{-1};
@@ -172,9 +173,9 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
             plan->rowptr.assign((size_t)n + 1, 0);
             for (int64_t i = 0; i < n; ++i) plan->rowptr[i + 1] = plan->rowptr[i] + plan->deg[i];
             const int64_t nnz = plan->rowptr[n];
-            if (nnz >= (INT64_C(1) << 47)) {
+            if (nnz >= (INT64_C(1) << 40)) {
                 delete plan;
-                return fail(GP_ERR_OVERFLOW, "non-zero count %lld exceeds the 47-bit list index", (long long)nnz);
+                return fail(GP_ERR_OVERFLOW, "non-zero count %lld exceeds the 40-bit list index", (long long)nnz);
             }
             plan->nnz = nnz;
             plan->col.resize((size_t)nnz);
@@ -232,7 +233,7 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
         // so it must stay short against the whole hop: about nnz / 65536, kept within
         // 64 .. 1024 (small graphs: split hubs finely; large graphs: split rarely, so
         // few rows need partial sums).
-        int64_t L = options().segment_edges;
+        int64_t L = plan->opt.segment_edges;
         if (L <= 0) {
             L = 64;
             while (L < 1024 && L * 2 <= nnz / 65536) L *= 2;

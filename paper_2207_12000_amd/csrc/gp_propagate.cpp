@@ -29,9 +29,11 @@ void release(DevicePlan& D)
     (void)hipFree(D.split);
     (void)hipFree(D.carry);
     (void)hipFree(D.edge_ws);
+    (void)hipFree(D.ctrl);
     (void)hipFree(D.ping[0]);
     (void)hipFree(D.ping[1]);
     (void)hipFree(D.comb);
+    for (XcdWork& w : D.work) (void)hipFree(w.recs);
     D = DevicePlan();
 }
 
@@ -52,6 +54,11 @@ gp_status ensure_device(const gp_plan* plan, int32_t d, bool want_edge_weights, 
             (st = upload(D.split, plan->split, stream)) != GP_OK) {
             release(D);
             return st;
+        }
+        if (hipMalloc((void**)&D.ctrl, kHopCtrlWords * sizeof(unsigned long long)) != hipSuccess ||
+            hipMemsetAsync(D.ctrl, 0, kHopCtrlWords * sizeof(unsigned long long), stream) != hipSuccess) {
+            release(D);
+            return fail(GP_ERR_OOM_DEVICE, "cursor buffer of the hop kernel");
         }
         // pageable sources: the copies above are staged, but finish them before returning
         // so the host vectors may be touched freely afterwards
@@ -81,15 +88,112 @@ gp_status ensure_device(const gp_plan* plan, int32_t d, bool want_edge_weights, 
 // width of one kernel pass over the columns: everything at once unless the row is
 // wider than the kernels hold; a pass is a multiple of 16 bytes so every pass keeps
 // the alignment of the first
-int64_t pass_width(gp_dtype dtype, int32_t d, int64_t lda, int64_t ldb, const void* pa, const void* pb)
+int64_t pass_width(int64_t tile, gp_dtype dtype, int32_t d, int64_t lda, int64_t ldb, const void* pa, const void* pb)
 {
     const int es = dtype == GP_F32 ? 4 : 2;
     const int64_t unit = 16 / es;
     const int64_t cap = max_columns_per_pass(vector_width(dtype, d, lda, ldb, pa, pb));
-    int64_t tile = options().column_tile;
     if (tile <= 0 || tile > cap) tile = d <= cap ? d : cap;
     if (tile < d) tile = std::max<int64_t>(unit, tile / unit * unit);
     return tile;
+}
+
+// Decides whether this plan's hops run from explicit per-XCD work lists and with which
+// slice shape.  The lists pay when the rows of a cluster draw most of their sources
+// from the cluster itself and one slice of a cluster's rows fits the share of an XCD's
+// L2 that the streams beside it (column ids, written rows, sources outside the cluster)
+// leave free.  A slice is at least 128 bytes (one cache line) wide.
+constexpr double kL2Share = 0.6;
+constexpr int64_t kLineBytes = 128;
+
+int64_t l2_bytes_per_xcd()
+{
+    static const int64_t v = [] {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return (int64_t)4 << 20;
+        const int64_t l2 = prop.l2CacheSize;
+        return (l2 >= (1 << 20) && l2 <= (64 << 20)) ? l2 : (int64_t)4 << 20;
+    }();
+    return v;
+}
+
+}  // namespace
+
+bool choose_cache_schedule(const gp_plan* plan, int32_t d, int es, int vec, int& num_slices, int& slice_elems)
+{
+    if (plan->opt.cache_schedule == 2 || plan->segs.empty()) return false;
+    const bool forced = plan->opt.cache_schedule == 1;
+    if (!plan->clusters.ready) cluster_rows(*plan, plan->clusters);
+    const RowClusters& C = plan->clusters;
+    if (!forced && (C.num < 2 || C.inside_fraction < 0.5)) return false;
+    const int nvec = (d + vec - 1) / vec;
+    const int64_t vec_bytes = (int64_t)vec * es;
+    int S = 0;
+    if (plan->opt.column_slices > 0) {
+        S = (int)std::min<int64_t>(plan->opt.column_slices, nvec);
+    } else {
+        const double room = kL2Share * (double)l2_bytes_per_xcd();
+        for (int s = 1; s <= 16 && s <= nvec; ++s) {
+            const int64_t bytes = (int64_t)((nvec + s - 1) / s) * vec_bytes;
+            if (s > 1 && bytes < kLineBytes) break;
+            // a slice of a row that does not start on a line boundary touches one more line
+            if (C.typical_rows * (double)(bytes + kLineBytes - vec_bytes) <= room) {
+                S = s;
+                break;
+            }
+        }
+        if (S == 0) {
+            if (!forced) return false;
+            S = std::min(nvec, 8);
+        }
+    }
+    const int slice_vecs = (nvec + S - 1) / S;
+    num_slices = (nvec + slice_vecs - 1) / slice_vecs;
+    slice_elems = slice_vecs * vec;
+    return true;
+}
+
+namespace {
+
+// Gives the launch explicit work lists if the plan's cache schedule applies to it
+// (building and uploading them on first use of a slice shape).
+gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream)
+{
+    const int es = a.dtype == GP_F32 ? 4 : 2;
+    const int vec = hop_vector_width(a);
+    // several column passes: implicit lists (explicit ones are cut for the whole row)
+    if (pass_width(a.column_tile, a.dtype, a.d, a.ldin, a.xout ? a.ldout : a.ldin, a.xin, a.xout ? a.xout : a.xin) < a.d)
+        return GP_OK;
+    std::lock_guard<std::mutex> lk(plan->mu);
+    int S = 0, elems = 0;
+    if (!choose_cache_schedule(plan, a.d, es, vec, S, elems)) return GP_OK;
+    DevicePlan& D = plan->dev;
+    const XcdWork* found = nullptr;
+    for (const XcdWork& w : D.work)
+        if (w.num_slices == S && w.slice_elems == elems) found = &w;
+    if (!found) {
+        std::vector<Segment> recs;
+        XcdWork w;
+        w.num_slices = S;
+        w.slice_elems = elems;
+        build_xcd_lists(*plan, plan->clusters, S, elems, a.d, recs, w.off);
+        GP_HIP(hipMalloc((void**)&w.recs, recs.size() * sizeof(Segment)));
+        hipError_t e = hipMemcpyAsync(w.recs, recs.data(), recs.size() * sizeof(Segment), hipMemcpyHostToDevice, stream);
+        if (e == hipSuccess) e = hipStreamSynchronize(stream);  // pageable source: done before `recs` goes away
+        if (e != hipSuccess) {
+            (void)hipFree(w.recs);
+            return fail(GP_ERR_DEVICE, "upload of the work lists failed: %s", hipGetErrorString(e));
+        }
+        D.work.push_back(w);
+        found = &D.work.back();
+    }
+    a.segs = found->recs;
+    a.num_segs = found->off[8];
+    a.xcd_off = found->off;
+    a.num_slices = found->num_slices;
+    a.slice_elems = found->slice_elems;
+    return GP_OK;
 }
 
 }  // namespace
@@ -97,7 +201,7 @@ int64_t pass_width(gp_dtype dtype, int32_t d, int64_t lda, int64_t ldb, const vo
 gp_status hop_passes(const HopArgs& a0, hipStream_t stream)
 {
     const int es = a0.dtype == GP_F32 ? 4 : 2;
-    const int64_t tile = pass_width(a0.dtype, a0.d, a0.ldin, a0.xout ? a0.ldout : a0.ldin, a0.xin, a0.xout ? a0.xout : a0.xin);
+    const int64_t tile = pass_width(a0.column_tile, a0.dtype, a0.d, a0.ldin, a0.xout ? a0.ldout : a0.ldin, a0.xin, a0.xout ? a0.xout : a0.xin);
     for (int64_t c0 = 0; c0 < a0.d; c0 += tile) {
         HopArgs a = a0;
         a.d = (int32_t)std::min<int64_t>(tile, a0.d - c0);
@@ -106,6 +210,7 @@ gp_status hop_passes(const HopArgs& a0, hipStream_t stream)
         a.carry = a0.carry ? a0.carry + c0 : nullptr;
         a.xout = a0.xout ? (char*)a0.xout + c0 * es : nullptr;
         a.comb = a0.comb ? a0.comb + c0 : nullptr;
+        if (tile < a0.d && a0.xcd_off) return fail(GP_ERR_INVALID_ARG, "explicit work lists need a single column pass");
         profile_begin("gp_hop_segments", stream);
         gp_status st = launch_hop(a, stream);
         profile_end(stream);
@@ -117,8 +222,8 @@ gp_status hop_passes(const HopArgs& a0, hipStream_t stream)
 gp_status fixup_passes(const FixupArgs& f0, hipStream_t stream)
 {
     const int es = f0.dtype == GP_F32 ? 4 : 2;
-    const int64_t tile = f0.xout ? pass_width(f0.dtype, f0.d, f0.ldout, f0.ldout, f0.xout, f0.xout)
-                                 : pass_width(GP_F32, f0.d, f0.ldc, f0.ldc, f0.comb, f0.comb);
+    const int64_t tile = f0.xout ? pass_width(f0.column_tile, f0.dtype, f0.d, f0.ldout, f0.ldout, f0.xout, f0.xout)
+                                 : pass_width(f0.column_tile, GP_F32, f0.d, f0.ldc, f0.ldc, f0.comb, f0.comb);
     for (int64_t c0 = 0; c0 < f0.d; c0 += tile) {
         FixupArgs f = f0;
         f.d = (int32_t)std::min<int64_t>(tile, f0.d - c0);
@@ -171,8 +276,13 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
         a.ldout = ldo;
         a.carry = D.carry;
         a.carry_ld = D.carry_ld;
+        a.ctrl = D.ctrl;
         a.d = d;
         a.dtype = dtype;
+        a.column_slices = plan->opt.column_slices;
+        a.persistent_blocks = plan->opt.persistent_blocks;
+        a.column_tile = plan->opt.column_tile;
+        if ((st = attach_work_lists(plan, a, stream)) != GP_OK) return st;
         if ((st = hop_passes(a, stream)) != GP_OK) return st;
         if (!plan->split.empty()) {
             FixupArgs f;
@@ -185,6 +295,7 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
             f.ldout = ldo;
             f.d = d;
             f.dtype = dtype;
+            f.column_tile = plan->opt.column_tile;
             if ((st = fixup_passes(f, stream)) != GP_OK) return st;
         }
     }
@@ -252,11 +363,16 @@ gp_status propagate_combine(const gp_plan* plan, const void* X, int64_t ldx, int
         a.ldout = ldp;
         a.carry = D.carry;
         a.carry_ld = D.carry_ld;
+        a.ctrl = D.ctrl;
         a.d = d;
         a.dtype = dtype;
+        a.column_slices = plan->opt.column_slices;
+        a.persistent_blocks = plan->opt.persistent_blocks;
+        a.column_tile = plan->opt.column_tile;
         a.comb = comb;
         a.ldc = ldc;
         a.gamma = coeff[k];
+        if ((st = attach_work_lists(plan, a, stream)) != GP_OK) return st;
         if ((st = hop_passes(a, stream)) != GP_OK) return st;
         if (!plan->split.empty()) {
             FixupArgs f;
@@ -269,6 +385,7 @@ gp_status propagate_combine(const gp_plan* plan, const void* X, int64_t ldx, int
             f.ldout = ldp;
             f.d = d;
             f.dtype = dtype;
+            f.column_tile = plan->opt.column_tile;
             f.comb = comb;
             f.ldc = ldc;
             f.gamma = coeff[k];
@@ -288,16 +405,64 @@ gp_status propagate_combine(const gp_plan* plan, const void* X, int64_t ldx, int
 
 using namespace gp;
 
+extern "C" gp_status gp_plan_row_clusters(const gp_plan* plan, int32_t* label, int32_t* num_clusters, double* inside_fraction,
+                                          double* typical_rows)
+{
+    if (!plan) return fail(GP_ERR_INVALID_ARG, "plan is NULL");
+    try {
+        std::lock_guard<std::mutex> lk(plan->mu);
+        if (!plan->clusters.ready) cluster_rows(*plan, plan->clusters);
+        const RowClusters& C = plan->clusters;
+        if (label) std::copy(C.label.begin(), C.label.end(), label);
+        if (num_clusters) *num_clusters = C.num;
+        if (inside_fraction) *inside_fraction = C.inside_fraction;
+        if (typical_rows) *typical_rows = C.typical_rows;
+    } catch (const std::exception& e) {
+        return fail(GP_ERR_OOM_HOST, "gp_plan_row_clusters: %s", e.what());
+    }
+    return GP_OK;
+}
+
+extern "C" gp_status gp_plan_work_lists(const gp_plan* plan, int32_t d, gp_dtype dtype, int32_t vec, int32_t* num_slices,
+                                        int32_t* slice_elems, int64_t* xcd_off, void* records, int64_t capacity)
+{
+    if (!plan || !num_slices || !slice_elems || !xcd_off) return fail(GP_ERR_INVALID_ARG, "NULL argument");
+    if (d <= 0 || (dtype != GP_F32 && dtype != GP_BF16)) return fail(GP_ERR_INVALID_ARG, "bad d or dtype");
+    const int es = dtype == GP_F32 ? 4 : 2;
+    if (vec != 1 && vec != 2 && vec != 4 && !(vec == 8 && es == 2)) return fail(GP_ERR_INVALID_ARG, "vec = %d is no vector width", vec);
+    try {
+        std::lock_guard<std::mutex> lk(plan->mu);
+        int S = 0, elems = 0;
+        *num_slices = 0;
+        *slice_elems = 0;
+        for (int x = 0; x <= 8; ++x) xcd_off[x] = 0;
+        if (!choose_cache_schedule(plan, d, es, vec, S, elems)) return GP_OK;  // implicit lists
+        std::vector<Segment> recs;
+        build_xcd_lists(*plan, plan->clusters, S, elems, d, recs, xcd_off);
+        *num_slices = S;
+        *slice_elems = elems;
+        if (records) {
+            if (capacity < (int64_t)recs.size())
+                return fail(GP_ERR_INVALID_ARG, "records has room for %lld of %lld", (long long)capacity, (long long)recs.size());
+            std::copy(recs.begin(), recs.end(), (Segment*)records);
+        }
+    } catch (const std::exception& e) {
+        return fail(GP_ERR_OOM_HOST, "gp_plan_work_lists: %s", e.what());
+    }
+    return GP_OK;
+}
+
 extern "C" void gp_plan_destroy(gp_plan* plan)
 {
     if (!plan) return;
     if (plan->dev.device >= 0) {
+        const int home = plan->dev.device;  // release() resets the record
         int cur = -1;
         if (hipGetDevice(&cur) == hipSuccess) {
-            if (cur != plan->dev.device) (void)hipSetDevice(plan->dev.device);
+            if (cur != home) (void)hipSetDevice(home);
             (void)hipDeviceSynchronize();
             release(plan->dev);
-            if (cur != plan->dev.device && cur >= 0) (void)hipSetDevice(cur);
+            if (cur != home && cur >= 0) (void)hipSetDevice(cur);
         }
     }
     release_pinned(plan);

@@ -155,7 +155,8 @@ gp_status build_schedule(gp_plan* plan)
             cut.walk(p, [&](int64_t r, int64_t s, int64_t len, int64_t idx) {
                 Segment g;
                 g.start_lo = (uint32_t)(s & 0xFFFFFFFF);
-                g.start_hi = (uint16_t)(s >> 32);
+                g.start_hi = (uint8_t)(s >> 32);
+                g.slice = 0;
                 g.len = (uint16_t)len;
                 g.row = (int32_t)r;
                 const int64_t fs = first_slot_of((int32_t)r);

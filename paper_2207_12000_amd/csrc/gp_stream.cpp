@@ -202,6 +202,7 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
     Streams S;
     if ((st = S.init((int)nbuf)) != GP_OK) return st;
     float *d_dinv_sqrt, *d_dinv, *d_carry;
+    unsigned long long* d_ctrl;
     SplitRow* d_split;
     char* d_slab[2];
     std::vector<int32_t*> d_col((size_t)nbuf, nullptr);
@@ -209,12 +210,14 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
     if ((st = S.alloc(d_dinv_sqrt, (size_t)n * 4)) != GP_OK || (st = S.alloc(d_dinv, (size_t)n * 4)) != GP_OK ||
         (st = S.alloc(d_split, plan->split.size() * sizeof(SplitRow))) != GP_OK ||
         (st = S.alloc(d_carry, (size_t)plan->num_slots * wpad * 4)) != GP_OK ||
+        (st = S.alloc(d_ctrl, kHopCtrlWords * sizeof(unsigned long long))) != GP_OK ||
         (st = S.alloc(d_slab[0], (size_t)n * w * es)) != GP_OK || (st = S.alloc(d_slab[1], (size_t)n * w * es)) != GP_OK)
         return st;
     for (int64_t i = 0; i < nbuf; ++i)
         if ((st = S.alloc(d_col[i], (size_t)max_edges * 4)) != GP_OK ||
             (st = S.alloc(d_segs[i], (size_t)max_segs * sizeof(Segment))) != GP_OK)
             return st;
+    GP_HIP(hipMemsetAsync(d_ctrl, 0, kHopCtrlWords * sizeof(unsigned long long), S.cmp));
     // small vectors: pageable sources, so these two copies are synchronous in effect
     GP_HIP(hipMemcpyAsync(d_dinv_sqrt, plan->dinv_sqrt.data(), (size_t)n * 4, hipMemcpyHostToDevice, S.cmp));
     GP_HIP(hipMemcpyAsync(d_dinv, plan->dinv.data(), (size_t)n * 4, hipMemcpyHostToDevice, S.cmp));
@@ -293,8 +296,12 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
                 a.ldout = w;
                 a.carry = d_carry;
                 a.carry_ld = wpad;
+                a.ctrl = d_ctrl;
                 a.d = wc;
                 a.dtype = dtype;
+                a.column_slices = plan->opt.column_slices <= 8 ? plan->opt.column_slices : 0;
+                a.persistent_blocks = plan->opt.persistent_blocks;
+                a.column_tile = plan->opt.column_tile;
                 if ((st = hop_passes(a, S.cmp)) != GP_OK) return st;
                 GP_HIP(hipEventRecord(S.blk_free[buf], S.cmp));
                 blk_used[buf] = 1;
@@ -312,6 +319,7 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
                     f.ldout = w;
                     f.d = wc;
                     f.dtype = dtype;
+                    f.column_tile = plan->opt.column_tile;
                     if ((st = fixup_passes(f, S.cmp)) != GP_OK) return st;
                     split_done = split_to;
                 }
