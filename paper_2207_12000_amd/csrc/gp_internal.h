@@ -72,7 +72,7 @@ struct RowClusters {
 
 // Explicit per-XCD work lists on the device, for one slice shape.
 struct XcdWork {
-    int num_slices = 0, slice_elems = 0;
+    int num_slices = 0, slice_elems = 0, chunk_records = 1;
     Segment* recs = nullptr;  // DEVICE
     int64_t off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
 };
@@ -175,6 +175,7 @@ struct HopArgs {
     // naming its slice; num_slices / slice_elems are then the caller's (slice_elems a
     // multiple of hop_vector_width()).
     const int64_t* xcd_off = nullptr;
+    int chunk_records = 1;  // explicit lists: consecutive records handed out per request
     int num_slices = 1;
     int slice_elems = 0;
     int64_t column_slices = 0;

@@ -23,9 +23,13 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kUnroll = 4;
 
+// Vectors of N elements that need no more than 4-byte alignment: gfx950 loads and stores
+// 8 and 16 bytes per lane from any dword boundary, so rows need not start on a multiple
+// of the vector size (a row of 602 floats is 2408 bytes: every other row starts 8 bytes
+// off a 16-byte boundary).
 template <typename E, int N>
 struct VecOf {
-    typedef E type __attribute__((ext_vector_type(N)));
+    typedef E type __attribute__((ext_vector_type(N), aligned(N * sizeof(E) < 4 ? N * sizeof(E) : 4)));
 };
 template <typename E>
 struct VecOf<E, 1> {
@@ -41,15 +45,6 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
     if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
-}
-
-template <typename V, int N>
-__device__ __forceinline__ auto elem(const V& v, int i)
-{
-    if constexpr (N == 1)
-        return v;
-    else
-        return v[i];
 }
 
 // Row<T, VEC>: one aligned VEC-element vector of a feature row, widened to fp32.
@@ -73,15 +68,23 @@ struct Row<float, VEC> {
     }
     __device__ static __forceinline__ void widen(const V& t, float (&x)[VEC])
     {
+        if constexpr (VEC == 1) {
+            x[0] = t;
+        } else {
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) x[i] = elem<V, VEC>(t, i);
+            for (int i = 0; i < VEC; ++i) x[i] = t[i];
+        }
     }
     __device__ static __forceinline__ void load(const float* p, float (&x)[VEC])
     {
         const V* q = reinterpret_cast<const V*>(p);
         const V t = *q;
+        if constexpr (VEC == 1) {
+            x[0] = t;
+        } else {
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) x[i] = elem<V, VEC>(t, i);
+            for (int i = 0; i < VEC; ++i) x[i] = t[i];
+        }
     }
     __device__ static __forceinline__ void store(float* p, const float (&x)[VEC])
     {
@@ -126,15 +129,23 @@ struct Row<uint16_t, VEC> {
     }
     __device__ static __forceinline__ void widen(const V& t, float (&x)[VEC])
     {
+        if constexpr (VEC == 1) {
+            x[0] = bf16_to_f32(t);
+        } else {
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(elem<V, VEC>(t, i));
+            for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(t[i]);
+        }
     }
     __device__ static __forceinline__ void load(const uint16_t* p, float (&x)[VEC])
     {
         const V* q = reinterpret_cast<const V*>(p);
         const V t = *q;
+        if constexpr (VEC == 1) {
+            x[0] = bf16_to_f32(t);
+        } else {
 #pragma unroll
-        for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(elem<V, VEC>(t, i));
+            for (int i = 0; i < VEC; ++i) x[i] = bf16_to_f32(t[i]);
+        }
     }
     __device__ static __forceinline__ void store(uint16_t* p, const float (&x)[VEC])
     {
@@ -200,17 +211,19 @@ struct XcdLists {
     int explicit_lists;
 };
 
-// Work is handed out record by record from one cursor per XCD (ctrl[0..8)), so that all
-// lane groups of an XCD work inside a narrow window of its list whatever their speeds:
-// with fixed shares the groups drift apart and the window -- what the L2 has to hold --
-// grows to many times the intended size.  A group keeps three tickets in flight (the
-// record it gathers, the next one whose column ids it has requested, and the one after
-// whose record it has requested).  ctrl[8] counts the groups that are done; the last one
-// puts all nine words back to zero, so the buffer is zero between launches.
+// Implicit lists are walked in fixed shares: group q of an XCD takes positions q,
+// q + groups, q + 2 groups, ...  Explicit lists are handed out in chunks of
+// `chunk_records` consecutive positions from one cursor per XCD (ctrl[0..8)): with fixed
+// shares the groups of an XCD drift apart (they do not run at the same speed) and the
+// window of the list they work in -- what the L2 has to hold -- grows to many times the
+// intended size.  Every group starts with the chunk of its own number and asks for the
+// next one while it works; ctrl[8] counts the groups that are done and the last one puts
+// all nine words back to zero, so the buffer is zero between launches.
 template <typename T, int VEC, int G, int VPL, int EDGE_W>
 __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __restrict__ segs, int64_t num_segs,
                                                             const XcdLists lists, unsigned long long* __restrict__ ctrl,
-                                                            const int32_t* __restrict__ col, int64_t col_base,
+                                                            int chunk_records, const int32_t* __restrict__ col,
+                                                            int64_t col_base,
                                                             const float* __restrict__ edge_w,
                                                             const float* __restrict__ row_scale,
                                                             const T* __restrict__ xin, int64_t ldin,
@@ -243,17 +256,34 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         rstep = reps;
         xcd_slice = xcd & (num_slices - 1);
     }
-    // next position of this XCD's list (one atomic per group, result shared inside the group)
-    auto take = [&]() -> int64_t {
+    // Positions of this group, in the order it visits them.  A chunk is chunk_records
+    // consecutive positions; chunk numbers below `groups` are fixed (the group's own
+    // number), later ones come from the XCD's cursor.  chunk_records == 0: fixed shares.
+    const bool dynamic = chunk_records > 0;
+    const int64_t csize = dynamic ? chunk_records : 1;
+    const int64_t groups = (int64_t)(gridDim.x >> 3) * GPB;  // lane groups of this XCD
+    auto take = [&]() -> int64_t {  // one atomic per group, result shared inside the group
         unsigned long long t = 0;
         if (lane == 0) t = atomicAdd(ctrl + xcd, 1ULL);
         const unsigned lo = __shfl((unsigned)t, 0, G), hi = __shfl((unsigned)(t >> 32), 0, G);
-        return (int64_t)(((unsigned long long)hi << 32) | lo);
+        return groups + (int64_t)(((unsigned long long)hi << 32) | lo);
+    };
+    int64_t chunk = (int64_t)(blockIdx.x >> 3) * GPB + threadIdx.x / G;
+    int64_t pos = chunk * csize, pos_end = pos + csize;
+    int64_t next_chunk = (dynamic && pos < count) ? take() : chunk + groups;
+    auto advance = [&]() -> int64_t {  // the position after `pos`, or one past the end of the list
+        if (pos >= count) return pos;
+        if (++pos < pos_end) return pos;
+        chunk = next_chunk;
+        pos = chunk * csize;
+        pos_end = pos + csize;
+        next_chunk = (dynamic && pos < count) ? take() : chunk + groups;
+        return pos;
     };
 
     const v4i* sp = reinterpret_cast<const v4i*>(segs) + base;
     const v4i none = {0, 0, 0, -1};  // length 0: nothing to fetch
-    int64_t t0 = take(), t1 = take(), t2 = take();
+    int64_t t0 = pos, t1 = advance(), t2 = advance();
     SegRegs s0 = unpack_segment(t0 < count ? sp[t0 * rstep] : none, col_base);
     v4i raw1 = t1 < count ? sp[t1 * rstep] : none;
     int c0[PF];
@@ -264,10 +294,12 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         c0[j] = in ? col[s0.e0 + j * G + lane] : 0;
         w0[j] = (EDGE_W == 2 && in) ? edge_w[s0.e0 + j * G + lane] : 0.0f;
     }
+    const int nvec = (d + VEC - 1) / VEC;
+    const int slice_vecs = slice_elems / VEC;
 
     while (t0 < count) {
         // ---- requests for the segments to come -----------------------------------
-        const int64_t t3 = take();
+        const int64_t t3 = advance();
         const SegRegs s1 = unpack_segment(raw1, col_base);
         const v4i raw2 = t2 < count ? sp[t2 * rstep] : none;
         int c1[PF];
@@ -280,15 +312,36 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         }
 
         // ---- this segment ----------------------------------------------------------
-        // column offsets of this lane's vectors; a vector is live if it starts inside the slice
-        const int cbase = (xcd_slice >= 0 ? xcd_slice : s0.slice) * slice_elems;
-        const int cend = min(d, cbase + slice_elems);
+        // A group that is a whole wavefront keeps the record in scalar registers.
+        SegRegs r = s0;
+        if constexpr (G == 64) {
+            r.len = __builtin_amdgcn_readfirstlane(s0.len);
+            r.row = __builtin_amdgcn_readfirstlane(s0.row);
+            r.slot = __builtin_amdgcn_readfirstlane(s0.slot);
+            r.slice = __builtin_amdgcn_readfirstlane(s0.slice);
+            r.e0 = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)((uint64_t)s0.e0 >> 32)) << 32) |
+                             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)s0.e0));
+        }
+        // This lane's vectors: vector j of a row covers columns [j*VEC, j*VEC + VEC), except
+        // that the last vector of a row whose length is no multiple of VEC is moved back to
+        // end with the row (its first `fresh` columns then repeat the vector before it: they
+        // are computed twice, identically).  A lane past the slice's end is not live: it
+        // follows the slice's first vector and stores nothing.
+        const int slice = xcd_slice >= 0 ? xcd_slice : r.slice;
+        const int vlo = slice * slice_vecs, vhi = min(nvec, vlo + slice_vecs);
         bool live[VPL];
-        int coff[VPL];
+        int coff[VPL], fresh[VPL];
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
-            coff[v] = cbase + (v * G + lane) * VEC;
-            live[v] = coff[v] < cend;
+            const int j = vlo + v * G + lane;
+            live[v] = j < vhi;
+            int c = (live[v] ? j : vlo) * VEC;
+            fresh[v] = 0;
+            if (c + VEC > d) {
+                fresh[v] = c + VEC - d;
+                c = d - VEC;
+            }
+            coff[v] = c;
         }
         float acc[NACC][VPL][VEC];
 #pragma unroll
@@ -298,83 +351,155 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc[u][v][i] = 0.0f;
 
-        // gathers rows for the `cnt` (<= G) edges whose ids sit one per lane in (ids, wts)
-        auto gather_batch = [&](int ids, float wts, int cnt) {
-            for (int t = 0; t < cnt; t += U) {
-                typename Row<T, VEC>::V x[U][VPL];  // rows stay in their stored form while in flight
-                float w[U];
+        const int len = r.len;
+        if constexpr (G == 64) {
+            // One row per load instruction: id and weight come out of the lane that holds them
+            // into scalar registers and the row address is scalar arithmetic; lanes that are
+            // not live take no part in the load.  Two sets of row registers alternate, so the
+            // rows of the next US edges are on their way while the last US are added up, and
+            // the ids of the next 64 edges are requested before the current 64 are gathered.
+            using V = typename Row<T, VEC>::V;
+            constexpr int US = VPL == 1 ? 8 : VPL == 2 ? 4 : 2;
+            auto request = [&](V (&x)[US][VPL], float (&w)[US], int ids, float wts, int t, int cnt) {
+                if (t + US <= cnt) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    // lanes past cnt hold id 0 / weight 0; their rows are not read
-                    const int c = __shfl(ids, t + u, G);
-                    w[u] = EDGE_W ? __shfl(wts, t + u, G) : 1.0f;
-                    const bool on = t + u < cnt;
-                    const T* src = xin + (int64_t)c * ldin;
+                    for (int u = 0; u < US; ++u) {
+                        const uint32_t c = (uint32_t)__builtin_amdgcn_readlane(ids, t + u);
+                        w[u] = EDGE_W ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wts), t + u)) : 1.0f;
+                        const T* src = xin + (uint64_t)c * (uint64_t)ldin;
 #pragma unroll
-                    for (int v = 0; v < VPL; ++v) {
-                        x[u][v] = (on && live[v]) ? Row<T, VEC>::load_raw(src + coff[v]) : Row<T, VEC>::zero_raw();
+                        for (int v = 0; v < VPL; ++v)
+                            x[u][v] = live[v] ? Row<T, VEC>::load_raw(src + coff[v]) : Row<T, VEC>::zero_raw();
+                    }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < US; ++u) {
+                        const bool on = t + u < cnt;  // the same for the whole wavefront
+                        const uint32_t c = (uint32_t)__builtin_amdgcn_readlane(ids, on ? t + u : t);
+                        w[u] = (EDGE_W && on) ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wts), on ? t + u : t)) : 0.0f;
+                        const T* src = xin + (uint64_t)c * (uint64_t)ldin;
+#pragma unroll
+                        for (int v = 0; v < VPL; ++v)
+                            x[u][v] = (live[v] && (EDGE_W || on)) ? Row<T, VEC>::load_raw(src + coff[v]) : Row<T, VEC>::zero_raw();
                     }
                 }
+            };
+            auto add_up = [&](const V (&x)[US][VPL], const float (&w)[US], int first_acc) {
 #pragma unroll
-                for (int u = 0; u < U; ++u)
+                for (int u = 0; u < US; ++u)
 #pragma unroll
                     for (int v = 0; v < VPL; ++v) {
                         float xf[VEC];
                         Row<T, VEC>::widen(x[u][v], xf);
+                        float(&a)[VEC] = acc[(first_acc + u) % NACC][v];
 #pragma unroll
-                        for (int i = 0; i < VEC; ++i)
-                            acc[u % NACC][v][i] =
-                                EDGE_W ? fmaf(w[u], xf[i], acc[u % NACC][v][i]) : acc[u % NACC][v][i] + xf[i];
+                        for (int i = 0; i < VEC; ++i) a[i] = EDGE_W ? fmaf(w[u], xf[i], a[i]) : a[i] + xf[i];
                     }
+            };
+            int ids = c0[0];
+            float wts = w0[0];
+            if (EDGE_W == 1 && lane < len) wts = edge_w[ids];
+            for (int base_e = 0; base_e < len; base_e += 64) {
+                const int cnt = min(64, len - base_e);
+                const int left = len - base_e - 64;  // edges past this batch
+                int idn = 0;
+                float wn = 0.0f;
+                if (lane < left) {
+                    idn = col[r.e0 + base_e + 64 + lane];
+                    if (EDGE_W == 2) wn = edge_w[r.e0 + base_e + 64 + lane];
+                }
+                V xa[US][VPL], xb[US][VPL];
+                float wa[US], wb[US];
+                request(xa, wa, ids, wts, 0, cnt);
+                for (int t = 0; t < cnt; t += 2 * US) {
+                    const bool more = t + US < cnt;
+                    if (more) request(xb, wb, ids, wts, t + US, cnt);
+                    add_up(xa, wa, 0);
+                    if (more) {
+                        if (t + 2 * US < cnt) request(xa, wa, ids, wts, t + 2 * US, cnt);
+                        add_up(xb, wb, US);
+                    }
+                }
+                if (EDGE_W == 1 && lane < left) wn = edge_w[idn];
+                ids = idn;
+                wts = wn;
             }
-        };
-
-        const int len = s0.len;
+        } else {
+            // several lane groups per wavefront, each with a record of its own: ids and weights
+            // are handed round inside the group
+            auto gather_batch = [&](int ids, float wts, int cnt) {
+                for (int t = 0; t < cnt; t += U) {
+                    typename Row<T, VEC>::V x[U][VPL];  // rows stay in their stored form while in flight
+                    float w[U];
 #pragma unroll
-        for (int j = 0; j < PF; ++j) {
-            const int cnt = min(G, len - j * G);
-            if (cnt > 0) {
-                float wj = w0[j];
-                if (EDGE_W == 1 && lane < cnt) wj = edge_w[c0[j]];
-                gather_batch(c0[j], wj, cnt);
+                    for (int u = 0; u < U; ++u) {
+                        // lanes past cnt hold id 0 / weight 0; their rows are not read
+                        const int c = __shfl(ids, t + u, G);
+                        w[u] = EDGE_W ? __shfl(wts, t + u, G) : 1.0f;
+                        const bool on = t + u < cnt;
+                        const T* src = xin + (int64_t)c * ldin;
+#pragma unroll
+                        for (int v = 0; v < VPL; ++v) {
+                            x[u][v] = (on && live[v]) ? Row<T, VEC>::load_raw(src + coff[v]) : Row<T, VEC>::zero_raw();
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+#pragma unroll
+                        for (int v = 0; v < VPL; ++v) {
+                            float xf[VEC];
+                            Row<T, VEC>::widen(x[u][v], xf);
+#pragma unroll
+                            for (int i = 0; i < VEC; ++i)
+                                acc[u % NACC][v][i] =
+                                    EDGE_W ? fmaf(w[u], xf[i], acc[u % NACC][v][i]) : acc[u % NACC][v][i] + xf[i];
+                        }
+                }
+            };
+#pragma unroll
+            for (int j = 0; j < PF; ++j) {
+                const int cnt = min(G, len - j * G);
+                if (cnt > 0) {
+                    float wj = w0[j];
+                    if (EDGE_W == 1 && lane < cnt) wj = edge_w[c0[j]];
+                    gather_batch(c0[j], wj, cnt);
+                }
             }
-        }
-        for (int base = WIN; base < len; base += G) {  // the part of a long segment past the prefetch
-            const int cnt = min(G, len - base);
-            int id = 0;
-            float wj = 0.0f;
-            if (lane < cnt) {
-                id = col[s0.e0 + base + lane];
-                if (EDGE_W == 1) wj = edge_w[id];
-                if (EDGE_W == 2) wj = edge_w[s0.e0 + base + lane];
+            for (int base_e = WIN; base_e < len; base_e += G) {  // the part of a long segment past the prefetch
+                const int cnt = min(G, len - base_e);
+                int id = 0;
+                float wj = 0.0f;
+                if (lane < cnt) {
+                    id = col[r.e0 + base_e + lane];
+                    if (EDGE_W == 1) wj = edge_w[id];
+                    if (EDGE_W == 2) wj = edge_w[r.e0 + base_e + lane];
+                }
+                gather_batch(id, wj, cnt);
             }
-            gather_batch(id, wj, cnt);
         }
 
-        const bool partial = s0.slot >= 0;
-        const float rs = (!partial && row_scale) ? row_scale[s0.row] : 1.0f;
+        const bool partial = r.slot >= 0;
+        const float rs = (!partial && row_scale) ? row_scale[r.row] : 1.0f;
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
             if (!live[v]) continue;
-            float r[VEC];
+            float o[VEC];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
                 float t = acc[0][v][i];
                 if constexpr (NACC == 2) t += acc[1][v][i];
                 if constexpr (NACC == 4) t = (t + acc[1][v][i]) + (acc[2][v][i] + acc[3][v][i]);
-                r[i] = t * rs;
+                o[i] = t * rs;
             }
             if (partial) {
-                Row<float, VEC>::store(carry + (int64_t)s0.slot * carry_ld + coff[v], r);
+                Row<float, VEC>::store(carry + (int64_t)r.slot * carry_ld + coff[v], o);
             } else {
-                if (xout) Row<T, VEC>::store_stream(xout + (int64_t)s0.row * ldout + coff[v], r);
-                if (comb) {  // running filter output: comb[row] += gamma * (A^^k X)[row]
-                    float* cp = comb + (int64_t)s0.row * ldc + coff[v];
-                    float c[VEC];
-                    Row<float, VEC>::load(cp, c);
+                if (xout) Row<T, VEC>::store_stream(xout + (int64_t)r.row * ldout + coff[v], o);
+                if (comb) {  // running filter output: comb[row] += gamma * (A^^k X)[row], every column once
+                    float* cp = comb + (int64_t)r.row * ldc + coff[v];
 #pragma unroll
-                    for (int i = 0; i < VEC; ++i) c[i] = fmaf(gamma, r[i], c[i]);
-                    Row<float, VEC>::store(cp, c);
+                    for (int i = 0; i < VEC; ++i)
+                        if (i >= fresh[v]) cp[i] = fmaf(gamma, o[i], cp[i]);
                 }
             }
         }
@@ -393,9 +518,9 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
 
     // every ticket this group asked for has been answered by now; the last group to get
     // here puts the cursors back to zero for the next launch
-    if (lane == 0) {
-        const unsigned long long groups = (unsigned long long)gridDim.x * GPB;
-        if (atomicAdd(ctrl + 8, 1ULL) == groups - 1) {
+    if (dynamic && lane == 0) {
+        const unsigned long long all_groups = (unsigned long long)gridDim.x * GPB;
+        if (atomicAdd(ctrl + 8, 1ULL) == all_groups - 1) {
             __threadfence();
 #pragma unroll
             for (int i = 0; i < 9; ++i) atomicExch(ctrl + i, 0ULL);
@@ -430,8 +555,12 @@ __global__ __launch_bounds__(kThreads) void gp_fixup_rows(const SplitRow* __rest
     const float rs = row_scale ? row_scale[sr.row] : 1.0f;
 #pragma unroll
     for (int v = 0; v < VPL; ++v) {
-        const int c0 = (v * G + lane) * VEC;
+        int c0 = (v * G + lane) * VEC, fresh = 0;
         if (c0 >= d) continue;
+        if (c0 + VEC > d) {  // last vector of a row whose length is no multiple of VEC: moved back to end with the row
+            fresh = c0 + VEC - d;
+            c0 = d - VEC;
+        }
         float acc[kUnroll][VEC];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
@@ -455,11 +584,9 @@ __global__ __launch_bounds__(kThreads) void gp_fixup_rows(const SplitRow* __rest
         if (xout) Row<T, VEC>::store_stream(xout + (int64_t)sr.row * ldout + c0, r);
         if (comb) {
             float* cp = comb + (int64_t)sr.row * ldc + c0;
-            float c[VEC];
-            Row<float, VEC>::load(cp, c);
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) c[i] = fmaf(gamma, r[i], c[i]);
-            Row<float, VEC>::store(cp, c);
+            for (int i = 0; i < VEC; ++i)
+                if (i >= fresh) cp[i] = fmaf(gamma, r[i], cp[i]);
         }
     }
 }
@@ -515,11 +642,11 @@ __global__ __launch_bounds__(kThreads) void gp_copy_rows(const U* __restrict__ s
 int vector_width(gp_dtype dtype, int32_t d, int64_t ld_a, int64_t ld_b, const void* pa, const void* pb)
 {
     const int es = dtype == GP_F32 ? 4 : 2;
-    int vec = 16 / es;  // 16-byte vectors when everything is aligned for them
+    int vec = 16 / es;  // 16 bytes per lane whenever rows are at least that long and start on dword boundaries
     while (vec > 1) {
-        const int64_t bytes = (int64_t)vec * es;
-        const bool ok = d % vec == 0 && (ld_a * es) % bytes == 0 && (ld_b * es) % bytes == 0 &&
-                        ((uintptr_t)pa % bytes) == 0 && ((uintptr_t)pb % bytes) == 0;
+        const int64_t need = std::min<int64_t>((int64_t)vec * es, 4);  // loads and stores want dword alignment at most
+        const bool ok = vec <= d && (ld_a * es) % need == 0 && (ld_b * es) % need == 0 &&
+                        ((uintptr_t)pa % need) == 0 && ((uintptr_t)pb % need) == 0;
         if (ok) break;
         vec /= 2;
     }
@@ -546,7 +673,9 @@ gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
     }
     const int64_t chunks = (longest + GPB - 1) / GPB;  // workgroups per XCD that find work
     if (chunks == 0) return GP_OK;
-    if (!a.ctrl) return fail(GP_ERR_INVALID_ARG, "hop launch without its cursor buffer");
+    // explicit lists are handed out from cursors, in chunks of about 64 non-zeros
+    const int chunk_records = a.xcd_off ? std::max(1, a.chunk_records) : 0;
+    if (chunk_records && !a.ctrl) return fail(GP_ERR_INVALID_ARG, "hop launch without its cursor buffer");
     // persistent lane groups: as many workgroups as stay resident, fewer if the lists are short
     static const int resident = [] {
         int per_cu = 0, dev = 0;
@@ -562,15 +691,15 @@ gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
     const int64_t blocks = std::min<int64_t>(persist, 8 * chunks);
     const dim3 grid((unsigned)blocks), block(kThreads);
     if (a.edge_w && a.edge_w_per_edge)
-        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 2>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, a.col,
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 2>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, chunk_records, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
                            a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
     else if (a.edge_w)
-        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 1>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, a.col,
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 1>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, chunk_records, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
                            a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
     else
-        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 0>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, a.col,
+        hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 0>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, chunk_records, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
                            a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
     GP_HIP(hipGetLastError());

@@ -103,7 +103,7 @@ int64_t pass_width(int64_t tile, gp_dtype dtype, int32_t d, int64_t lda, int64_t
 // from the cluster itself and one slice of a cluster's rows fits the share of an XCD's
 // L2 that the streams beside it (column ids, written rows, sources outside the cluster)
 // leave free.  A slice is at least 128 bytes (one cache line) wide.
-constexpr double kL2Share = 0.6;
+constexpr double kL2Share = 0.75;
 constexpr int64_t kLineBytes = 128;
 
 int64_t l2_bytes_per_xcd()
@@ -178,6 +178,9 @@ gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream)
         w.num_slices = S;
         w.slice_elems = elems;
         build_xcd_lists(*plan, plan->clusters, S, elems, a.d, recs, w.off);
+        // a request to the cursor should be worth about 64 non-zeros of gathering
+        const int64_t mean_len = std::max<int64_t>(1, plan->nnz / std::max<int64_t>(1, (int64_t)plan->segs.size()));
+        w.chunk_records = (int)std::min<int64_t>(32, std::max<int64_t>(1, 64 / mean_len));
         GP_HIP(hipMalloc((void**)&w.recs, recs.size() * sizeof(Segment)));
         hipError_t e = hipMemcpyAsync(w.recs, recs.data(), recs.size() * sizeof(Segment), hipMemcpyHostToDevice, stream);
         if (e == hipSuccess) e = hipStreamSynchronize(stream);  // pageable source: done before `recs` goes away
@@ -191,6 +194,7 @@ gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream)
     a.segs = found->recs;
     a.num_segs = found->off[8];
     a.xcd_off = found->off;
+    a.chunk_records = found->chunk_records;
     a.num_slices = found->num_slices;
     a.slice_elems = found->slice_elems;
     return GP_OK;
