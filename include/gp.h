@@ -175,6 +175,31 @@ gp_status gp_propagate(const gp_plan *plan, const void *X, int64_t ldx, int32_t 
                        gp_agg agg, int32_t K, void *out_stack, int64_t ldo, void *hip_stream);
 
 /* ---------------------------------------------------------------------------
+ * gp_propagate_noalloc -- gp_propagate for callers that cannot allocate: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and the same bits in out_stack as gp_propagate on
+ * device-resident operands, but the call makes no allocation of any kind: the scratch
+ * the kernels need (work cursors, partial rows of rows that were cut) is a fixed array
+ * in device memory of 64 MiB + 256 bytes that each GPU the library is used on holds
+ * until the process ends.
+ *
+ *  plan   must already be on the current device (the first gp_propagate on a plan
+ *         uploads it); else GP_ERR_INVALID_ARG.  What earlier calls built is used (work
+ *         lists, per-edge weights); what they did not build is done without (implicit
+ *         lists, weights gathered by column id -- the same numbers).
+ *  X, out_stack  DEVICE only (pinned-host operands: GP_ERR_INVALID_ARG).
+ *
+ * Limit: plan partial rows x round_up(d, 4) x 4 bytes <= gp_noalloc_partial_row_bytes()
+ * (64 MiB), else GP_ERR_UNSUPPORTED with the sizes in gp_last_error().  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU race (also with
+ * different plans or streams).  Enqueued on hip_stream; nothing in it is a memset, so the
+ * call may be captured.  Errors: INVALID_ARG, UNSUPPORTED, DEVICE.
+ */
+gp_status gp_propagate_noalloc(const gp_plan *plan, const void *X, int64_t ldx, int32_t d, gp_dtype dtype,
+                               gp_agg agg, int32_t K, void *out_stack, int64_t ldo, void *hip_stream);
+int64_t gp_noalloc_partial_row_bytes(void);
+
+/* ---------------------------------------------------------------------------
  * gp_propagate_combine -- a constant polynomial graph filter without the stack:
  *     out = sum_{k=0..K} coeff[k] * A^^k X.
  * (Appendix A, Eq. 13: the generalized-PageRank propagation sum_k gamma_k S^k H

@@ -49,6 +49,9 @@ _SIGNATURES = {
                                       _c.POINTER(_c.c_int32), _c.c_void_p, _c.c_void_p, _c.c_int64]),
     "gp_propagate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                 _c.c_void_p, _c.c_int64, _c.c_void_p]),
+    "gp_propagate_noalloc": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
+                                        _c.c_void_p, _c.c_int64, _c.c_void_p]),
+    "gp_noalloc_partial_row_bytes": (_c.c_int64, []),
     "gp_propagate_combine": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                         _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_lc_forward": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int, _c.c_int64, _c.c_int32, _c.c_int32, _c.c_void_p, _c.c_int64,
@@ -244,6 +247,17 @@ def gp_propagate(plan: Plan, X_ptr: int, ldx: int, d: int, dtype: int, agg: int,
     """Raw-pointer form: X_ptr / out_ptr are device (or pinned host) addresses."""
     st = lib().gp_propagate(plan.handle, X_ptr, ldx, d, dtype, agg, K, out_ptr, ldo, stream or None)
     _check(st, "gp_propagate")
+
+
+def gp_propagate_noalloc(plan: Plan, X_ptr: int, ldx: int, d: int, dtype: int, agg: int, K: int, out_ptr: int, ldo: int,
+                         stream: Optional[int] = None):
+    """gp_propagate without any allocation (device operands, plan already on the device)."""
+    st = lib().gp_propagate_noalloc(plan.handle, X_ptr, ldx, d, dtype, agg, K, out_ptr, ldo, stream or None)
+    _check(st, "gp_propagate_noalloc")
+
+
+def gp_noalloc_partial_row_bytes() -> int:
+    return lib().gp_noalloc_partial_row_bytes()
 
 
 def gp_propagate_combine(plan: Plan, X_ptr: int, ldx: int, d: int, dtype: int, agg: int, K: int, coeff, out_ptr: int,

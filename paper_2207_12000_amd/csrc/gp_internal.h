@@ -143,6 +143,9 @@ gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64
 // resident schedule: everything already in HBM
 gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,
                              gp_agg agg, int32_t K, void* out, int64_t ldo, hipStream_t stream);
+gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg, int32_t K,
+                        void* out, int64_t ldo, hipStream_t stream, float* carry, int64_t carry_ld,
+                        unsigned long long* ctrl, bool may_allocate);
 // streamed schedule: operands in pinned host memory
 gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,
                              gp_agg agg, int32_t K, void* out, int64_t ldo);
@@ -210,6 +213,7 @@ gp_status launch_fixup(const FixupArgs& a, hipStream_t stream);
 
 gp_status launch_scale_convert(const void* src, int64_t lds, gp_dtype src_type, void* dst, int64_t ldd, gp_dtype dst_type,
                                int64_t n, int32_t d, float gamma, hipStream_t stream);
+gp_status launch_zero_words(unsigned long long* p, int count, hipStream_t stream);
 gp_status launch_fill_edge_weights(const int32_t* col, const float* by_col, float* w, int64_t nnz, hipStream_t stream);
 // max_blocks > 0 caps the grid (copies over the host link need few workgroups and
 // must leave the compute units to the kernels running beside them)

@@ -528,6 +528,12 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     }
 }
 
+// a few 64-bit words put to zero (a fill kernel, so that a caller may capture it in a graph)
+__global__ void gp_zero_words(unsigned long long* p, int count)
+{
+    if ((int)threadIdx.x < count) p[threadIdx.x] = 0ULL;
+}
+
 // per-edge weights for the sym operator: w[e] = dinv_sqrt[col[e]] (built once per plan)
 __global__ __launch_bounds__(kThreads) void gp_fill_edge_weights(const int32_t* __restrict__ col,
                                                                  const float* __restrict__ by_col, float* __restrict__ w,
@@ -839,6 +845,14 @@ gp_status launch_scale_convert(const void* src, int64_t lds, gp_dtype src_type, 
         hipLaunchKernelGGL((gp_scale_convert<float, uint16_t>), grid, block, 0, stream, (const float*)src, lds, (uint16_t*)dst, ldd, n, d, gamma);
     else
         return fail(GP_ERR_UNSUPPORTED, "scale/convert between these types is not needed");
+    GP_HIP(hipGetLastError());
+    return GP_OK;
+}
+
+gp_status launch_zero_words(unsigned long long* p, int count, hipStream_t stream)
+{
+    if (count <= 0 || count > 64) return fail(GP_ERR_INVALID_ARG, "zero_words: count %d outside 1 .. 64", count);
+    hipLaunchKernelGGL(gp_zero_words, dim3(1), dim3(64), 0, stream, p, count);
     GP_HIP(hipGetLastError());
     return GP_OK;
 }

@@ -158,7 +158,7 @@ namespace {
 
 // Gives the launch explicit work lists if the plan's cache schedule applies to it
 // (building and uploading them on first use of a slice shape).
-gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream)
+gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream, bool may_build = true)
 {
     const int es = a.dtype == GP_F32 ? 4 : 2;
     const int vec = hop_vector_width(a);
@@ -167,11 +167,13 @@ gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream)
         return GP_OK;
     std::lock_guard<std::mutex> lk(plan->mu);
     int S = 0, elems = 0;
+    if (!may_build && !plan->clusters.ready) return GP_OK;  // nothing built yet: implicit lists
     if (!choose_cache_schedule(plan, a.d, es, vec, S, elems)) return GP_OK;
     DevicePlan& D = plan->dev;
     const XcdWork* found = nullptr;
     for (const XcdWork& w : D.work)
         if (w.num_slices == S && w.slice_elems == elems) found = &w;
+    if (!found && !may_build) return GP_OK;
     if (!found) {
         std::vector<Segment> recs;
         XcdWork w;
@@ -249,6 +251,19 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
     gp_status st = ensure_device(plan, d, agg == GP_AGG_SYM, stream);
     if (st != GP_OK) return st;
     const DevicePlan& D = plan->dev;
+    return resident_hops(plan, X, ldx, d, dtype, agg, K, out, ldo, stream, D.carry, D.carry_ld, D.ctrl, true);
+}
+
+// The hop loop on a plan that is already on the device.  may_allocate = false: only what
+// exists is used (work lists that have been built, else the implicit ones; for the sym
+// operator the per-edge weight array if it exists, else the weights gathered by column id,
+// which are the same numbers) and nothing is allocated.
+gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg, int32_t K,
+                        void* out, int64_t ldo, hipStream_t stream, float* carry, int64_t carry_ld,
+                        unsigned long long* ctrl, bool may_allocate)
+{
+    gp_status st = GP_OK;
+    const DevicePlan& D = plan->dev;
     const int64_t n = plan->n;
     const int es = dtype == GP_F32 ? 4 : 2;
     char* base = (char*)out;
@@ -262,7 +277,8 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
         if (st != GP_OK) return st;
     }
 
-    const float* edge_w = agg == GP_AGG_SYM ? D.edge_ws : nullptr;
+    const bool per_edge = D.edge_ws != nullptr;
+    const float* edge_w = agg == GP_AGG_SYM ? (per_edge ? D.edge_ws : D.dinv_sqrt) : nullptr;
     const float* row_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : agg == GP_AGG_MEAN ? D.dinv : nullptr;
 
     for (int32_t k = 1; k <= K; ++k) {
@@ -272,28 +288,28 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
         a.col = D.col;
         a.col_base = 0;
         a.edge_w = edge_w;
-        a.edge_w_per_edge = true;
+        a.edge_w_per_edge = per_edge;
         a.row_scale = row_scale;
         a.xin = base + (int64_t)(k - 1) * slab;
         a.ldin = ldo;
         a.xout = base + (int64_t)k * slab;
         a.ldout = ldo;
-        a.carry = D.carry;
-        a.carry_ld = D.carry_ld;
-        a.ctrl = D.ctrl;
+        a.carry = carry;
+        a.carry_ld = carry_ld;
+        a.ctrl = ctrl;
         a.d = d;
         a.dtype = dtype;
         a.column_slices = plan->opt.column_slices;
         a.persistent_blocks = plan->opt.persistent_blocks;
         a.column_tile = plan->opt.column_tile;
-        if ((st = attach_work_lists(plan, a, stream)) != GP_OK) return st;
+        if ((st = attach_work_lists(plan, a, stream, may_allocate)) != GP_OK) return st;
         if ((st = hop_passes(a, stream)) != GP_OK) return st;
         if (!plan->split.empty()) {
             FixupArgs f;
             f.split = D.split;
             f.num_split = (int64_t)plan->split.size();
-            f.carry = D.carry;
-            f.carry_ld = D.carry_ld;
+            f.carry = carry;
+            f.carry_ld = carry_ld;
             f.row_scale = row_scale;
             f.xout = a.xout;
             f.ldout = ldo;
