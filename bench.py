@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the K-hop precompute on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all|1..5]
 
 One step = one gp_propagate call: the whole hot path (slot-0 copy, K hops of
 gather/scale/accumulate over all edge blocks, completion of cut rows) on one
@@ -10,6 +10,9 @@ throughput in giga edge-feature updates per second (nnz * d * K / t / 1e9), the
 HBM roofline of the dominant kernel (algorithmic bytes per launch over the
 kernel's mean duration, timed with HIP events on the launch stream), and the CPU
 oracle timed beside it on the host cores as a baseline.
+
+The default times all four in-HBM workloads; the line is the one of the largest
+(config 4) and carries the others under "other_workloads".
 """
 from __future__ import annotations
 
@@ -26,10 +29,26 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel, measured with rocprofv3 --pmc
-# (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); the
-# summaries are in profiles/gp_hop_segments_<workload>.md.  Per launch, default options.
-MEASURED_TRAFFIC_BYTES = {1: 32_612_875, 2: 1_072_032_400, 3: 60_522_738_707, 4: 285_626_792_016}
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+HEADLINE_WORKLOAD = 4            # the largest workload that is resident in HBM
+IN_HBM_WORKLOADS = (1, 2, 3, 4)
+
+# HBM bytes per launch of the dominant kernel as the last counter run recorded them
+# (bench_counters.py: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes over this script, each
+# scaled by what the same counter reads for the library's plain copy kernel).  The figure is
+# reported only when it was recorded for the same workload and library options.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hop_traffic.json")
+
+
+def recorded_traffic(workload: int, options: dict):
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f).get(str(workload))
+    except (OSError, ValueError):
+        return None
+    if not rec or rec.get("options") != options:
+        return None
+    return rec.get("bytes_per_launch")
 
 WORKLOAD_NAMES = {
     1: "config1: G(n,M) 10k nodes / 210k nnz, d=128 fp32, sym, K=2, 4 edge blocks",
@@ -136,53 +155,14 @@ def cpu_model() -> str:
     return "unknown"
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=2, choices=sorted(WORKLOAD_NAMES))
-    ap.add_argument("--scale", type=float, default=1.0,
-                    help="shrink node and pair counts together (workload 5 is only practical below 1)")
-    ap.add_argument("--memory", choices=["device", "pinned"], default=None,
-                    help="where X and the stack live: device (resident schedule) or pinned host memory "
-                         "(streamed schedule; the default for workload 5)")
-    ap.add_argument("--hbm-budget-gb", type=float, default=0.0, help="streamed schedule: HBM budget (0 = automatic)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
-                    help="library option (gp_set_option), e.g. column_tile=32")
-    ap.add_argument("--lc", action="store_true",
-                    help="time the LC-version forward pass (gp_lc_forward) over the hop stack instead of the precompute")
-    ap.add_argument("--lc-batch", type=int, default=4096, help="--lc: mini-batch rows per call (0 = all rows in one call)")
-    ap.add_argument("--contiguous-ids", action="store_true",
-                    help="workload 4 only: community-contiguous node ids (locality given) instead of permuted ids")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
-        return 2
-
-    import torch
+def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
+    """Plans, times and (optionally) baselines one workload; returns its record, or an
+    int return code when --lc took over."""
     import gp_synth
-    import paper_2207_12000_amd as gp
-    if not os.path.exists(gp.LIB_PATH):      # load what is built; build only if nothing is
-        from paper_2207_12000_amd import build as libbuild
-        libbuild.build()
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        return 2
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    for kv in args.option:
-        name, val = kv.split("=")
-        gp.gp_set_option(name, int(val))
-
     t0 = time.time()
-    w = gp_synth.make_workload(args.workload, scale=args.scale, contiguous_ids=args.contiguous_ids)
+    w = gp_synth.make_workload(workload, scale=args.scale, contiguous_ids=args.contiguous_ids)
     memory = args.memory or ("pinned" if w.streamed else "device")
-    if args.hbm_budget_gb > 0:
-        gp.gp_set_hbm_budget_bytes(int(args.hbm_budget_gb * 2**30))
     t_gen = time.time() - t0
     budget = w.block_budget_edges
     if budget is None:
@@ -213,6 +193,7 @@ def main() -> int:
             return 2
         step()
         torch.cuda.synchronize()
+        args.workload = workload
         rc = bench_lc(args, gp, torch, w, plan, out, t_gen, t_plan)
         plan.close()
         return rc
@@ -253,11 +234,19 @@ def main() -> int:
     if memory == "device":
         per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
 
-    # dominant kernel: per-launch duration from HIP events around each launch
+    # dominant kernel: per-launch duration from HIP events the library records around each
+    # launch on the launch stream.  The event pairs themselves cost time between the
+    # launches, so this pass runs a few per cent slower than the timed one (its own
+    # ms per step is reported beside the kernel times); the durations are the kernels' own.
     gp.gp_profile_enable(True)
+    b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    b0.record()
     for _ in range(args.steps):
         step()
+    b1.record()
     torch.cuda.synchronize()
+    bracketed_ms = b0.elapsed_time(b1) / args.steps if memory == "device" else (time.perf_counter() - t0) * 1e3 / args.steps
     launches, hop_ms = gp.gp_profile_read("gp_hop_segments")
     fix_launches, fix_ms = gp.gp_profile_read("gp_fixup_rows")
     _, copy_ms = gp.gp_profile_read("gp_copy_rows")
@@ -268,7 +257,11 @@ def main() -> int:
     launches_per_hop = max(1, round(launches / max(args.steps * K, 1)))
     bytes_per_launch = algorithmic_bytes_per_hop(n, nnz, d, elem) // launches_per_hop
     achieved = bytes_per_launch / avg_launch_s / 1e9
-    traffic = MEASURED_TRAFFIC_BYTES.get(args.workload) if (args.scale == 1.0 and memory == "device") else None
+    options = {k: gp.gp_get_option(k) for k in ("segment_edges", "column_tile", "column_slices", "cache_schedule")}
+    traffic = recorded_traffic(workload, options) if (args.scale == 1.0 and memory == "device" and not args.contiguous_ids) else None
+    flops_per_launch = 2 * nnz * d // launches_per_hop          # one multiply-add per non-zero and column
+    gathered_per_launch = nnz * d * elem // launches_per_hop    # bytes the lanes read if every row comes from cache
+    S, slice_elems, _, _ = plan.work_lists(d, w.dtype, max(1, min(16 // elem, d)))
 
     rec = {
         "metric": "edge-feature updates/s (GEFU/s) for K-hop A^k X precompute",
@@ -285,15 +278,25 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32" if w.dtype == gp.GP_F32 else "bf16 storage, f32 accumulate",
         "data": "synthetic",
-        "config": {"workload": WORKLOAD_NAMES[args.workload] + (" [community-contiguous ids]" if args.contiguous_ids else "")
+        "config": {"workload": WORKLOAD_NAMES[workload] + (" [community-contiguous ids]" if args.contiguous_ids else "")
                    + (f" [scale {args.scale}]" if args.scale != 1.0 else ""), "memory": memory, "n": n, "nnz": nnz, "d": d, "K": K,
                    "edge_blocks": plan.num_blocks, "agg": ["sym", "mean", "sum"][w.agg],
                    "segments": int(plan.segments.size), "partial_rows": plan.num_partial_rows,
-                   "options": {k: gp.gp_get_option(k) for k in ("segment_edges", "column_tile", "column_slices")}},
+                   "work_lists": ("explicit per XCD, %d column slices of %d" % (S, slice_elems)) if S else "implicit",
+                   "options": options},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "kernel": "gp_hop_segments", "launches": launches, "launches_per_hop": launches_per_hop,
-                     "avg_launch_us": round(avg_launch_s * 1e6, 3), "algorithmic_bytes_per_launch": bytes_per_launch},
+                     "avg_launch_us": round(avg_launch_s * 1e6, 3), "algorithmic_bytes_per_launch": bytes_per_launch,
+                     "kernel_times_from": f"event-bracketed pass, {bracketed_ms:.5f} ms per step",
+                     # the other ceilings of the same launch: plain fp32 vector arithmetic, and the rate at
+                     # which the lanes are fed gathered rows (useful bytes only)
+                     "other_bounds": {
+                         "alu": {"achieved": round(flops_per_launch / avg_launch_s / 1e12, 3), "peak": FP32_VECTOR_PEAK_TFLOPS,
+                                 "unit": "TFLOP/s", "frac": round(flops_per_launch / avg_launch_s / 1e12 / FP32_VECTOR_PEAK_TFLOPS, 4)},
+                         "gathered_rows": {"achieved": round(gathered_per_launch / avg_launch_s / 1e9, 1), "unit": "GB/s",
+                                           "note": "nnz * d * element size per launch over its duration; rows served by the "
+                                                   "XCDs' L2 arrive at 20 - 27 TB/s on this machine, rows that miss it at about 7"}}},
         "other_kernels_ms_per_step": {"gp_fixup_rows": round(fix_ms / args.steps, 5),
                                       "gp_copy_rows": round(copy_ms / args.steps, 5)},
         "host_s": {"generate": round(t_gen, 2), "gp_plan_blocks": round(t_plan, 3),
@@ -308,9 +311,10 @@ def main() -> int:
         link_bytes = n * d * elem * (K + 1) + 4 * nnz + 16 * int(plan.segments.size)
         rec["host_link"] = {"min_bytes_per_step": link_bytes, "GB/s_on_min_bytes": round(link_bytes / (ms_per_step * 1e-3) / 1e9, 2),
                             "column_slabs": slabs}
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         import oracle
         cores = min(16, os.cpu_count() or 1)
+        del out
         op = oracle.plan_blocks(w.src, w.dst, n, budget, w.flags)
         Xw = (w.X if w.dtype == gp.GP_F32 else gp_synth.bf16_bits_to_f32(w.X)).astype(np.float64)
         # bounded sample: whole hops of the same workload (the K-hop chain restarted
@@ -324,22 +328,100 @@ def main() -> int:
             hops += 1
             if hops % K == 0:
                 cur = Xw
-        # the same loop on one thread, a shorter sample (about 3 s)
-        hops1, t1 = 0, 0.0
-        cur = Xw
-        while t1 < 3.0:
-            t0 = time.perf_counter()
-            cur = oracle.hop(op, cur, w.agg, threads=1)
-            t1 += time.perf_counter() - t0
-            hops1 += 1
-            if hops1 % K == 0:
-                cur = Xw
         rec["cpu_baseline"] = {"value": round(nnz * d * hops / t_cpu / 1e9, 4), "unit": "GEFU/s", "cores": cores,
                                "kind": "oracle", "sample": f"{hops} hops ({hops / K:.1f} passes of the K={K} chain) of "
                                                             f"the same workload, fp64, {t_cpu:.2f} s",
-                               "single_thread_value": round(nnz * d * hops1 / t1 / 1e9, 4), "cpu": cpu_model()}
-    print(json.dumps(rec))
+                               "cpu": cpu_model()}
+        if t_cpu / hops * cores < 3.0:
+            # the same loop on one thread, a shorter sample (about 3 s), where a hop is short enough
+            hops1, t1 = 0, 0.0
+            cur = Xw
+            while t1 < 3.0:
+                t0 = time.perf_counter()
+                cur = oracle.hop(op, cur, w.agg, threads=1)
+                t1 += time.perf_counter() - t0
+                hops1 += 1
+                if hops1 % K == 0:
+                    cur = Xw
+            rec["cpu_baseline"]["single_thread_value"] = round(nnz * d * hops1 / t1 / 1e9, 4)
     plan.close()
+    return rec
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="all",
+                    help="all (default): the four workloads that are resident in HBM, the line being the largest one's; "
+                         "or one of 1..5")
+    ap.add_argument("--scale", type=float, default=1.0,
+                    help="shrink node and pair counts together (workload 5 is only practical below 1)")
+    ap.add_argument("--memory", choices=["device", "pinned"], default=None,
+                    help="where X and the stack live: device (resident schedule) or pinned host memory "
+                         "(streamed schedule; the default for workload 5)")
+    ap.add_argument("--hbm-budget-gb", type=float, default=0.0, help="streamed schedule: HBM budget (0 = automatic)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="library option (gp_set_option), e.g. column_tile=32")
+    ap.add_argument("--lc", action="store_true",
+                    help="time the LC-version forward pass (gp_lc_forward) over the hop stack instead of the precompute")
+    ap.add_argument("--lc-batch", type=int, default=4096, help="--lc: mini-batch rows per call (0 = all rows in one call)")
+    ap.add_argument("--contiguous-ids", action="store_true",
+                    help="workload 4 only: community-contiguous node ids (locality given) instead of permuted ids")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        return 2
+    if args.workload != "all" and args.workload not in [str(k) for k in WORKLOAD_NAMES]:
+        print("bench.py: --workload must be all or 1..5", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2207_12000_amd as gp
+    if not os.path.exists(gp.LIB_PATH):      # load what is built; build only if nothing is
+        from paper_2207_12000_amd import build as libbuild
+        libbuild.build()
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(torch.device("cuda:0"))
+
+    for kv in args.option:
+        name, val = kv.split("=")
+        gp.gp_set_option(name, int(val))
+    if args.hbm_budget_gb > 0:
+        gp.gp_set_hbm_budget_bytes(int(args.hbm_budget_gb * 2**30))
+
+    if args.workload != "all":
+        rec = time_workload(args, gp, torch, int(args.workload), not args.no_cpu_baseline)
+        if isinstance(rec, int):
+            return rec
+        print(json.dumps(rec))
+        return 0
+    if args.lc:
+        rc = time_workload(args, gp, torch, 2, False)
+        return rc if isinstance(rc, int) else 0
+
+    # every in-HBM workload; the line is the largest one's, the others ride along in short form
+    others = {}
+    head = None
+    for wl in IN_HBM_WORKLOADS:
+        rec = time_workload(args, gp, torch, wl, wl == HEADLINE_WORKLOAD and not args.no_cpu_baseline)
+        torch.cuda.empty_cache()
+        if wl == HEADLINE_WORKLOAD:
+            head = rec
+        else:
+            others[f"config{wl}"] = {
+                "workload": rec["config"]["workload"], "value": rec["value"], "unit": rec["unit"],
+                "ms_per_step": rec["ms_per_step"], "work_lists": rec["config"]["work_lists"],
+                "roofline": {k: rec["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
+                                                             "avg_launch_us", "algorithmic_bytes_per_launch")},
+                "host_s": rec["host_s"]}
+    head["other_workloads"] = others
+    print(json.dumps(head))
     return 0
 
 
