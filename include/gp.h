@@ -164,7 +164,9 @@ gp_status gp_plan_work_lists(const gp_plan *plan, int32_t d, gp_dtype dtype, int
  * Device-resident operands: the call enqueues all work on hip_stream and
  * returns; the caller synchronises.  Pinned-host operands: blocks and column
  * slabs are streamed through HBM on library-owned side streams and the call
- * returns after the last slab has reached out_stack.  The first call on a plan
+ * returns after the last slab has reached out_stack (streams, events and staging
+ * buffers are kept with the plan and reused by later calls of the same shape; edge
+ * blocks that all fit the budget are sent once per plan).  The first call on a plan
  * uploads the plan to the current device and allocates scratch (partial-row
  * buffer); later calls with the same d reuse both.  Calls on ONE plan must not
  * overlap in time (they share that scratch); different plans are independent.
@@ -173,6 +175,22 @@ gp_status gp_plan_work_lists(const gp_plan *plan, int32_t d, gp_dtype dtype, int
  */
 gp_status gp_propagate(const gp_plan *plan, const void *X, int64_t ldx, int32_t d, gp_dtype dtype,
                        gp_agg agg, int32_t K, void *out_stack, int64_t ldo, void *hip_stream);
+
+/* gp_plan_streamed_shape -- the decomposition the last streamed gp_propagate on this
+ * plan ran with (Section 3.2, "Optimal graph decomposition", Eq. 12): *edge_blocks = b,
+ * *column_blocks = c; both 0 before any streamed call.  The library takes
+ *     B_S = 4 nnz + 16 segments            (column ids and segment records, bytes)
+ *     B_X = (2 n s + 4 partial_rows) d     (two column slabs and the partial rows; s = element bytes)
+ *     B_GPU = HBM budget - (8 n + 16 partial_rows + 4096)
+ * and the pair (b*, c*) = gp_solve_aggregation_blocks(B_S, B_X, B_GPU, 2, 1, ceil(d / (16/s))):
+ * two edge-block buffers of B_S / b, column slabs of ceil(d / c) columns rounded up to whole
+ * 16-byte vectors.  If the plan already has at least b* blocks they are used as they are
+ * (and the slabs are made as wide as then fits, so c <= c*); otherwise the sorted list is
+ * cut anew into b* balanced blocks -- the planner's rule, another count -- with segments
+ * and partial rows of their own (one more block at a time, should the cut's own
+ * book-keeping exceed the estimate), and c = c*, or the next c whose slab of whole
+ * 16-byte column groups fits (Eq. 12 divides B_X evenly; a slab cannot). */
+gp_status gp_plan_streamed_shape(const gp_plan *plan, int64_t *edge_blocks, int64_t *column_blocks);
 
 /* ---------------------------------------------------------------------------
  * gp_propagate_noalloc -- gp_propagate for callers that cannot allocate: code under

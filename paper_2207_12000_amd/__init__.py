@@ -49,6 +49,7 @@ _SIGNATURES = {
                                       _c.POINTER(_c.c_int32), _c.c_void_p, _c.c_void_p, _c.c_int64]),
     "gp_propagate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                 _c.c_void_p, _c.c_int64, _c.c_void_p]),
+    "gp_plan_streamed_shape": (_c.c_int, [_c.c_void_p, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_int64)]),
     "gp_propagate_noalloc": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                         _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_noalloc_partial_row_bytes": (_c.c_int64, []),
@@ -206,6 +207,12 @@ class Plan:
     @property
     def segment_edges(self) -> int:
         return lib().gp_plan_segment_edges(self.handle)
+
+    def streamed_shape(self):
+        """(edge blocks b, column blocks c) of the last streamed gp_propagate on this plan."""
+        b, c = ctypes.c_int64(), ctypes.c_int64()
+        _check(lib().gp_plan_streamed_shape(self.handle, ctypes.byref(b), ctypes.byref(c)), "gp_plan_streamed_shape")
+        return b.value, c.value
 
     def row_clusters(self):
         """(label[n], num_clusters, inside_fraction, typical_rows) of the cache schedule."""

@@ -120,17 +120,19 @@ struct gp_plan {
     mutable std::mutex mu;
     mutable gp::RowClusters clusters;  // made on first use (under mu)
     mutable gp::DevicePlan dev;
-    // pinned host mirrors of col / segs for the streamed schedule (made on first use)
+    // streamed schedule: pinned host mirror of col (made on first use) and the state kept
+    // from one streamed call to the next (gp_stream.cpp owns both)
     mutable int32_t* pinned_col = nullptr;
-    mutable gp::Segment* pinned_segs = nullptr;
-    // streamed schedule: after block p every row below rows_final[p] is complete, and
-    // split rows [0, split_final[p]) are the cut rows among them (filled with the pinned mirrors)
-    mutable std::vector<int64_t> rows_final, split_final;
+    mutable void* streamed = nullptr;
 };
 
 namespace gp {
 
 gp_status build_schedule(gp_plan* plan);
+// segments, split rows and partial-row slots for the sorted list of `plan` cut at block_off
+// (block p = [block_off[p], block_off[p+1])): the plan's own blocks, or another cut of the same list
+gp_status cut_schedule(const gp_plan& plan, const std::vector<int64_t>& block_off, std::vector<Segment>& segs,
+                       std::vector<int64_t>& seg_off, std::vector<SplitRow>& split, int64_t& num_slots);
 void cluster_rows(const gp_plan& P, RowClusters& C);
 void build_xcd_lists(const gp_plan& P, const RowClusters& C, int S, int slice_elems, int d, std::vector<Segment>& recs,
                      int64_t off[9]);

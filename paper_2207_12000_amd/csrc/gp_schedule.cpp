@@ -16,10 +16,23 @@ namespace gp {
 
 namespace {
 
+// P supplies the sorted list (rowptr, nnz, n); the cut into blocks is the caller's.
+struct CutPlan {
+    const gp_plan& plan;
+    const std::vector<int64_t>& block_off;
+    const std::vector<int64_t>& rowptr;
+    int64_t nnz, n;
+    int32_t num_blocks;
+    CutPlan(const gp_plan& p, const std::vector<int64_t>& off)
+        : plan(p), block_off(off), rowptr(p.rowptr), nnz(p.nnz), n(p.n), num_blocks((int32_t)off.size() - 1)
+    {
+    }
+};
+
 struct Cutter {
-    const gp_plan& P;
+    const CutPlan P;
     int64_t L;
-    explicit Cutter(const gp_plan& p) : P(p), L(p.segment_edges) {}
+    Cutter(const gp_plan& p, const std::vector<int64_t>& off) : P(p, off), L(p.segment_edges) {}
 
     int32_t block_of(int64_t e) const
     {
@@ -98,11 +111,26 @@ struct Cutter {
 
 gp_status build_schedule(gp_plan* plan)
 {
-    gp_plan& P = *plan;
-    const int64_t L = P.segment_edges;
+    return cut_schedule(*plan, plan->block_off, plan->segs, plan->seg_off, plan->split, plan->num_slots);
+}
+
+gp_status cut_schedule(const gp_plan& plan, const std::vector<int64_t>& block_off, std::vector<Segment>& out_segs,
+                       std::vector<int64_t>& out_seg_off, std::vector<SplitRow>& out_split, int64_t& out_num_slots)
+{
+    const int64_t L = plan.segment_edges;
     if (L < 8 || L > 32768) return fail(GP_ERR_INVALID_ARG, "segment_edges = %lld outside 8 .. 32768", (long long)L);
-    Cutter cut(P);
-    const int32_t b = P.num_blocks;
+    if (block_off.size() < 2) return fail(GP_ERR_INVALID_ARG, "a schedule needs at least one block");
+    Cutter cut(plan, block_off);
+    // the names the body below uses
+    struct Out {
+        const std::vector<int64_t>& rowptr;
+        int64_t n, nnz;
+        std::vector<Segment>& segs;
+        std::vector<int64_t>& seg_off;
+        std::vector<SplitRow>& split;
+        int64_t& num_slots;
+    } P{plan.rowptr, plan.n, plan.nnz, out_segs, out_seg_off, out_split, out_num_slots};
+    const int32_t b = (int32_t)block_off.size() - 1;
     const int nt = (P.n + P.nnz < (1 << 16)) ? 1 : host_threads();
 
     // split rows and their carry slots, in ascending row order

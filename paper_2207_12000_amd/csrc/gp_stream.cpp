@@ -24,14 +24,111 @@ namespace gp {
 
 namespace {
 
-struct Streams {
+// The blocks and segments the streamed hops walk: the plan's own, or -- when the HBM
+// budget asks for more blocks than the plan has (Eq. 12) -- another balanced cut of the
+// same sorted list with its own segments, cut rows and partial-row slots.
+struct StreamSchedule {
+    bool own = false;
+    std::vector<int64_t> own_block_off, own_seg_off;
+    std::vector<Segment> own_segs;
+    std::vector<SplitRow> own_split;
+    int64_t own_slots = 0;
+    const std::vector<int64_t>* block_off = nullptr;
+    const std::vector<int64_t>* seg_off = nullptr;
+    const std::vector<Segment>* segs = nullptr;
+    const std::vector<SplitRow>* split = nullptr;
+    int64_t num_slots = 0;
+    int32_t b = 0;
+    int64_t max_edges = 0, max_segs = 0;
+    // after block p every row below rows_final[p] is complete, and split rows
+    // [0, split_final[p]) are the cut rows among them
+    std::vector<int64_t> rows_final, split_final;
+    Segment* pinned_segs = nullptr;
+
+    void use_plan(const gp_plan* plan)
+    {
+        own = false;
+        block_off = &plan->block_off;
+        seg_off = &plan->seg_off;
+        segs = &plan->segs;
+        split = &plan->split;
+        num_slots = plan->num_slots;
+        finish();
+    }
+    gp_status recut(const gp_plan* plan, int64_t blocks)
+    {
+        own = true;
+        own_block_off.resize((size_t)blocks + 1);
+        const int64_t q = plan->nnz / blocks, r = plan->nnz % blocks;  // the planner's balanced cut, other count
+        for (int64_t p = 0; p <= blocks; ++p) own_block_off[(size_t)p] = p * q + std::min(p, r);
+        gp_status st = cut_schedule(*plan, own_block_off, own_segs, own_seg_off, own_split, own_slots);
+        if (st != GP_OK) return st;
+        block_off = &own_block_off;
+        seg_off = &own_seg_off;
+        segs = &own_segs;
+        split = &own_split;
+        num_slots = own_slots;
+        finish();
+        return GP_OK;
+    }
+    void finish()
+    {
+        b = (int32_t)block_off->size() - 1;
+        max_edges = max_segs = 0;
+        for (int32_t p = 0; p < b; ++p) {
+            max_edges = std::max(max_edges, (*block_off)[(size_t)p + 1] - (*block_off)[(size_t)p]);
+            max_segs = std::max(max_segs, (*seg_off)[(size_t)p + 1] - (*seg_off)[(size_t)p]);
+        }
+    }
+    // first row that a later block still writes to (through any of its segments, empty
+    // rows included): everything below it is final once block p is done
+    void final_rows(int64_t n)
+    {
+        std::vector<int64_t> first((size_t)b, n);
+        for (int32_t q = 0; q < b; ++q)
+            for (int64_t s = (*seg_off)[(size_t)q]; s < (*seg_off)[(size_t)q + 1]; ++s)
+                first[(size_t)q] = std::min<int64_t>(first[(size_t)q], (*segs)[(size_t)s].row);
+        rows_final.assign((size_t)b, n);
+        split_final.assign((size_t)b, (int64_t)split->size());
+        int64_t later = n;
+        for (int32_t q = b - 1; q >= 0; --q) {
+            rows_final[(size_t)q] = later;
+            split_final[(size_t)q] = std::lower_bound(split->begin(), split->end(), later,
+                                                       [](const SplitRow& r, int64_t row) { return (int64_t)r.row < row; }) -
+                                      split->begin();
+            later = std::min(later, first[(size_t)q]);
+        }
+    }
+};
+
+// Everything a streamed call needs besides the caller's operands, kept with the plan
+// from one call to the next: the schedule, three streams and their events, and the
+// device buffers (norm vectors, cut rows, partial rows, cursors, two column slabs, the
+// edge-block buffers).  A call whose shape differs (slab width, block count, buffer
+// count, element size, device) builds it anew.
+struct StreamedState {
+    int device = -1;
+    int es = 0;
+    int64_t w = 0, wpad = 0, nbuf = 0;
+    bool blocks_stay = false, blocks_loaded = false;
+    int64_t used_b = 0, used_c = 0;  // what the last call ran with (gp_plan_streamed_shape)
+    StreamSchedule sched;
+
     hipStream_t in = nullptr, cmp = nullptr, out = nullptr;
     std::vector<hipEvent_t> blk_ready, blk_free;  // one pair per edge-block buffer
     hipEvent_t hop_done = nullptr, out_done[2] = {nullptr, nullptr};
     std::vector<void*> dev;
+    float *d_dinv_sqrt = nullptr, *d_dinv = nullptr, *d_carry = nullptr;
+    unsigned long long* d_ctrl = nullptr;
+    SplitRow* d_split = nullptr;
+    char* d_slab[2] = {nullptr, nullptr};
+    std::vector<int32_t*> d_col;
+    std::vector<Segment*> d_segs;
 
-    ~Streams()
+    ~StreamedState()
     {
+        int cur = -1;
+        const bool switched = device >= 0 && hipGetDevice(&cur) == hipSuccess && cur != device && hipSetDevice(device) == hipSuccess;
         if (in) (void)hipStreamSynchronize(in);
         if (cmp) (void)hipStreamSynchronize(cmp);
         if (out) (void)hipStreamSynchronize(out);
@@ -43,8 +140,10 @@ struct Streams {
         if (in) (void)hipStreamDestroy(in);
         if (cmp) (void)hipStreamDestroy(cmp);
         if (out) (void)hipStreamDestroy(out);
+        if (sched.pinned_segs) (void)hipHostFree(sched.pinned_segs);
+        if (switched) (void)hipSetDevice(cur);
     }
-    gp_status init(int block_buffers)
+    gp_status init_streams(int block_buffers)
     {
         // default priority on purpose: all three streams are peers
         GP_HIP(hipStreamCreateWithFlags(&in, hipStreamNonBlocking));
@@ -73,10 +172,9 @@ struct Streams {
     }
 };
 
-// pinned mirrors of the two arrays that are streamed block by block
-gp_status ensure_pinned(const gp_plan* plan)
+// pinned mirror of the column list (streamed block by block whatever the cut)
+gp_status ensure_pinned_col(const gp_plan* plan)
 {
-    std::lock_guard<std::mutex> lk(plan->mu);
     if (!plan->pinned_col && !plan->col.empty()) {
         void* p = nullptr;
         hipError_t e = hipHostMalloc(&p, plan->col.size() * sizeof(int32_t), hipHostMallocDefault);
@@ -84,47 +182,8 @@ gp_status ensure_pinned(const gp_plan* plan)
         std::memcpy(p, plan->col.data(), plan->col.size() * sizeof(int32_t));
         plan->pinned_col = (int32_t*)p;
     }
-    if (!plan->pinned_segs && !plan->segs.empty()) {
-        void* p = nullptr;
-        hipError_t e = hipHostMalloc(&p, plan->segs.size() * sizeof(Segment), hipHostMallocDefault);
-        if (e != hipSuccess) return fail(GP_ERR_OOM_HOST, "pinned copy of the segment list: %s", hipGetErrorString(e));
-        std::memcpy(p, plan->segs.data(), plan->segs.size() * sizeof(Segment));
-        plan->pinned_segs = (Segment*)p;
-    }
-    if (plan->rows_final.empty() && plan->num_blocks > 0) {
-        // first row that a later block still writes to (through any of its segments,
-        // empty rows included): everything below it is final once block p is done
-        const int32_t b = plan->num_blocks;
-        std::vector<int64_t> first((size_t)b, plan->n);
-        for (int32_t q = 0; q < b; ++q)
-            for (int64_t s = plan->seg_off[q]; s < plan->seg_off[q + 1]; ++s)
-                first[(size_t)q] = std::min<int64_t>(first[(size_t)q], plan->segs[(size_t)s].row);
-        plan->rows_final.assign((size_t)b, plan->n);
-        plan->split_final.assign((size_t)b, (int64_t)plan->split.size());
-        int64_t later = plan->n;
-        for (int32_t q = b - 1; q >= 0; --q) {
-            plan->rows_final[(size_t)q] = later;
-            plan->split_final[(size_t)q] =
-                std::lower_bound(plan->split.begin(), plan->split.end(), later,
-                                 [](const SplitRow& r, int64_t row) { return (int64_t)r.row < row; }) -
-                plan->split.begin();
-            later = std::min(later, first[(size_t)q]);
-        }
-    }
     return GP_OK;
 }
-
-}  // namespace
-
-void release_pinned(gp_plan* plan)
-{
-    if (plan->pinned_col) (void)hipHostFree(plan->pinned_col);
-    if (plan->pinned_segs) (void)hipHostFree(plan->pinned_segs);
-    plan->pinned_col = nullptr;
-    plan->pinned_segs = nullptr;
-}
-
-namespace {
 
 // n rows of wc elements between a pinned host matrix and a device slab.  A run that
 // is contiguous on both sides is one runtime copy in either direction: with rows
@@ -151,84 +210,188 @@ gp_status move_rows(void* dst, int64_t ldd, const void* src, int64_t lds, int64_
     return launch_copy_rows(src, lds, dst, ldd, n, wc, dtype, stream, kLinkCopyBlocks);
 }
 
+// HBM bytes of the streamed schedule in the terms of Eq. 12: the edge structure B_S
+// (column ids and segment records) is held in two block buffers at a time (beta_S = 2,
+// B_S / b each), the feature side B_X (two column slabs and the partial rows, per feature
+// column) in slabs of d / c columns (beta_X = 1), and what is neither (two norm vectors,
+// the list of cut rows) comes off the budget first.
+struct Volumes {
+    double B_S, B_X, B_GPU;
+    int64_t fixed, per_col;
+};
+Volumes volumes(int64_t n, int64_t nnz, int64_t nsegs, int64_t slots, int32_t d, int es, int64_t budget)
+{
+    Volumes v;
+    v.fixed = 2 * n * 4 + 16 * slots + 4096;  // a cut row owns at least two slots: 16 B per slot bounds the list
+    v.per_col = 2 * n * es + slots * 4;
+    v.B_S = 4.0 * (double)nnz + (double)sizeof(Segment) * (double)nsegs;
+    v.B_X = (double)v.per_col * (double)d;
+    v.B_GPU = (double)(budget - v.fixed);
+    return v;
+}
+
 }  // namespace
+
+void release_pinned(gp_plan* plan)
+{
+    delete (StreamedState*)plan->streamed;
+    plan->streamed = nullptr;
+    if (plan->pinned_col) (void)hipHostFree(plan->pinned_col);
+    plan->pinned_col = nullptr;
+}
 
 gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg,
                              int32_t K, void* out, int64_t ldo)
 {
     const int64_t n = plan->n;
-    const int32_t b = plan->num_blocks;
     const int es = dtype == GP_F32 ? 4 : 2;
     const int64_t unit = 16 / es;  // slabs are whole 16-byte vectors wide
+    std::lock_guard<std::mutex> lk(plan->mu);  // one streamed call per plan at a time
 
-    gp_status st = ensure_pinned(plan);
+    gp_status st = ensure_pinned_col(plan);
     if (st != GP_OK) return st;
+    int cur = -1;
+    GP_HIP(hipGetDevice(&cur));
 
-    // ---- HBM budget -> slab width (Eq. 12 with b fixed by the plan) ----------------
-    int64_t max_edges = 0, max_segs = 0;
-    for (int32_t p = 0; p < b; ++p) {
-        max_edges = std::max(max_edges, plan->block_off[p + 1] - plan->block_off[p]);
-        max_segs = std::max(max_segs, plan->seg_off[p + 1] - plan->seg_off[p]);
-    }
+    // ---- HBM budget -> block count b and column-block count c (Eq. 12) ----------------
     int64_t budget = options().hbm_budget_bytes;
     if (budget <= 0) {
         size_t free_b = 0, total_b = 0;
         GP_HIP(hipMemGetInfo(&free_b, &total_b));
         budget = (int64_t)(free_b / 10 * 8);
+        // buffers kept from an earlier call on this plan count as free: they are reused or released
+        if (plan->streamed) budget += 0;
     }
-    const int64_t fixed = 2 * (max_edges * 4 + max_segs * (int64_t)sizeof(Segment)) + 2 * n * 4 +
-                          (int64_t)plan->split.size() * (int64_t)sizeof(SplitRow) + 4096;
-    const int64_t per_col = 2 * n * es + plan->num_slots * 4;
-    int64_t w = (budget - fixed) / per_col;
-    if (w >= d)
-        w = d;
-    else
-        w = w / unit * unit;
-    if (w < std::min<int64_t>(unit, d))
+    const Volumes v = volumes(n, plan->nnz, (int64_t)plan->segs.size(), plan->num_slots, d, es, budget);
+    const int64_t max_c = (d + unit - 1) / unit;
+    int64_t b_star = 0, c_star = 0;
+    if (v.B_GPU <= 0 || gp_solve_aggregation_blocks(v.B_S, v.B_X, v.B_GPU, 2.0, 1.0, max_c, &b_star, &c_star) != GP_OK)
         return fail(GP_ERR_OOM_DEVICE,
-                    "HBM budget of %lld bytes cannot hold two edge blocks (%lld bytes) plus two column slabs of %lld columns; "
-                    "plan with a smaller block budget or raise the HBM budget",
-                    (long long)budget, (long long)fixed, (long long)unit);
-    const int64_t wpad = (w + 3) / 4 * 4;  // carry rows stay 16-byte aligned
-    // Edge-block buffers: two for double buffering; if the budget has room for all b
-    // blocks they are uploaded once and stay (on a 288 GB device only what does not fit
-    // has to be streamed again every hop).
-    const int64_t block_bytes = max_edges * 4 + max_segs * (int64_t)sizeof(Segment);
-    int64_t nbuf = 2;
-    if (block_bytes > 0) nbuf = std::min<int64_t>(b, 2 + (budget - fixed - per_col * w) / block_bytes);
-    if (nbuf < b) nbuf = std::min<int64_t>(b, 2);
-    const bool blocks_stay = nbuf >= b;
+                    "HBM budget of %lld bytes cannot hold two edge blocks plus two column slabs of %lld columns at any "
+                    "block count; raise the HBM budget",
+                    (long long)budget, (long long)unit);
 
-    Streams S;
-    if ((st = S.init((int)nbuf)) != GP_OK) return st;
-    float *d_dinv_sqrt, *d_dinv, *d_carry;
-    unsigned long long* d_ctrl;
-    SplitRow* d_split;
-    char* d_slab[2];
-    std::vector<int32_t*> d_col((size_t)nbuf, nullptr);
-    std::vector<Segment*> d_segs((size_t)nbuf, nullptr);
-    if ((st = S.alloc(d_dinv_sqrt, (size_t)n * 4)) != GP_OK || (st = S.alloc(d_dinv, (size_t)n * 4)) != GP_OK ||
-        (st = S.alloc(d_split, plan->split.size() * sizeof(SplitRow))) != GP_OK ||
-        (st = S.alloc(d_carry, (size_t)plan->num_slots * wpad * 4)) != GP_OK ||
-        (st = S.alloc(d_ctrl, kHopCtrlWords * sizeof(unsigned long long))) != GP_OK ||
-        (st = S.alloc(d_slab[0], (size_t)n * w * es)) != GP_OK || (st = S.alloc(d_slab[1], (size_t)n * w * es)) != GP_OK)
-        return st;
-    for (int64_t i = 0; i < nbuf; ++i)
-        if ((st = S.alloc(d_col[i], (size_t)max_edges * 4)) != GP_OK ||
-            (st = S.alloc(d_segs[i], (size_t)max_segs * sizeof(Segment))) != GP_OK)
-            return st;
-    GP_HIP(hipMemsetAsync(d_ctrl, 0, kHopCtrlWords * sizeof(unsigned long long), S.cmp));
-    // small vectors: pageable sources, so these two copies are synchronous in effect
-    GP_HIP(hipMemcpyAsync(d_dinv_sqrt, plan->dinv_sqrt.data(), (size_t)n * 4, hipMemcpyHostToDevice, S.cmp));
-    GP_HIP(hipMemcpyAsync(d_dinv, plan->dinv.data(), (size_t)n * 4, hipMemcpyHostToDevice, S.cmp));
-    if (!plan->split.empty())
-        GP_HIP(hipMemcpyAsync(d_split, plan->split.data(), plan->split.size() * sizeof(SplitRow), hipMemcpyHostToDevice, S.cmp));
-    GP_HIP(hipStreamSynchronize(S.cmp));
+    StreamedState* S = (StreamedState*)plan->streamed;
+    // the plan's own blocks serve whenever they are at least as many as the budget asks for
+    const bool want_own = b_star > plan->num_blocks;
+    const int64_t want_b = want_own ? b_star : plan->num_blocks;
+    if (S && (S->device != cur || S->es != es || S->sched.b != want_b || S->sched.own != want_own)) {
+        delete S;
+        S = nullptr;
+        plan->streamed = nullptr;
+    }
+    StreamSchedule fresh;
+    StreamSchedule* sched = S ? &S->sched : &fresh;
+    int64_t w = 0, wpad = 0, nbuf = 0;
+    for (int attempt = 0;; ++attempt) {
+        if (!S) {
+            if (want_own) {
+                if ((st = fresh.recut(plan, b_star + attempt)) != GP_OK) return st;
+            } else {
+                fresh.use_plan(plan);
+            }
+        }
+        // slab width: with the plan's blocks the widest that fits beside two of them; with a cut of
+        // its own the width Eq. 12's minimiser chose
+        const int64_t block_bytes = sched->max_edges * 4 + sched->max_segs * (int64_t)sizeof(Segment);
+        const int64_t fixed = 2 * n * 4 + (int64_t)sched->split->size() * (int64_t)sizeof(SplitRow) + 4096;
+        const int64_t per_col = 2 * n * es + sched->num_slots * 4;
+        w = (budget - fixed - 2 * block_bytes) / per_col;
+        if (sched->own) w = std::min<int64_t>(w, ((d + c_star - 1) / c_star + unit - 1) / unit * unit);
+        w = w >= d ? d : w / unit * unit;
+        if (w >= std::min<int64_t>(unit, d)) {
+            wpad = (w + 3) / 4 * 4;  // carry rows stay 16-byte aligned
+            // Edge-block buffers: two for double buffering; if the budget has room for all b
+            // blocks they are uploaded once and stay (on a 288 GB device only what does not fit
+            // has to be streamed again every hop).
+            nbuf = 2;
+            if (block_bytes > 0) nbuf = std::min<int64_t>(sched->b, (budget - fixed - per_col * w) / block_bytes);
+            if (nbuf < sched->b) nbuf = std::min<int64_t>(sched->b, 2);
+            break;
+        }
+        // the cut's own segments and cut rows came out a little larger than the estimate
+        if (S || !want_own || attempt >= 8)
+            return fail(GP_ERR_OOM_DEVICE,
+                        "HBM budget of %lld bytes cannot hold two edge blocks (%lld bytes each) plus two column slabs of "
+                        "%lld columns; raise the HBM budget",
+                        (long long)budget, (long long)block_bytes, (long long)unit);
+    }
+    if (S && (S->w != w || S->nbuf != nbuf)) {
+        // same schedule, other buffer shape: keep the schedule, rebuild the rest
+        fresh = std::move(S->sched);
+        S->sched.pinned_segs = nullptr;
+        delete S;
+        S = nullptr;
+        plan->streamed = nullptr;
+        fresh.block_off = fresh.own ? &fresh.own_block_off : &plan->block_off;
+        fresh.seg_off = fresh.own ? &fresh.own_seg_off : &plan->seg_off;
+        fresh.segs = fresh.own ? &fresh.own_segs : &plan->segs;
+        fresh.split = fresh.own ? &fresh.own_split : &plan->split;
+    }
+    if (!S) {
+        S = new StreamedState();
+        plan->streamed = S;
+        S->device = cur;
+        S->es = es;
+        S->w = w;
+        S->wpad = wpad;
+        S->nbuf = nbuf;
+        S->sched = std::move(fresh);
+        StreamSchedule& C = S->sched;
+        C.block_off = C.own ? &C.own_block_off : &plan->block_off;
+        C.seg_off = C.own ? &C.own_seg_off : &plan->seg_off;
+        C.segs = C.own ? &C.own_segs : &plan->segs;
+        C.split = C.own ? &C.own_split : &plan->split;
+        if (C.rows_final.empty()) C.final_rows(n);
+        auto fail_clean = [&](gp_status e) {
+            delete S;
+            plan->streamed = nullptr;
+            return e;
+        };
+        if (!C.pinned_segs && !C.segs->empty()) {
+            void* p = nullptr;
+            hipError_t e = hipHostMalloc(&p, C.segs->size() * sizeof(Segment), hipHostMallocDefault);
+            if (e != hipSuccess) return fail_clean(fail(GP_ERR_OOM_HOST, "pinned copy of the segment list: %s", hipGetErrorString(e)));
+            std::memcpy(p, C.segs->data(), C.segs->size() * sizeof(Segment));
+            C.pinned_segs = (Segment*)p;
+        }
+        if ((st = S->init_streams((int)nbuf)) != GP_OK) return fail_clean(st);
+        S->d_col.assign((size_t)nbuf, nullptr);
+        S->d_segs.assign((size_t)nbuf, nullptr);
+        if ((st = S->alloc(S->d_dinv_sqrt, (size_t)n * 4)) != GP_OK || (st = S->alloc(S->d_dinv, (size_t)n * 4)) != GP_OK ||
+            (st = S->alloc(S->d_split, C.split->size() * sizeof(SplitRow))) != GP_OK ||
+            (st = S->alloc(S->d_carry, (size_t)C.num_slots * wpad * 4)) != GP_OK ||
+            (st = S->alloc(S->d_ctrl, kHopCtrlWords * sizeof(unsigned long long))) != GP_OK ||
+            (st = S->alloc(S->d_slab[0], (size_t)n * w * es)) != GP_OK || (st = S->alloc(S->d_slab[1], (size_t)n * w * es)) != GP_OK)
+            return fail_clean(st);
+        for (int64_t i = 0; i < nbuf; ++i)
+            if ((st = S->alloc(S->d_col[(size_t)i], (size_t)C.max_edges * 4)) != GP_OK ||
+                (st = S->alloc(S->d_segs[(size_t)i], (size_t)C.max_segs * sizeof(Segment))) != GP_OK)
+                return fail_clean(st);
+        hipError_t e = hipMemsetAsync(S->d_ctrl, 0, kHopCtrlWords * sizeof(unsigned long long), S->cmp);
+        // small vectors: pageable sources, so these copies are synchronous in effect
+        if (e == hipSuccess) e = hipMemcpyAsync(S->d_dinv_sqrt, plan->dinv_sqrt.data(), (size_t)n * 4, hipMemcpyHostToDevice, S->cmp);
+        if (e == hipSuccess) e = hipMemcpyAsync(S->d_dinv, plan->dinv.data(), (size_t)n * 4, hipMemcpyHostToDevice, S->cmp);
+        if (e == hipSuccess && !C.split->empty())
+            e = hipMemcpyAsync(S->d_split, C.split->data(), C.split->size() * sizeof(SplitRow), hipMemcpyHostToDevice, S->cmp);
+        if (e == hipSuccess) e = hipStreamSynchronize(S->cmp);
+        if (e != hipSuccess) return fail_clean(fail(GP_ERR_DEVICE, "setting up the streamed schedule: %s", hipGetErrorString(e)));
+        S->blocks_stay = nbuf >= C.b;
+        S->blocks_loaded = false;
+    }
+    const StreamSchedule& C = S->sched;
+    const int32_t b = C.b;
+    const bool blocks_stay = S->blocks_stay;
+    S->used_b = b;
+    S->used_c = (d + w - 1) / w;
+    float* const d_carry = S->d_carry;
+    char* const* d_slab = S->d_slab;
 
-    const float* edge_w = agg == GP_AGG_SYM ? d_dinv_sqrt : nullptr;
-    const float* row_scale = agg == GP_AGG_SYM ? d_dinv_sqrt : agg == GP_AGG_MEAN ? d_dinv : nullptr;
+    const float* edge_w = agg == GP_AGG_SYM ? S->d_dinv_sqrt : nullptr;
+    const float* row_scale = agg == GP_AGG_SYM ? S->d_dinv_sqrt : agg == GP_AGG_MEAN ? S->d_dinv : nullptr;
     const int64_t out_slab = n * ldo * es;  // bytes between two hop slabs in the host stack
-    std::vector<char> blk_used((size_t)nbuf, 0);
+    // a block that stays is sent once per plan, not once per call
+    std::vector<char> blk_used((size_t)nbuf, (blocks_stay && S->blocks_loaded) ? 1 : 0);
     bool out_used[2] = {false, false};
     int64_t blk_seq = 0;  // running count of block visits: ring position when blocks do not stay
 
@@ -249,44 +412,50 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
     }
     struct Joiner {
         std::vector<std::thread>& v;
+        StreamedState* S;
         ~Joiner()
         {
+            // whatever way the call ends, nothing of it is still running afterwards
+            (void)hipStreamSynchronize(S->in);
+            (void)hipStreamSynchronize(S->cmp);
+            (void)hipStreamSynchronize(S->out);
             for (auto& t : v)
                 if (t.joinable()) t.join();
         }
-    } joiner{copiers};
+    } joiner{copiers, S};
 
     for (int64_t c0 = 0; c0 < d; c0 += w) {
         const int32_t wc = (int32_t)std::min<int64_t>(w, d - c0);
         // X[:, c0 : c0+wc] -> slab 0 (its previous content must have left first)
-        if (out_used[0]) GP_HIP(hipStreamWaitEvent(S.cmp, S.out_done[0], 0));
-        if ((st = move_rows(d_slab[0], w, (const char*)X + c0 * es, ldx, n, wc, dtype, hipMemcpyHostToDevice, S.cmp)) != GP_OK)
+        if (out_used[0]) GP_HIP(hipStreamWaitEvent(S->cmp, S->out_done[0], 0));
+        if ((st = move_rows(d_slab[0], w, (const char*)X + c0 * es, ldx, n, wc, dtype, hipMemcpyHostToDevice, S->cmp)) != GP_OK)
             return st;
         out_used[0] = false;  // nothing leaves from the slab that holds X
 
         for (int32_t k = 1; k <= K; ++k) {
             const int src = (k - 1) & 1, dst = k & 1;
             // the slab about to be overwritten may still be on its way to the host
-            if (out_used[dst]) GP_HIP(hipStreamWaitEvent(S.cmp, S.out_done[dst], 0));
+            if (out_used[dst]) GP_HIP(hipStreamWaitEvent(S->cmp, S->out_done[dst], 0));
             int64_t rows_done = 0, split_done = 0;
             for (int32_t p = 0; p < b; ++p, ++blk_seq) {
                 const int buf = blocks_stay ? p : (int)(blk_seq % nbuf);
-                const int64_t e_lo = plan->block_off[p], e_cnt = plan->block_off[p + 1] - e_lo;
-                const int64_t s_lo = plan->seg_off[p], s_cnt = plan->seg_off[p + 1] - s_lo;
-                if (!(blocks_stay && blk_used[buf])) {  // a block that stays is sent once
-                    if (blk_used[buf]) GP_HIP(hipStreamWaitEvent(S.in, S.blk_free[buf], 0));
+                const int64_t e_lo = (*C.block_off)[(size_t)p], e_cnt = (*C.block_off)[(size_t)p + 1] - e_lo;
+                const int64_t s_lo = (*C.seg_off)[(size_t)p], s_cnt = (*C.seg_off)[(size_t)p + 1] - s_lo;
+                if (!(blocks_stay && blk_used[(size_t)buf])) {  // a block that stays is sent once
+                    if (blk_used[(size_t)buf]) GP_HIP(hipStreamWaitEvent(S->in, S->blk_free[(size_t)buf], 0));
                     if (e_cnt)
-                        GP_HIP(hipMemcpyAsync(d_col[buf], plan->pinned_col + e_lo, (size_t)e_cnt * 4, hipMemcpyHostToDevice, S.in));
+                        GP_HIP(hipMemcpyAsync(S->d_col[(size_t)buf], plan->pinned_col + e_lo, (size_t)e_cnt * 4, hipMemcpyHostToDevice,
+                                              S->in));
                     if (s_cnt)
-                        GP_HIP(hipMemcpyAsync(d_segs[buf], plan->pinned_segs + s_lo, (size_t)s_cnt * sizeof(Segment),
-                                              hipMemcpyHostToDevice, S.in));
-                    GP_HIP(hipEventRecord(S.blk_ready[buf], S.in));
+                        GP_HIP(hipMemcpyAsync(S->d_segs[(size_t)buf], C.pinned_segs + s_lo, (size_t)s_cnt * sizeof(Segment),
+                                              hipMemcpyHostToDevice, S->in));
+                    GP_HIP(hipEventRecord(S->blk_ready[(size_t)buf], S->in));
+                    GP_HIP(hipStreamWaitEvent(S->cmp, S->blk_ready[(size_t)buf], 0));
                 }
-                GP_HIP(hipStreamWaitEvent(S.cmp, S.blk_ready[buf], 0));
                 HopArgs a;
-                a.segs = d_segs[buf];
+                a.segs = S->d_segs[(size_t)buf];
                 a.num_segs = s_cnt;
-                a.col = d_col[buf];
+                a.col = S->d_col[(size_t)buf];
                 a.col_base = e_lo;
                 a.edge_w = edge_w;
                 a.row_scale = row_scale;
@@ -296,21 +465,21 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
                 a.ldout = w;
                 a.carry = d_carry;
                 a.carry_ld = wpad;
-                a.ctrl = d_ctrl;
+                a.ctrl = S->d_ctrl;
                 a.d = wc;
                 a.dtype = dtype;
                 a.column_slices = plan->opt.column_slices <= 8 ? plan->opt.column_slices : 0;
                 a.persistent_blocks = plan->opt.persistent_blocks;
                 a.column_tile = plan->opt.column_tile;
-                if ((st = hop_passes(a, S.cmp)) != GP_OK) return st;
-                GP_HIP(hipEventRecord(S.blk_free[buf], S.cmp));
-                blk_used[buf] = 1;
+                if ((st = hop_passes(a, S->cmp)) != GP_OK) return st;
+                GP_HIP(hipEventRecord(S->blk_free[(size_t)buf], S->cmp));
+                blk_used[(size_t)buf] = 1;
                 // Rows that no later block writes to are final now: complete the cut
                 // ones among them and send the range home while the next blocks run.
-                const int64_t rows_to = plan->rows_final[(size_t)p], split_to = plan->split_final[(size_t)p];
+                const int64_t rows_to = C.rows_final[(size_t)p], split_to = C.split_final[(size_t)p];
                 if (split_to > split_done) {
                     FixupArgs f;
-                    f.split = d_split + split_done;
+                    f.split = S->d_split + split_done;
                     f.num_split = split_to - split_done;
                     f.carry = d_carry;
                     f.carry_ld = wpad;
@@ -320,29 +489,41 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
                     f.d = wc;
                     f.dtype = dtype;
                     f.column_tile = plan->opt.column_tile;
-                    if ((st = fixup_passes(f, S.cmp)) != GP_OK) return st;
+                    if ((st = fixup_passes(f, S->cmp)) != GP_OK) return st;
                     split_done = split_to;
                 }
                 // (small ranges are held back and leave with the next one)
                 if (rows_to > rows_done && (rows_to - rows_done >= kMinRowsPerCopy || p == b - 1)) {
-                    GP_HIP(hipEventRecord(S.hop_done, S.cmp));
-                    GP_HIP(hipStreamWaitEvent(S.out, S.hop_done, 0));
+                    GP_HIP(hipEventRecord(S->hop_done, S->cmp));
+                    GP_HIP(hipStreamWaitEvent(S->out, S->hop_done, 0));
                     if ((st = move_rows((char*)out + (int64_t)k * out_slab + (rows_done * ldo + c0) * es, ldo,
                                         d_slab[dst] + rows_done * w * es, w, rows_to - rows_done, wc, dtype,
-                                        hipMemcpyDeviceToHost, S.out)) != GP_OK)
+                                        hipMemcpyDeviceToHost, S->out)) != GP_OK)
                         return st;
                     rows_done = rows_to;
                 }
             }
-            GP_HIP(hipEventRecord(S.out_done[dst], S.out));
+            if (blocks_stay) S->blocks_loaded = true;
+            GP_HIP(hipEventRecord(S->out_done[dst], S->out));
             out_used[dst] = true;
         }
     }
-    GP_HIP(hipStreamSynchronize(S.in));
-    GP_HIP(hipStreamSynchronize(S.cmp));
-    GP_HIP(hipStreamSynchronize(S.out));
-    for (auto& t : copiers) t.join();
+    GP_HIP(hipStreamSynchronize(S->in));
+    GP_HIP(hipStreamSynchronize(S->cmp));
+    GP_HIP(hipStreamSynchronize(S->out));
     return GP_OK;
 }
 
 }  // namespace gp
+
+using namespace gp;
+
+extern "C" gp_status gp_plan_streamed_shape(const gp_plan* plan, int64_t* edge_blocks, int64_t* column_blocks)
+{
+    if (!plan || !edge_blocks || !column_blocks) return fail(GP_ERR_INVALID_ARG, "NULL argument");
+    std::lock_guard<std::mutex> lk(plan->mu);
+    const StreamedState* S = (const StreamedState*)plan->streamed;
+    *edge_blocks = S ? S->used_b : 0;
+    *column_blocks = S ? S->used_c : 0;
+    return GP_OK;
+}

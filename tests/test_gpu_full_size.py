@@ -101,67 +101,95 @@ class _Widened:
         return gp_synth.bf16_bits_to_f32(self.bits[idx])
 
 
-def test_config5_streamed_sampled_rows_every_hop():
-    """The out-of-core workload (bf16 storage, sym, K = 3) through the streamed
-    schedule from pinned host memory.  Scale from GP_TEST_CONFIG5_SCALE (default
-    0.05 = 5.55 M nodes / 161 M non-zeros; 1.0 is the full 111 M-node graph and needs
-    about 200 GB of host memory and several minutes).  Each hop is checked on sampled
-    rows against the oracle applied to the library's own stored previous hop: one RNE
-    store plus fp32 accumulation, |err| <= 2^-8 * A^|X_{k-1}|, which implies the
+# Pinned host memory on the GPU machine: hipHostMalloc succeeds up to 65.5 GiB in total (measured in
+# 0.5 GiB steps; a single 64 GiB request succeeds, anything past 65.5 GiB returns hipErrorOutOfMemory
+# although the host has 309 GB).  The streamed schedule keeps, pinned: the hop stack (K + 1 slabs of
+# n x 128 bf16 = 1024 B per node with X living in slab 0), a copy of the column list (4 B per
+# non-zero, 29.8 non-zeros per node) and of the segment list (16 B per node): 1159 B per node.
+# 65.5 GiB / 1159 B = 60.6 M nodes = 0.546 of the full 111,059,956; the committed scale keeps
+# 17 % of that in reserve for whatever else the process has pinned.
+CONFIG5_DEFAULT_SCALE = 0.45
+PINNED_LIMIT_GIB = 65.5
+
+
+def run_config5(scale):
+    """The out-of-core workload (bf16 storage, sym, K = 3) through the streamed schedule
+    from pinned host memory, X living in slab 0 of the stack.  Each hop is checked on
+    sampled rows against the oracle applied to the library's own stored previous hop: one
+    RNE store plus fp32 accumulation, |err| <= 2^-8 * A^|X_{k-1}|, which implies the
     end-to-end 1e-2 bound for K = 3.  Up to scale 0.3 the oracle's planner is built in
     full (and the plan compared bit for bit); above it, or with
     GP_TEST_CONFIG5_ORACLE=sampled, the sampled rows' neighbour sets and degrees come
     from a scan of the pair list (oracle.sampled)."""
-    import os
     import time
 
-    import torch
+    from hostmem import Pinned
     from oracle import sampled
-    scale = float(os.environ.get("GP_TEST_CONFIG5_SCALE", "0.05"))
     full_oracle = scale <= 0.3 and os.environ.get("GP_TEST_CONFIG5_ORACLE", "full") != "sampled"
     t0 = time.time()
     w = gp_synth.make_workload(5, scale=scale, with_features=False)
-    x = torch.empty((w.n, w.d), dtype=torch.bfloat16, pin_memory=True)
-    gp_synth.fill_features(x.view(torch.int16).numpy().view(np.uint16), "normal",
-                           gp_synth.rng_for(gp_synth.BASE_SEED + 5, 1))
-    out = torch.empty((w.K + 1, w.n, w.d), dtype=torch.bfloat16, pin_memory=True)
-    print(f"config 5 scale {scale}: n {w.n}, pairs {w.m}, generated in {time.time() - t0:.0f} s", flush=True)
-    op = oracle.plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) if full_oracle else None
-    t0 = time.time()
-    with gp.gp_plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) as lp:
-        print(f"planned in {time.time() - t0:.0f} s: nnz {lp.nnz}, {lp.num_blocks} blocks", flush=True)
-        if full_oracle:
-            same_plan(lp, op)
-            # a budget that forces two column slabs and streams every edge block per hop and slab
-            per_col = 2 * w.n * 2 + lp.num_partial_rows * 4
-            fixed = 2 * (int(np.diff(lp.block_off).max()) * 4 + int(np.diff(lp.segment_off).max()) * 16) + 8 * w.n \
-                + 16 * lp.num_partial_rows + 4096
-            gp.gp_set_hbm_budget_bytes(fixed + per_col * 72)
-        rng = np.random.default_rng(5005)
-        deg_l = lp.deg
-        rows = np.unique(np.concatenate([
-            rng.integers(0, w.n, 600 if full_oracle else 200),
-            lp.block_row_lo, lp.block_row_hi,                               # rows cut by block boundaries
-            np.argsort(deg_l)[-8:] if full_oracle else np.flatnonzero((deg_l > 2000) & (deg_l < 6000))[:4]]))
+    mem = Pinned((w.K + 1) * w.n * w.d * 2)
+    try:
+        stack = mem.array(np.uint16, (w.K + 1, w.n, w.d))
+        gp_synth.fill_features(stack[0], "normal", gp_synth.rng_for(gp_synth.BASE_SEED + 5, 1))
+        x_first = stack[0, :4096].copy()
+        print(f"config 5 scale {scale}: n {w.n}, pairs {w.m}, stack {mem.nbytes / 2**30:.1f} GiB pinned, "
+              f"generated in {time.time() - t0:.0f} s", flush=True)
+        op = oracle.plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) if full_oracle else None
         t0 = time.time()
-        try:
-            gp.gp_propagate(lp, x.data_ptr(), w.d, w.d, gp.GP_BF16, w.agg, w.K, out.data_ptr(), w.d, None)
-        finally:
-            gp.gp_set_hbm_budget_bytes(0)
-        dt = time.time() - t0
-        print(f"streamed propagate (first call, incl. pinned mirrors): {dt:.2f} s = "
-              f"{lp.nnz * w.d * w.K / dt / 1e9:.0f} GEFU/s", flush=True)
-    assert torch.equal(out[0].view(torch.int16), x.view(torch.int16))
-    stack = out.view(torch.int16).numpy().view(np.uint16)
-    if not full_oracle:
-        cols, deg = sampled.neighbourhoods(w.src, w.dst, w.n, w.flags, rows)
-    for k in range(1, w.K + 1):
-        prev = _Widened(stack[k - 1])
-        if full_oracle:
-            want, bound = oracle.hop_rows(op, prev, w.agg, rows)
-        else:
-            want, bound = sampled.hop_rows(cols, deg, rows, prev, w.agg)
-        got = gp_synth.bf16_bits_to_f32(stack[k][rows]).astype(np.float64)
-        err = np.abs(got - want)
-        assert np.all(err <= 2.0 ** -8 * bound + 1e-30), \
-            f"hop {k}: worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {2.0 ** -8:.3g})"
+        with gp.gp_plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) as lp:
+            print(f"planned in {time.time() - t0:.0f} s: nnz {lp.nnz}, {lp.num_blocks} blocks", flush=True)
+            if full_oracle:
+                same_plan(lp, op)
+                # a budget that forces two column slabs and streams every edge block per hop and slab
+                per_col = 2 * w.n * 2 + lp.num_partial_rows * 4
+                fixed = 2 * (int(np.diff(lp.block_off).max()) * 4 + int(np.diff(lp.segment_off).max()) * 16) + 8 * w.n \
+                    + 16 * lp.num_partial_rows + 4096
+                gp.gp_set_hbm_budget_bytes(fixed + per_col * 72)
+            rng = np.random.default_rng(5005)
+            deg_l = lp.deg
+            rows = np.unique(np.concatenate([
+                rng.integers(0, w.n, 600 if full_oracle else 200),
+                lp.block_row_lo, lp.block_row_hi,                               # rows cut by block boundaries
+                np.argsort(deg_l)[-8:] if full_oracle else np.flatnonzero((deg_l > 2000) & (deg_l < 6000))[:4]]))
+            t0 = time.time()
+            try:
+                # X is slab 0 itself: no copy, and nothing pinned twice
+                gp.gp_propagate(lp, mem.ptr, w.d, w.d, gp.GP_BF16, w.agg, w.K, mem.ptr, w.d, None)
+            finally:
+                gp.gp_set_hbm_budget_bytes(0)
+            dt = time.time() - t0
+            print(f"streamed propagate (first call, incl. pinned mirrors): {dt:.2f} s = "
+                  f"{lp.nnz * w.d * w.K / dt / 1e9:.0f} GEFU/s", flush=True)
+        assert np.array_equal(stack[0, :4096], x_first)
+        if not full_oracle:
+            cols, deg = sampled.neighbourhoods(w.src, w.dst, w.n, w.flags, rows)
+        for k in range(1, w.K + 1):
+            prev = _Widened(stack[k - 1])
+            if full_oracle:
+                want, bound = oracle.hop_rows(op, prev, w.agg, rows)
+            else:
+                want, bound = sampled.hop_rows(cols, deg, rows, prev, w.agg)
+            got = gp_synth.bf16_bits_to_f32(stack[k][rows]).astype(np.float64)
+            err = np.abs(got - want)
+            assert np.all(err <= 2.0 ** -8 * bound + 1e-30), \
+                f"hop {k}: worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {2.0 ** -8:.3g})"
+            print(f"config 5 hop {k}: {rows.size} sampled rows within 2^-8 * bound "
+                  f"(worst ratio {np.max(err / (bound + 1e-300)):.3g})", flush=True)
+    finally:
+        stack = None
+        mem.free()
+
+
+def test_config5_streamed_sampled_rows_every_hop():
+    """Config 5 at the largest scale the box's pinned host memory holds with a margin
+    (see CONFIG5_DEFAULT_SCALE above; GP_TEST_CONFIG5_SCALE overrides)."""
+    run_config5(float(os.environ.get("GP_TEST_CONFIG5_SCALE", str(CONFIG5_DEFAULT_SCALE))))
+
+
+@pytest.mark.skip(reason="config 5 at full size needs 119.9 GiB of pinned host memory (111,059,956 nodes x 1159 B: "
+                         "the 4-slab bf16 stack 105.9 GiB, the column list 12.3 GiB, the segment list 1.7 GiB); "
+                         "hipHostMalloc on the GPU box stops at 65.5 GiB in total, so 0.546 of the full size is the "
+                         "most that can run there; the same code path is checked at 0.45 by the test above")
+def test_config5_streamed_full_size():
+    run_config5(1.0)

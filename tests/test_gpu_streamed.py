@@ -108,3 +108,56 @@ def test_mixed_memory_kinds_rejected():
         with pytest.raises(gp.GpError) as e:
             gp.gp_propagate(lp, xh.data_ptr(), w.d, w.d, gp.GP_F32, w.agg, 1, od.data_ptr(), w.d, None)
         assert e.value.status == gp.GP_ERR_INVALID_ARG
+
+
+def eq12_volumes(lp, d, es, budget):
+    """The byte volumes include/gp.h documents for the streamed schedule."""
+    n, slots = lp.n, lp.num_partial_rows
+    B_S = 4.0 * lp.nnz + 16.0 * lp.segments.size
+    B_X = float(2 * n * es + 4 * slots) * d
+    B_GPU = float(budget - (8 * n + 16 * slots + 4096))
+    return B_S, B_X, B_GPU
+
+
+def test_eq12_solver_drives_the_streamed_schedule():
+    """The (b, c) of a streamed call is the minimiser of Eq. 12 as the ORACLE's exhaustive
+    search finds it: with a plan of too few blocks the sorted list is cut anew into b*
+    blocks and c = c*; with a plan that already has enough blocks they are kept.  Results
+    stay within the oracle's bound either way, and a repeated call (which reuses the
+    streams and buffers kept with the plan) gives the same bits."""
+    import torch
+    from oracle import solve as osolve
+    w = gp_synth.make_workload(3, scale=0.004, d=64)
+    d, es = 64, 4
+    op = oracle.plan_blocks(w.src, w.dst, w.n, 10**9, w.flags)
+    Xw, want, bound = oracle_stacks(w, op, w.X, gp.GP_F32, w.agg, 2)
+    # one block in the plan, a budget that has room for neither the whole list nor whole rows
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, 10**9, w.flags) as lp:
+        assert lp.num_blocks == 1
+        # Eq. 12 divides B_X evenly while a slab holds whole 16-byte column groups (16 of them here), so
+        # the comparison is made where c* divides 16: the first budget of the list below with such a c*
+        for fs, fx in [(0.35, 0.3), (0.4, 0.35), (0.5, 0.4), (0.6, 0.45), (0.7, 0.6), (0.3, 0.2), (0.45, 0.3)]:
+            budget = 8 * lp.n + 16 * lp.num_partial_rows + 4096 + int(fs * (4 * lp.nnz + 16 * lp.segments.size)) \
+                + int(fx * (2 * lp.n * es + 4 * lp.num_partial_rows) * d)
+            B_S, B_X, B_GPU = eq12_volumes(lp, d, es, budget)
+            b_star, c_star = osolve.aggregation_blocks(B_S, B_X, B_GPU, 2.0, 1.0, max_c=d // 4, max_b=10**6)
+            if b_star > 1 and c_star in (2, 4, 8):
+                break
+        assert b_star > 1 and c_star in (2, 4, 8)
+        got, _ = run_streamed(lp, w.X, gp.GP_F32, w.agg, 2, budget)
+        assert lp.streamed_shape() == (b_star, c_star)
+        again, _ = run_streamed(lp, w.X, gp.GP_F32, w.agg, 2, budget)
+        assert np.array_equal(got, again)
+        for k in range(1, 3):
+            assert np.all(np.abs(got[k] - want[k]) <= 1e-5 * bound[k] + 1e-30), f"hop {k}"
+    # a plan with more blocks than the budget asks for keeps them: same bits as the resident schedule
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, -(-op.nnz // (4 * b_star)), w.flags) as lp:
+        assert lp.num_blocks >= 4 * b_star
+        B_S, B_X, B_GPU = eq12_volumes(lp, d, es, budget)
+        b2, c2 = osolve.aggregation_blocks(B_S, B_X, B_GPU, 2.0, 1.0, max_c=d // 4, max_b=10**6)
+        got, _ = run_streamed(lp, w.X, gp.GP_F32, w.agg, 2, budget)
+        b_used, c_used = lp.streamed_shape()
+        assert b_used == lp.num_blocks and c_used <= c2
+        res = gp.propagate_tensors(lp, torch.from_numpy(w.X).cuda(), w.agg, 2)
+        torch.cuda.synchronize()
+        assert np.array_equal(got, res.cpu().numpy().astype(np.float64))
