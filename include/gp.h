@@ -63,9 +63,14 @@ enum { GP_SYMMETRISE = 1u, GP_ADD_SELF_LOOPS = 2u, GP_PLAN_ON_DEVICE = 4u };
  *  block_budget_edges  largest number of non-zeros one block may hold, > 0.
  *  flags     GP_SYMMETRISE also inserts (row j, col i); GP_ADD_SELF_LOOPS
  *            inserts (i, i) for every i.  GP_PLAN_ON_DEVICE sorts and de-duplicates
- *            the non-zeros on the current GPU instead of on the host threads
- *            (same plan, bit for bit; needs a GPU; at most 2^31 - 1 candidate
- *            entries, else GP_ERR_UNSUPPORTED).
+ *            the non-zeros and computes the degree and normalisation vectors on the
+ *            current GPU instead of on the host threads (same plan, bit for bit;
+ *            needs a GPU).  The entries are sorted in row ranges of at most
+ *            2^31 - 1 candidates each (option "device_plan_chunk" lowers that), so
+ *            only a single row with more candidates than that is GP_ERR_UNSUPPORTED.
+ *            The column list and the norm vectors then stay on that GPU, which is
+ *            the plan's device from then on: the first gp_propagate sends only the
+ *            kernel schedule.
  *  out_plan  HOST; receives the plan (NULL on error).  Free with gp_plan_destroy.
  *
  * The non-zeros form a SET: duplicate pairs collapse, input pairs with
@@ -345,6 +350,8 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
  *   "lc_tile_rows"       batch rows per work item of gp_lc_forward: 32 or 64 (0 = by batch size).
  *   "column_slices"   column slices one pass is divided into (1 .. 16; 0 = automatic).
  *                     Implicit work lists take 1, 2, 4 or 8 (anything else = automatic).
+ *   "device_plan_chunk"  GP_PLAN_ON_DEVICE: most candidate entries sorted at once
+ *                     (1 .. 2^31 - 1; 0 = 2^31 - 1).  Read by gp_plan_blocks.
  *   "cache_schedule"  0 = explicit per-XCD work lists where the plan's row clusters
  *                     call for them (see gp_plan_work_lists), 1 = always, 2 = never.
  */

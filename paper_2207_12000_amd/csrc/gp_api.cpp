@@ -130,6 +130,11 @@ gp_status gp_set_option(const char* name, int64_t value)
         options().cache_schedule = value;
         return GP_OK;
     }
+    if (!strcmp(name, "device_plan_chunk")) {
+        if (value < 0 || value > (INT64_C(1) << 31) - 1) return fail(GP_ERR_INVALID_ARG, "device_plan_chunk must be 0 .. 2^31 - 1");
+        options().device_plan_chunk = value;
+        return GP_OK;
+    }
     if (!strcmp(name, "persistent_blocks")) {
         if (value < 0 || value > (1 << 20)) return fail(GP_ERR_INVALID_ARG, "persistent_blocks must be 0 .. 2^20");
         options().persistent_blocks = value;
@@ -151,6 +156,7 @@ int64_t gp_get_option(const char* name)
     if (!strcmp(name, "column_slices")) return options().column_slices;
     if (!strcmp(name, "persistent_blocks")) return options().persistent_blocks;
     if (!strcmp(name, "cache_schedule")) return options().cache_schedule;
+    if (!strcmp(name, "device_plan_chunk")) return options().device_plan_chunk;
     if (!strcmp(name, "lc_tile_rows")) return options().lc_tile_rows;
     if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
     return -1;

@@ -33,6 +33,7 @@ struct Options {
     int64_t cache_schedule = 0;  // 0 = decided per plan, 1 = explicit per-XCD lists always, 2 = never
     int64_t lc_tile_rows = 0;  // 0 = chosen per call from the batch size
     int64_t hbm_budget_bytes = 0;
+    int64_t device_plan_chunk = 0;  // GP_PLAN_ON_DEVICE: most candidate entries sorted at once, 0 = 2^31 - 1
 };
 Options& options();
 
@@ -116,6 +117,7 @@ struct gp_plan {
     int64_t num_slots = 0;
 
     gp::Options opt;  // the library options as they stood when the plan was made
+    bool norms_on_device = false;  // GP_PLAN_ON_DEVICE: deg / dinv_sqrt / dinv came from the device
 
     mutable std::mutex mu;
     mutable gp::RowClusters clusters;  // made on first use (under mu)
@@ -141,6 +143,8 @@ void build_xcd_lists(const gp_plan& P, const RowClusters& C, int S, int slice_el
 bool choose_cache_schedule(const gp_plan* plan, int32_t d, int es, int vec, int& num_slices, int& slice_elems);
 // fills plan->nnz, rowptr, col, deg from validated input pairs, on the current GPU
 gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64_t n, bool sym, bool loops, gp_plan* plan);
+// fills block_row_lo / block_row_hi from rowptr and block_off, on the current GPU
+gp_status block_rows_on_device(gp_plan* plan);
 
 // resident schedule: everything already in HBM
 gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,

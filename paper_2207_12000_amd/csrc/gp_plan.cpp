@@ -99,7 +99,7 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
         });
         if (bad.load() >= 0) {
             const int64_t e = bad.load();
-            delete plan;
+            gp_plan_destroy(plan);
             return fail(GP_ERR_INDEX_RANGE, "pair %lld = (%d, %d) has a node id outside [0, %lld)", (long long)e,
                         src[e], dst[e], (long long)n);
         }
@@ -108,7 +108,7 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
             // sort / unique / row pointers on the current GPU; same arrays, bit for bit
             gp_status st = csr_on_device(src, dst, m, n, sym, loops, plan);
             if (st != GP_OK) {
-                delete plan;
+                gp_plan_destroy(plan);
                 return st;
             }
         } else {
@@ -174,7 +174,7 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
             for (int64_t i = 0; i < n; ++i) plan->rowptr[i + 1] = plan->rowptr[i] + plan->deg[i];
             const int64_t nnz = plan->rowptr[n];
             if (nnz >= (INT64_C(1) << 40)) {
-                delete plan;
+                gp_plan_destroy(plan);
                 return fail(GP_ERR_OVERFLOW, "non-zero count %lld exceeds the 40-bit list index", (long long)nnz);
             }
             plan->nnz = nnz;
@@ -192,9 +192,12 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
         const int64_t nnz = plan->nnz;
 
         // 6. normalisation vectors: one correctly rounded recipe, fp64 then narrowed once
-        plan->dinv_sqrt.resize((size_t)n);
-        plan->dinv.resize((size_t)n);
-        parallel_run(nt, [&](int t, int k) {
+        //    (the device planner has made them already, by the same recipe)
+        if (!plan->norms_on_device) {
+            plan->dinv_sqrt.resize((size_t)n);
+            plan->dinv.resize((size_t)n);
+        }
+        if (!plan->norms_on_device) parallel_run(nt, [&](int t, int k) {
             int64_t lo, hi;
             chunk_of(n, t, k, lo, hi);
             for (int64_t i = lo; i < hi; ++i) {
@@ -208,7 +211,7 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
         int64_t b = (nnz + block_budget_edges - 1) / block_budget_edges;
         if (b < 1) b = 1;
         if (b > INT32_MAX) {
-            delete plan;
+            gp_plan_destroy(plan);
             return fail(GP_ERR_OVERFLOW, "block count %lld does not fit int32", (long long)b);
         }
         plan->num_blocks = (int32_t)b;
@@ -217,7 +220,14 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
         plan->block_row_hi.assign((size_t)b, -1);
         const int64_t q = nnz / b, r = nnz % b;
         for (int64_t p = 0; p <= b; ++p) plan->block_off[p] = p * q + std::min(p, r);
-        for (int64_t p = 0; p < b; ++p) {
+        if (flags & GP_PLAN_ON_DEVICE) {
+            gp_status st = block_rows_on_device(plan);
+            if (st != GP_OK) {
+                gp_plan_destroy(plan);
+                return st;
+            }
+        }
+        for (int64_t p = 0; p < b && !(flags & GP_PLAN_ON_DEVICE); ++p) {
             const int64_t lo = plan->block_off[p], hi = plan->block_off[p + 1];
             if (hi <= lo) continue;
             // row of entry e = (first i with rowptr[i+1] > e)
@@ -241,15 +251,15 @@ extern "C" gp_status gp_plan_blocks(const int32_t* src, const int32_t* dst, int6
         plan->segment_edges = L;
         gp_status st = build_schedule(plan);
         if (st != GP_OK) {
-            delete plan;
+            gp_plan_destroy(plan);
             return st;
         }
     } catch (const std::bad_alloc&) {
-        delete plan;
+        gp_plan_destroy(plan);
         return fail(GP_ERR_OOM_HOST, "host allocation failed while planning (m = %lld, n = %lld)", (long long)m,
                     (long long)n);
     } catch (const std::exception& e) {  // e.g. no more threads: a host resource ran out
-        delete plan;
+        gp_plan_destroy(plan);
         return fail(GP_ERR_OOM_HOST, "planning failed: %s", e.what());
     }
     *out_plan = plan;

@@ -1,12 +1,17 @@
 // Device side of gp_plan_blocks (flag GP_PLAN_ON_DEVICE): the non-zero set of the
-// matrix being normalised, sorted and de-duplicated on the GPU.  The paper runs its
-// adjacency normalisation block-wise on the GPU (Section 3.2, Section 4.2); here the
-// normalisation needs no matrix at all, only the sorted set and its row counts, so
-// the GPU's share is: emit one 64-bit key (row << 32 | col) per candidate entry,
-// radix-sort the keys, drop duplicates, split them back into columns, and find
-// every row's first entry by binary search.  Integers only, so the result is the
-// host planner's bit for bit.  The sort and the duplicate removal are rocPRIM's
-// device-wide primitives; the kernels around them are this file's.
+// matrix being normalised, sorted and de-duplicated on the GPU, and the degree and
+// normalisation vectors of Eq. 1 computed there.  The paper runs its adjacency
+// normalisation block-wise on the GPU (Section 3.2, Section 4.2); here the
+// normalisation needs no matrix at all, only the sorted set and its row counts, so the
+// GPU's share is: count the candidate entries of every row, cut the rows into ranges
+// whose candidates fit one sort, and per range emit one 64-bit key (row << 32 | col)
+// per candidate, radix-sort the keys, drop duplicates, split them back into columns and
+// find every row's first entry by binary search; then degrees, 1/sqrt(deg) and 1/deg
+// (in fp64, narrowed once: the host planner's recipe) and the rows at the block
+// boundaries.  Integers and correctly rounded operations only, so the result is the host
+// planner's bit for bit.  The sort and the duplicate removal are rocPRIM's device-wide
+// primitives; every other kernel is this file's.  The column list and the two norm
+// vectors stay on the device for gp_propagate.
 #include <hip/hip_runtime.h>
 
 #include <cstring>
@@ -21,26 +26,6 @@ namespace gp {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr uint64_t kNoKey = ~UINT64_C(0);  // sorts after every real key
-
-// pair e -> key slots [e*per, e*per + per): (row = dst, col = src) and, when
-// symmetrising, its mirror; a self pair leaves its slots empty.
-__global__ __launch_bounds__(kThreads) void gp_emit_keys(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
-                                                         int64_t m, int per, uint64_t* __restrict__ keys)
-{
-    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < m; e += (int64_t)gridDim.x * kThreads) {
-        const uint32_t s = (uint32_t)src[e], t = (uint32_t)dst[e];
-        const bool self = s == t;
-        keys[e * per] = self ? kNoKey : ((uint64_t)t << 32) | s;
-        if (per == 2) keys[e * per + 1] = self ? kNoKey : ((uint64_t)s << 32) | t;
-    }
-}
-
-__global__ __launch_bounds__(kThreads) void gp_emit_loop_keys(int64_t n, uint64_t* __restrict__ keys)
-{
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads)
-        keys[i] = ((uint64_t)i << 32) | (uint64_t)i;
-}
 
 __global__ __launch_bounds__(kThreads) void gp_keys_to_columns(const uint64_t* __restrict__ keys, int64_t nnz,
                                                                int32_t* __restrict__ col)
@@ -49,13 +34,50 @@ __global__ __launch_bounds__(kThreads) void gp_keys_to_columns(const uint64_t* _
         col[e] = (int32_t)(keys[e] & 0xFFFFFFFFu);
 }
 
-// rowptr[i] = number of keys below (i << 32), i = 0 .. n
-__global__ __launch_bounds__(kThreads) void gp_row_starts(const uint64_t* __restrict__ keys, int64_t nnz, int64_t n,
-                                                          int64_t* __restrict__ rowptr)
+// candidates of every row before duplicates collapse (cnt is preset to the self-loop count)
+__global__ __launch_bounds__(kThreads) void gp_count_candidates(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                                                int64_t m, int sym, unsigned long long* __restrict__ cnt)
 {
-    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i <= n; i += (int64_t)gridDim.x * kThreads) {
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < m; e += (int64_t)gridDim.x * kThreads) {
+        const int32_t s = src[e], t = dst[e];
+        if (s == t) continue;
+        atomicAdd(cnt + t, 1ULL);
+        if (sym) atomicAdd(cnt + s, 1ULL);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void gp_fill_words(unsigned long long* __restrict__ p, int64_t count, unsigned long long v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += (int64_t)gridDim.x * kThreads) p[i] = v;
+}
+
+// keys of the candidates whose row lies in [r0, r1), in any order (the sort follows):
+// every candidate takes the next free slot from one cursor
+__global__ __launch_bounds__(kThreads) void gp_emit_keys_range(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                                               int64_t m, int sym, int loops, int64_t r0, int64_t r1,
+                                                               uint64_t* __restrict__ keys, unsigned long long* __restrict__ cursor)
+{
+    const int64_t span = m + (loops ? r1 - r0 : 0);
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < span; e += (int64_t)gridDim.x * kThreads) {
+        if (e >= m) {  // the self-loop of row r0 + (e - m)
+            const uint64_t i = (uint64_t)(r0 + (e - m));
+            keys[atomicAdd(cursor, 1ULL)] = (i << 32) | i;
+            continue;
+        }
+        const uint32_t s = (uint32_t)src[e], t = (uint32_t)dst[e];
+        if (s == t) continue;
+        if ((int64_t)t >= r0 && (int64_t)t < r1) keys[atomicAdd(cursor, 1ULL)] = ((uint64_t)t << 32) | s;
+        if (sym && (int64_t)s >= r0 && (int64_t)s < r1) keys[atomicAdd(cursor, 1ULL)] = ((uint64_t)s << 32) | t;
+    }
+}
+
+// rowptr[i] = base + number of keys below (i << 32), i = r0 .. r1 (keys hold rows [r0, r1) only)
+__global__ __launch_bounds__(kThreads) void gp_row_starts_range(const uint64_t* __restrict__ keys, int64_t count, int64_t r0,
+                                                                int64_t r1, int64_t base, int64_t* __restrict__ rowptr)
+{
+    for (int64_t i = r0 + (int64_t)blockIdx.x * kThreads + threadIdx.x; i <= r1; i += (int64_t)gridDim.x * kThreads) {
         const uint64_t probe = (uint64_t)i << 32;
-        int64_t lo = 0, hi = nnz;
+        int64_t lo = 0, hi = count;
         while (lo < hi) {
             const int64_t mid = lo + (hi - lo) / 2;
             if (keys[mid] < probe)
@@ -63,8 +85,49 @@ __global__ __launch_bounds__(kThreads) void gp_row_starts(const uint64_t* __rest
             else
                 hi = mid;
         }
-        rowptr[i] = lo;
+        rowptr[i] = base + lo;
     }
+}
+
+// deg[i] = entries of row i; the norm vectors of Eq. 1: fp64 square root and division (both
+// correctly rounded), narrowed once; 0 where the row is empty
+__global__ __launch_bounds__(kThreads) void gp_degrees_and_norms(const int64_t* __restrict__ rowptr, int64_t n,
+                                                                 int32_t* __restrict__ deg, float* __restrict__ dinv_sqrt,
+                                                                 float* __restrict__ dinv)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n; i += (int64_t)gridDim.x * kThreads) {
+        const int32_t g = (int32_t)(rowptr[i + 1] - rowptr[i]);
+        deg[i] = g;
+        dinv_sqrt[i] = g > 0 ? (float)(1.0 / sqrt((double)g)) : 0.0f;
+        dinv[i] = g > 0 ? (float)(1.0 / (double)g) : 0.0f;
+    }
+}
+
+// rows of the first and last entry of every block (0 and -1 for an empty block)
+__global__ void gp_block_rows(const int64_t* __restrict__ rowptr, int64_t n, const int64_t* __restrict__ block_off, int32_t b,
+                              int32_t* __restrict__ row_lo, int32_t* __restrict__ row_hi)
+{
+    const int32_t p = (int32_t)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (p >= b) return;
+    const int64_t lo = block_off[p], hi = block_off[p + 1];
+    int32_t rl = 0, rh = -1;
+    if (hi > lo) {
+        auto row_of = [&](int64_t e) {  // the i with rowptr[i] <= e < rowptr[i + 1]
+            int64_t a = 0, z = n;       // invariant: rowptr[a] <= e, rowptr[z] > e
+            while (z - a > 1) {
+                const int64_t mid = a + (z - a) / 2;
+                if (rowptr[mid] <= e)
+                    a = mid;
+                else
+                    z = mid;
+            }
+            return (int32_t)a;
+        };
+        rl = row_of(lo);
+        rh = row_of(hi - 1);
+    }
+    row_lo[p] = rl;
+    row_hi[p] = rh;
 }
 
 inline unsigned grid_for(int64_t items) { return (unsigned)std::min<int64_t>((items + kThreads - 1) / kThreads, 256 * 32); }
@@ -91,76 +154,167 @@ struct DeviceBuffers {
 
 gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64_t n, bool sym, bool loops, gp_plan* plan)
 {
-    const int per = sym ? 2 : 1;
-    const int64_t total = m * per + (loops ? n : 0);
-    if (total >= (INT64_C(1) << 31))
-        return fail(GP_ERR_UNSUPPORTED, "%lld candidate entries: planning on the device is limited to 2^31 - 1; plan on the host",
-                    (long long)total);
     hipStream_t stream = nullptr;
     DeviceBuffers B;
-    int32_t *d_src, *d_dst, *d_col;
-    uint64_t *d_keys, *d_sorted, *d_unique;
+    int32_t *d_src, *d_dst;
+    unsigned long long *d_cnt, *d_cursor;
     int64_t* d_rowptr;
     size_t* d_count;
     gp_status st;
     if ((st = B.alloc(d_src, (size_t)m)) != GP_OK || (st = B.alloc(d_dst, (size_t)m)) != GP_OK ||
-        (st = B.alloc(d_keys, (size_t)total)) != GP_OK || (st = B.alloc(d_sorted, (size_t)total)) != GP_OK ||
+        (st = B.alloc(d_cnt, (size_t)n)) != GP_OK || (st = B.alloc(d_cursor, 1)) != GP_OK ||
         (st = B.alloc(d_count, 1)) != GP_OK || (st = B.alloc(d_rowptr, (size_t)n + 1)) != GP_OK)
         return st;
+    // ---- candidates per row, and row ranges whose candidates fit one sort ------------
+    hipLaunchKernelGGL(gp_fill_words, dim3(grid_for(n)), dim3(kThreads), 0, stream, d_cnt, n, loops ? 1ULL : 0ULL);
+    GP_HIP(hipGetLastError());
     if (m) {
         GP_HIP(hipMemcpyAsync(d_src, src, (size_t)m * 4, hipMemcpyHostToDevice, stream));
         GP_HIP(hipMemcpyAsync(d_dst, dst, (size_t)m * 4, hipMemcpyHostToDevice, stream));
-        hipLaunchKernelGGL(gp_emit_keys, dim3(grid_for(m)), dim3(kThreads), 0, stream, d_src, d_dst, m, per, d_keys);
+        hipLaunchKernelGGL(gp_count_candidates, dim3(grid_for(m)), dim3(kThreads), 0, stream, d_src, d_dst, m, sym ? 1 : 0, d_cnt);
         GP_HIP(hipGetLastError());
     }
-    if (loops) {
-        hipLaunchKernelGGL(gp_emit_loop_keys, dim3(grid_for(n)), dim3(kThreads), 0, stream, n, d_keys + m * per);
-        GP_HIP(hipGetLastError());
+    std::vector<unsigned long long> cnt((size_t)n);
+    GP_HIP(hipMemcpyAsync(cnt.data(), d_cnt, (size_t)n * sizeof(unsigned long long), hipMemcpyDeviceToHost, stream));
+    GP_HIP(hipStreamSynchronize(stream));
+    int64_t limit = options().device_plan_chunk > 0 ? options().device_plan_chunk : (INT64_C(1) << 31) - 1;
+    std::vector<int64_t> range_lo, range_cnt;  // row ranges [range_lo[k], range_lo[k+1]) and their candidate counts
+    int64_t total = 0, largest = 0;
+    {
+        int64_t acc = 0;
+        range_lo.push_back(0);
+        for (int64_t i = 0; i < n; ++i) {
+            const int64_t c = (int64_t)cnt[(size_t)i];
+            if (c > (INT64_C(1) << 31) - 1)
+                return fail(GP_ERR_UNSUPPORTED, "row %lld alone has %lld candidate entries: plan on the host", (long long)i, (long long)c);
+            if (acc > 0 && acc + c > limit) {
+                range_cnt.push_back(acc);
+                range_lo.push_back(i);
+                acc = 0;
+            }
+            acc += c;
+            total += c;
+        }
+        range_cnt.push_back(acc);
+        range_lo.push_back(n);
+        for (int64_t c : range_cnt) largest = std::max(largest, c);
     }
+    std::vector<unsigned long long>().swap(cnt);
+
+    uint64_t *d_keys, *d_sorted;
+    int32_t* d_col = nullptr;  // stays with the plan
+    if ((st = B.alloc(d_keys, (size_t)largest)) != GP_OK || (st = B.alloc(d_sorted, (size_t)largest)) != GP_OK) return st;
+    GP_HIP(hipMalloc((void**)&d_col, (size_t)std::max<int64_t>(total, 1) * sizeof(int32_t)));
+    struct ColGuard {
+        int32_t*& p;
+        bool keep = false;
+        ~ColGuard()
+        {
+            if (!keep) {
+                (void)hipFree(p);
+                p = nullptr;
+            }
+        }
+    } col_guard{d_col};
+    char* d_tmp = nullptr;
+    size_t tmp_cap = 0;
 
     int64_t nnz = 0;
-    if (total > 0) {
-        // all 64 bits are sorted: empty slots are all ones and must end up last
-        size_t tmp_bytes = 0;
-        GP_HIP(rocprim::radix_sort_keys(nullptr, tmp_bytes, d_keys, d_sorted, (size_t)total, 0u, 64u, stream));
-        char* d_tmp = nullptr;
-        if ((st = B.alloc(d_tmp, tmp_bytes)) != GP_OK) return st;
-        GP_HIP(rocprim::radix_sort_keys(d_tmp, tmp_bytes, d_keys, d_sorted, (size_t)total, 0u, 64u, stream));
-        d_unique = d_keys;  // the unsorted keys are no longer needed
-        size_t tmp2 = 0;
-        GP_HIP(rocprim::unique(nullptr, tmp2, d_sorted, d_unique, d_count, (size_t)total, rocprim::equal_to<uint64_t>(), stream));
-        char* d_tmp2 = d_tmp;
-        if (tmp2 > tmp_bytes && (st = B.alloc(d_tmp2, tmp2)) != GP_OK) return st;
-        GP_HIP(rocprim::unique(d_tmp2, tmp2, d_sorted, d_unique, d_count, (size_t)total, rocprim::equal_to<uint64_t>(), stream));
-        size_t count = 0;
-        uint64_t last = 0;
-        GP_HIP(hipMemcpyAsync(&count, d_count, sizeof(size_t), hipMemcpyDeviceToHost, stream));
-        GP_HIP(hipStreamSynchronize(stream));
-        if (count > 0) {
-            GP_HIP(hipMemcpy(&last, d_unique + (count - 1), sizeof(uint64_t), hipMemcpyDeviceToHost));
-            if (last == kNoKey) --count;  // the one survivor of all empty slots
+    for (size_t k = 0; k < range_cnt.size(); ++k) {
+        const int64_t r0 = range_lo[k], r1 = range_lo[k + 1], cand = range_cnt[k];
+        int64_t uniq = 0;
+        if (cand > 0) {
+            hipLaunchKernelGGL(gp_fill_words, dim3(1), dim3(kThreads), 0, stream, d_cursor, (int64_t)1, 0ULL);
+            hipLaunchKernelGGL(gp_emit_keys_range, dim3(grid_for(m + (loops ? r1 - r0 : 0))), dim3(kThreads), 0, stream, d_src, d_dst,
+                               m, sym ? 1 : 0, loops ? 1 : 0, r0, r1, d_keys, d_cursor);
+            GP_HIP(hipGetLastError());
+            size_t need = 0, need2 = 0;
+            GP_HIP(rocprim::radix_sort_keys(nullptr, need, d_keys, d_sorted, (size_t)cand, 0u, 64u, stream));
+            GP_HIP(rocprim::unique(nullptr, need2, d_sorted, d_keys, d_count, (size_t)cand, rocprim::equal_to<uint64_t>(), stream));
+            need = std::max(need, need2);
+            if (need > tmp_cap) {
+                if ((st = B.alloc(d_tmp, need)) != GP_OK) return st;
+                tmp_cap = need;
+            }
+            GP_HIP(rocprim::radix_sort_keys(d_tmp, need, d_keys, d_sorted, (size_t)cand, 0u, 64u, stream));
+            // the unsorted keys are no longer needed: the distinct ones go back into their buffer
+            GP_HIP(rocprim::unique(d_tmp, need, d_sorted, d_keys, d_count, (size_t)cand, rocprim::equal_to<uint64_t>(), stream));
+            size_t count = 0;
+            GP_HIP(hipMemcpyAsync(&count, d_count, sizeof(size_t), hipMemcpyDeviceToHost, stream));
+            GP_HIP(hipStreamSynchronize(stream));
+            uniq = (int64_t)count;
+            hipLaunchKernelGGL(gp_keys_to_columns, dim3(grid_for(uniq)), dim3(kThreads), 0, stream, d_keys, uniq, d_col + nnz);
+            GP_HIP(hipGetLastError());
         }
-        nnz = (int64_t)count;
-    } else {
-        d_unique = d_keys;
+        // first entries of rows r0 .. r1 (row r1's start is written again, identically, by the next range)
+        hipLaunchKernelGGL(gp_row_starts_range, dim3(grid_for(r1 - r0 + 1)), dim3(kThreads), 0, stream, d_keys, uniq, r0, r1, nnz,
+                           d_rowptr);
+        GP_HIP(hipGetLastError());
+        GP_HIP(hipStreamSynchronize(stream));  // d_keys is refilled by the next range
+        nnz += uniq;
     }
 
-    hipLaunchKernelGGL(gp_row_starts, dim3(grid_for(n + 1)), dim3(kThreads), 0, stream, d_unique, nnz, n, d_rowptr);
-    GP_HIP(hipGetLastError());
-    d_col = (int32_t*)d_sorted;  // reuse: the sorted keys with duplicates are done with
-    if (nnz) {
-        hipLaunchKernelGGL(gp_keys_to_columns, dim3(grid_for(nnz)), dim3(kThreads), 0, stream, d_unique, nnz, d_col);
-        GP_HIP(hipGetLastError());
+    // ---- degrees and the normalisation vectors of Eq. 1 -------------------------------
+    int32_t* d_deg;
+    float *d_dinv_sqrt = nullptr, *d_dinv = nullptr;  // stay with the plan
+    if ((st = B.alloc(d_deg, (size_t)n)) != GP_OK) return st;
+    if (hipMalloc((void**)&d_dinv_sqrt, (size_t)n * sizeof(float)) != hipSuccess ||
+        hipMalloc((void**)&d_dinv, (size_t)n * sizeof(float)) != hipSuccess) {
+        (void)hipFree(d_dinv_sqrt);
+        (void)hipFree(d_dinv);
+        return fail(GP_ERR_OOM_DEVICE, "normalisation vectors on the device");
     }
+    hipLaunchKernelGGL(gp_degrees_and_norms, dim3(grid_for(n)), dim3(kThreads), 0, stream, d_rowptr, n, d_deg, d_dinv_sqrt, d_dinv);
 
     plan->nnz = nnz;
     plan->rowptr.resize((size_t)n + 1);
     plan->col.resize((size_t)nnz);
     plan->deg.resize((size_t)n);
-    GP_HIP(hipMemcpyAsync(plan->rowptr.data(), d_rowptr, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, stream));
-    if (nnz) GP_HIP(hipMemcpyAsync(plan->col.data(), d_col, (size_t)nnz * sizeof(int32_t), hipMemcpyDeviceToHost, stream));
-    GP_HIP(hipStreamSynchronize(stream));
-    for (int64_t i = 0; i < n; ++i) plan->deg[i] = (int32_t)(plan->rowptr[i + 1] - plan->rowptr[i]);
+    plan->dinv_sqrt.resize((size_t)n);
+    plan->dinv.resize((size_t)n);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpyAsync(plan->rowptr.data(), d_rowptr, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess && nnz) e = hipMemcpyAsync(plan->col.data(), d_col, (size_t)nnz * sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(plan->deg.data(), d_deg, (size_t)n * sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(plan->dinv_sqrt.data(), d_dinv_sqrt, (size_t)n * sizeof(float), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(plan->dinv.data(), d_dinv, (size_t)n * sizeof(float), hipMemcpyDeviceToHost, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) {
+        (void)hipFree(d_dinv_sqrt);
+        (void)hipFree(d_dinv);
+        return fail(GP_ERR_DEVICE, "planning on the device: %s", hipGetErrorString(e));
+    }
+    // what gp_propagate needs of the plan is already where it will be used
+    int cur = -1;
+    GP_HIP(hipGetDevice(&cur));
+    plan->dev.device = cur;
+    plan->dev.col = nnz ? d_col : nullptr;
+    col_guard.keep = nnz > 0;
+    plan->dev.dinv_sqrt = d_dinv_sqrt;
+    plan->dev.dinv = d_dinv;
+    plan->norms_on_device = true;
+    return GP_OK;
+}
+
+// rows at the block boundaries, found on the device from the row pointers
+gp_status block_rows_on_device(gp_plan* plan)
+{
+    const int32_t b = plan->num_blocks;
+    const int64_t n = plan->n;
+    DeviceBuffers B;
+    int64_t *d_rowptr, *d_off;
+    int32_t *d_lo, *d_hi;
+    gp_status st;
+    if ((st = B.alloc(d_rowptr, (size_t)n + 1)) != GP_OK || (st = B.alloc(d_off, (size_t)b + 1)) != GP_OK ||
+        (st = B.alloc(d_lo, (size_t)b)) != GP_OK || (st = B.alloc(d_hi, (size_t)b)) != GP_OK)
+        return st;
+    GP_HIP(hipMemcpy(d_rowptr, plan->rowptr.data(), ((size_t)n + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+    GP_HIP(hipMemcpy(d_off, plan->block_off.data(), ((size_t)b + 1) * sizeof(int64_t), hipMemcpyHostToDevice));
+    hipLaunchKernelGGL(gp_block_rows, dim3((unsigned)((b + kThreads - 1) / kThreads)), dim3(kThreads), 0, nullptr, d_rowptr, n, d_off, b,
+                       d_lo, d_hi);
+    GP_HIP(hipGetLastError());
+    GP_HIP(hipMemcpy(plan->block_row_lo.data(), d_lo, (size_t)b * sizeof(int32_t), hipMemcpyDeviceToHost));
+    GP_HIP(hipMemcpy(plan->block_row_hi.data(), d_hi, (size_t)b * sizeof(int32_t), hipMemcpyDeviceToHost));
     return GP_OK;
 }
 

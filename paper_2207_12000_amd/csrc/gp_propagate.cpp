@@ -13,8 +13,7 @@ namespace {
 template <class T>
 gp_status upload(T*& dptr, const std::vector<T>& h, hipStream_t stream)
 {
-    dptr = nullptr;
-    if (h.empty()) return GP_OK;
+    if (dptr || h.empty()) return GP_OK;  // already there (the device planner leaves its results), or nothing to send
     GP_HIP(hipMalloc((void**)&dptr, h.size() * sizeof(T)));
     GP_HIP(hipMemcpyAsync(dptr, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice, stream));
     return GP_OK;
@@ -47,7 +46,7 @@ gp_status ensure_device(const gp_plan* plan, int32_t d, bool want_edge_weights, 
     GP_HIP(hipGetDevice(&cur));
     if (D.device >= 0 && D.device != cur)
         return fail(GP_ERR_INVALID_ARG, "plan lives on device %d but device %d is current", D.device, cur);
-    if (D.device < 0) {
+    if (D.device < 0 || !D.ctrl) {
         gp_status st;
         if ((st = upload(D.col, plan->col, stream)) != GP_OK || (st = upload(D.dinv_sqrt, plan->dinv_sqrt, stream)) != GP_OK ||
             (st = upload(D.dinv, plan->dinv, stream)) != GP_OK || (st = upload(D.segs, plan->segs, stream)) != GP_OK ||

@@ -80,3 +80,17 @@ def test_errors_keep_their_codes():
     with pytest.raises(gp.GpError) as e:
         gp.gp_plan_blocks([0], [1], 3, 1, 8)
     assert e.value.status == gp.GP_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("chunk", [1, 7, 1000, 50_000])
+def test_row_range_chunks_give_the_same_plan(chunk):
+    """The device planner sorts the candidate entries in row ranges of bounded size (what
+    lifts the one-sort limit of 2^31 - 1 entries); a tiny bound forces many ranges."""
+    w = gp_synth.make_workload(2, scale=0.05, with_features=False)
+    op = oracle.plan_blocks(w.src, w.dst, w.n, 9000, w.flags)
+    gp.gp_set_option("device_plan_chunk", chunk)
+    try:
+        with gp.gp_plan_blocks(w.src, w.dst, w.n, 9000, w.flags | gp.GP_PLAN_ON_DEVICE) as lp:
+            same(lp, op)
+    finally:
+        gp.gp_set_option("device_plan_chunk", 0)
