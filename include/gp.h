@@ -320,8 +320,8 @@ gp_status gp_lc_softmax(float *H, int64_t B, int32_t C, int64_t ld, void *hip_st
  *     beta_S*B_S / b + beta_X*B_X / c <= B_GPU,
  * by exhaustive search; among equal products the pair with the smaller c wins
  * (the paper does not say; fewer column blocks means fewer re-sends of every
- * edge block).  Errors: INVALID_ARG (non-positive volume, negative coefficient,
- * NULL output), UNSUPPORTED when no block count can satisfy the constraint (the
+ * edge block).  Errors: INVALID_ARG (negative volume or coefficient, B_GPU <= 0,
+ * max_c < 1, NULL output), UNSUPPORTED when no block count can satisfy the constraint (the
  * fixed term alone exceeds B_GPU, or max_c is too small).
  */
 gp_status gp_solve_normalisation_blocks(double B_A, double B_S, double B_D, double B_GPU, double alpha_A,

@@ -33,8 +33,10 @@ struct Timed {
 std::mutex g_prof_mu;
 bool g_prof_on = false;
 std::vector<Timed> g_prof;
-hipEvent_t g_open = nullptr;
-std::string g_open_name;
+// the launch a thread is in the middle of bracketing: one per calling thread, so that
+// threads (and the streams they launch on) do not pair up each other's events
+thread_local hipEvent_t g_open = nullptr;
+thread_local const char* g_open_name = "";
 
 void clear_profile()
 {
@@ -51,7 +53,7 @@ bool profiling_on() { return g_prof_on; }
 void profile_begin(const char* name, hipStream_t stream)
 {
     if (!g_prof_on) return;
-    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_open) (void)hipEventDestroy(g_open);  // a begin without its end: dropped
     if (hipEventCreate(&g_open) != hipSuccess) {
         g_open = nullptr;
         return;
@@ -62,17 +64,18 @@ void profile_begin(const char* name, hipStream_t stream)
 
 void profile_end(hipStream_t stream)
 {
-    if (!g_prof_on) return;
-    std::lock_guard<std::mutex> lk(g_prof_mu);
     if (!g_open) return;
     hipEvent_t b;
-    if (hipEventCreate(&b) != hipSuccess) {
+    if (!g_prof_on || hipEventCreate(&b) != hipSuccess) {
         (void)hipEventDestroy(g_open);
         g_open = nullptr;
         return;
     }
     (void)hipEventRecord(b, stream);
-    g_prof.push_back(Timed{g_open_name, g_open, b});
+    {
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        g_prof.push_back(Timed{g_open_name, g_open, b});
+    }
     g_open = nullptr;
 }
 

@@ -94,6 +94,7 @@ struct DevicePlan {
     float* comb = nullptr;
     int64_t ping_bytes = 0, comb_elems = 0;
     std::vector<XcdWork> work;  // explicit work lists built so far (one per slice shape)
+    std::vector<void*> retired;  // buffers that were outgrown: freed with the plan, never while work may still use them
 };
 
 }  // namespace gp

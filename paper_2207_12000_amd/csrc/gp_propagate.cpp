@@ -33,6 +33,7 @@ void release(DevicePlan& D)
     (void)hipFree(D.ping[1]);
     (void)hipFree(D.comb);
     for (XcdWork& w : D.work) (void)hipFree(w.recs);
+    for (void* p : D.retired) (void)hipFree(p);
     D = DevicePlan();
 }
 
@@ -73,9 +74,8 @@ gp_status ensure_device(const gp_plan* plan, int32_t d, bool want_edge_weights, 
     }
     const int64_t need_ld = ((int64_t)d + 3) / 4 * 4;
     if (plan->num_slots > 0 && need_ld > D.carry_ld) {
-        // a running kernel on another stream could still be using the old buffer
-        GP_HIP(hipDeviceSynchronize());
-        (void)hipFree(D.carry);
+        // work enqueued earlier may still be using the old buffer: it is kept until the plan goes
+        if (D.carry) D.retired.push_back(D.carry);
         D.carry = nullptr;
         D.carry_ld = 0;
         GP_HIP(hipMalloc((void**)&D.carry, (size_t)plan->num_slots * need_ld * sizeof(float)));
@@ -338,9 +338,8 @@ gp_status propagate_combine(const gp_plan* plan, const void* X, int64_t ldx, int
         std::lock_guard<std::mutex> lk(plan->mu);
         const int64_t need = n * ldp * es;
         if (K >= 2 && need > D.ping_bytes) {
-            GP_HIP(hipDeviceSynchronize());
-            (void)hipFree(D.ping[0]);
-            (void)hipFree(D.ping[1]);
+            if (D.ping[0]) D.retired.push_back(D.ping[0]);
+            if (D.ping[1]) D.retired.push_back(D.ping[1]);
             D.ping[0] = D.ping[1] = nullptr;
             D.ping_bytes = 0;
             GP_HIP(hipMalloc(&D.ping[0], (size_t)need));
@@ -348,8 +347,7 @@ gp_status propagate_combine(const gp_plan* plan, const void* X, int64_t ldx, int
             D.ping_bytes = need;
         }
         if (dtype == GP_BF16 && n * ldc_scratch > D.comb_elems) {
-            GP_HIP(hipDeviceSynchronize());
-            (void)hipFree(D.comb);
+            if (D.comb) D.retired.push_back(D.comb);
             D.comb = nullptr;
             D.comb_elems = 0;
             GP_HIP(hipMalloc((void**)&D.comb, (size_t)(n * ldc_scratch) * sizeof(float)));

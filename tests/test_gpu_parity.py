@@ -268,3 +268,45 @@ def test_many_hops_and_repeated_calls_on_one_plan():
             Xw = widen(X, dtype)
             check(got, oracle.propagate(op, Xw, agg, K, 4), oracle.bound_stack(op, Xw, agg, K, 4), TOL[dtype],
                   f"d={d} dtype={dtype} agg={agg} K={K}")
+
+
+# ---- work mapping: column slices, workgroup count, explicit per-XCD lists ----------------
+
+@pytest.fixture
+def _mapping_defaults():
+    yield
+    for k in ("column_slices", "persistent_blocks", "cache_schedule", "segment_edges"):
+        gp.gp_set_option(k, 0)
+
+
+@pytest.mark.parametrize("dtype,d", [(gp.GP_F32, 136), (gp.GP_BF16, 264), (gp.GP_F32, 602)])
+@pytest.mark.parametrize("slices", [1, 2, 4, 8])
+def test_implicit_lists_any_slice_count_and_grid(dtype, d, slices, _mapping_defaults):
+    """Column slices and the number of workgroups change which lane group computes what,
+    not what is computed: every (slices, grid) gives the bits of the default mapping."""
+    w = gp_synth.make_workload(3, scale=0.004, d=d)
+    gp.gp_set_option("cache_schedule", 2)
+    ref = parity_case(w, K=2, dtype=dtype, agg=gp.GP_AGG_SYM)
+    gp.gp_set_option("column_slices", slices)
+    gp.gp_set_option("persistent_blocks", 40)          # fewer workgroups than stay resident: every group walks far
+    got = parity_case(w, K=2, dtype=dtype, agg=gp.GP_AGG_SYM)
+    assert np.array_equal(ref, got)
+
+
+@pytest.mark.parametrize("dtype,d,agg", [(gp.GP_F32, 602, gp.GP_AGG_SUM), (gp.GP_F32, 100, gp.GP_AGG_MEAN),
+                                         (gp.GP_BF16, 128, gp.GP_AGG_SYM), (gp.GP_F32, 37, gp.GP_AGG_SYM)])
+@pytest.mark.parametrize("slices", [0, 1, 3, 5, 16])
+def test_explicit_lists_match_the_oracle_and_the_implicit_bits(dtype, d, agg, slices, _mapping_defaults):
+    """The cache schedule (explicit per-XCD work lists handed out from cursors) forced on a
+    community graph and on a graph without communities: the oracle's bound holds and the
+    bits are those of the implicit lists (a record's sum does not depend on who adds it up)."""
+    for cfg, scale in ((4, 0.004), (2, 0.03)):
+        w = gp_synth.make_workload(cfg, scale=scale, d=d)
+        gp.gp_set_option("segment_edges", 16)          # cut rows too
+        gp.gp_set_option("cache_schedule", 2)
+        gp.gp_set_option("column_slices", 0)
+        ref = parity_case(w, K=2, dtype=dtype, agg=agg, budget=20_000)
+        gp.gp_set_option("cache_schedule", 1)
+        gp.gp_set_option("column_slices", slices)
+        got = parity_case(w, K=2, dtype=dtype, agg=agg, budget=20_000)
+        assert np.array_equal(ref, got), f"config {cfg}"
