@@ -175,7 +175,9 @@ gp_status gp_plan_work_lists(const gp_plan *plan, int32_t d, gp_dtype dtype, int
  * uploads the plan to the current device and allocates scratch (partial-row
  * buffer); later calls with the same d reuse both.  Calls on ONE plan must not
  * overlap in time (they share that scratch); different plans are independent.
- * Results are deterministic: the same inputs give the same bits on every call.
+ * Results are deterministic: the same inputs and options give the same bits on every
+ * call (how a row's partial sums are grouped depends on the schedule, so the streamed and
+ * the resident schedule, or two settings of "split_records", may differ in the last bits).
  * Errors: INVALID_ARG, OOM_DEVICE, DEVICE, UNSUPPORTED.
  */
 gp_status gp_propagate(const gp_plan *plan, const void *X, int64_t ldx, int32_t d, gp_dtype dtype,
@@ -200,8 +202,10 @@ gp_status gp_plan_streamed_shape(const gp_plan *plan, int64_t *edge_blocks, int6
 /* ---------------------------------------------------------------------------
  * gp_propagate_noalloc -- gp_propagate for callers that cannot allocate: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
- * arguments, same kernels and the same bits in out_stack as gp_propagate on
- * device-resident operands, but the call makes no allocation of any kind: the scratch
+ * arguments and same kernels as gp_propagate on device-resident operands, and the same
+ * bits in out_stack whenever that call works on whole records (option "split_records"
+ * = 2, or a graph without row clusters; with cut records its partial sums are grouped
+ * differently and the two agree to rounding), but the call makes no allocation of any kind: the scratch
  * the kernels need (work cursors, partial rows of rows that were cut) is a fixed array
  * in device memory of 64 MiB + 256 bytes that each GPU the library is used on holds
  * until the process ends.
@@ -350,6 +354,10 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
  *   "lc_tile_rows"       batch rows per work item of gp_lc_forward: 32 or 64 (0 = by batch size).
  *   "column_slices"   column slices one pass is divided into (1 .. 16; 0 = automatic).
  *                     Implicit work lists take 1, 2, 4 or 8 (anything else = automatic).
+ *   "split_records"   explicit work lists: 0 / 1 = every record is cut into the non-zeros
+ *                     whose source lies in the row's cluster and the others; the others are
+ *                     gathered first, whole rows wide, in a launch of their own, and the two
+ *                     partial rows are joined by the fix-up; 2 = whole records.
  *   "device_plan_chunk"  GP_PLAN_ON_DEVICE: most candidate entries sorted at once
  *                     (1 .. 2^31 - 1; 0 = 2^31 - 1).  Read by gp_plan_blocks.
  *   "cache_schedule"  0 = explicit per-XCD work lists where the plan's row clusters

@@ -133,6 +133,11 @@ gp_status gp_set_option(const char* name, int64_t value)
         options().cache_schedule = value;
         return GP_OK;
     }
+    if (!strcmp(name, "split_records")) {
+        if (value < 0 || value > 2) return fail(GP_ERR_INVALID_ARG, "split_records must be 0 (automatic), 1 (on) or 2 (off)");
+        options().split_records = value;
+        return GP_OK;
+    }
     if (!strcmp(name, "device_plan_chunk")) {
         if (value < 0 || value > (INT64_C(1) << 31) - 1) return fail(GP_ERR_INVALID_ARG, "device_plan_chunk must be 0 .. 2^31 - 1");
         options().device_plan_chunk = value;
@@ -160,6 +165,7 @@ int64_t gp_get_option(const char* name)
     if (!strcmp(name, "persistent_blocks")) return options().persistent_blocks;
     if (!strcmp(name, "cache_schedule")) return options().cache_schedule;
     if (!strcmp(name, "device_plan_chunk")) return options().device_plan_chunk;
+    if (!strcmp(name, "split_records")) return options().split_records;
     if (!strcmp(name, "lc_tile_rows")) return options().lc_tile_rows;
     if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
     return -1;

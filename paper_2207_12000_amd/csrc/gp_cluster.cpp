@@ -147,10 +147,10 @@ void cluster_rows(const gp_plan& P, RowClusters& C)
 // (chunk, slice) pair goes, in that order, to the XCD with the least work so far, so
 // the slices of one chunk run on different XCDs at about the same time and every XCD
 // moves through the clusters at the same pace.
-void build_xcd_lists(const gp_plan& P, const RowClusters& C, int S, int slice_elems, int d, std::vector<Segment>& recs,
-                     int64_t off[9])
+void build_xcd_lists(const gp_plan& P, const std::vector<Segment>& segs, const RowClusters& C, int S, int slice_elems, int d,
+                     std::vector<Segment>& recs, int64_t off[9])
 {
-    const int64_t n = P.n, nsegs = (int64_t)P.segs.size();
+    const int64_t n = P.n, nsegs = (int64_t)segs.size();
     // rows in (cluster, row) order
     std::vector<int64_t> cstart((size_t)C.num + 1, 0);
     for (int64_t i = 0; i < n; ++i) ++cstart[(size_t)C.label[(size_t)i] + 1];
@@ -163,7 +163,7 @@ void build_xcd_lists(const gp_plan& P, const RowClusters& C, int S, int slice_el
     // chunks: a chunk ends at a cluster boundary once it holds min_rows rows, and inside
     // a cluster when it holds max_work non-zeros
     const int64_t min_rows = 512;
-    const int64_t max_work = std::max<int64_t>(P.nnz / 64, 1 << 16);
+    const int64_t max_work = std::max<int64_t>(P.nnz / 64, 1 << 16);  // in non-zeros of the whole rows
     std::vector<int32_t> chunk_of_row((size_t)n, 0);
     int32_t chunks = 0;
     {
@@ -183,23 +183,23 @@ void build_xcd_lists(const gp_plan& P, const RowClusters& C, int S, int slice_el
     }
     // segments by chunk (counting sort), longest first inside a chunk
     std::vector<int64_t> koff((size_t)chunks + 1, 0);
-    for (int64_t s = 0; s < nsegs; ++s) ++koff[(size_t)chunk_of_row[(size_t)P.segs[(size_t)s].row] + 1];
+    for (int64_t s = 0; s < nsegs; ++s) ++koff[(size_t)chunk_of_row[(size_t)segs[(size_t)s].row] + 1];
     for (int32_t k = 0; k < chunks; ++k) koff[(size_t)k + 1] += koff[(size_t)k];
     std::vector<int64_t> sidx((size_t)nsegs);
     {
         std::vector<int64_t> cur(koff.begin(), koff.end() - 1);
-        for (int64_t s = 0; s < nsegs; ++s) sidx[(size_t)cur[(size_t)chunk_of_row[(size_t)P.segs[(size_t)s].row]]++] = s;
+        for (int64_t s = 0; s < nsegs; ++s) sidx[(size_t)cur[(size_t)chunk_of_row[(size_t)segs[(size_t)s].row]]++] = s;
     }
     const int nt = nsegs < (1 << 16) ? 1 : host_threads();
     parallel_run(nt, [&](int t, int k) {
         for (int32_t c = t; c < chunks; c += k)
             std::stable_sort(sidx.begin() + (ptrdiff_t)koff[(size_t)c], sidx.begin() + (ptrdiff_t)koff[(size_t)c + 1],
-                             [&](int64_t a, int64_t b) { return P.segs[(size_t)a].len > P.segs[(size_t)b].len; });
+                             [&](int64_t a, int64_t b) { return segs[(size_t)a].len > segs[(size_t)b].len; });
     });
     // (chunk, slice) pairs to XCDs
     std::vector<int64_t> chunk_work((size_t)chunks, 0);
     for (int32_t c = 0; c < chunks; ++c)
-        for (int64_t j = koff[(size_t)c]; j < koff[(size_t)c + 1]; ++j) chunk_work[(size_t)c] += P.segs[(size_t)sidx[(size_t)j]].len + 4;
+        for (int64_t j = koff[(size_t)c]; j < koff[(size_t)c + 1]; ++j) chunk_work[(size_t)c] += segs[(size_t)sidx[(size_t)j]].len + 4;
     std::vector<int8_t> owner((size_t)chunks * (size_t)S);
     int64_t load[8] = {0, 0, 0, 0, 0, 0, 0, 0}, count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     for (int32_t c = 0; c < chunks; ++c)
@@ -221,11 +221,71 @@ void build_xcd_lists(const gp_plan& P, const RowClusters& C, int S, int slice_el
         for (int s = 0; s < S; ++s) {
             const int x = owner[(size_t)c * (size_t)S + (size_t)s];
             for (int64_t j = koff[(size_t)c]; j < koff[(size_t)c + 1]; ++j) {
-                Segment g = P.segs[(size_t)sidx[(size_t)j]];
+                Segment g = segs[(size_t)sidx[(size_t)j]];
                 g.slice = (uint8_t)s;
                 recs[(size_t)cur[x]++] = g;
             }
         }
+}
+
+// Every segment cut in two: the non-zeros whose source lies in the row's own cluster (the
+// ones worth a place in the cache) first, the others after them.  out.col is the column
+// list with every segment's range reordered that way (stable inside each part); a segment
+// with both kinds becomes a hot and a cold record, and a row that ends up with more than one
+// record owns consecutive partial-row slots in (segment, hot before cold) order.
+void build_split_schedule(const gp_plan& P, const RowClusters& C, SplitSchedule& out)
+{
+    const int64_t nsegs = (int64_t)P.segs.size();
+    out.col.resize(P.col.size());
+    std::vector<int32_t> hot_len((size_t)nsegs);
+    const int nt = P.nnz < (1 << 16) ? 1 : host_threads();
+    parallel_run(nt, [&](int t, int k) {
+        for (int64_t s = nsegs * t / k; s < nsegs * (t + 1) / k; ++s) {
+            const Segment& g = P.segs[(size_t)s];
+            const int64_t e0 = ((int64_t)g.start_hi << 32) | g.start_lo;
+            const int32_t li = C.label[(size_t)g.row];
+            int64_t w = e0;
+            for (int64_t e = e0; e < e0 + g.len; ++e)
+                if (C.label[(size_t)P.col[(size_t)e]] == li) out.col[(size_t)w++] = P.col[(size_t)e];
+            hot_len[(size_t)s] = (int32_t)(w - e0);
+            for (int64_t e = e0; e < e0 + g.len; ++e)
+                if (C.label[(size_t)P.col[(size_t)e]] != li) out.col[(size_t)w++] = P.col[(size_t)e];
+        }
+    });
+    // records per row, in the order the plan lists a row's segments (ascending start)
+    std::vector<int32_t> pieces((size_t)P.n, 0);
+    for (int64_t s = 0; s < nsegs; ++s) {
+        const int32_t h = hot_len[(size_t)s], len = P.segs[(size_t)s].len;
+        pieces[(size_t)P.segs[(size_t)s].row] += (h > 0 && h < len) ? 2 : 1;
+    }
+    out.split.clear();
+    std::vector<int64_t> next_slot((size_t)P.n, -1);
+    int64_t slot = 0;
+    for (int64_t i = 0; i < P.n; ++i)
+        if (pieces[(size_t)i] > 1) {
+            out.split.push_back(SplitRow{(int32_t)i, pieces[(size_t)i], slot});
+            next_slot[(size_t)i] = slot;
+            slot += pieces[(size_t)i];
+        }
+    out.num_slots = slot;
+    out.hot.clear();
+    out.cold.clear();
+    for (int64_t s = 0; s < nsegs; ++s) {
+        const Segment& g = P.segs[(size_t)s];
+        const int64_t e0 = ((int64_t)g.start_hi << 32) | g.start_lo;
+        const int32_t h = hot_len[(size_t)s];
+        auto piece = [&](int64_t start, int32_t len) {
+            Segment q = g;
+            q.start_lo = (uint32_t)(start & 0xFFFFFFFF);
+            q.start_hi = (uint8_t)(start >> 32);
+            q.len = (uint16_t)len;
+            int64_t& ns = next_slot[(size_t)g.row];
+            q.slot = ns < 0 ? -1 : (int32_t)ns++;
+            return q;
+        };
+        if (h > 0 || g.len == 0) out.hot.push_back(piece(e0, h));  // a row without non-zeros still owes its zero row
+        if (g.len - h > 0) out.cold.push_back(piece(e0 + h, g.len - h));
+    }
 }
 
 }  // namespace gp

@@ -31,6 +31,7 @@ struct Options {
     int64_t column_slices = 0;
     int64_t persistent_blocks = 0;
     int64_t cache_schedule = 0;  // 0 = decided per plan, 1 = explicit per-XCD lists always, 2 = never
+    int64_t split_records = 0;   // explicit lists: 0 / 1 = hot and cold pieces in phases of their own, 2 = whole records
     int64_t lc_tile_rows = 0;  // 0 = chosen per call from the batch size
     int64_t hbm_budget_bytes = 0;
     int64_t device_plan_chunk = 0;  // GP_PLAN_ON_DEVICE: most candidate entries sorted at once, 0 = 2^31 - 1
@@ -74,6 +75,7 @@ struct RowClusters {
 // Explicit per-XCD work lists on the device, for one slice shape.
 struct XcdWork {
     int num_slices = 0, slice_elems = 0, chunk_records = 1;
+    bool split = false;       // the records are the hot pieces of the split schedule
     Segment* recs = nullptr;  // DEVICE
     int64_t off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
 };
@@ -94,6 +96,17 @@ struct DevicePlan {
     float* comb = nullptr;
     int64_t ping_bytes = 0, comb_elems = 0;
     std::vector<XcdWork> work;  // explicit work lists built so far (one per slice shape)
+    // split schedule (hot / cold pieces of every segment), made on first use
+    bool split_ready = false;
+    int32_t* split_col = nullptr;     // reordered column list
+    float* split_edge_ws = nullptr;   // per-edge weights in that order (sym operator)
+    Segment* split_cold = nullptr;    // cold records, walked as an implicit list
+    int64_t split_num_cold = 0;
+    SplitRow* split_rows = nullptr;
+    int64_t split_num_rows = 0, split_num_slots = 0;
+    float* split_carry = nullptr;
+    int64_t split_carry_ld = 0;
+    std::vector<Segment> split_hot_host;  // hot records in plan order (source of the per-XCD lists)
     std::vector<void*> retired;  // buffers that were outgrown: freed with the plan, never while work may still use them
 };
 
@@ -137,8 +150,17 @@ gp_status build_schedule(gp_plan* plan);
 gp_status cut_schedule(const gp_plan& plan, const std::vector<int64_t>& block_off, std::vector<Segment>& segs,
                        std::vector<int64_t>& seg_off, std::vector<SplitRow>& split, int64_t& num_slots);
 void cluster_rows(const gp_plan& P, RowClusters& C);
-void build_xcd_lists(const gp_plan& P, const RowClusters& C, int S, int slice_elems, int d, std::vector<Segment>& recs,
-                     int64_t off[9]);
+void build_xcd_lists(const gp_plan& P, const std::vector<Segment>& segs, const RowClusters& C, int S, int slice_elems, int d,
+                     std::vector<Segment>& recs, int64_t off[9]);
+// The plan's segments cut into records that gather inside the row's cluster (hot) and records
+// that gather outside it (cold), with a column list reordered to match (gp_cluster.cpp).
+struct SplitSchedule {
+    std::vector<int32_t> col;
+    std::vector<Segment> hot, cold;
+    std::vector<SplitRow> split;
+    int64_t num_slots = 0;
+};
+void build_split_schedule(const gp_plan& P, const RowClusters& C, SplitSchedule& out);
 // Slice shape of the explicit work lists for rows of d elements in vectors of `vec`
 // (element size es), or false if this plan keeps the implicit lists.
 bool choose_cache_schedule(const gp_plan* plan, int32_t d, int es, int vec, int& num_slices, int& slice_elems);

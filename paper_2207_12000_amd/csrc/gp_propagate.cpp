@@ -34,6 +34,11 @@ void release(DevicePlan& D)
     (void)hipFree(D.comb);
     for (XcdWork& w : D.work) (void)hipFree(w.recs);
     for (void* p : D.retired) (void)hipFree(p);
+    (void)hipFree(D.split_col);
+    (void)hipFree(D.split_edge_ws);
+    (void)hipFree(D.split_cold);
+    (void)hipFree(D.split_rows);
+    (void)hipFree(D.split_carry);
     D = DevicePlan();
 }
 
@@ -155,10 +160,64 @@ bool choose_cache_schedule(const gp_plan* plan, int32_t d, int es, int vec, int&
 
 namespace {
 
-// Gives the launch explicit work lists if the plan's cache schedule applies to it
-// (building and uploading them on first use of a slice shape).
-gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream, bool may_build = true)
+template <class T>
+gp_status upload_now(T*& dptr, const std::vector<T>& h, hipStream_t stream)
 {
+    dptr = nullptr;
+    if (h.empty()) return GP_OK;
+    GP_HIP(hipMalloc((void**)&dptr, h.size() * sizeof(T)));
+    hipError_t e = hipMemcpyAsync(dptr, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice, stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(stream);  // pageable source: done before the vector goes away
+    if (e != hipSuccess) {
+        (void)hipFree(dptr);
+        dptr = nullptr;
+        return fail(GP_ERR_DEVICE, "upload failed: %s", hipGetErrorString(e));
+    }
+    return GP_OK;
+}
+
+// The split schedule on the device (plan->mu held): reordered column list, cold records,
+// the rows that own partial rows, and a partial-row buffer wide enough for d columns.
+gp_status ensure_split(const gp_plan* plan, int32_t d, bool want_edge_weights, hipStream_t stream)
+{
+    DevicePlan& D = plan->dev;
+    gp_status st;
+    if (!D.split_ready) {
+        SplitSchedule sch;
+        build_split_schedule(*plan, plan->clusters, sch);
+        if (sch.num_slots > INT32_MAX) return fail(GP_ERR_OVERFLOW, "%lld partial rows exceed int32", (long long)sch.num_slots);
+        if ((st = upload_now(D.split_col, sch.col, stream)) != GP_OK || (st = upload_now(D.split_cold, sch.cold, stream)) != GP_OK ||
+            (st = upload_now(D.split_rows, sch.split, stream)) != GP_OK)
+            return st;
+        D.split_num_cold = (int64_t)sch.cold.size();
+        D.split_num_rows = (int64_t)sch.split.size();
+        D.split_num_slots = sch.num_slots;
+        D.split_hot_host.swap(sch.hot);
+        D.split_ready = true;
+    }
+    if (want_edge_weights && !D.split_edge_ws && plan->nnz > 0) {
+        GP_HIP(hipMalloc((void**)&D.split_edge_ws, (size_t)plan->nnz * sizeof(float)));
+        if ((st = launch_fill_edge_weights(D.split_col, D.dinv_sqrt, D.split_edge_ws, plan->nnz, stream)) != GP_OK) return st;
+        GP_HIP(hipStreamSynchronize(stream));
+    }
+    const int64_t need_ld = ((int64_t)d + 3) / 4 * 4;
+    if (D.split_num_slots > 0 && need_ld > D.split_carry_ld) {
+        if (D.split_carry) D.retired.push_back(D.split_carry);
+        D.split_carry = nullptr;
+        D.split_carry_ld = 0;
+        GP_HIP(hipMalloc((void**)&D.split_carry, (size_t)D.split_num_slots * need_ld * sizeof(float)));
+        D.split_carry_ld = need_ld;
+    }
+    return GP_OK;
+}
+
+// Gives the launch explicit work lists if the plan's cache schedule applies to it
+// (building and uploading them on first use of a slice shape).  *split comes back true
+// when the lists hold the hot pieces of the split schedule: the caller then runs the cold
+// records first and reads column ids, weights and partial rows from the split schedule.
+gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream, bool may_build = true, bool* split = nullptr)
+{
+    if (split) *split = false;
     const int es = a.dtype == GP_F32 ? 4 : 2;
     const int vec = hop_vector_width(a);
     // several column passes: implicit lists (explicit ones are cut for the whole row)
@@ -169,16 +228,25 @@ gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream,
     if (!may_build && !plan->clusters.ready) return GP_OK;  // nothing built yet: implicit lists
     if (!choose_cache_schedule(plan, a.d, es, vec, S, elems)) return GP_OK;
     DevicePlan& D = plan->dev;
+    // hot and cold pieces in phases of their own need buffers of their own: only where the caller may allocate
+    // (not worth it when hardly anything leaves the clusters: every row then pays two partial rows for nothing)
+    const bool want_split = split && may_build && plan->opt.split_records != 2 &&
+                            (plan->opt.split_records == 1 || plan->clusters.inside_fraction < 0.98);
+    if (want_split) {
+        gp_status st = ensure_split(plan, a.d, a.edge_w != nullptr, stream);
+        if (st != GP_OK) return st;
+    }
     const XcdWork* found = nullptr;
     for (const XcdWork& w : D.work)
-        if (w.num_slices == S && w.slice_elems == elems) found = &w;
+        if (w.num_slices == S && w.slice_elems == elems && w.split == want_split) found = &w;
     if (!found && !may_build) return GP_OK;
     if (!found) {
         std::vector<Segment> recs;
         XcdWork w;
         w.num_slices = S;
         w.slice_elems = elems;
-        build_xcd_lists(*plan, plan->clusters, S, elems, a.d, recs, w.off);
+        w.split = want_split;
+        build_xcd_lists(*plan, want_split ? D.split_hot_host : plan->segs, plan->clusters, S, elems, a.d, recs, w.off);
         // a request to the cursor should be worth about 64 non-zeros of gathering
         const int64_t mean_len = std::max<int64_t>(1, plan->nnz / std::max<int64_t>(1, (int64_t)plan->segs.size()));
         w.chunk_records = (int)std::min<int64_t>(32, std::max<int64_t>(1, 64 / mean_len));
@@ -198,6 +266,7 @@ gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream,
     a.chunk_records = found->chunk_records;
     a.num_slices = found->num_slices;
     a.slice_elems = found->slice_elems;
+    if (split) *split = found->split;
     return GP_OK;
 }
 
@@ -301,14 +370,32 @@ gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t
         a.column_slices = plan->opt.column_slices;
         a.persistent_blocks = plan->opt.persistent_blocks;
         a.column_tile = plan->opt.column_tile;
-        if ((st = attach_work_lists(plan, a, stream, may_allocate)) != GP_OK) return st;
+        bool split = false;
+        HopArgs cold = a;  // as it stands: implicit lists
+        if ((st = attach_work_lists(plan, a, stream, may_allocate, &split)) != GP_OK) return st;
+        if (split) {
+            // Records that gather outside their row's cluster first, whole rows wide: nothing of
+            // theirs is worth keeping in a cache, and run on their own they evict nothing that is.
+            // Then the records that gather inside it, from the per-XCD lists.  Both kinds leave
+            // partial rows; the fix-up below joins them.
+            a.col = cold.col = D.split_col;
+            if (a.edge_w) {
+                a.edge_w = cold.edge_w = D.split_edge_ws;
+                a.edge_w_per_edge = cold.edge_w_per_edge = true;
+            }
+            a.carry = cold.carry = D.split_carry;
+            a.carry_ld = cold.carry_ld = D.split_carry_ld;
+            cold.segs = D.split_cold;
+            cold.num_segs = D.split_num_cold;
+            if (cold.num_segs > 0 && (st = hop_passes(cold, stream)) != GP_OK) return st;
+        }
         if ((st = hop_passes(a, stream)) != GP_OK) return st;
-        if (!plan->split.empty()) {
+        if (split ? D.split_num_rows > 0 : !plan->split.empty()) {
             FixupArgs f;
-            f.split = D.split;
-            f.num_split = (int64_t)plan->split.size();
-            f.carry = carry;
-            f.carry_ld = carry_ld;
+            f.split = split ? D.split_rows : D.split;
+            f.num_split = split ? D.split_num_rows : (int64_t)plan->split.size();
+            f.carry = split ? D.split_carry : carry;
+            f.carry_ld = split ? D.split_carry_ld : carry_ld;
             f.row_scale = row_scale;
             f.xout = a.xout;
             f.ldout = ldo;
@@ -455,7 +542,7 @@ extern "C" gp_status gp_plan_work_lists(const gp_plan* plan, int32_t d, gp_dtype
         for (int x = 0; x <= 8; ++x) xcd_off[x] = 0;
         if (!choose_cache_schedule(plan, d, es, vec, S, elems)) return GP_OK;  // implicit lists
         std::vector<Segment> recs;
-        build_xcd_lists(*plan, plan->clusters, S, elems, d, recs, xcd_off);
+        build_xcd_lists(*plan, plan->segs, plan->clusters, S, elems, d, recs, xcd_off);
         *num_slices = S;
         *slice_elems = elems;
         if (records) {

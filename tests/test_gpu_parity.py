@@ -136,12 +136,14 @@ def test_leading_dimension_and_alias(dtype, agg, ld_pad, alias):
 
 def test_column_tile_option_changes_nothing():
     w = gp_synth.make_workload(2, scale=0.02, d=200)
-    a = parity_case(w, K=2)
-    gp.gp_set_option("column_tile", 64)
+    gp.gp_set_option("split_records", 2)     # whole records on both sides (cut records group the sums differently)
     try:
+        a = parity_case(w, K=2)
+        gp.gp_set_option("column_tile", 64)
         b = parity_case(w, K=2)
     finally:
         gp.gp_set_option("column_tile", 0)
+        gp.gp_set_option("split_records", 0)
     assert np.array_equal(a, b)          # per-row summation order does not depend on the tile
 
 
@@ -275,7 +277,7 @@ def test_many_hops_and_repeated_calls_on_one_plan():
 @pytest.fixture
 def _mapping_defaults():
     yield
-    for k in ("column_slices", "persistent_blocks", "cache_schedule", "segment_edges"):
+    for k in ("column_slices", "persistent_blocks", "cache_schedule", "segment_edges", "split_records"):
         gp.gp_set_option(k, 0)
 
 
@@ -299,7 +301,10 @@ def test_implicit_lists_any_slice_count_and_grid(dtype, d, slices, _mapping_defa
 def test_explicit_lists_match_the_oracle_and_the_implicit_bits(dtype, d, agg, slices, _mapping_defaults):
     """The cache schedule (explicit per-XCD work lists handed out from cursors) forced on a
     community graph and on a graph without communities: the oracle's bound holds and the
-    bits are those of the implicit lists (a record's sum does not depend on who adds it up)."""
+    bits are those of the implicit lists (a record's sum does not depend on who adds it up);
+    with every record cut into a piece that gathers inside the row's cluster and one that
+    gathers outside it, in phases of their own, the sums are grouped differently and are
+    checked against the oracle."""
     for cfg, scale in ((4, 0.004), (2, 0.03)):
         w = gp_synth.make_workload(cfg, scale=scale, d=d)
         gp.gp_set_option("segment_edges", 16)          # cut rows too
@@ -308,5 +313,8 @@ def test_explicit_lists_match_the_oracle_and_the_implicit_bits(dtype, d, agg, sl
         ref = parity_case(w, K=2, dtype=dtype, agg=agg, budget=20_000)
         gp.gp_set_option("cache_schedule", 1)
         gp.gp_set_option("column_slices", slices)
+        gp.gp_set_option("split_records", 2)           # whole records: the very same sums
         got = parity_case(w, K=2, dtype=dtype, agg=agg, budget=20_000)
         assert np.array_equal(ref, got), f"config {cfg}"
+        gp.gp_set_option("split_records", 1)           # hot and cold pieces: other partial sums, the oracle's bound holds
+        parity_case(w, K=2, dtype=dtype, agg=agg, budget=20_000)

@@ -13,7 +13,11 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(scope="module", autouse=True)
 def _need_gpu(gpu_or_skip):
+    # bit-for-bit comparisons with the resident schedule: whole records there too (its split
+    # schedule groups a row's partial sums differently)
+    gp.gp_set_option("split_records", 2)
     yield
+    gp.gp_set_option("split_records", 0)
     gp.gp_set_hbm_budget_bytes(0)
 
 
