@@ -35,7 +35,7 @@ typedef struct gp_plan gp_plan; /* opaque; owned by the library */
 
 typedef enum {
     GP_OK = 0,
-    GP_ERR_INVALID_ARG = 1,  /* null pointer, negative size, ld < d, unknown enum/flag, pageable host memory */
+    GP_ERR_INVALID_ARG = 1,  /* null pointer, negative size, ld < d, unknown enum/flag, device and host operands mixed */
     GP_ERR_INDEX_RANGE = 2,  /* a node id outside [0, n) */
     GP_ERR_OVERFLOW = 3,     /* a count does not fit the type the layout stores it in */
     GP_ERR_OOM_HOST = 4,
@@ -153,8 +153,13 @@ gp_status gp_plan_work_lists(const gp_plan *plan, int32_t d, gp_dtype dtype, int
  *
  *  plan      from gp_plan_blocks.
  *  X         n x d row-major, leading dimension ldx elements (ldx >= d), of
- *            `dtype`.  DEVICE pointer, or PINNED HOST pointer (then out_stack
- *            must be pinned host too and the streamed schedule is used).
+ *            `dtype`.  DEVICE pointer, or HOST pointer (then out_stack must be host
+ *            memory too and the streamed schedule is used).  Host memory should be
+ *            PINNED: the link then runs at its rate.  Ordinary (pageable) host
+ *            memory is accepted when ldx = ldo = d and the HBM budget holds whole
+ *            rows; its copies are staged by the runtime, at a fraction of the rate
+ *            (GP_ERR_UNSUPPORTED otherwise).  It is the way to run operands larger
+ *            than the pinned memory a machine grants.
  *  d         feature columns, >= 1.
  *  dtype     GP_F32, or GP_BF16 storage (accumulation is always fp32; a stored
  *            bf16 value is the fp32 accumulator rounded to nearest even).

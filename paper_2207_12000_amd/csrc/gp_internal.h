@@ -177,7 +177,7 @@ gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t
                         unsigned long long* ctrl, bool may_allocate);
 // streamed schedule: operands in pinned host memory
 gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype,
-                             gp_agg agg, int32_t K, void* out, int64_t ldo);
+                             gp_agg agg, int32_t K, void* out, int64_t ldo, bool pageable);
 
 // ---- kernel launchers (gp_kernels.hip) -------------------------------------
 constexpr int kHopCtrlWords = 16;

@@ -619,18 +619,25 @@ extern "C" gp_status gp_propagate(const gp_plan* plan, const void* X, int64_t ld
     if (((uintptr_t)X % es) || ((uintptr_t)out_stack % es))
         return fail(GP_ERR_INVALID_ARG, "X / out_stack not aligned to the element size");
 
-    hipPointerAttribute_t ax, ao;
-    if (hipPointerGetAttributes(&ax, X) != hipSuccess || hipPointerGetAttributes(&ao, out_stack) != hipSuccess) {
-        (void)hipGetLastError();
-        return fail(GP_ERR_INVALID_ARG, "X / out_stack is neither device memory nor pinned host memory");
-    }
-    const bool xdev = ax.type == hipMemoryTypeDevice, odev = ao.type == hipMemoryTypeDevice;
-    const bool xhost = ax.type == hipMemoryTypeHost, ohost = ao.type == hipMemoryTypeHost;
+    // 0 = device memory, 1 = pinned host memory, 2 = ordinary (pageable) host memory, which the
+    // runtime does not know about
+    auto kind_of = [](const void* p) {
+        hipPointerAttribute_t at;
+        if (hipPointerGetAttributes(&at, p) != hipSuccess) {
+            (void)hipGetLastError();
+            return 2;
+        }
+        if (at.type == hipMemoryTypeDevice) return 0;
+        if (at.type == hipMemoryTypeHost) return 1;
+        return at.type == hipMemoryTypeUnregistered ? 2 : 3;
+    };
+    const int kx = kind_of(X), ko = kind_of(out_stack);
     try {  // nothing may leave the C boundary as an exception
-        if (xdev && odev) return propagate_resident(plan, X, ldx, d, dtype, agg, K, out_stack, ldo, (hipStream_t)hip_stream);
-        if (xhost && ohost) return propagate_streamed(plan, X, ldx, d, dtype, agg, K, out_stack, ldo);
+        if (kx == 0 && ko == 0) return propagate_resident(plan, X, ldx, d, dtype, agg, K, out_stack, ldo, (hipStream_t)hip_stream);
+        if ((kx == 1 || kx == 2) && (ko == 1 || ko == 2))
+            return propagate_streamed(plan, X, ldx, d, dtype, agg, K, out_stack, ldo, kx == 2 || ko == 2);
     } catch (const std::exception& e) {
         return fail(GP_ERR_OOM_HOST, "gp_propagate: %s", e.what());
     }
-    return fail(GP_ERR_INVALID_ARG, "X and out_stack must both be device memory or both be pinned host memory");
+    return fail(GP_ERR_INVALID_ARG, "X and out_stack must both be device memory or both be host memory");
 }

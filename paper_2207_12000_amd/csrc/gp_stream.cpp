@@ -241,7 +241,7 @@ void release_pinned(gp_plan* plan)
 }
 
 gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, int32_t d, gp_dtype dtype, gp_agg agg,
-                             int32_t K, void* out, int64_t ldo)
+                             int32_t K, void* out, int64_t ldo, bool pageable)
 {
     const int64_t n = plan->n;
     const int es = dtype == GP_F32 ? 4 : 2;
@@ -379,6 +379,14 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
         S->blocks_stay = nbuf >= C.b;
         S->blocks_loaded = false;
     }
+    // Ordinary host memory cannot be read or written by a kernel and its copies are staged by
+    // the runtime (slower, and the enqueuing thread waits for them): accepted where every
+    // transfer is one contiguous run, i.e. whole rows of operands without row padding.
+    if (pageable && (w < d || ldx != d || ldo != d))
+        return fail(GP_ERR_UNSUPPORTED,
+                    "operands in pageable host memory need contiguous rows (ldx = ldo = d) and an HBM budget that holds "
+                    "whole rows (slab width %lld of %d columns); use pinned host memory",
+                    (long long)w, d);
     const StreamSchedule& C = S->sched;
     const int32_t b = C.b;
     const bool blocks_stay = S->blocks_stay;

@@ -165,3 +165,24 @@ def test_eq12_solver_drives_the_streamed_schedule():
         res = gp.propagate_tensors(lp, torch.from_numpy(w.X).cuda(), w.agg, 2)
         torch.cuda.synchronize()
         assert np.array_equal(got, res.cpu().numpy().astype(np.float64))
+
+
+def test_pageable_host_operands_are_staged_by_the_runtime():
+    """Ordinary host memory (what operands larger than the machine's pinned-memory grant
+    live in): same bits as from pinned memory; strided operands are refused."""
+    w = gp_synth.make_workload(3, scale=0.004, d=40)
+    n, d, K = w.n, 40, 2
+    with gp.gp_plan_blocks(w.src, w.dst, w.n, 50_000, w.flags) as lp:
+        pinned_result, _ = run_streamed(lp, w.X, gp.GP_F32, w.agg, K, 10**9)
+        x = np.ascontiguousarray(w.X)
+        out = np.full((K + 1, n, d), np.nan, dtype=np.float32)
+        gp.gp_propagate(lp, x.ctypes.data, d, d, gp.GP_F32, w.agg, K, out.ctypes.data, d, None)
+        assert np.array_equal(out.astype(np.float64), pinned_result)
+        stack = np.full((K + 1, n, d), np.nan, dtype=np.float32)       # X living in slab 0
+        stack[0] = w.X
+        gp.gp_propagate(lp, stack.ctypes.data, d, d, gp.GP_F32, w.agg, K, stack.ctypes.data, d, None)
+        assert np.array_equal(stack.astype(np.float64), pinned_result)
+        wide = np.zeros((n, d + 4), dtype=np.float32)
+        with pytest.raises(gp.GpError) as e:
+            gp.gp_propagate(lp, wide.ctypes.data, d + 4, d, gp.GP_F32, w.agg, K, out.ctypes.data, d, None)
+        assert e.value.status == gp.GP_ERR_UNSUPPORTED
