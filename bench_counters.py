@@ -103,13 +103,28 @@ def main() -> int:
                   f"options {json.dumps(rec['config']['options'])}.", "",
                   "## Kernel durations", "", "Command (from the repository root):", "", "    " + " ".join(cmd), "",
                   "| kernel | calls | average ns | % of GPU time | min ns | max ns |", "|---|---|---|---|---|---|"]
-        hop_avg_ns = None
+        # one row per kernel name (a hop may use two instantiations of the hop kernel: the launch over the
+        # records that gather outside the row's cluster and the one over those that gather inside it)
+        agg = collections.OrderedDict()
         for s in stats:
             k = kernel_of(s["Name"])
-            lines.append(f"| {k} | {s['Calls']} | {float(s['AverageNs']):.0f} | {float(s['Percentage']):.2f} | {s['MinNs']} | {s['MaxNs']} |")
+            a = agg.setdefault(k, {"calls": 0, "total": 0.0, "pct": 0.0, "min": None, "max": None, "kinds": 0})
+            a["calls"] += int(s["Calls"])
+            a["total"] += float(s["AverageNs"]) * int(s["Calls"])
+            a["pct"] += float(s["Percentage"])
+            a["min"] = int(s["MinNs"]) if a["min"] is None else min(a["min"], int(s["MinNs"]))
+            a["max"] = int(s["MaxNs"]) if a["max"] is None else max(a["max"], int(s["MaxNs"]))
+            a["kinds"] += 1
+        hop_avg_ns = None
+        for k, a in agg.items():
+            note = f" ({a['kinds']} instantiations)" if a["kinds"] > 1 else ""
+            lines.append(f"| {k}{note} | {a['calls']} | {a['total'] / a['calls']:.0f} | {a['pct']:.2f} | {a['min']} | {a['max']} |")
             if k == "gp_hop_segments":
-                hop_avg_ns = float(s["AverageNs"])
+                hop_avg_ns = a["total"] / a["calls"]
         rl = rec["roofline"]
+        if rl["launches_per_hop"] > 1:
+            lines += ["", f"A hop is {rl['launches_per_hop']} launches of the hop kernel here; every per-launch figure below is the mean "
+                          f"over all of them, a hop is {rl['launches_per_hop']} times that."]
         lines += ["", f"bench.py in the same run: {rec['value']} GEFU/s, {rec['ms_per_step']} ms per step; hop kernel timed with HIP "
                       f"events inside bench.py: {rl['avg_launch_us']} us per launch (rocprofv3 average above: {hop_avg_ns / 1e3:.1f} us).",
                   f"Algorithmic bytes per launch {rl['algorithmic_bytes_per_launch']} -> {rl['achieved']} GB/s = {rl['frac']} of the "
@@ -152,7 +167,7 @@ def main() -> int:
         lines += ["", f"Hop kernel, scaled: fetch {fetch_b / 1e9:.4f} GB + write {write_b / 1e9:.4f} GB = **{total / 1e9:.4f} GB per launch** "
                       f"({total / (hop_avg_ns * 1e-9) / 1e12:.2f} TB/s over the {hop_avg_ns / 1e3:.1f} us launch).  Algorithmic (compulsory) bytes "
                       f"per launch: {alg / 1e9:.4f} GB; measured / algorithmic = {total / alg:.2f}.  All rows gathered: "
-                      f"{rec['config']['nnz'] * dd * 4 / 1e9:.3f} GB per launch.  L2 hit rate over all requests (rows, ids, weights, "
+                      f"{rec['config']['nnz'] * dd * 4 / 1e9:.3f} GB per hop.  L2 hit rate over all requests (rows, ids, weights, "
                       f"stores): {100 * hit / max(hit + miss, 1):.1f} %.", ""]
         with open(os.path.join(PROFILES, f"gp_hop_segments_{tag}.md"), "w") as f:
             f.write("\n".join(lines))
