@@ -118,6 +118,7 @@ struct StreamedState {
     std::vector<hipEvent_t> blk_ready, blk_free;  // one pair per edge-block buffer
     hipEvent_t hop_done = nullptr, out_done[2] = {nullptr, nullptr};
     std::vector<void*> dev;
+    size_t dev_bytes = 0;  // sum of the device allocations below
     float *d_dinv_sqrt = nullptr, *d_dinv = nullptr, *d_carry = nullptr;
     unsigned long long* d_ctrl = nullptr;
     SplitRow* d_split = nullptr;
@@ -167,6 +168,7 @@ struct StreamedState {
         void* q = nullptr;
         GP_HIP(hipMalloc(&q, bytes));
         dev.push_back(q);
+        dev_bytes += bytes;
         p = (T*)q;
         return GP_OK;
     }
@@ -258,9 +260,9 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
     if (budget <= 0) {
         size_t free_b = 0, total_b = 0;
         GP_HIP(hipMemGetInfo(&free_b, &total_b));
-        budget = (int64_t)(free_b / 10 * 8);
-        // buffers kept from an earlier call on this plan count as free: they are reused or released
-        if (plan->streamed) budget += 0;
+        // what an earlier call on this plan left on the device counts as free: it is reused or released
+        const StreamedState* kept = (const StreamedState*)plan->streamed;
+        budget = (int64_t)((free_b + (kept ? kept->dev_bytes : 0)) / 10 * 8);
     }
     const Volumes v = volumes(n, plan->nnz, (int64_t)plan->segs.size(), plan->num_slots, d, es, budget);
     const int64_t max_c = (d + unit - 1) / unit;
