@@ -32,7 +32,7 @@ import subprocess
 import sys
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
-OUT = os.path.join(ROOT, "gpurun_out", "counters")
+OUT = os.path.join(os.environ.get("TMPDIR", "/tmp"), "gp_counters")   # raw rocprofv3 output and logs: scratch
 PROFILES = os.path.join(ROOT, "profiles")
 NAMES = {1: "config1_tiny", 2: "config2_chunglu_arxiv_like", 3: "config3_chunglu_mean_d100", 4: "config4_sbm_sum_d602"}
 PMC_SETS = ["FETCH_SIZE", "WRITE_SIZE", "TCC_HIT_sum TCC_MISS_sum", "MeanOccupancyPerCU"]
@@ -43,7 +43,8 @@ def run(cmd, log, limit):
         rc = subprocess.call(["timeout", "-s", "KILL", str(limit)] + cmd, stdout=f, stderr=subprocess.STDOUT, cwd=ROOT,
                              env=dict(os.environ, TMPDIR="/tmp"))
     if rc != 0:
-        sys.exit(f"bench_counters.py: {' '.join(cmd)} ended with {rc}; see {log}")
+        tail = "".join(open(log).readlines()[-15:])
+        sys.exit(f"bench_counters.py: {' '.join(cmd)} ended with {rc}; end of {log}:\n{tail}")
 
 
 def kernel_of(name: str) -> str:
@@ -88,7 +89,7 @@ def main() -> int:
         # ---- durations ------------------------------------------------------------
         d = os.path.join(OUT, f"trace_w{wl}")
         shutil.rmtree(d, ignore_errors=True)
-        cmd = ["rocprofv3", "--kernel-trace", "--stats", "-d", os.path.relpath(d, ROOT), "-o", "t", "--output-format", "csv",
+        cmd = ["rocprofv3", "--kernel-trace", "--stats", "-d", d, "-o", "t", "--output-format", "csv",
                "--"] + bench + ["--steps", str(args.steps)]
         log = os.path.join(OUT, f"trace_w{wl}.log")
         run(cmd, log, 600)
@@ -137,7 +138,7 @@ def main() -> int:
             name = cset.replace(" ", "_")
             d = os.path.join(OUT, f"pmc_w{wl}_{name}")
             shutil.rmtree(d, ignore_errors=True)
-            cmd = ["rocprofv3", "--pmc"] + cset.split() + ["--kernel-trace", "-d", os.path.relpath(d, ROOT), "-o", "p",
+            cmd = ["rocprofv3", "--pmc"] + cset.split() + ["--kernel-trace", "-d", d, "-o", "p",
                                                           "--output-format", "csv", "--"] + bench + ["--steps", "3", "--warmup", "1"]
             run(cmd, os.path.join(OUT, f"pmc_w{wl}_{name}.log"), 600)
             cmds.append("    " + " ".join(cmd))
