@@ -286,6 +286,8 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
                    "options": options},
         "roofline": {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     # the same launch on the bytes the counters saw (fetch + write, per launch): how busy the memory system was
+                     "traffic_frac": round(traffic / avg_launch_s / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
                      "kernel": "gp_hop_segments", "launches": launches, "launches_per_hop": launches_per_hop,
                      "avg_launch_us": round(avg_launch_s * 1e6, 3), "algorithmic_bytes_per_launch": bytes_per_launch,
                      "kernel_times_from": f"event-bracketed pass, {bracketed_ms:.5f} ms per step",
@@ -417,7 +419,7 @@ def main() -> int:
             others[f"config{wl}"] = {
                 "workload": rec["config"]["workload"], "value": rec["value"], "unit": rec["unit"],
                 "ms_per_step": rec["ms_per_step"], "work_lists": rec["config"]["work_lists"],
-                "roofline": {k: rec["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
+                "roofline": {k: rec["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "traffic_frac",
                                                              "avg_launch_us", "algorithmic_bytes_per_launch")},
                 "host_s": rec["host_s"]}
     head["other_workloads"] = others
