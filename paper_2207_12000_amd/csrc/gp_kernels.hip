@@ -3,15 +3,17 @@
 // fixed-order completion of rows that were cut, and the slot-0 copy.
 //
 // Work shape.  A wavefront (64 lanes) is divided into lane groups of G lanes.
-// One group owns one segment: a run of at most a few hundred consecutive
-// non-zeros of one destination row.  The lanes of a group span the feature
-// columns, each lane holding VPL vectors of VEC consecutive elements, so a
-// gathered feature row is read by one coalesced 16-byte-per-lane load.  The
-// group reads its column ids G at a time with one coalesced load (each lane a
-// different id, plus that id's normalisation weight), then hands them round with
-// in-group shuffles; four gathers are kept in flight per group, each with its
-// own accumulator (also what keeps the fp32 sum short-chained).  No cross-lane
-// reduction is needed: lanes own columns, not edges.
+// One group owns one record at a time: a segment (a run of at most a few hundred
+// consecutive non-zeros of one destination row) and a column slice of it.  The
+// lanes of a group span the slice's columns, each lane holding VPL vectors of VEC
+// consecutive elements, so a gathered feature row is read by one coalesced
+// 16-byte-per-lane load.  The group reads its column ids G at a time with one
+// coalesced load (each lane a different id, plus that id's weight).  A group that
+// is a whole wavefront lifts one id at a time into scalar registers and computes
+// the row address there; narrower groups hand the ids round with in-group
+// shuffles.  Eight rows are in flight per group, spread over four accumulators
+// (also what keeps the fp32 sums short-chained).  No cross-lane reduction is
+// needed: lanes own columns, not edges.
 #include <hip/hip_runtime.h>
 
 #include "gp_internal.h"
