@@ -69,7 +69,7 @@ LC_WIDTHS = [256, 256, 256, 40]      # hidden 256 (Appendix B), four MLP layers 
 MFMA_F32_PEAK_TFLOPS = 157.3
 
 
-def bench_lc(args, gp, torch, w, plan, stack, t_gen, t_plan) -> int:
+def bench_lc(args, gp, torch, w, plan, stack, t_gen, t_plan, cpu_baseline=True):
     """One step = the LC-version forward pass (Appendix A) over all n rows of the hop
     stack gp_propagate left in HBM, in mini-batches of --lc-batch randomly permuted
     rows (the paper trains with batches of 4096)."""
@@ -126,7 +126,7 @@ def bench_lc(args, gp, torch, w, plan, stack, t_gen, t_plan) -> int:
         "other_kernels_ms_per_step": {"gp_lc_reduce": round(red_ms / args.steps, 5)},
         "host_s": {"generate": round(t_gen, 2), "gp_plan_blocks": round(t_plan, 3)},
     }
-    if not args.no_cpu_baseline:
+    if cpu_baseline and not args.no_cpu_baseline:
         from oracle import lc
         stack_np = stack.cpu().numpy()
         rows, t_cpu = 0, 0.0
@@ -140,8 +140,7 @@ def bench_lc(args, gp, torch, w, plan, stack, t_gen, t_plan) -> int:
             i = (i + 4096) % max(n - 4096, 1)
         rec["cpu_baseline"] = {"value": round(rows / t_cpu / 1e6, 4), "unit": "Mrows/s", "cores": int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
                                "kind": "oracle", "sample": f"{rows} rows in mini-batches of 4096, fp64 numpy, {t_cpu:.2f} s"}
-    print(json.dumps(rec))
-    return 0
+    return rec
 
 
 def cpu_model() -> str:
@@ -194,9 +193,17 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
         step()
         torch.cuda.synchronize()
         args.workload = workload
-        rc = bench_lc(args, gp, torch, w, plan, out, t_gen, t_plan)
+        if args.lc == "both":           # the consumer rides along with the default run: all rows at once, and the paper's batch size
+            recs = []
+            for batch in (0, 4096):
+                args.lc_batch = batch
+                recs.append(bench_lc(args, gp, torch, w, plan, out, t_gen, t_plan, cpu_baseline=False))
+            plan.close()
+            return recs
+        rec = bench_lc(args, gp, torch, w, plan, out, t_gen, t_plan)
         plan.close()
-        return rc
+        print(json.dumps(rec))
+        return 0
 
     t0 = time.perf_counter()
     step()                                   # the first call also uploads the plan and sizes the scratch
@@ -423,6 +430,14 @@ def main() -> int:
                                                              "avg_launch_us", "algorithmic_bytes_per_launch")},
                 "host_s": rec["host_s"]}
     head["other_workloads"] = others
+    # the LC-version consumer over config 2's stack (its own metric and roofline: fp32 MFMA), in short form
+    args.lc = "both"
+    lc_recs = time_workload(args, gp, torch, 2, False)
+    if isinstance(lc_recs, list):
+        head["lc_consumer"] = [{"workload": r["config"]["workload"], "value": r["value"], "unit": r["unit"],
+                                "ms_per_step": r["ms_per_step"],
+                                "roofline": {k: r["roofline"][k] for k in ("bound", "achieved", "peak", "unit", "frac", "avg_launch_us")}}
+                               for r in lc_recs]
     print(json.dumps(head))
     return 0
 
