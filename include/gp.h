@@ -157,9 +157,10 @@ gp_status gp_plan_work_lists(const gp_plan *plan, int32_t d, gp_dtype dtype, int
  *            memory too and the streamed schedule is used).  Host memory should be
  *            PINNED: the link then runs at its rate.  Ordinary (pageable) host
  *            memory is accepted when ldx = ldo = d and the HBM budget holds whole
- *            rows; its copies are staged by the runtime, at a fraction of the rate
- *            (GP_ERR_UNSUPPORTED otherwise).  It is the way to run operands larger
- *            than the pinned memory a machine grants.
+ *            rows (GP_ERR_UNSUPPORTED otherwise): it moves through a ring of pinned
+ *            buffers (512 MiB, kept with the plan) filled and emptied by host
+ *            threads of the library.  It is the way to run operands larger than
+ *            the pinned memory a machine grants.
  *  d         feature columns, >= 1.
  *  dtype     GP_F32, or GP_BF16 storage (accumulation is always fp32; a stored
  *            bf16 value is the fp32 accumulator rounded to nearest even).

@@ -15,7 +15,9 @@
 // side stream while the previous block is being computed -- or sent just once and
 // kept, when the budget has room for all of them.
 #include <algorithm>
+#include <condition_variable>
 #include <cstring>
+#include <deque>
 #include <thread>
 
 #include "gp_internal.h"
@@ -101,6 +103,169 @@ struct StreamSchedule {
     }
 };
 
+// Ordinary (pageable) host memory cannot be the end of an asynchronous copy, and left to
+// the runtime its copies are staged one after the other with the enqueuing thread waiting.
+// The stager moves such operands through a ring of pinned buffers instead: on the way in,
+// host threads fill one buffer while the one before it is on the link; on the way out, a
+// drain thread waits for each buffer's copy to land and host threads empty it into the
+// caller's memory while the next buffers are on the link.  One stager per plan, kept
+// between calls.
+class Stager {
+public:
+    static constexpr int kInSlots = 2, kOutSlots = 6;
+    static constexpr size_t kSlotBytes = (size_t)64 << 20;
+
+    ~Stager()
+    {
+        stop();
+        for (int i = 0; i < kInSlots + kOutSlots; ++i) {
+            if (ev_[i]) (void)hipEventDestroy(ev_[i]);
+            if (buf_[i]) (void)hipHostFree(buf_[i]);
+        }
+    }
+    gp_status init(int device)
+    {
+        device_ = device;
+        for (int i = 0; i < kInSlots + kOutSlots; ++i) {
+            hipError_t e = hipHostMalloc(&buf_[i], kSlotBytes, hipHostMallocDefault);
+            if (e != hipSuccess) return fail(GP_ERR_OOM_HOST, "pinned staging buffers: %s", hipGetErrorString(e));
+            GP_HIP(hipEventCreateWithFlags(&ev_[i], hipEventDisableTiming));
+        }
+        worker_ = std::thread([this] { drain(); });
+        return GP_OK;
+    }
+    // host (pageable) -> device, in order on `stream`; returns when the last piece is enqueued
+    gp_status upload(void* dst, const void* src, size_t bytes, hipStream_t stream)
+    {
+        for (size_t off = 0, i = 0; off < bytes; off += kSlotBytes, ++i) {
+            const int s = (int)(i % kInSlots);
+            const size_t n = std::min(kSlotBytes, bytes - off);
+            if (in_used_[s]) GP_HIP(hipEventSynchronize(ev_[s]));  // its last piece has left the buffer
+            copy_parallel(buf_[s], (const char*)src + off, n);
+            GP_HIP(hipMemcpyAsync((char*)dst + off, buf_[s], n, hipMemcpyHostToDevice, stream));
+            GP_HIP(hipEventRecord(ev_[s], stream));
+            in_used_[s] = true;
+        }
+        return GP_OK;
+    }
+    // device -> host (pageable), in order on `stream`; the drain thread finishes the job
+    gp_status download(void* dst, const void* src, size_t bytes, hipStream_t stream)
+    {
+        for (size_t off = 0; off < bytes; off += kSlotBytes) {
+            const size_t n = std::min(kSlotBytes, bytes - off);
+            int s = -1;
+            {
+                std::unique_lock<std::mutex> lk(mu_);
+                cv_.wait(lk, [&] { return failed_ || !free_.empty(); });
+                if (failed_) return fail(GP_ERR_DEVICE, "staging thread: %s", error_.c_str());
+                s = free_.front();
+                free_.pop_front();
+            }
+            hipError_t e = hipMemcpyAsync(buf_[s], (const char*)src + off, n, hipMemcpyDeviceToHost, stream);
+            if (e == hipSuccess) e = hipEventRecord(ev_[s], stream);
+            if (e != hipSuccess) {
+                std::lock_guard<std::mutex> lk(mu_);
+                free_.push_back(s);
+                return fail(GP_ERR_DEVICE, "staged copy to the host: %s", hipGetErrorString(e));
+            }
+            std::lock_guard<std::mutex> lk(mu_);
+            jobs_.push_back(Job{s, (char*)dst + off, n});
+            cv_.notify_all();
+        }
+        return GP_OK;
+    }
+    // waits until every download has reached the caller's memory
+    gp_status finish()
+    {
+        std::unique_lock<std::mutex> lk(mu_);
+        cv_.wait(lk, [&] { return failed_ || (jobs_.empty() && !busy_); });
+        for (bool& u : in_used_) u = false;
+        if (failed_) {
+            const gp_status st = fail(GP_ERR_DEVICE, "staging thread: %s", error_.c_str());
+            failed_ = false;  // the next call starts clean (its streams are synchronised by then)
+            jobs_.clear();
+            free_.clear();
+            for (int i = kInSlots; i < kInSlots + kOutSlots; ++i) free_.push_back(i);
+            return st;
+        }
+        return GP_OK;
+    }
+
+private:
+    struct Job {
+        int slot;
+        char* dst;
+        size_t bytes;
+    };
+    static void copy_parallel(void* dst, const void* src, size_t n)
+    {
+        const int nt = n < ((size_t)4 << 20) ? 1 : std::min(8, host_threads());
+        parallel_run(nt, [&](int t, int k) {
+            const size_t lo = n * (size_t)t / (size_t)k, hi = n * (size_t)(t + 1) / (size_t)k;
+            std::memcpy((char*)dst + lo, (const char*)src + lo, hi - lo);
+        });
+    }
+    void drain()
+    {
+        (void)hipSetDevice(device_);
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            for (int i = kInSlots; i < kInSlots + kOutSlots; ++i) free_.push_back(i);
+            cv_.notify_all();
+        }
+        for (;;) {
+            Job j;
+            {
+                std::unique_lock<std::mutex> lk(mu_);
+                cv_.wait(lk, [&] { return quit_ || !jobs_.empty(); });
+                if (jobs_.empty()) return;  // quit_ and nothing left
+                j = jobs_.front();
+                jobs_.pop_front();
+                busy_ = true;
+            }
+            hipError_t e = hipEventSynchronize(ev_[j.slot]);
+            if (e == hipSuccess) {
+                try {
+                    copy_parallel(j.dst, buf_[j.slot], j.bytes);
+                } catch (const std::exception& ex) {
+                    std::lock_guard<std::mutex> lk(mu_);
+                    failed_ = true;
+                    error_ = ex.what();
+                }
+            }
+            std::lock_guard<std::mutex> lk(mu_);
+            if (e != hipSuccess) {
+                failed_ = true;
+                error_ = hipGetErrorString(e);
+            }
+            free_.push_back(j.slot);
+            busy_ = false;
+            cv_.notify_all();
+        }
+    }
+    void stop()
+    {
+        {
+            std::lock_guard<std::mutex> lk(mu_);
+            quit_ = true;
+            cv_.notify_all();
+        }
+        if (worker_.joinable()) worker_.join();
+    }
+
+    int device_ = 0;
+    void* buf_[kInSlots + kOutSlots] = {};
+    hipEvent_t ev_[kInSlots + kOutSlots] = {};
+    bool in_used_[kInSlots] = {};
+    std::mutex mu_;
+    std::condition_variable cv_;
+    std::deque<int> free_;
+    std::deque<Job> jobs_;
+    bool busy_ = false, quit_ = false, failed_ = false;
+    std::string error_;
+    std::thread worker_;
+};
+
 // Everything a streamed call needs besides the caller's operands, kept with the plan
 // from one call to the next: the schedule, three streams and their events, and the
 // device buffers (norm vectors, cut rows, partial rows, cursors, two column slabs, the
@@ -125,6 +290,7 @@ struct StreamedState {
     char* d_slab[2] = {nullptr, nullptr};
     std::vector<int32_t*> d_col;
     std::vector<Segment*> d_segs;
+    Stager* stager = nullptr;  // made by the first call with operands in pageable memory
 
     ~StreamedState()
     {
@@ -142,6 +308,7 @@ struct StreamedState {
         if (cmp) (void)hipStreamDestroy(cmp);
         if (out) (void)hipStreamDestroy(out);
         if (sched.pinned_segs) (void)hipHostFree(sched.pinned_segs);
+        delete stager;
         if (switched) (void)hipSetDevice(cur);
     }
     gp_status init_streams(int block_buffers)
@@ -202,9 +369,13 @@ gp_status ensure_pinned_col(const gp_plan* plan)
 constexpr int kLinkCopyBlocks = 16;
 constexpr int64_t kMinRowsPerCopy = 4096;  // a finished row range smaller than this waits for the next block
 gp_status move_rows(void* dst, int64_t ldd, const void* src, int64_t lds, int64_t n, int32_t wc, gp_dtype dtype,
-                    hipMemcpyKind kind, hipStream_t stream)
+                    hipMemcpyKind kind, hipStream_t stream, Stager* stager = nullptr)
 {
     const int es = dtype == GP_F32 ? 4 : 2;
+    if (stager) {  // the host side is pageable memory (contiguous runs only: the caller has checked)
+        const size_t bytes = (size_t)n * wc * es;
+        return kind == hipMemcpyHostToDevice ? stager->upload(dst, src, bytes, stream) : stager->download(dst, src, bytes, stream);
+    }
     if (ldd == wc && lds == wc) {
         GP_HIP(hipMemcpyAsync(dst, src, (size_t)n * wc * es, kind, stream));
         return GP_OK;
@@ -381,14 +552,23 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
         S->blocks_stay = nbuf >= C.b;
         S->blocks_loaded = false;
     }
-    // Ordinary host memory cannot be read or written by a kernel and its copies are staged by
-    // the runtime (slower, and the enqueuing thread waits for them): accepted where every
-    // transfer is one contiguous run, i.e. whole rows of operands without row padding.
+    // Ordinary host memory cannot be read or written by a kernel; it goes through the plan's
+    // pinned staging ring.  Accepted where every transfer is one contiguous run, i.e. whole
+    // rows of operands without row padding.
     if (pageable && (w < d || ldx != d || ldo != d))
         return fail(GP_ERR_UNSUPPORTED,
                     "operands in pageable host memory need contiguous rows (ldx = ldo = d) and an HBM budget that holds "
                     "whole rows (slab width %lld of %d columns); use pinned host memory",
                     (long long)w, d);
+    if (pageable && !S->stager) {
+        S->stager = new Stager();
+        if ((st = S->stager->init(cur)) != GP_OK) {
+            delete S->stager;
+            S->stager = nullptr;
+            return st;
+        }
+    }
+    Stager* const stager = pageable ? S->stager : nullptr;
     const StreamSchedule& C = S->sched;
     const int32_t b = C.b;
     const bool blocks_stay = S->blocks_stay;
@@ -423,22 +603,25 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
     struct Joiner {
         std::vector<std::thread>& v;
         StreamedState* S;
+        Stager* stager;
         ~Joiner()
         {
             // whatever way the call ends, nothing of it is still running afterwards
             (void)hipStreamSynchronize(S->in);
             (void)hipStreamSynchronize(S->cmp);
             (void)hipStreamSynchronize(S->out);
+            if (stager) (void)stager->finish();
             for (auto& t : v)
                 if (t.joinable()) t.join();
         }
-    } joiner{copiers, S};
+    } joiner{copiers, S, stager};
 
     for (int64_t c0 = 0; c0 < d; c0 += w) {
         const int32_t wc = (int32_t)std::min<int64_t>(w, d - c0);
         // X[:, c0 : c0+wc] -> slab 0 (its previous content must have left first)
         if (out_used[0]) GP_HIP(hipStreamWaitEvent(S->cmp, S->out_done[0], 0));
-        if ((st = move_rows(d_slab[0], w, (const char*)X + c0 * es, ldx, n, wc, dtype, hipMemcpyHostToDevice, S->cmp)) != GP_OK)
+        if ((st = move_rows(d_slab[0], w, (const char*)X + c0 * es, ldx, n, wc, dtype, hipMemcpyHostToDevice, S->cmp, stager)) !=
+            GP_OK)
             return st;
         out_used[0] = false;  // nothing leaves from the slab that holds X
 
@@ -508,7 +691,7 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
                     GP_HIP(hipStreamWaitEvent(S->out, S->hop_done, 0));
                     if ((st = move_rows((char*)out + (int64_t)k * out_slab + (rows_done * ldo + c0) * es, ldo,
                                         d_slab[dst] + rows_done * w * es, w, rows_to - rows_done, wc, dtype,
-                                        hipMemcpyDeviceToHost, S->out)) != GP_OK)
+                                        hipMemcpyDeviceToHost, S->out, stager)) != GP_OK)
                         return st;
                     rows_done = rows_to;
                 }
@@ -521,7 +704,7 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
     GP_HIP(hipStreamSynchronize(S->in));
     GP_HIP(hipStreamSynchronize(S->cmp));
     GP_HIP(hipStreamSynchronize(S->out));
-    return GP_OK;
+    return stager ? stager->finish() : GP_OK;
 }
 
 }  // namespace gp
