@@ -47,6 +47,8 @@ _SIGNATURES = {
                                         _c.POINTER(_c.c_double)]),
     "gp_plan_work_lists": (_c.c_int, [_c.c_void_p, _c.c_int32, _c.c_int, _c.c_int32, _c.POINTER(_c.c_int32),
                                       _c.POINTER(_c.c_int32), _c.c_void_p, _c.c_void_p, _c.c_int64]),
+    "gp_plan_lds_schedule": (_c.c_int, [_c.c_void_p, _c.c_int32, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_int64),
+                                        _c.POINTER(_c.c_int32)] + [_c.c_void_p] * 6 + [_c.c_int64, _c.c_int64]),
     "gp_propagate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                 _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_plan_streamed_shape": (_c.c_int, [_c.c_void_p, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_int64)]),
@@ -234,6 +236,24 @@ class Plan:
             _check(lib().gp_plan_work_lists(self.handle, d, dtype, vec, ctypes.byref(S), ctypes.byref(elems),
                                             off.ctypes.data, recs.ctypes.data, recs.size), "gp_plan_work_lists")
         return S.value, elems.value, off, recs
+
+    def lds_schedule(self, order: int = 0):
+        """The LDS pass's schedule over the hot pieces, or None where it does not apply: dict with
+        conflict_free, group_cluster, group_id_off, group_steps (per group), rec_row, rec_slot
+        (64 per group) and ids (uint16 local source indices)."""
+        ng, ni, cf = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
+        _check(lib().gp_plan_lds_schedule(self.handle, order, ctypes.byref(ng), ctypes.byref(ni), ctypes.byref(cf),
+                                          None, None, None, None, None, None, 0, 0), "gp_plan_lds_schedule")
+        if ng.value == 0:
+            return None
+        G = ng.value
+        out = {"group_cluster": np.zeros(G, np.int32), "group_id_off": np.zeros(G, np.int64), "group_steps": np.zeros(G, np.int32),
+               "rec_row": np.zeros(G * 64, np.int32), "rec_slot": np.zeros(G * 64, np.int32), "ids": np.zeros(ni.value, np.uint16)}
+        _check(lib().gp_plan_lds_schedule(self.handle, order, ctypes.byref(ng), ctypes.byref(ni), ctypes.byref(cf),
+                                          *[out[k].ctypes.data for k in ("group_cluster", "group_id_off", "group_steps", "rec_row",
+                                                                         "rec_slot", "ids")], G, ni.value), "gp_plan_lds_schedule")
+        out["conflict_free"] = bool(cf.value)
+        return out
 
 
 def gp_plan_blocks(src, dst, n: int, block_budget_edges: int, flags: int) -> Plan:

@@ -138,6 +138,14 @@ gp_status gp_set_option(const char* name, int64_t value)
         options().split_records = value;
         return GP_OK;
     }
+    if (!strcmp(name, "lds_pass")) {
+        if (value < 0 || value > 3)
+            return fail(GP_ERR_INVALID_ARG,
+                        "lds_pass must be 0 (automatic), 1 (wherever possible), 2 (never) or 3 (wherever possible, reads in "
+                        "column-list order)");
+        options().lds_pass = value;
+        return GP_OK;
+    }
     if (!strcmp(name, "device_plan_chunk")) {
         if (value < 0 || value > (INT64_C(1) << 31) - 1) return fail(GP_ERR_INVALID_ARG, "device_plan_chunk must be 0 .. 2^31 - 1");
         options().device_plan_chunk = value;
@@ -166,6 +174,7 @@ int64_t gp_get_option(const char* name)
     if (!strcmp(name, "cache_schedule")) return options().cache_schedule;
     if (!strcmp(name, "device_plan_chunk")) return options().device_plan_chunk;
     if (!strcmp(name, "split_records")) return options().split_records;
+    if (!strcmp(name, "lds_pass")) return options().lds_pass;
     if (!strcmp(name, "lc_tile_rows")) return options().lc_tile_rows;
     if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
     return -1;

@@ -288,4 +288,279 @@ void build_split_schedule(const gp_plan& P, const RowClusters& C, SplitSchedule&
     }
 }
 
+namespace {
+
+// Lanes whose 16-byte LDS reads are served together.  A ds_read_b128 of a wavefront goes
+// through the LDS in four passes of 16 lanes, and two lanes of one pass that ask for
+// different rows of the same 16 banks cost an extra pass.  Which lanes share a pass was
+// measured with a two-lane probe on gfx950: lanes {0-3, 12-15, 20-27} and {4-11, 16-19,
+// 28-31} of each half of the wavefront.
+inline int lds_pass_of_lane(int l)
+{
+    const int h = l & 31;
+    const bool first = h < 4 || (h >= 12 && h < 16) || (h >= 20 && h < 28);
+    return ((l >> 5) << 1) | (first ? 0 : 1);
+}
+
+// The reads of the 16 records of one pass group, ordered so that every step asks for 16
+// different bank groups (row index mod 16).  Records and bank groups form a bipartite
+// multigraph (one edge per non-zero); padded with reads of zero rows until every record
+// and every bank group has `steps` edges it is regular, and a regular bipartite multigraph
+// is a sum of perfect matchings (Hall): each matching is one conflict-free step.
+struct PassGroup {
+    int32_t count[16][16];               // real reads of record j in bank group r still to place
+    std::vector<uint16_t> bucket[16];    // record j's local indices, sorted by bank group, column-list order inside one
+    int32_t next[16][16];                // position in bucket[j] of the next unplaced read of bank group r
+    int32_t len[16];
+
+    void load(int j, const int32_t* col, int32_t n, const int32_t* local)
+    {
+        len[j] = n;
+        int32_t start[17] = {0};
+        for (int r = 0; r < 16; ++r) count[j][r] = 0;
+        for (int32_t e = 0; e < n; ++e) ++count[j][local[col[e]] & 15];
+        for (int r = 0; r < 16; ++r) start[r + 1] = start[r] + count[j][r];
+        bucket[j].resize((size_t)n);
+        for (int r = 0; r < 16; ++r) next[j][r] = start[r];
+        int32_t fill[16];
+        for (int r = 0; r < 16; ++r) fill[r] = start[r];
+        for (int32_t e = 0; e < n; ++e) {
+            const uint16_t id = (uint16_t)local[col[e]];
+            bucket[j][(size_t)fill[id & 15]++] = id;
+        }
+    }
+    void clear(int j)
+    {
+        len[j] = 0;
+        bucket[j].clear();
+        for (int r = 0; r < 16; ++r) count[j][r] = next[j][r] = 0;
+    }
+    // fewest steps a conflict-free order needs
+    int32_t degree() const
+    {
+        int32_t m = 0;
+        for (int j = 0; j < 16; ++j) m = std::max(m, len[j]);
+        for (int r = 0; r < 16; ++r) {
+            int32_t c = 0;
+            for (int j = 0; j < 16; ++j) c += count[j][r];
+            m = std::max(m, c);
+        }
+        return m;
+    }
+    // emit(j, step, local index) for all 16 records and `steps` >= degree() steps
+    // (false if no matching was found: cannot happen for steps >= degree(), checked all the same)
+    template <class Emit>
+    bool schedule(int32_t steps, uint16_t zero_base, Emit emit)
+    {
+        int32_t w[16][16];  // reads of record j in bank group r still to place, padding included
+        int32_t row_need[16], col_need[16];
+        for (int r = 0; r < 16; ++r) col_need[r] = steps;
+        for (int j = 0; j < 16; ++j) {
+            row_need[j] = steps - len[j];
+            for (int r = 0; r < 16; ++r) {
+                w[j][r] = count[j][r];
+                col_need[r] -= count[j][r];
+            }
+        }
+        for (int j = 0, r = 0; j < 16 && r < 16;) {  // padding: any matrix with these margins will do
+            const int32_t c = std::min(row_need[j], col_need[r]);
+            w[j][r] += c;
+            row_need[j] -= c;
+            col_need[r] -= c;
+            if (row_need[j] == 0) ++j;
+            else ++r;
+        }
+        int rec_of[16], grp_of[16];  // the current matching
+        for (int i = 0; i < 16; ++i) rec_of[i] = grp_of[i] = -1;
+        for (int32_t done = 0; done < steps;) {
+            for (int j = 0; j < 16; ++j)
+                if (grp_of[j] < 0) {
+                    uint32_t seen = 0;
+                    if (!augment(j, w, rec_of, grp_of, seen)) return false;
+                }
+            int32_t c = steps - done;
+            for (int j = 0; j < 16; ++j) c = std::min(c, w[j][grp_of[j]]);
+            for (int j = 0; j < 16; ++j) {
+                const int r = grp_of[j];
+                for (int32_t t = 0; t < c; ++t) {
+                    uint16_t id = (uint16_t)(zero_base + r);
+                    if (count[j][r] > 0) {
+                        id = bucket[j][(size_t)next[j][r]++];
+                        --count[j][r];
+                    }
+                    emit(j, done + t, id);
+                }
+                w[j][r] -= c;
+                if (w[j][r] == 0) {
+                    rec_of[r] = -1;
+                    grp_of[j] = -1;
+                }
+            }
+            done += c;
+        }
+        return true;
+    }
+
+private:
+    static bool augment(int j, const int32_t (&w)[16][16], int (&rec_of)[16], int (&grp_of)[16], uint32_t& seen)
+    {
+        for (int r = 0; r < 16; ++r) {
+            if (w[j][r] <= 0 || (seen >> r & 1)) continue;
+            seen |= 1u << r;
+            if (rec_of[r] < 0 || augment(rec_of[r], w, rec_of, grp_of, seen)) {
+                rec_of[r] = j;
+                grp_of[j] = r;
+                return true;
+            }
+        }
+        return false;
+    }
+};
+
+}  // namespace
+
+// Groups of 64 hot records per cluster, longest first (every lane walks as many steps as
+// its group needs, so records of like length share a group), with their source indices
+// local to the cluster.  Two orders for a record's reads: the column list's, or (where the
+// padding it costs is acceptable) the conflict-free order of PassGroup.  Either way the
+// order is fixed by the schedule, so a record's sum repeats bit for bit.
+bool build_lds_schedule(const gp_plan& P, const RowClusters& C, const SplitSchedule& S, double max_padding, int order,
+                        LdsSchedule& out)
+{
+    const int64_t n = P.n;
+    const int32_t num = C.num;
+    const int64_t nhot = (int64_t)S.hot.size();
+    if (num <= 0 || nhot == 0) return false;
+    // hot records and rows per cluster
+    std::vector<int64_t> rec_off((size_t)num + 1, 0);
+    out.member_off.assign((size_t)num + 1, 0);
+    for (int64_t i = 0; i < n; ++i) ++out.member_off[(size_t)C.label[(size_t)i] + 1];
+    out.hot_edges = 0;
+    for (int64_t r = 0; r < nhot; ++r) {
+        ++rec_off[(size_t)C.label[(size_t)S.hot[(size_t)r].row] + 1];
+        out.hot_edges += S.hot[(size_t)r].len;
+    }
+    out.max_members = 0;
+    for (int32_t c = 0; c < num; ++c) {
+        if (rec_off[(size_t)c + 1] > 0) out.max_members = (int32_t)std::max<int64_t>(out.max_members, out.member_off[(size_t)c + 1]);
+        if (rec_off[(size_t)c + 1] > 0 && out.member_off[(size_t)c + 1] > kLdsMaxMembers) return false;
+        out.member_off[(size_t)c + 1] += out.member_off[(size_t)c];
+        rec_off[(size_t)c + 1] += rec_off[(size_t)c];
+    }
+    out.members.resize((size_t)n);
+    std::vector<int32_t> local((size_t)n);
+    {
+        std::vector<int64_t> fill(out.member_off.begin(), out.member_off.end() - 1);
+        for (int64_t i = 0; i < n; ++i) {
+            const int32_t c = C.label[(size_t)i];
+            local[(size_t)i] = (int32_t)(fill[(size_t)c] - out.member_off[(size_t)c]);
+            out.members[(size_t)fill[(size_t)c]++] = (int32_t)i;
+        }
+    }
+    std::vector<int64_t> recs((size_t)nhot);
+    {
+        std::vector<int64_t> fill(rec_off.begin(), rec_off.end() - 1);
+        for (int64_t r = 0; r < nhot; ++r) recs[(size_t)fill[(size_t)C.label[(size_t)S.hot[(size_t)r].row]]++] = r;
+    }
+    const int nt = S.col.size() < (1u << 16) ? 1 : host_threads();
+    parallel_run(nt, [&](int t, int k) {
+        for (int32_t c = (int32_t)((int64_t)num * t / k); c < (int32_t)((int64_t)num * (t + 1) / k); ++c)
+            std::stable_sort(recs.begin() + rec_off[(size_t)c], recs.begin() + rec_off[(size_t)c + 1],
+                             [&](int64_t a, int64_t b) { return S.hot[(size_t)a].len > S.hot[(size_t)b].len; });
+    });
+    // groups: cluster c owns records recs[rec_off[c] ...], 64 to a group
+    out.group_off.assign((size_t)num + 1, 0);
+    std::vector<int32_t> group_cluster;
+    for (int32_t c = 0; c < num; ++c) {
+        const int64_t g = (rec_off[(size_t)c + 1] - rec_off[(size_t)c] + 63) / 64;
+        if ((int64_t)group_cluster.size() + g > INT32_MAX) return false;
+        group_cluster.insert(group_cluster.end(), (size_t)g, c);
+        out.group_off[(size_t)c + 1] = (int32_t)group_cluster.size();
+    }
+    const int64_t ngroups = (int64_t)group_cluster.size();
+    auto record_of = [&](int64_t g, int lane) -> const Segment* {
+        const int32_t c = group_cluster[(size_t)g];
+        const int64_t r = rec_off[(size_t)c] + 64 * (g - out.group_off[(size_t)c]) + lane;
+        return r < rec_off[(size_t)c + 1] ? &S.hot[(size_t)recs[(size_t)r]] : nullptr;
+    };
+    auto load_pass = [&](PassGroup& pg, int64_t g, int pass, int (&lanes)[16]) {
+        int k = 0;
+        for (int l = 0; l < 64; ++l)
+            if (lds_pass_of_lane(l) == pass) lanes[k++] = l;
+        for (int j = 0; j < 16; ++j) {
+            const Segment* q = record_of(g, lanes[j]);
+            if (q) pg.load(j, S.col.data() + (((int64_t)q->start_hi << 32) | q->start_lo), q->len, local.data());
+            else pg.clear(j);
+        }
+    };
+    // steps per group in either order
+    std::vector<int32_t> steps_plain((size_t)ngroups), steps_free((size_t)ngroups, 0);
+    parallel_run(nt, [&](int t, int k) {
+        PassGroup pg;
+        int lanes[16];
+        for (int64_t g = ngroups * t / k; g < ngroups * (t + 1) / k; ++g) {
+            steps_plain[(size_t)g] = (record_of(g, 0)->len + 7) / 8 * 8;
+            if (order == 1) continue;
+            int32_t need = 0;
+            for (int pass = 0; pass < 4; ++pass) {
+                load_pass(pg, g, pass, lanes);
+                need = std::max(need, pg.degree());
+            }
+            steps_free[(size_t)g] = (need + 7) / 8 * 8;
+        }
+    });
+    int64_t total_plain = 0, total_free = 0;
+    for (int64_t g = 0; g < ngroups; ++g) {
+        total_plain += 64 * (int64_t)steps_plain[(size_t)g];
+        total_free += 64 * (int64_t)steps_free[(size_t)g];
+    }
+    const double allowed = (1.0 + max_padding) * (double)std::max<int64_t>(out.hot_edges, 1);
+    out.conflict_free = order == 2 || (order == 0 && (double)total_free <= allowed);
+    const std::vector<int32_t>& steps = out.conflict_free ? steps_free : steps_plain;
+    if ((double)(out.conflict_free ? total_free : total_plain) > allowed) return false;
+    out.groups.resize((size_t)ngroups);
+    int64_t id_total = 0;
+    for (int64_t g = 0; g < ngroups; ++g) {
+        out.groups[(size_t)g] = LdsGroup{id_total, steps[(size_t)g], 0};
+        id_total += 64 * (int64_t)steps[(size_t)g];
+    }
+    out.rec_row.assign((size_t)ngroups * 64, -1);
+    out.rec_slot.assign((size_t)ngroups * 64, -1);
+    out.ids.resize((size_t)id_total);
+    std::atomic<bool> ok{true};
+    parallel_run(nt, [&](int t, int k) {
+        PassGroup pg;
+        int lanes[16];
+        for (int64_t g = ngroups * t / k; g < ngroups * (t + 1) / k; ++g) {
+            const int32_t c = group_cluster[(size_t)g];
+            const int64_t m = out.member_off[(size_t)c + 1] - out.member_off[(size_t)c];
+            const uint16_t zero_base = (uint16_t)((m + 15) / 16 * 16);  // 16 zero rows, one per bank group
+            const LdsGroup& G = out.groups[(size_t)g];
+            auto slot_of = [&](int lane, int32_t step) -> uint16_t& {
+                return out.ids[(size_t)(G.id_off + (int64_t)(step / 8) * 512 + lane * 8 + step % 8)];
+            };
+            for (int l = 0; l < 64; ++l)
+                if (const Segment* q = record_of(g, l)) {
+                    out.rec_row[(size_t)g * 64 + l] = q->row;
+                    out.rec_slot[(size_t)g * 64 + l] = q->slot;
+                }
+            if (out.conflict_free) {
+                for (int pass = 0; pass < 4; ++pass) {
+                    load_pass(pg, g, pass, lanes);
+                    if (!pg.schedule(G.steps, zero_base, [&](int j, int32_t step, uint16_t id) { slot_of(lanes[j], step) = id; }))
+                        ok = false;
+                }
+            } else {
+                for (int l = 0; l < 64; ++l) {
+                    const Segment* q = record_of(g, l);
+                    const int32_t len = q ? q->len : 0;
+                    const int32_t* col = q ? S.col.data() + (((int64_t)q->start_hi << 32) | q->start_lo) : nullptr;
+                    for (int32_t s = 0; s < G.steps; ++s) slot_of(l, s) = s < len ? (uint16_t)local[(size_t)col[s]] : zero_base;
+                }
+            }
+        }
+    });
+    return ok;
+}
+
 }  // namespace gp

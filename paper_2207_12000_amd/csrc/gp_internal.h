@@ -34,6 +34,8 @@ struct Options {
     int64_t split_records = 0;   // explicit lists: 0 / 1 = hot and cold pieces in phases of their own, 2 = whole records
     int64_t lc_tile_rows = 0;  // 0 = chosen per call from the batch size
     int64_t hbm_budget_bytes = 0;
+    int64_t lds_pass = 0;        // hot pieces gathered from LDS where the clusters fit it: 0 = automatic, 1 = wherever possible
+                                 // (conflict-free order), 2 = never, 3 = wherever possible (column-list order)
     int64_t device_plan_chunk = 0;  // GP_PLAN_ON_DEVICE: most candidate entries sorted at once, 0 = 2^31 - 1
 };
 Options& options();
@@ -80,6 +82,7 @@ struct XcdWork {
     int64_t off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
 };
 
+struct LdsGroup;
 struct DevicePlan {
     int device = -1;
     int32_t* col = nullptr;
@@ -107,6 +110,13 @@ struct DevicePlan {
     float* split_carry = nullptr;
     int64_t split_carry_ld = 0;
     std::vector<Segment> split_hot_host;  // hot records in plan order (source of the per-XCD lists)
+    // LDS pass over the hot pieces: 0 = not looked at yet, 1 = ready, 2 = does not apply to this plan
+    int lds_state = 0;
+    int32_t *lds_members = nullptr, *lds_group_off = nullptr, *lds_rec_row = nullptr, *lds_rec_slot = nullptr;
+    int64_t* lds_member_off = nullptr;
+    LdsGroup* lds_groups = nullptr;
+    uint16_t* lds_ids = nullptr;
+    int32_t lds_max_members = 0;
     std::vector<void*> retired;  // buffers that were outgrown: freed with the plan, never while work may still use them
 };
 
@@ -161,6 +171,59 @@ struct SplitSchedule {
     int64_t num_slots = 0;
 };
 void build_split_schedule(const gp_plan& P, const RowClusters& C, SplitSchedule& out);
+
+// The hot pieces arranged for the LDS pass (gp_cluster.cpp builds it, gp_hot_lds.hip runs it): a
+// cluster's source rows are staged in LDS one strip of four fp32 columns at a time, and
+// its hot records, 64 to a group (one per lane, longest first), gather from there.
+constexpr int kLdsBytesPerCu = 160 * 1024;
+constexpr int kLdsMaxMembers = 10192;  // (rows rounded up to 16, + 16 zero rows) x 16 bytes and a few words must fit the LDS
+struct LdsGroup {
+    int64_t id_off;  // first of its steps x 64 local source indices; 8 consecutive steps of a lane lie together
+    int32_t steps;   // multiple of 8; shorter records are padded with reads of zero rows
+    int32_t pad;
+};
+struct LdsSchedule {
+    std::vector<int32_t> members;     // rows of cluster c, ascending: members[member_off[c] .. member_off[c+1])
+    std::vector<int64_t> member_off;  // num + 1
+    std::vector<int32_t> group_off;   // num + 1: groups of cluster c
+    std::vector<LdsGroup> groups;
+    std::vector<int32_t> rec_row, rec_slot;  // 64 per group: where lane l's sum goes (row -1: no record)
+    std::vector<uint16_t> ids;
+    int32_t max_members = 0;  // largest cluster that has hot records
+    int64_t hot_edges = 0;
+    bool conflict_free = false;  // reads ordered so that the lanes of one LDS pass hit different banks
+};
+// Rows a strip occupies in LDS for a cluster of m rows: the rows, rounded up to 16, and 16 zero
+// rows (one per bank group) that padding reads point at.
+constexpr double kLdsMaxPadding = 0.3;  // padding reads the automatic choice accepts, as a share of the hot non-zeros
+inline int64_t lds_rows(int64_t m) { return (m + 15) / 16 * 16 + 16; }
+// false (and `out` unspecified) where the pass does not apply: a cluster with hot records is
+// too large for the LDS, or padding would add more than `max_padding` of the hot non-zeros.
+// order: 0 = conflict-free if its padding is acceptable, else the column list's; 1 = the
+// column list's; 2 = conflict-free.
+bool build_lds_schedule(const gp_plan& P, const RowClusters& C, const SplitSchedule& S, double max_padding, int order,
+                        LdsSchedule& out);
+struct HotLdsArgs {
+    // DEVICE arrays of the schedule
+    const int32_t* members;
+    const int64_t* member_off;
+    const int32_t* group_off;
+    const LdsGroup* groups;
+    const int32_t *rec_row, *rec_slot;
+    const uint16_t* ids;
+    int32_t num_clusters, max_members;
+    const float* src_scale;  // DEVICE n weights applied to source rows, or nullptr
+    const float* row_scale;  // DEVICE n scales applied to rows stored whole, or nullptr
+    const float* xin;
+    int64_t ldin;
+    float* xout;
+    int64_t ldout;
+    float* carry;
+    int64_t carry_ld;
+    int32_t d;
+    unsigned long long* ctrl;  // as HopArgs::ctrl
+};
+gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream);
 // Slice shape of the explicit work lists for rows of d elements in vectors of `vec`
 // (element size es), or false if this plan keeps the implicit lists.
 bool choose_cache_schedule(const gp_plan* plan, int32_t d, int es, int vec, int& num_slices, int& slice_elems);

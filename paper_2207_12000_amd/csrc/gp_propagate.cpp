@@ -38,6 +38,9 @@ void release(DevicePlan& D)
     (void)hipFree(D.split_edge_ws);
     (void)hipFree(D.split_cold);
     (void)hipFree(D.split_rows);
+    for (void* q : {(void*)D.lds_members, (void*)D.lds_member_off, (void*)D.lds_group_off, (void*)D.lds_groups, (void*)D.lds_rec_row,
+                    (void*)D.lds_rec_slot, (void*)D.lds_ids})
+        (void)hipFree(q);
     (void)hipFree(D.split_carry);
     D = DevicePlan();
 }
@@ -178,21 +181,44 @@ gp_status upload_now(T*& dptr, const std::vector<T>& h, hipStream_t stream)
 
 // The split schedule on the device (plan->mu held): reordered column list, cold records,
 // the rows that own partial rows, and a partial-row buffer wide enough for d columns.
-gp_status ensure_split(const gp_plan* plan, int32_t d, bool want_edge_weights, hipStream_t stream)
+gp_status ensure_split(const gp_plan* plan, int32_t d, bool want_edge_weights, bool want_lds, hipStream_t stream)
 {
     DevicePlan& D = plan->dev;
     gp_status st;
-    if (!D.split_ready) {
+    if (plan->opt.lds_pass == 2) D.lds_state = 2;
+    if (!D.split_ready || (want_lds && D.lds_state == 0)) {
         SplitSchedule sch;
         build_split_schedule(*plan, plan->clusters, sch);
         if (sch.num_slots > INT32_MAX) return fail(GP_ERR_OVERFLOW, "%lld partial rows exceed int32", (long long)sch.num_slots);
-        if ((st = upload_now(D.split_col, sch.col, stream)) != GP_OK || (st = upload_now(D.split_cold, sch.cold, stream)) != GP_OK ||
-            (st = upload_now(D.split_rows, sch.split, stream)) != GP_OK)
-            return st;
-        D.split_num_cold = (int64_t)sch.cold.size();
-        D.split_num_rows = (int64_t)sch.split.size();
-        D.split_num_slots = sch.num_slots;
-        D.split_hot_host.swap(sch.hot);
+        if (!D.split_ready) {
+            if ((st = upload_now(D.split_col, sch.col, stream)) != GP_OK || (st = upload_now(D.split_cold, sch.cold, stream)) != GP_OK ||
+                (st = upload_now(D.split_rows, sch.split, stream)) != GP_OK)
+                return st;
+            D.split_num_cold = (int64_t)sch.cold.size();
+            D.split_num_rows = (int64_t)sch.split.size();
+            D.split_num_slots = sch.num_slots;
+        }
+        if (want_lds && D.lds_state == 0) {
+            // Padding of the record groups is work without result: beyond kLdsMaxPadding of the
+            // hot non-zeros the per-XCD lists are the better schedule (unless the pass is forced).
+            LdsSchedule L;
+            const bool forced = plan->opt.lds_pass == 1 || plan->opt.lds_pass == 3;
+            if (build_lds_schedule(*plan, plan->clusters, sch, forced ? 16.0 : kLdsMaxPadding,
+                                   plan->opt.lds_pass == 1 ? 2 : plan->opt.lds_pass == 3 ? 1 : 0, L)) {
+                if ((st = upload_now(D.lds_members, L.members, stream)) != GP_OK ||
+                    (st = upload_now(D.lds_member_off, L.member_off, stream)) != GP_OK ||
+                    (st = upload_now(D.lds_group_off, L.group_off, stream)) != GP_OK ||
+                    (st = upload_now(D.lds_groups, L.groups, stream)) != GP_OK ||
+                    (st = upload_now(D.lds_rec_row, L.rec_row, stream)) != GP_OK ||
+                    (st = upload_now(D.lds_rec_slot, L.rec_slot, stream)) != GP_OK || (st = upload_now(D.lds_ids, L.ids, stream)) != GP_OK)
+                    return st;
+                D.lds_max_members = L.max_members;
+                D.lds_state = 1;
+            } else {
+                D.lds_state = 2;
+            }
+        }
+        if (!D.split_ready) D.split_hot_host.swap(sch.hot);
         D.split_ready = true;
     }
     if (want_edge_weights && !D.split_edge_ws && plan->nnz > 0) {
@@ -215,9 +241,11 @@ gp_status ensure_split(const gp_plan* plan, int32_t d, bool want_edge_weights, h
 // (building and uploading them on first use of a slice shape).  *split comes back true
 // when the lists hold the hot pieces of the split schedule: the caller then runs the cold
 // records first and reads column ids, weights and partial rows from the split schedule.
-gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream, bool may_build = true, bool* split = nullptr)
+gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream, bool may_build = true, bool* split = nullptr,
+                            bool* lds = nullptr)
 {
     if (split) *split = false;
+    if (lds) *lds = false;
     const int es = a.dtype == GP_F32 ? 4 : 2;
     const int vec = hop_vector_width(a);
     // several column passes: implicit lists (explicit ones are cut for the whole row)
@@ -233,8 +261,14 @@ gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream,
     const bool want_split = split && may_build && plan->opt.split_records != 2 &&
                             (plan->opt.split_records == 1 || plan->clusters.inside_fraction < 0.98);
     if (want_split) {
-        gp_status st = ensure_split(plan, a.d, a.edge_w != nullptr, stream);
+        // the hot pieces can come out of LDS: fp32 rows of at least one strip, a plain hop
+        const bool want_lds = lds && a.dtype == GP_F32 && a.d >= 4 && !a.comb && a.xout && plan->opt.lds_pass != 2;
+        gp_status st = ensure_split(plan, a.d, a.edge_w != nullptr, want_lds, stream);
         if (st != GP_OK) return st;
+        if (want_lds && D.lds_state == 1) {
+            *split = *lds = true;
+            return GP_OK;
+        }
     }
     const XcdWork* found = nullptr;
     for (const XcdWork& w : D.work)
@@ -370,9 +404,9 @@ gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t
         a.column_slices = plan->opt.column_slices;
         a.persistent_blocks = plan->opt.persistent_blocks;
         a.column_tile = plan->opt.column_tile;
-        bool split = false;
+        bool split = false, lds = false;
         HopArgs cold = a;  // as it stands: implicit lists
-        if ((st = attach_work_lists(plan, a, stream, may_allocate, &split)) != GP_OK) return st;
+        if ((st = attach_work_lists(plan, a, stream, may_allocate, &split, &lds)) != GP_OK) return st;
         if (split) {
             // Records that gather outside their row's cluster first, whole rows wide: nothing of
             // theirs is worth keeping in a cache, and run on their own they evict nothing that is.
@@ -389,7 +423,34 @@ gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t
             cold.num_segs = D.split_num_cold;
             if (cold.num_segs > 0 && (st = hop_passes(cold, stream)) != GP_OK) return st;
         }
-        if ((st = hop_passes(a, stream)) != GP_OK) return st;
+        if (lds) {
+            HotLdsArgs h;
+            h.members = D.lds_members;
+            h.member_off = D.lds_member_off;
+            h.group_off = D.lds_group_off;
+            h.groups = D.lds_groups;
+            h.rec_row = D.lds_rec_row;
+            h.rec_slot = D.lds_rec_slot;
+            h.ids = D.lds_ids;
+            h.num_clusters = plan->clusters.num;
+            h.max_members = D.lds_max_members;
+            h.src_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : nullptr;
+            h.row_scale = row_scale;
+            h.xin = (const float*)a.xin;
+            h.ldin = a.ldin;
+            h.xout = (float*)a.xout;
+            h.ldout = a.ldout;
+            h.carry = D.split_carry;
+            h.carry_ld = D.split_carry_ld;
+            h.d = d;
+            h.ctrl = ctrl;
+            profile_begin("gp_hop_cluster_lds", stream);
+            st = launch_hot_lds(h, stream);
+            profile_end(stream);
+            if (st != GP_OK) return st;
+        } else if ((st = hop_passes(a, stream)) != GP_OK) {
+            return st;
+        }
         if (split ? D.split_num_rows > 0 : !plan->split.empty()) {
             FixupArgs f;
             f.split = split ? D.split_rows : D.split;
@@ -552,6 +613,46 @@ extern "C" gp_status gp_plan_work_lists(const gp_plan* plan, int32_t d, gp_dtype
         }
     } catch (const std::exception& e) {
         return fail(GP_ERR_OOM_HOST, "gp_plan_work_lists: %s", e.what());
+    }
+    return GP_OK;
+}
+
+extern "C" gp_status gp_plan_lds_schedule(const gp_plan* plan, int32_t order, int64_t* num_groups, int64_t* num_ids,
+                                          int32_t* conflict_free, int32_t* group_cluster, int64_t* group_id_off,
+                                          int32_t* group_steps, int32_t* rec_row, int32_t* rec_slot, uint16_t* ids,
+                                          int64_t group_capacity, int64_t id_capacity)
+{
+    if (!plan || !num_groups || !num_ids || !conflict_free) return fail(GP_ERR_INVALID_ARG, "NULL argument");
+    if (order < 0 || order > 2) return fail(GP_ERR_INVALID_ARG, "order must be 0, 1 or 2");
+    try {
+        std::lock_guard<std::mutex> lk(plan->mu);
+        *num_groups = *num_ids = 0;
+        *conflict_free = 0;
+        if (plan->segs.empty()) return GP_OK;
+        if (!plan->clusters.ready) cluster_rows(*plan, plan->clusters);
+        SplitSchedule sch;
+        build_split_schedule(*plan, plan->clusters, sch);
+        LdsSchedule L;
+        if (!build_lds_schedule(*plan, plan->clusters, sch, order == 0 ? kLdsMaxPadding : 16.0, order, L)) return GP_OK;
+        *num_groups = (int64_t)L.groups.size();
+        *num_ids = (int64_t)L.ids.size();
+        *conflict_free = L.conflict_free ? 1 : 0;
+        const bool want = group_cluster || group_id_off || group_steps || rec_row || rec_slot || ids;
+        if (!want) return GP_OK;
+        if (group_capacity < *num_groups || id_capacity < *num_ids)
+            return fail(GP_ERR_INVALID_ARG, "room for %lld groups and %lld ids, the schedule has %lld and %lld", (long long)group_capacity,
+                        (long long)id_capacity, (long long)*num_groups, (long long)*num_ids);
+        for (int32_t c = 0; c < plan->clusters.num; ++c)
+            for (int32_t g = L.group_off[(size_t)c]; g < L.group_off[(size_t)c + 1]; ++g) {
+                if (group_cluster) group_cluster[g] = c;
+                if (group_id_off) group_id_off[g] = L.groups[(size_t)g].id_off;
+                if (group_steps) group_steps[g] = L.groups[(size_t)g].steps;
+            }
+        if (rec_row) std::copy(L.rec_row.begin(), L.rec_row.end(), rec_row);
+        if (rec_slot) std::copy(L.rec_slot.begin(), L.rec_slot.end(), rec_slot);
+        if (ids) std::copy(L.ids.begin(), L.ids.end(), ids);
+    } catch (const std::exception& e) {
+        return fail(GP_ERR_OOM_HOST, "gp_plan_lds_schedule: %s", e.what());
     }
     return GP_OK;
 }

@@ -277,7 +277,7 @@ def test_many_hops_and_repeated_calls_on_one_plan():
 @pytest.fixture
 def _mapping_defaults():
     yield
-    for k in ("column_slices", "persistent_blocks", "cache_schedule", "segment_edges", "split_records"):
+    for k in ("column_slices", "persistent_blocks", "cache_schedule", "segment_edges", "split_records", "lds_pass"):
         gp.gp_set_option(k, 0)
 
 
@@ -318,3 +318,42 @@ def test_explicit_lists_match_the_oracle_and_the_implicit_bits(dtype, d, agg, sl
         assert np.array_equal(ref, got), f"config {cfg}"
         gp.gp_set_option("split_records", 1)           # hot and cold pieces: other partial sums, the oracle's bound holds
         parity_case(w, K=2, dtype=dtype, agg=agg, budget=20_000)
+
+
+def community_workload(n_comm, comm, pairs, d, seed):
+    """A small stochastic block model of the config-4 kind with communities of a chosen size."""
+    g = gp_synth.rng_for(seed, 0)
+    src, dst = gp_synth.sbm_pairs(n_comm, comm, pairs, 0.9, g)
+    X = gp_synth.features(n_comm * comm, d, "uniform", gp_synth.rng_for(seed, 1))
+    return gp_synth.Workload("sbm_test", n_comm * comm, d, 2, gp.GP_AGG_SUM, gp.GP_F32,
+                             gp_synth.SYMMETRISE | gp_synth.ADD_SELF_LOOPS, None, 4, src, dst, X)
+
+
+@pytest.mark.parametrize("d,agg", [(602, gp.GP_AGG_SUM), (100, gp.GP_AGG_MEAN), (37, gp.GP_AGG_SYM), (4, gp.GP_AGG_SYM),
+                                   (7, gp.GP_AGG_SUM)])
+@pytest.mark.parametrize("segment_edges,order", [(0, 1), (16, 1), (0, 3)])
+def test_lds_pass_matches_the_oracle(d, agg, segment_edges, order, _mapping_defaults):
+    """The hot pieces gathered from LDS, reads in conflict-free order (1) and in the column
+    list's (3), forced (with rows cut into short segments the automatic choice would decline
+    the padding): community graphs whose clusters take one
+    strip in half of a compute unit's LDS and more than half of it, column counts that
+    end in a partial strip, rows with and without partial-row slots, every operator.
+    A second call on the same plan's twin repeats the first bit for bit."""
+    cases = [gp_synth.make_workload(4, scale=0.004, d=d), gp_synth.make_workload(4, scale=0.04, d=d)]
+    if d <= 37:
+        cases.append(community_workload(3, 6000, 400_000, d, 77))    # clusters beyond half the LDS: one workgroup per unit
+    for w in cases:
+        gp.gp_set_option("segment_edges", segment_edges)
+        gp.gp_set_option("cache_schedule", 1)
+        gp.gp_set_option("split_records", 1)
+        gp.gp_set_option("lds_pass", order)
+        budget = max(20_000, w.m // 3)
+        gp.gp_profile_enable(True)
+        try:
+            a = parity_case(w, K=2, dtype=gp.GP_F32, agg=agg, budget=budget)
+            b = parity_case(w, K=2, dtype=gp.GP_F32, agg=agg, budget=budget)
+            launches, _ = gp.gp_profile_read("gp_hop_cluster_lds")
+        finally:
+            gp.gp_profile_enable(False)
+        assert launches == 4, f"{w.name} n {w.n}: the LDS pass ran {launches} times, expected once per hop"
+        assert np.array_equal(a, b)
