@@ -36,6 +36,7 @@ OUT = os.path.join(os.environ.get("TMPDIR", "/tmp"), "gp_counters")   # raw rocp
 PROFILES = os.path.join(ROOT, "profiles")
 NAMES = {1: "config1_tiny", 2: "config2_chunglu_arxiv_like", 3: "config3_chunglu_mean_d100", 4: "config4_sbm_sum_d602"}
 PMC_SETS = ["FETCH_SIZE", "WRITE_SIZE", "TCC_HIT_sum TCC_MISS_sum", "MeanOccupancyPerCU"]
+HOP_KERNELS = ("gp_hop_segments", "gp_hop_cluster_lds")   # a hop's launches: the figures below are means over all of them
 
 
 def run(cmd, log, limit):
@@ -61,7 +62,11 @@ def per_kernel_means(csv_path):
     per = collections.defaultdict(list)
     for d, c in acc.items():
         per[kn[d]].append(c)
-    return {k: {c: sum(x[c] for x in v) / len(v) for c in v[0]} for k, v in per.items()}
+    out = {k: {c: sum(x[c] for x in v) / len(v) for c in v[0]} for k, v in per.items()}
+    hop = [c for k in HOP_KERNELS for c in per.get(k, [])]
+    if hop:
+        out["hop launches together"] = {c: sum(x[c] for x in hop) / len(hop) for c in hop[0]}
+    return out
 
 
 def main() -> int:
@@ -116,16 +121,14 @@ def main() -> int:
             a["min"] = int(s["MinNs"]) if a["min"] is None else min(a["min"], int(s["MinNs"]))
             a["max"] = int(s["MaxNs"]) if a["max"] is None else max(a["max"], int(s["MaxNs"]))
             a["kinds"] += 1
-        hop_avg_ns = None
         for k, a in agg.items():
             note = f" ({a['kinds']} instantiations)" if a["kinds"] > 1 else ""
             lines.append(f"| {k}{note} | {a['calls']} | {a['total'] / a['calls']:.0f} | {a['pct']:.2f} | {a['min']} | {a['max']} |")
-            if k == "gp_hop_segments":
-                hop_avg_ns = a["total"] / a["calls"]
+        hop_avg_ns = sum(agg[k]["total"] for k in HOP_KERNELS if k in agg) / sum(agg[k]["calls"] for k in HOP_KERNELS if k in agg)
         rl = rec["roofline"]
         if rl["launches_per_hop"] > 1:
-            lines += ["", f"A hop is {rl['launches_per_hop']} launches of the hop kernel here; every per-launch figure below is the mean "
-                          f"over all of them, a hop is {rl['launches_per_hop']} times that."]
+            lines += ["", f"A hop is {rl['launches_per_hop']} launches here ({rl['kernel']}); every per-launch figure below is the mean "
+                          f"over all of them ({hop_avg_ns:.0f} ns in the table above), a hop is {rl['launches_per_hop']} times that."]
         lines += ["", f"bench.py in the same run: {rec['value']} GEFU/s, {rec['ms_per_step']} ms per step; hop kernel timed with HIP "
                       f"events inside bench.py: {rl['avg_launch_us']} us per launch (rocprofv3 average above: {hop_avg_ns / 1e3:.1f} us).",
                   f"Algorithmic bytes per launch {rl['algorithmic_bytes_per_launch']} -> {rl['achieved']} GB/s = {rl['frac']} of the "
@@ -148,7 +151,7 @@ def main() -> int:
             shutil.rmtree(d, ignore_errors=True)
         n, dd = rec["config"]["n"], rec["config"]["d"]
         copy_kib = n * dd * 4 / 1024.0
-        cp, hop = means.get("gp_copy_rows", {}), means["gp_hop_segments"]
+        cp, hop = means.get("gp_copy_rows", {}), means["hop launches together"]
         f_fetch = copy_kib / cp["FETCH_SIZE"] if cp.get("FETCH_SIZE") else 2.0
         f_write = copy_kib / cp["WRITE_SIZE"] if cp.get("WRITE_SIZE") else 1.0
         fetch_b = hop["FETCH_SIZE"] * f_fetch * 1024
@@ -162,10 +165,10 @@ def main() -> int:
                   f"WRITE_SIZE reads {cp.get('WRITE_SIZE', float('nan')):.1f} -> factor {f_write:.4f}.", "",
                   "| kernel | FETCH_SIZE (KiB) | WRITE_SIZE (KiB) | TCC_HIT_sum | TCC_MISS_sum | MeanOccupancyPerCU |", "|---|---|---|---|---|---|"]
         for k, v in sorted(means.items()):
-            if k.startswith("gp_"):
+            if k.startswith("gp_") or k.startswith("hop "):
                 lines.append(f"| {k} | {v.get('FETCH_SIZE', 0):.1f} | {v.get('WRITE_SIZE', 0):.1f} | {v.get('TCC_HIT_sum', 0):.0f} | "
                              f"{v.get('TCC_MISS_sum', 0):.0f} | {v.get('MeanOccupancyPerCU', 0):.1f} |")
-        lines += ["", f"Hop kernel, scaled: fetch {fetch_b / 1e9:.4f} GB + write {write_b / 1e9:.4f} GB = **{total / 1e9:.4f} GB per launch** "
+        lines += ["", f"Hop launches, scaled: fetch {fetch_b / 1e9:.4f} GB + write {write_b / 1e9:.4f} GB = **{total / 1e9:.4f} GB per launch** "
                       f"({total / (hop_avg_ns * 1e-9) / 1e12:.2f} TB/s over the {hop_avg_ns / 1e3:.1f} us launch).  Algorithmic (compulsory) bytes "
                       f"per launch: {alg / 1e9:.4f} GB; measured / algorithmic = {total / alg:.2f}.  All rows gathered: "
                       f"{rec['config']['nnz'] * dd * 4 / 1e9:.3f} GB per hop.  L2 hit rate over all requests (rows, ids, weights, "

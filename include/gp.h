@@ -388,6 +388,10 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
  *                     whose source lies in the row's cluster and the others; the others are
  *                     gathered first, whole rows wide, in a launch of their own, and the two
  *                     partial rows are joined by the fix-up; 2 = whole records.
+ *   "lds_pass"        fp32 hops with cut records: 0 = the in-cluster pieces are gathered from LDS
+ *                     where gp_plan_lds_schedule has a schedule for the plan; 1 = the same, with
+ *                     the conflict-free order whatever padding it costs; 3 = the same, with the
+ *                     column list's order; 2 = never (per-XCD work lists through the L2s).
  *   "device_plan_chunk"  GP_PLAN_ON_DEVICE: most candidate entries sorted at once
  *                     (1 .. 2^31 - 1; 0 = 2^31 - 1).  Read by gp_plan_blocks.
  *   "cache_schedule"  0 = explicit per-XCD work lists where the plan's row clusters
