@@ -100,7 +100,7 @@ def chung_lu_offset(n: int, draws: int, gamma: float, max_expected_degree: float
 
 
 def chung_lu_pairs(n: int, M: int, gamma: float, max_expected_degree: float,
-                   rng: np.random.Generator, chunk: int = 1 << 24):
+                   rng: np.random.Generator, chunk: int = 1 << 24, progress=None):
     """Chung-Lu style power-law graph: M pairs whose two endpoints are drawn
     independently with probability proportional to w_i; self pairs are kept
     (the planner drops them) and duplicates may occur (the planner collapses
@@ -114,6 +114,8 @@ def chung_lu_pairs(n: int, M: int, gamma: float, max_expected_degree: float,
         e = min(M, s + chunk)
         src[s:e] = perm[_powerlaw_inverse_cdf(rng.random(e - s), n, a, i0)]
         dst[s:e] = perm[_powerlaw_inverse_cdf(rng.random(e - s), n, a, i0)]
+        if progress:
+            progress("pairs drawn", e, M)
     return src, dst
 
 
@@ -173,7 +175,7 @@ def features(n: int, d: int, dist: str, rng: np.random.Generator) -> np.ndarray:
     raise ValueError(dist)
 
 
-def fill_features(out: np.ndarray, dist: str, rng: np.random.Generator, chunk_rows: int = 1 << 18) -> None:
+def fill_features(out: np.ndarray, dist: str, rng: np.random.Generator, chunk_rows: int = 1 << 18, progress=None) -> None:
     """Draws features() row chunk by row chunk into `out` (float32, or uint16 for
     bf16 bit patterns), so that a matrix too large to hold twice can be generated
     in place (e.g. into pinned host memory).  Same stream, same numbers."""
@@ -181,6 +183,8 @@ def fill_features(out: np.ndarray, dist: str, rng: np.random.Generator, chunk_ro
     for r0 in range(0, n, chunk_rows):
         x = features(min(chunk_rows, n - r0), d, dist, rng)
         out[r0:r0 + x.shape[0]] = f32_to_bf16_bits(x) if out.dtype == np.uint16 else x
+        if progress:
+            progress("feature rows drawn", r0 + x.shape[0], n)
 
 
 # --------------------------------------------------------------------------
@@ -213,11 +217,13 @@ def _scaled(x: int, scale: float, lo: int = 1) -> int:
 
 
 def make_workload(config: int, scale: float = 1.0, d: Optional[int] = None,
-                  with_features: bool = True, contiguous_ids: bool = False) -> Workload:
+                  with_features: bool = True, contiguous_ids: bool = False, progress=None) -> Workload:
     """Workload `config` (1..5).  scale < 1 shrinks node and pair counts
     together (mean degree kept) for tests; scale = 1 is the full size.
     contiguous_ids (config 4 only) keeps every community's nodes on consecutive
-    ids instead of permuting them: the same graph with its locality given."""
+    ids instead of permuting them: the same graph with its locality given.
+    progress (config 5: minutes at full size): called as progress(what, done, total)
+    after every chunk of generated pairs."""
     seed = BASE_SEED + config
     g = rng_for(seed, 0)
     xr = rng_for(seed, 1)
@@ -251,7 +257,7 @@ def make_workload(config: int, scale: float = 1.0, d: Optional[int] = None,
         dist = "uniform"
     elif config == 5:
         n, M, dd, K = _scaled(111_059_956, scale, 8), _scaled(1_615_685_872, scale), d or 128, 3
-        src, dst = chung_lu_pairs(n, M, 2.1, min(1.0e5, n / 4), g)
+        src, dst = chung_lu_pairs(n, M, 2.1, min(1.0e5, n / 4), g, progress=progress)
         w = Workload("chunglu_papers_like_streamed", n, dd, K, AGG_SYM, BF16,
                      SYMMETRISE | ADD_SELF_LOOPS, _scaled(1 << 28, scale, 16), None,
                      src, dst, None, streamed=True)

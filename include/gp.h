@@ -152,7 +152,8 @@ int64_t gp_plan_segment_edges(const gp_plan *plan);           /* the segment len
  * their own and the partial rows joined afterwards.  Records (the in-cluster pieces of the
  * plan's segments) are taken 64 to a group, longest first inside a cluster; lane l of group
  * g serves row rec_row[64 g + l] (-1: none) and stores to partial-row slot rec_slot[64 g + l]
- * (-1: the output row).  Every lane of a group walks group_steps[g] (a multiple of 8) reads;
+ * (-1: the output row; s <= -2: the output row, after adding partial row -2 - s, which the
+ * launch over the out-of-cluster pieces wrote before).  Every lane of a group walks group_steps[g] (a multiple of 8) reads;
  * read t of lane l is ids[group_id_off[g] + (t / 8) * 512 + l * 8 + t % 8]: the position of
  * the source row among its cluster's rows in ascending order, or, for padding, one of 16
  * zero rows that follow them from the next multiple of 16.  order 2 (and order 0 where its

@@ -14,7 +14,7 @@ import numpy as np
 from .plan import ADD_SELF_LOOPS, SYMMETRISE, OracleError
 
 
-def neighbourhoods(src, dst, n: int, flags: int, rows, chunk: int = 1 << 26):
+def neighbourhoods(src, dst, n: int, flags: int, rows, chunk: int = 1 << 26, progress=None):
     """Returns (cols, deg): cols[t] = ascending distinct column ids of row rows[t];
     deg = dict node -> degree for every node in rows or in any cols[t]."""
     rows = np.asarray(rows, dtype=np.int64)
@@ -39,6 +39,8 @@ def neighbourhoods(src, dst, n: int, flags: int, rows, chunk: int = 1 << 26):
                 hit = lut[s] & ok                 # and its mirror (row j, col i)
                 rr.append(s[hit].astype(np.int64))
                 cc.append(t[hit].astype(np.int64))
+            if progress:
+                progress("pairs scanned", min(s0 + chunk, m), m)
         if loops:
             rr.append(targets.astype(np.int64))
             cc.append(targets.astype(np.int64))

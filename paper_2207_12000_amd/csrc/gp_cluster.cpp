@@ -527,6 +527,20 @@ bool build_lds_schedule(const gp_plan& P, const RowClusters& C, const SplitSched
     out.rec_row.assign((size_t)ngroups * 64, -1);
     out.rec_slot.assign((size_t)ngroups * 64, -1);
     out.ids.resize((size_t)id_total);
+    // A row made of exactly one hot and one cold piece needs no fix-up: the cold launch runs first, and
+    // the lane that has the hot sum adds the cold partial row and finishes the row (joins[row] = the cold
+    // piece's slot).  Other cut rows stay on the fix-up list.
+    std::vector<int32_t> joins((size_t)n, -1);
+    {
+        std::vector<uint8_t> hot_pieces((size_t)n, 0), cold_pieces((size_t)n, 0);
+        for (const Segment& q : S.hot) hot_pieces[(size_t)q.row] = (uint8_t)std::min(2, hot_pieces[(size_t)q.row] + 1);
+        for (const Segment& q : S.cold) cold_pieces[(size_t)q.row] = (uint8_t)std::min(2, cold_pieces[(size_t)q.row] + 1);
+        for (const Segment& q : S.cold)
+            if (hot_pieces[(size_t)q.row] == 1 && cold_pieces[(size_t)q.row] == 1) joins[(size_t)q.row] = q.slot;
+        out.fixup_rows.clear();
+        for (const SplitRow& r : S.split)
+            if (joins[(size_t)r.row] < 0) out.fixup_rows.push_back(r);
+    }
     std::atomic<bool> ok{true};
     parallel_run(nt, [&](int t, int k) {
         PassGroup pg;
@@ -542,7 +556,7 @@ bool build_lds_schedule(const gp_plan& P, const RowClusters& C, const SplitSched
             for (int l = 0; l < 64; ++l)
                 if (const Segment* q = record_of(g, l)) {
                     out.rec_row[(size_t)g * 64 + l] = q->row;
-                    out.rec_slot[(size_t)g * 64 + l] = q->slot;
+                    out.rec_slot[(size_t)g * 64 + l] = joins[(size_t)q->row] >= 0 ? -2 - joins[(size_t)q->row] : q->slot;
                 }
             if (out.conflict_free) {
                 for (int pass = 0; pass < 4; ++pass) {

@@ -15,8 +15,9 @@
 // take items from that XCD's cursor (ctrl[0..8)); ctrl[8] counts finished workgroups and
 // the last one zeroes all nine words, as in the segment kernel.
 //
-// Results: a record's sum goes where the record says (a partial-row slot, or the output
-// row scaled by row_scale); the fix-up pass joins partial rows as for any other launch.
+// Results: a record's sum goes where the record says: a partial-row slot (the fix-up pass
+// joins partial rows as for any other launch), or the output row scaled by row_scale,
+// after adding the one partial row the launch before this one left for it, if any.
 // Summation order per record is fixed by the schedule (eight interleaved chains), so
 // runs repeat bit for bit.
 #include "gp_internal.h"
@@ -70,6 +71,8 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
     extern __shared__ __align__(16) char lds_raw[];
     v4f_a16* lds = reinterpret_cast<v4f_a16*>(lds_raw);
     unsigned long long& next_item = *reinterpret_cast<unsigned long long*>(lds_raw + (size_t)lds_rows_max * 16);
+    // ... and the count of the item's record groups handed out so far (a wave's first group is its own number)
+    int& groups_taken = *reinterpret_cast<int*>(lds_raw + (size_t)lds_rows_max * 16 + 8);
 
     const int lane = threadIdx.x & (kLanes - 1);
     const int wave = threadIdx.x / kLanes, waves = blockDim.x / kLanes;
@@ -83,7 +86,10 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
 
     int64_t item = blockIdx.x >> 3;
     while (item < items) {
-        if (threadIdx.x == 0) next_item = (unsigned long long)wgs + atomicAdd(ctrl + xcd, 1ULL);
+        if (threadIdx.x == 0) {
+            next_item = (unsigned long long)wgs + atomicAdd(ctrl + xcd, 1ULL);
+            groups_taken = waves;
+        }
         const int64_t octet = (item >> 3) * 8 + xcd;
         const int c = (int)(octet / opc);
         const int strip = (int)(octet % opc) * 8 + (int)(item & 7);
@@ -121,7 +127,8 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
         __syncthreads();
         const int64_t following = (int64_t)next_item;
         if (valid) {
-            for (int g = g_lo + wave; g < g_hi; g += waves) {
+            // groups are listed longest first: handing them out one by one keeps the waves level to the end
+            for (int g = g_lo + wave; g < g_hi;) {
                 const LdsGroup G = groups[g];
                 // A lane's indices come kStepBlock (8, one 16-byte load) at a time.  Two register
                 // sets of kAhead such loads alternate: while one is worked through the other is in
@@ -166,12 +173,18 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
                 if (row >= 0) {
                     const int slot = rec_slot[(int64_t)g * kLanes + lane];
                     if (slot < 0) {
+                        // the whole row, or all of it but one partial row that an earlier launch left in its slot
+                        v4f_a16 total = sum;
+                        if (slot < -1) total += *reinterpret_cast<const v4f_a4*>(carry + (int64_t)(-2 - slot) * carry_ld + col0);
                         const float s = row_scale ? row_scale[row] : 1.0f;
-                        *reinterpret_cast<v4f_a4*>(xout + (int64_t)row * ldout + col0) = sum * s;
+                        *reinterpret_cast<v4f_a4*>(xout + (int64_t)row * ldout + col0) = total * s;
                     } else {
                         *reinterpret_cast<v4f_a4*>(carry + (int64_t)slot * carry_ld + col0) = sum;
                     }
                 }
+                int taken = 0;
+                if (lane == 0) taken = atomicAdd(&groups_taken, 1);
+                g = g_lo + __builtin_amdgcn_readfirstlane(taken);
             }
         }
         __syncthreads();  // every read of this strip is done before the next one is staged
@@ -195,7 +208,7 @@ gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
     if (a.max_members < 0 || a.max_members > kLdsMaxMembers)
         return fail(GP_ERR_INVALID_ARG, "LDS pass: a cluster of %d rows does not fit the LDS", a.max_members);
     if (a.carry && a.carry_ld < a.d) return fail(GP_ERR_INVALID_ARG, "LDS pass: partial rows narrower than d");
-    const size_t shm = (size_t)lds_rows(a.max_members) * 16 + 16;  // the rows and the item word
+    const size_t shm = (size_t)lds_rows(a.max_members) * 16 + 16;  // the rows, the item word and the group count
     // the kernel addresses its dynamic LDS from 0: true as long as it has no static LDS before it
     hipFuncAttributes attr;
     GP_HIP(hipFuncGetAttributes(&attr, (const void*)gp_hop_cluster_lds));

@@ -117,6 +117,8 @@ struct DevicePlan {
     LdsGroup* lds_groups = nullptr;
     uint16_t* lds_ids = nullptr;
     int32_t lds_max_members = 0;
+    SplitRow* lds_fixup_rows = nullptr;
+    int64_t lds_num_fixup_rows = 0;
     std::vector<void*> retired;  // buffers that were outgrown: freed with the plan, never while work may still use them
 };
 
@@ -187,7 +189,10 @@ struct LdsSchedule {
     std::vector<int64_t> member_off;  // num + 1
     std::vector<int32_t> group_off;   // num + 1: groups of cluster c
     std::vector<LdsGroup> groups;
-    std::vector<int32_t> rec_row, rec_slot;  // 64 per group: where lane l's sum goes (row -1: no record)
+    // 64 per group: where lane l's sum goes (row -1: no record).  slot >= 0: that partial row; -1: the
+    // output row; <= -2: the output row, after adding partial row -2 - slot (written by the cold launch)
+    std::vector<int32_t> rec_row, rec_slot;
+    std::vector<SplitRow> fixup_rows;  // the cut rows this pass does not finish itself
     std::vector<uint16_t> ids;
     int32_t max_members = 0;  // largest cluster that has hot records
     int64_t hot_edges = 0;

@@ -39,7 +39,7 @@ void release(DevicePlan& D)
     (void)hipFree(D.split_cold);
     (void)hipFree(D.split_rows);
     for (void* q : {(void*)D.lds_members, (void*)D.lds_member_off, (void*)D.lds_group_off, (void*)D.lds_groups, (void*)D.lds_rec_row,
-                    (void*)D.lds_rec_slot, (void*)D.lds_ids})
+                    (void*)D.lds_rec_slot, (void*)D.lds_ids, (void*)D.lds_fixup_rows})
         (void)hipFree(q);
     (void)hipFree(D.split_carry);
     D = DevicePlan();
@@ -210,8 +210,10 @@ gp_status ensure_split(const gp_plan* plan, int32_t d, bool want_edge_weights, b
                     (st = upload_now(D.lds_group_off, L.group_off, stream)) != GP_OK ||
                     (st = upload_now(D.lds_groups, L.groups, stream)) != GP_OK ||
                     (st = upload_now(D.lds_rec_row, L.rec_row, stream)) != GP_OK ||
-                    (st = upload_now(D.lds_rec_slot, L.rec_slot, stream)) != GP_OK || (st = upload_now(D.lds_ids, L.ids, stream)) != GP_OK)
+                    (st = upload_now(D.lds_rec_slot, L.rec_slot, stream)) != GP_OK || (st = upload_now(D.lds_ids, L.ids, stream)) != GP_OK ||
+                    (st = upload_now(D.lds_fixup_rows, L.fixup_rows, stream)) != GP_OK)
                     return st;
+                D.lds_num_fixup_rows = (int64_t)L.fixup_rows.size();
                 D.lds_max_members = L.max_members;
                 D.lds_state = 1;
             } else {
@@ -451,10 +453,11 @@ gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t
         } else if ((st = hop_passes(a, stream)) != GP_OK) {
             return st;
         }
-        if (split ? D.split_num_rows > 0 : !plan->split.empty()) {
+        // (the LDS launch finishes rows made of one hot and one cold piece itself)
+        if (lds ? D.lds_num_fixup_rows > 0 : split ? D.split_num_rows > 0 : !plan->split.empty()) {
             FixupArgs f;
-            f.split = split ? D.split_rows : D.split;
-            f.num_split = split ? D.split_num_rows : (int64_t)plan->split.size();
+            f.split = lds ? D.lds_fixup_rows : split ? D.split_rows : D.split;
+            f.num_split = lds ? D.lds_num_fixup_rows : split ? D.split_num_rows : (int64_t)plan->split.size();
             f.carry = split ? D.split_carry : carry;
             f.carry_ld = split ? D.split_carry_ld : carry_ld;
             f.row_scale = row_scale;

@@ -75,7 +75,7 @@ def test_full_size_whole_stack_elementwise(config, samples):
                              f"worst ratio {np.max(err / (bound + 1e-300)):.3g}"
             assert np.all(cur[bound == 0] == 0)
             print(f"config {config} hop {k}: all {cur.size} elements within 1e-5 * bound "
-                  f"(worst ratio {np.max(err / (bound + 1e-300)):.3g})", flush=True)
+                  f"(worst ratio {np.max(err / (bound + 1e-300)):.3g})")
             del err, ok
             want_r, bound_r = oracle.hop_rows(op, prev, w.agg, rows)
             err = np.abs(cur[rows].astype(np.float64) - want_r)
@@ -128,7 +128,28 @@ class _Pageable:
         self.buf = None
 
 
-def run_config5(scale, memory="pinned"):
+class Narrator:
+    """Progress lines of a test that works for minutes, printed past pytest's capture (a run
+    that says nothing for three minutes is taken for hung): what a step reports, at most
+    one line per 20 s per kind of step, plus the test's own result lines."""
+
+    def __init__(self, capsys):
+        self.capsys = capsys
+        self.last = {}
+
+    def say(self, text):
+        with self.capsys.disabled():
+            print(text, flush=True)
+
+    def step(self, what, done, total):
+        import time
+        now = time.time()
+        if done >= total or now - self.last.get(what, 0.0) >= 20.0:
+            self.last[what] = now
+            self.say(f"    ... {what}: {done} of {total}")
+
+
+def run_config5(scale, capsys, memory="pinned"):
     """The out-of-core workload (bf16 storage, sym, K = 3) through the streamed schedule
     from pinned host memory, X living in slab 0 of the stack.  Each hop is checked on
     sampled rows against the oracle applied to the library's own stored previous hop: one
@@ -142,19 +163,21 @@ def run_config5(scale, memory="pinned"):
     from hostmem import Pinned
     from oracle import sampled
     full_oracle = scale <= 0.3 and os.environ.get("GP_TEST_CONFIG5_ORACLE", "full") != "sampled"
+    tell = Narrator(capsys)
+    print = tell.say                         # this test's lines are its progress report
     t0 = time.time()
-    w = gp_synth.make_workload(5, scale=scale, with_features=False)
+    w = gp_synth.make_workload(5, scale=scale, with_features=False, progress=tell.step)
     mem = (Pinned if memory == "pinned" else _Pageable)((w.K + 1) * w.n * w.d * 2)
     try:
         stack = mem.array(np.uint16, (w.K + 1, w.n, w.d))
-        gp_synth.fill_features(stack[0], "normal", gp_synth.rng_for(gp_synth.BASE_SEED + 5, 1))
+        gp_synth.fill_features(stack[0], "normal", gp_synth.rng_for(gp_synth.BASE_SEED + 5, 1), progress=tell.step)
         x_first = stack[0, :4096].copy()
         print(f"config 5 scale {scale}: n {w.n}, pairs {w.m}, stack {mem.nbytes / 2**30:.1f} GiB {memory}, "
-              f"generated in {time.time() - t0:.0f} s", flush=True)
+              f"generated in {time.time() - t0:.0f} s")
         op = oracle.plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) if full_oracle else None
         t0 = time.time()
         with gp.gp_plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) as lp:
-            print(f"planned in {time.time() - t0:.0f} s: nnz {lp.nnz}, {lp.num_blocks} blocks", flush=True)
+            print(f"planned in {time.time() - t0:.0f} s: nnz {lp.nnz}, {lp.num_blocks} blocks")
             if full_oracle:
                 same_plan(lp, op)
                 # a budget that forces two column slabs and streams every edge block per hop and slab
@@ -176,10 +199,10 @@ def run_config5(scale, memory="pinned"):
                 gp.gp_set_hbm_budget_bytes(0)
             dt = time.time() - t0
             print(f"streamed propagate (first call, incl. pinned mirrors): {dt:.2f} s = "
-                  f"{lp.nnz * w.d * w.K / dt / 1e9:.0f} GEFU/s", flush=True)
+                  f"{lp.nnz * w.d * w.K / dt / 1e9:.0f} GEFU/s")
         assert np.array_equal(stack[0, :4096], x_first)
         if not full_oracle:
-            cols, deg = sampled.neighbourhoods(w.src, w.dst, w.n, w.flags, rows)
+            cols, deg = sampled.neighbourhoods(w.src, w.dst, w.n, w.flags, rows, progress=tell.step)
         for k in range(1, w.K + 1):
             prev = _Widened(stack[k - 1])
             if full_oracle:
@@ -191,19 +214,19 @@ def run_config5(scale, memory="pinned"):
             assert np.all(err <= 2.0 ** -8 * bound + 1e-30), \
                 f"hop {k}: worst ratio {np.max(err / (bound + 1e-300)):.3g} (allowed {2.0 ** -8:.3g})"
             print(f"config 5 hop {k}: {rows.size} sampled rows within 2^-8 * bound "
-                  f"(worst ratio {np.max(err / (bound + 1e-300)):.3g})", flush=True)
+                  f"(worst ratio {np.max(err / (bound + 1e-300)):.3g})")
     finally:
         stack = None
         mem.free()
 
 
-def test_config5_streamed_sampled_rows_every_hop():
+def test_config5_streamed_sampled_rows_every_hop(capsys):
     """Config 5 from pinned host memory, the fast path (see CONFIG5_DEFAULT_SCALE above;
     GP_TEST_CONFIG5_SCALE overrides, up to 0.54 on this machine)."""
-    run_config5(float(os.environ.get("GP_TEST_CONFIG5_SCALE", str(CONFIG5_DEFAULT_SCALE))))
+    run_config5(float(os.environ.get("GP_TEST_CONFIG5_SCALE", str(CONFIG5_DEFAULT_SCALE))), capsys)
 
 
-def test_config5_streamed_full_size():
+def test_config5_streamed_full_size(capsys):
     """Config 5 at its full size: 111,059,956 nodes, 1.6157 B pairs, 3.3 B non-zeros, bf16, K = 3.
     Pinned, it would need 119.9 GiB (1159 B per node) where the box grants 65.5 GiB, so the hop
     stack (105.9 GiB, X living in slab 0) is ordinary host memory, whose copies the runtime
@@ -211,4 +234,4 @@ def test_config5_streamed_full_size():
     every hop checked on sampled rows.  Needs about 180 GB of host memory."""
     if float(os.environ.get("GP_TEST_CONFIG5_FULL", "1")) == 0:
         pytest.skip("GP_TEST_CONFIG5_FULL=0")
-    run_config5(1.0, memory="pageable")
+    run_config5(1.0, capsys, memory="pageable")

@@ -68,6 +68,13 @@ def test_every_in_cluster_source_is_read_exactly_once(order, segment_edges, budg
             want = np.sort(src[label[src] == label[i]])
             have = np.sort(np.concatenate(got.get(i, [np.empty(0, np.int64)])))
             assert np.array_equal(want, have), f"row {i}"
+        # a row finished by the pass itself (slot <= -2: "add that partial row, store the row") is one record
+        # here, and the partial row it adds is none of the slots this pass writes
+        slot, row = sched["rec_slot"], sched["rec_row"]
+        joined = row[slot <= -2]
+        assert joined.size == np.unique(joined).size and (joined.size > 0 or segment_edges)   # short segments: hardly a row is two pieces
+        assert all(len(got[int(i)]) == 1 for i in joined)
+        assert not np.intersect1d(-2 - slot[slot <= -2], slot[slot >= 0]).size
 
 
 def test_conflict_free_order_never_puts_two_lanes_of_a_pass_on_one_bank():
