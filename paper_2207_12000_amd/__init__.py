@@ -47,8 +47,7 @@ _SIGNATURES = {
                                         _c.POINTER(_c.c_double)]),
     "gp_plan_work_lists": (_c.c_int, [_c.c_void_p, _c.c_int32, _c.c_int, _c.c_int32, _c.POINTER(_c.c_int32),
                                       _c.POINTER(_c.c_int32), _c.c_void_p, _c.c_void_p, _c.c_int64]),
-    "gp_plan_lds_schedule": (_c.c_int, [_c.c_void_p, _c.c_int32, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_int64),
-                                        _c.POINTER(_c.c_int32)] + [_c.c_void_p] * 6 + [_c.c_int64, _c.c_int64]),
+    "gp_plan_lds_schedule": (_c.c_int, [_c.c_void_p, _c.c_int32, _c.c_int32, _c.c_void_p]),
     "gp_propagate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int32, _c.c_int, _c.c_int, _c.c_int32,
                                 _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gp_plan_streamed_shape": (_c.c_int, [_c.c_void_p, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_int64)]),
@@ -237,23 +236,44 @@ class Plan:
                                             off.ctypes.data, recs.ctypes.data, recs.size), "gp_plan_work_lists")
         return S.value, elems.value, off, recs
 
-    def lds_schedule(self, order: int = 0):
-        """The LDS pass's schedule over the hot pieces, or None where it does not apply: dict with
-        conflict_free, group_cluster, group_id_off, group_steps (per group), rec_row, rec_slot
-        (64 per group) and ids (uint16 local source indices)."""
-        ng, ni, cf = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
-        _check(lib().gp_plan_lds_schedule(self.handle, order, ctypes.byref(ng), ctypes.byref(ni), ctypes.byref(cf),
-                                          None, None, None, None, None, None, 0, 0), "gp_plan_lds_schedule")
-        if ng.value == 0:
+    def lds_schedule(self, order: int = 0, d: int = 128):
+        """The LDS pass's schedule (see gp_plan_lds_schedule in gp.h), or None where it does not
+        apply: dict with hot_mode, conflict_free, group_set, group_id_off, group_steps (per
+        group), rec_pos (64 per group), ids (uint16 places on the set's list), list_of_set,
+        member_off, members, rest (segment records in position order), col (reordered)."""
+        v = LdsView()
+        _check(lib().gp_plan_lds_schedule(self.handle, d, order, ctypes.byref(v)), "gp_plan_lds_schedule")
+        if v.num_groups == 0:
             return None
-        G = ng.value
-        out = {"group_cluster": np.zeros(G, np.int32), "group_id_off": np.zeros(G, np.int64), "group_steps": np.zeros(G, np.int32),
-               "rec_row": np.zeros(G * 64, np.int32), "rec_slot": np.zeros(G * 64, np.int32), "ids": np.zeros(ni.value, np.uint16)}
-        _check(lib().gp_plan_lds_schedule(self.handle, order, ctypes.byref(ng), ctypes.byref(ni), ctypes.byref(cf),
-                                          *[out[k].ctypes.data for k in ("group_cluster", "group_id_off", "group_steps", "rec_row",
-                                                                         "rec_slot", "ids")], G, ni.value), "gp_plan_lds_schedule")
-        out["conflict_free"] = bool(cf.value)
+        G = v.num_groups
+        out = {"group_set": np.zeros(G, np.int32), "group_id_off": np.zeros(G, np.int64), "group_steps": np.zeros(G, np.int32),
+               "rec_pos": np.zeros(G * 64, np.int32), "ids": np.zeros(v.num_ids, np.uint16),
+               "list_of_set": np.zeros(v.num_sets, np.int32), "member_off": np.zeros(v.num_lists + 1, np.int64),
+               "members": np.zeros(v.num_members, np.int32), "rest": np.zeros(v.num_positions, self.SEGMENT_DTYPE),
+               "col": np.zeros(self.nnz, np.int32)}
+        v.group_capacity, v.id_capacity, v.member_capacity = G, v.num_ids, v.num_members
+        v.set_capacity = max(v.num_sets, v.num_lists + 1)
+        v.position_capacity = max(v.num_positions, self.nnz)
+        for k, a in out.items():
+            setattr(v, k, a.ctypes.data)
+        _check(lib().gp_plan_lds_schedule(self.handle, d, order, ctypes.byref(v)), "gp_plan_lds_schedule")
+        out["conflict_free"] = bool(v.conflict_free)
+        out["hot_mode"] = int(v.hot_mode)
         return out
+
+
+class LdsView(ctypes.Structure):
+    """gp_lds_view of gp.h."""
+    _fields_ = [("num_groups", ctypes.c_int64), ("num_ids", ctypes.c_int64), ("num_members", ctypes.c_int64),
+                ("num_positions", ctypes.c_int64),
+                ("num_sets", ctypes.c_int32), ("num_lists", ctypes.c_int32), ("conflict_free", ctypes.c_int32),
+                ("hot_mode", ctypes.c_int32),
+                ("group_capacity", ctypes.c_int64), ("id_capacity", ctypes.c_int64), ("set_capacity", ctypes.c_int64),
+                ("member_capacity", ctypes.c_int64), ("position_capacity", ctypes.c_int64),
+                ("group_set", ctypes.c_void_p), ("group_id_off", ctypes.c_void_p), ("group_steps", ctypes.c_void_p),
+                ("rec_pos", ctypes.c_void_p), ("ids", ctypes.c_void_p),
+                ("list_of_set", ctypes.c_void_p), ("member_off", ctypes.c_void_p), ("members", ctypes.c_void_p),
+                ("rest", ctypes.c_void_p), ("col", ctypes.c_void_p)]
 
 
 def gp_plan_blocks(src, dst, n: int, block_budget_edges: int, flags: int) -> Plan:

@@ -146,6 +146,11 @@ gp_status gp_set_option(const char* name, int64_t value)
         options().lds_pass = value;
         return GP_OK;
     }
+    if (!strcmp(name, "hub_pass")) {
+        if (value < 0 || value > 2) return fail(GP_ERR_INVALID_ARG, "hub_pass must be 0 (where it pays), 1 (always) or 2 (never)");
+        options().hub_pass = value;
+        return GP_OK;
+    }
     if (!strcmp(name, "device_plan_chunk")) {
         if (value < 0 || value > (INT64_C(1) << 31) - 1) return fail(GP_ERR_INVALID_ARG, "device_plan_chunk must be 0 .. 2^31 - 1");
         options().device_plan_chunk = value;
@@ -175,6 +180,7 @@ int64_t gp_get_option(const char* name)
     if (!strcmp(name, "device_plan_chunk")) return options().device_plan_chunk;
     if (!strcmp(name, "split_records")) return options().split_records;
     if (!strcmp(name, "lds_pass")) return options().lds_pass;
+    if (!strcmp(name, "hub_pass")) return options().hub_pass;
     if (!strcmp(name, "lc_tile_rows")) return options().lc_tile_rows;
     if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
     return -1;

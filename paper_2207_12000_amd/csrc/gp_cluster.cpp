@@ -233,25 +233,79 @@ void build_xcd_lists(const gp_plan& P, const std::vector<Segment>& segs, const R
 // list with every segment's range reordered that way (stable inside each part); a segment
 // with both kinds becomes a hot and a cold record, and a row that ends up with more than one
 // record owns consecutive partial-row slots in (segment, hot before cold) order.
-void build_split_schedule(const gp_plan& P, const RowClusters& C, SplitSchedule& out)
+HotSets hot_sets_from_clusters(const RowClusters& C)
+{
+    HotSets H;
+    H.num_sets = H.num_lists = C.num;
+    H.set_of_row = C.label;
+    H.list_of_row = C.label;
+    H.list_of_set.resize((size_t)C.num);
+    std::iota(H.list_of_set.begin(), H.list_of_set.end(), 0);
+    H.hot_fraction = C.inside_fraction;
+    return H;
+}
+
+// Popularity of a row = how many non-zeros have it as their source.  The `hubs` most popular
+// rows (ties to the smaller id) form the one list; rows are cut into sets of consecutive ids.
+HotSets hot_sets_from_hubs(const gp_plan& P, int32_t hubs, int64_t rows_per_set)
+{
+    HotSets H;
+    const int64_t n = P.n;
+    std::vector<int32_t> uses((size_t)n, 0);
+    for (int32_t j : P.col) ++uses[(size_t)j];
+    hubs = (int32_t)std::min<int64_t>(hubs, n);
+    std::vector<int32_t> order((size_t)n);
+    std::iota(order.begin(), order.end(), 0);
+    auto more_popular = [&](int32_t a, int32_t b) { return uses[(size_t)a] != uses[(size_t)b] ? uses[(size_t)a] > uses[(size_t)b] : a < b; };
+    if (hubs < n) std::nth_element(order.begin(), order.begin() + hubs, order.end(), more_popular);
+    H.list_of_row.assign((size_t)n, -1);
+    int64_t hot = 0;
+    for (int32_t k = 0; k < hubs; ++k) {
+        H.list_of_row[(size_t)order[(size_t)k]] = 0;
+        hot += uses[(size_t)order[(size_t)k]];
+    }
+    H.hot_fraction = P.nnz > 0 ? (double)hot / (double)P.nnz : 0.0;
+    H.num_lists = 1;
+    rows_per_set = std::max<int64_t>(rows_per_set, 64);
+    H.num_sets = (int32_t)std::max<int64_t>(1, (n + rows_per_set - 1) / rows_per_set);
+    H.list_of_set.assign((size_t)H.num_sets, 0);
+    H.set_of_row.resize((size_t)n);
+    for (int64_t i = 0; i < n; ++i) H.set_of_row[(size_t)i] = (int32_t)(i / rows_per_set);
+    return H;
+}
+
+namespace {
+
+// The column list with every segment's hot non-zeros moved to its front (stable on both
+// sides), and how many each segment has.
+void hot_first(const gp_plan& P, const HotSets& C, std::vector<int32_t>& col, std::vector<int32_t>& hot_len)
 {
     const int64_t nsegs = (int64_t)P.segs.size();
-    out.col.resize(P.col.size());
-    std::vector<int32_t> hot_len((size_t)nsegs);
+    col.resize(P.col.size());
+    hot_len.resize((size_t)nsegs);
     const int nt = P.nnz < (1 << 16) ? 1 : host_threads();
     parallel_run(nt, [&](int t, int k) {
         for (int64_t s = nsegs * t / k; s < nsegs * (t + 1) / k; ++s) {
             const Segment& g = P.segs[(size_t)s];
             const int64_t e0 = ((int64_t)g.start_hi << 32) | g.start_lo;
-            const int32_t li = C.label[(size_t)g.row];
+            const int32_t li = C.list_of_set[(size_t)C.set_of_row[(size_t)g.row]];
             int64_t w = e0;
             for (int64_t e = e0; e < e0 + g.len; ++e)
-                if (C.label[(size_t)P.col[(size_t)e]] == li) out.col[(size_t)w++] = P.col[(size_t)e];
+                if (C.list_of_row[(size_t)P.col[(size_t)e]] == li) col[(size_t)w++] = P.col[(size_t)e];
             hot_len[(size_t)s] = (int32_t)(w - e0);
             for (int64_t e = e0; e < e0 + g.len; ++e)
-                if (C.label[(size_t)P.col[(size_t)e]] != li) out.col[(size_t)w++] = P.col[(size_t)e];
+                if (C.list_of_row[(size_t)P.col[(size_t)e]] != li) col[(size_t)w++] = P.col[(size_t)e];
         }
     });
+}
+
+}  // namespace
+
+void build_split_schedule(const gp_plan& P, const HotSets& C, SplitSchedule& out)
+{
+    const int64_t nsegs = (int64_t)P.segs.size();
+    std::vector<int32_t> hot_len;
+    hot_first(P, C, out.col, hot_len);
     // records per row, in the order the plan lists a row's segments (ascending start)
     std::vector<int32_t> pieces((size_t)P.n, 0);
     for (int64_t s = 0; s < nsegs; ++s) {
@@ -419,77 +473,117 @@ private:
 
 }  // namespace
 
-// Groups of 64 hot records per cluster, longest first (every lane walks as many steps as
-// its group needs, so records of like length share a group), with their source indices
-// local to the cluster.  Two orders for a record's reads: the column list's, or (where the
-// padding it costs is acceptable) the conflict-free order of PassGroup.  Either way the
-// order is fixed by the schedule, so a record's sum repeats bit for bit.
-bool build_lds_schedule(const gp_plan& P, const RowClusters& C, const SplitSchedule& S, double max_padding, int order,
-                        LdsSchedule& out)
+// The schedule of the LDS pass.  Every segment of the plan is cut into its hot non-zeros
+// (source on the list its row's set gathers from) and the others.  Segments are put in an
+// order of their own -- set by set, most hot non-zeros first -- and a segment's place in it
+// is its *position*.  The LDS launch takes the hot parts, 64 consecutive positions to a
+// group (one per lane; every lane walks as many steps as its group needs, so segments of
+// like length share a group), and leaves each sum in the plane entry of its position; the
+// segment kernel then walks the other parts in position order, adds the plane entry and
+// finishes the segment as the plan says (output row or partial-row slot).  Two orders for a
+// segment's reads: the column list's, or (where the padding it costs is less than what it
+// gains) the conflict-free order of PassGroup.  Either way the order is fixed by the
+// schedule, so a sum repeats bit for bit.
+bool build_lds_schedule(const gp_plan& P, const HotSets& C, double max_cost, int order, LdsSchedule& out)
 {
     const int64_t n = P.n;
-    const int32_t num = C.num;
-    const int64_t nhot = (int64_t)S.hot.size();
-    if (num <= 0 || nhot == 0) return false;
-    // hot records and rows per cluster
-    std::vector<int64_t> rec_off((size_t)num + 1, 0);
-    out.member_off.assign((size_t)num + 1, 0);
-    for (int64_t i = 0; i < n; ++i) ++out.member_off[(size_t)C.label[(size_t)i] + 1];
-    out.hot_edges = 0;
-    for (int64_t r = 0; r < nhot; ++r) {
-        ++rec_off[(size_t)C.label[(size_t)S.hot[(size_t)r].row] + 1];
-        out.hot_edges += S.hot[(size_t)r].len;
-    }
-    out.max_members = 0;
-    for (int32_t c = 0; c < num; ++c) {
-        if (rec_off[(size_t)c + 1] > 0) out.max_members = (int32_t)std::max<int64_t>(out.max_members, out.member_off[(size_t)c + 1]);
-        if (rec_off[(size_t)c + 1] > 0 && out.member_off[(size_t)c + 1] > kLdsMaxMembers) return false;
-        out.member_off[(size_t)c + 1] += out.member_off[(size_t)c];
-        rec_off[(size_t)c + 1] += rec_off[(size_t)c];
-    }
-    out.members.resize((size_t)n);
-    std::vector<int32_t> local((size_t)n);
+    const int32_t num = C.num_sets;
+    const int64_t nsegs = (int64_t)P.segs.size();
+    if (num <= 0 || C.num_lists <= 0 || nsegs == 0) return false;
+    std::vector<int32_t> hot_len;
+    hot_first(P, C, out.col, hot_len);
+    // the lists' rows, ascending, and every row's place on its list
+    out.member_off.assign((size_t)C.num_lists + 1, 0);
+    for (int64_t i = 0; i < n; ++i)
+        if (C.list_of_row[(size_t)i] >= 0) ++out.member_off[(size_t)C.list_of_row[(size_t)i] + 1];
+    for (int32_t l = 0; l < C.num_lists; ++l) out.member_off[(size_t)l + 1] += out.member_off[(size_t)l];
+    out.members.resize((size_t)out.member_off[(size_t)C.num_lists]);
+    std::vector<int32_t> local((size_t)n, 0);
     {
         std::vector<int64_t> fill(out.member_off.begin(), out.member_off.end() - 1);
         for (int64_t i = 0; i < n; ++i) {
-            const int32_t c = C.label[(size_t)i];
-            local[(size_t)i] = (int32_t)(fill[(size_t)c] - out.member_off[(size_t)c]);
-            out.members[(size_t)fill[(size_t)c]++] = (int32_t)i;
+            const int32_t l = C.list_of_row[(size_t)i];
+            if (l < 0) continue;
+            local[(size_t)i] = (int32_t)(fill[(size_t)l] - out.member_off[(size_t)l]);
+            out.members[(size_t)fill[(size_t)l]++] = (int32_t)i;
         }
     }
-    std::vector<int64_t> recs((size_t)nhot);
-    {
-        std::vector<int64_t> fill(rec_off.begin(), rec_off.end() - 1);
-        for (int64_t r = 0; r < nhot; ++r) recs[(size_t)fill[(size_t)C.label[(size_t)S.hot[(size_t)r].row]]++] = r;
+    out.list_of_set = C.list_of_set;
+    auto members_of_set = [&](int32_t c) {
+        const int32_t l = C.list_of_set[(size_t)c];
+        return out.member_off[(size_t)l + 1] - out.member_off[(size_t)l];
+    };
+    // positions: the segments set by set, inside a set most hot non-zeros first (stable)
+    std::vector<int64_t> pos_off((size_t)num + 1, 0);
+    out.hot_edges = 0;
+    for (int64_t s = 0; s < nsegs; ++s) {
+        ++pos_off[(size_t)C.set_of_row[(size_t)P.segs[(size_t)s].row] + 1];
+        out.hot_edges += hot_len[(size_t)s];
     }
-    const int nt = S.col.size() < (1u << 16) ? 1 : host_threads();
+    if (out.hot_edges == 0) return false;
+    for (int32_t c = 0; c < num; ++c) pos_off[(size_t)c + 1] += pos_off[(size_t)c];
+    std::vector<int64_t> seg_at((size_t)nsegs);  // position -> segment
+    {
+        std::vector<int64_t> fill(pos_off.begin(), pos_off.end() - 1);
+        for (int64_t s = 0; s < nsegs; ++s) seg_at[(size_t)fill[(size_t)C.set_of_row[(size_t)P.segs[(size_t)s].row]]++] = s;
+    }
+    const int nt = P.nnz < (1 << 16) ? 1 : host_threads();
     parallel_run(nt, [&](int t, int k) {
         for (int32_t c = (int32_t)((int64_t)num * t / k); c < (int32_t)((int64_t)num * (t + 1) / k); ++c)
-            std::stable_sort(recs.begin() + rec_off[(size_t)c], recs.begin() + rec_off[(size_t)c + 1],
-                             [&](int64_t a, int64_t b) { return S.hot[(size_t)a].len > S.hot[(size_t)b].len; });
+            std::stable_sort(seg_at.begin() + pos_off[(size_t)c], seg_at.begin() + pos_off[(size_t)c + 1],
+                             [&](int64_t a, int64_t b) { return hot_len[(size_t)a] > hot_len[(size_t)b]; });
     });
-    // groups: cluster c owns records recs[rec_off[c] ...], 64 to a group
+    // the other parts, in position order, for the segment kernel
+    out.cold.resize((size_t)nsegs);
+    parallel_run(nt, [&](int t, int k) {
+        for (int64_t p = nsegs * t / k; p < nsegs * (t + 1) / k; ++p) {
+            const int64_t s = seg_at[(size_t)p];
+            Segment q = P.segs[(size_t)s];
+            const int64_t start = (((int64_t)q.start_hi << 32) | q.start_lo) + hot_len[(size_t)s];
+            q.start_lo = (uint32_t)(start & 0xFFFFFFFF);
+            q.start_hi = (uint8_t)(start >> 32);
+            q.len = (uint16_t)(q.len - hot_len[(size_t)s]);
+            q.slice = hot_len[(size_t)s] > 0 ? kAddPlaneEntry : 0;
+            out.cold[(size_t)p] = q;
+        }
+    });
+    // groups: 64 consecutive positions of one set, as far as the set's segments have hot non-zeros
+    out.max_members = 0;
     out.group_off.assign((size_t)num + 1, 0);
-    std::vector<int32_t> group_cluster;
+    std::vector<int32_t> group_set;
+    std::vector<int64_t> group_pos;  // first position of the group
     for (int32_t c = 0; c < num; ++c) {
-        const int64_t g = (rec_off[(size_t)c + 1] - rec_off[(size_t)c] + 63) / 64;
-        if ((int64_t)group_cluster.size() + g > INT32_MAX) return false;
-        group_cluster.insert(group_cluster.end(), (size_t)g, c);
-        out.group_off[(size_t)c + 1] = (int32_t)group_cluster.size();
+        int64_t with_hot = 0;  // (sorted: they come first)
+        while (pos_off[(size_t)c] + with_hot < pos_off[(size_t)c + 1] && hot_len[(size_t)seg_at[(size_t)(pos_off[(size_t)c] + with_hot)]] > 0)
+            ++with_hot;
+        if (with_hot > 0) {
+            if (members_of_set(c) > kLdsMaxMembers) return false;
+            out.max_members = (int32_t)std::max<int64_t>(out.max_members, members_of_set(c));
+        }
+        const int64_t g = (with_hot + 63) / 64;
+        if ((int64_t)group_set.size() + g > INT32_MAX) return false;
+        for (int64_t i = 0; i < g; ++i) {
+            group_set.push_back(c);
+            group_pos.push_back(pos_off[(size_t)c] + 64 * i);
+        }
+        out.group_off[(size_t)c + 1] = (int32_t)group_set.size();
     }
-    const int64_t ngroups = (int64_t)group_cluster.size();
-    auto record_of = [&](int64_t g, int lane) -> const Segment* {
-        const int32_t c = group_cluster[(size_t)g];
-        const int64_t r = rec_off[(size_t)c] + 64 * (g - out.group_off[(size_t)c]) + lane;
-        return r < rec_off[(size_t)c + 1] ? &S.hot[(size_t)recs[(size_t)r]] : nullptr;
+    const int64_t ngroups = (int64_t)group_set.size();
+    // lane l of group g: the segment at position group_pos[g] + l, if that is still in the set and has hot non-zeros
+    auto segment_of = [&](int64_t g, int lane) -> int64_t {
+        const int64_t p = group_pos[(size_t)g] + lane;
+        if (p >= pos_off[(size_t)group_set[(size_t)g] + 1]) return -1;
+        const int64_t s = seg_at[(size_t)p];
+        return hot_len[(size_t)s] > 0 ? s : -1;
     };
+    auto hot_start = [&](int64_t s) { return out.col.data() + (((int64_t)P.segs[(size_t)s].start_hi << 32) | P.segs[(size_t)s].start_lo); };
     auto load_pass = [&](PassGroup& pg, int64_t g, int pass, int (&lanes)[16]) {
         int k = 0;
         for (int l = 0; l < 64; ++l)
             if (lds_pass_of_lane(l) == pass) lanes[k++] = l;
         for (int j = 0; j < 16; ++j) {
-            const Segment* q = record_of(g, lanes[j]);
-            if (q) pg.load(j, S.col.data() + (((int64_t)q->start_hi << 32) | q->start_lo), q->len, local.data());
+            const int64_t s = segment_of(g, lanes[j]);
+            if (s >= 0) pg.load(j, hot_start(s), hot_len[(size_t)s], local.data());
             else pg.clear(j);
         }
     };
@@ -499,7 +593,7 @@ bool build_lds_schedule(const gp_plan& P, const RowClusters& C, const SplitSched
         PassGroup pg;
         int lanes[16];
         for (int64_t g = ngroups * t / k; g < ngroups * (t + 1) / k; ++g) {
-            steps_plain[(size_t)g] = (record_of(g, 0)->len + 7) / 8 * 8;
+            steps_plain[(size_t)g] = (hot_len[(size_t)segment_of(g, 0)] + 7) / 8 * 8;
             if (order == 1) continue;
             int32_t need = 0;
             for (int pass = 0; pass < 4; ++pass) {
@@ -514,50 +608,47 @@ bool build_lds_schedule(const gp_plan& P, const RowClusters& C, const SplitSched
         total_plain += 64 * (int64_t)steps_plain[(size_t)g];
         total_free += 64 * (int64_t)steps_free[(size_t)g];
     }
-    const double allowed = (1.0 + max_padding) * (double)std::max<int64_t>(out.hot_edges, 1);
-    out.conflict_free = order == 2 || (order == 0 && (double)total_free <= allowed);
+    // cost of an order = its reads, padding included, a conflict-free read counting 1 / kLdsConflictFreeGain
+    const double cost_free = (double)total_free / kLdsConflictFreeGain, cost_plain = (double)total_plain;
+    out.conflict_free = order == 2 || (order == 0 && cost_free <= cost_plain);
     const std::vector<int32_t>& steps = out.conflict_free ? steps_free : steps_plain;
-    if ((double)(out.conflict_free ? total_free : total_plain) > allowed) return false;
+    if ((out.conflict_free ? cost_free : cost_plain) > max_cost * (double)out.hot_edges) return false;
     out.groups.resize((size_t)ngroups);
     int64_t id_total = 0;
     for (int64_t g = 0; g < ngroups; ++g) {
-        out.groups[(size_t)g] = LdsGroup{id_total, steps[(size_t)g], 0};
+        int32_t count = 0;
+        while (count < 64 && segment_of(g, count) >= 0) ++count;  // (sorted: the lanes with a segment come first)
+        out.groups[(size_t)g] = LdsGroup{id_total, group_pos[(size_t)g], steps[(size_t)g], count};
         id_total += 64 * (int64_t)steps[(size_t)g];
     }
-    out.rec_row.assign((size_t)ngroups * 64, -1);
-    out.rec_slot.assign((size_t)ngroups * 64, -1);
-    out.ids.resize((size_t)id_total);
-    // A row made of exactly one hot and one cold piece needs no fix-up: the cold launch runs first, and
-    // the lane that has the hot sum adds the cold partial row and finishes the row (joins[row] = the cold
-    // piece's slot).  Other cut rows stay on the fix-up list.
-    std::vector<int32_t> joins((size_t)n, -1);
-    {
-        std::vector<uint8_t> hot_pieces((size_t)n, 0), cold_pieces((size_t)n, 0);
-        for (const Segment& q : S.hot) hot_pieces[(size_t)q.row] = (uint8_t)std::min(2, hot_pieces[(size_t)q.row] + 1);
-        for (const Segment& q : S.cold) cold_pieces[(size_t)q.row] = (uint8_t)std::min(2, cold_pieces[(size_t)q.row] + 1);
-        for (const Segment& q : S.cold)
-            if (hot_pieces[(size_t)q.row] == 1 && cold_pieces[(size_t)q.row] == 1) joins[(size_t)q.row] = q.slot;
-        out.fixup_rows.clear();
-        for (const SplitRow& r : S.split)
-            if (joins[(size_t)r.row] < 0) out.fixup_rows.push_back(r);
+    out.groups.push_back(LdsGroup{id_total, 0, 0, 0});  // sentinel: where the last group's indices end
+    out.set_reads.assign((size_t)num, 0);
+    for (int32_t c = 0; c < num; ++c)
+        out.set_reads[(size_t)c] = out.groups[(size_t)out.group_off[(size_t)c + 1]].id_off - out.groups[(size_t)out.group_off[(size_t)c]].id_off;
+    // a set's groups in kWaveCuts runs of about equal length in reads (a run per wave, or two)
+    out.wave_cut.assign((size_t)num * (kWaveCuts + 1), 0);
+    for (int32_t c = 0; c < num; ++c) {
+        const int32_t g0 = out.group_off[(size_t)c], g1 = out.group_off[(size_t)c + 1];
+        const int64_t lo = out.groups[(size_t)g0].id_off, hi = out.groups[(size_t)g1].id_off;
+        int32_t g = g0;
+        for (int w = 0; w <= kWaveCuts; ++w) {
+            const int64_t target = lo + (hi - lo) * w / kWaveCuts;
+            while (g < g1 && out.groups[(size_t)g].id_off < target) ++g;
+            out.wave_cut[(size_t)c * (kWaveCuts + 1) + w] = w == kWaveCuts ? g1 : g;
+        }
     }
+    out.ids.resize((size_t)id_total);
     std::atomic<bool> ok{true};
     parallel_run(nt, [&](int t, int k) {
         PassGroup pg;
         int lanes[16];
         for (int64_t g = ngroups * t / k; g < ngroups * (t + 1) / k; ++g) {
-            const int32_t c = group_cluster[(size_t)g];
-            const int64_t m = out.member_off[(size_t)c + 1] - out.member_off[(size_t)c];
+            const int64_t m = members_of_set(group_set[(size_t)g]);
             const uint16_t zero_base = (uint16_t)((m + 15) / 16 * 16);  // 16 zero rows, one per bank group
             const LdsGroup& G = out.groups[(size_t)g];
             auto slot_of = [&](int lane, int32_t step) -> uint16_t& {
                 return out.ids[(size_t)(G.id_off + (int64_t)(step / 8) * 512 + lane * 8 + step % 8)];
             };
-            for (int l = 0; l < 64; ++l)
-                if (const Segment* q = record_of(g, l)) {
-                    out.rec_row[(size_t)g * 64 + l] = q->row;
-                    out.rec_slot[(size_t)g * 64 + l] = joins[(size_t)q->row] >= 0 ? -2 - joins[(size_t)q->row] : q->slot;
-                }
             if (out.conflict_free) {
                 for (int pass = 0; pass < 4; ++pass) {
                     load_pass(pg, g, pass, lanes);
@@ -566,15 +657,38 @@ bool build_lds_schedule(const gp_plan& P, const RowClusters& C, const SplitSched
                 }
             } else {
                 for (int l = 0; l < 64; ++l) {
-                    const Segment* q = record_of(g, l);
-                    const int32_t len = q ? q->len : 0;
-                    const int32_t* col = q ? S.col.data() + (((int64_t)q->start_hi << 32) | q->start_lo) : nullptr;
-                    for (int32_t s = 0; s < G.steps; ++s) slot_of(l, s) = s < len ? (uint16_t)local[(size_t)col[s]] : zero_base;
+                    const int64_t s = segment_of(g, l);
+                    const int32_t len = s >= 0 ? hot_len[(size_t)s] : 0;
+                    const int32_t* col = s >= 0 ? hot_start(s) : nullptr;
+                    for (int32_t st = 0; st < G.steps; ++st) slot_of(l, st) = st < len ? (uint16_t)local[(size_t)col[st]] : zero_base;
                 }
             }
         }
     });
     return ok;
+}
+
+void deal_lds_octets(const std::vector<int64_t>& set_reads, int strips, std::vector<LdsOctet>& octets, int64_t (&off)[9])
+{
+    const int per_set = (strips + 7) / 8;
+    std::vector<std::vector<LdsOctet>> mine(8);
+    double load[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int32_t c = 0; c < (int32_t)set_reads.size(); ++c) {
+        if (set_reads[(size_t)c] == 0) continue;
+        for (int k = 0; k < per_set; ++k) {
+            int x = 0;
+            for (int y = 1; y < 8; ++y)
+                if (load[y] < load[x]) x = y;
+            mine[(size_t)x].push_back(LdsOctet{c, k});
+            load[x] += (double)set_reads[(size_t)c] * (double)std::min(8, strips - 8 * k);
+        }
+    }
+    octets.clear();
+    for (int x = 0; x < 8; ++x) {
+        off[x] = (int64_t)octets.size();
+        octets.insert(octets.end(), mine[(size_t)x].begin(), mine[(size_t)x].end());
+    }
+    off[8] = (int64_t)octets.size();
 }
 
 }  // namespace gp

@@ -1,25 +1,28 @@
-// gp: the hot pieces of the split schedule gathered from LDS (gfx950).
+// gp: the hot non-zeros of a hop gathered from LDS (gfx950).
 //
-// Where the non-zero pattern has row clusters small enough, a cluster's source rows fit
-// the 160 KB of LDS a compute unit has, four fp32 columns (16 bytes) at a time.  A
-// workgroup then stages one such column strip of one cluster, pre-multiplied by the
-// source's weight (Eq. 2's D^-1/2 on the right of A), and every hot record of the cluster
-// gathers from there: one lane per record, one 16-byte LDS read per non-zero, the local
-// source indices (16 bits) streamed from a list that is laid out so that a wavefront
-// reads whole lines.  Random 16-byte reads come out of LDS at about 43 TB/s over the
-// chip against 23 TB/s out of the L2s, and out-of-cluster traffic cannot evict anything.
+// A short list of rows (at most 10,192) fits the 160 KB of LDS a compute unit has, four
+// fp32 columns (16 bytes) at a time.  A list is a cluster of the non-zero pattern, served
+// to the rows of that cluster, or the most popular rows of a graph without clusters,
+// served to every set of rows.  A workgroup stages one such column strip of one list,
+// pre-multiplied by the source's weight (Eq. 2's D^-1/2 on the right of A), and the hot
+// part of every segment of the set -- the non-zeros whose source is on the list -- is
+// added up from there: one lane per segment, one 16-byte LDS read per non-zero, the
+// sources' places on the list (16 bits) streamed from an index list that is laid out so
+// that a wavefront reads whole lines.  Random 16-byte reads come out of LDS at about
+// 47 TB/s over the chip, conflict-free ones at about 90, against 23 TB/s out of the L2s.
 //
-// Work item = (cluster, strip).  Eight consecutive strips (one 128-byte line of a source
-// row) form an octet; octet o belongs to XCD o % 8, so that the lines a strip fill pulls
-// in serve the other strips of the octet from the same L2.  The workgroups of an XCD
-// take items from that XCD's cursor (ctrl[0..8)); ctrl[8] counts finished workgroups and
-// the last one zeroes all nine words, as in the segment kernel.
+// Work item = (set, strip).  Eight consecutive strips (one 128-byte line of a source row)
+// form an octet; octet o belongs to XCD o % 8, so that the lines a strip fill pulls in
+// serve the other strips of the octet from the same L2.  The workgroups of an XCD take
+// items from that XCD's cursor (ctrl[0..8)); ctrl[8] counts finished workgroups and the
+// last one zeroes all nine words, as in the segment kernel.
 //
-// Results: a record's sum goes where the record says: a partial-row slot (the fix-up pass
-// joins partial rows as for any other launch), or the output row scaled by row_scale,
-// after adding the one partial row the launch before this one left for it, if any.
-// Summation order per record is fixed by the schedule (eight interleaved chains), so
-// runs repeat bit for bit.
+// Results: plane t holds, for every position (a segment's place in the order this pass
+// takes them: 64 consecutive positions to a group, one per lane), the four sums of
+// strip t; a wavefront stores 64 consecutive entries, 1 KB.  The segment kernel, which
+// takes the segments' other non-zeros in the same order, adds them in.  Summation order
+// per segment is fixed by the schedule (four interleaved chains), so runs repeat bit for
+// bit.
 #include "gp_internal.h"
 
 namespace gp {
@@ -32,6 +35,7 @@ typedef unsigned v4u __attribute__((ext_vector_type(4)));
 constexpr int kLanes = 64;
 constexpr int kStepBlock = 8;  // steps of a lane that lie together in the id list
 constexpr int kAhead = 4;      // index loads in flight per lane
+constexpr int kChains = 4;     // interleaved summation chains per lane and column
 
 // 16 x the low / high 16 bits of a word: the byte offset of an LDS row from its index, in one
 // instruction (a shift whose operand is read as a zero-extended half word)
@@ -59,67 +63,109 @@ __device__ inline unsigned high_half_times_16(unsigned packed)
 typedef const __attribute__((address_space(3))) v4f_a16 lds_v4f;
 __device__ inline v4f_a16 lds_row(unsigned byte_offset) { return *reinterpret_cast<lds_v4f*>(byte_offset); }
 
+// The lists' rows strip by strip, one run of memory per (strip, list), each row times its
+// source weight: packed[(t * num_members + i) * 4 ..] = w(row) * X[row][4 t .. 4 t + 4), row =
+// members[i]; the last strip is moved back to end with the row.  A thread walks its row 16 bytes
+// at a time (a line serves eight consecutive steps out of the caches) and a wavefront stores
+// 64 consecutive entries, so that staging a strip later reads its 16 bytes per row once, not a
+// line per row.
+__global__ __launch_bounds__(256) void gp_pack_strips(const int32_t* __restrict__ members, int64_t num_members,
+                                                      const float* __restrict__ src_scale, const float* __restrict__ xin,
+                                                      int64_t ldin, int d, float* __restrict__ packed)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= num_members) return;
+    const int row = members[i];
+    const float w = src_scale ? src_scale[row] : 1.0f;
+    const float* src = xin + (int64_t)row * ldin;
+    const int nstrips = (d + 3) / 4;
+    for (int t0 = 0; t0 < nstrips; t0 += 8) {
+        v4f_a16 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int t = min(t0 + u, nstrips - 1);
+            v[u] = *reinterpret_cast<const v4f_a4*>(src + min(t * 4, d - 4));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (t0 + u < nstrips) *reinterpret_cast<v4f_a16*>(packed + ((int64_t)(t0 + u) * num_members + i) * 4) = v[u] * w;
+    }
+}
+
+struct OctetLists {
+    int64_t off[9];
+};
+
 __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
-    const int32_t* __restrict__ members, const int64_t* __restrict__ member_off, const int32_t* __restrict__ group_off,
-    const LdsGroup* __restrict__ groups, const int32_t* __restrict__ rec_row, const int32_t* __restrict__ rec_slot,
-    const uint16_t* __restrict__ ids, int num_clusters, const float* __restrict__ src_scale,
-    const float* __restrict__ row_scale, const float* __restrict__ xin, int64_t ldin, float* __restrict__ xout, int64_t ldout,
-    float* __restrict__ carry, int64_t carry_ld, int d, unsigned long long* __restrict__ ctrl, int lds_rows_max)
+    const int32_t* __restrict__ members, const int64_t* __restrict__ member_off, const int32_t* __restrict__ list_of_set,
+    const int32_t* __restrict__ group_off, const int32_t* __restrict__ wave_cut,
+    const LdsGroup* __restrict__ groups, const LdsOctet* __restrict__ octets, const OctetLists lists,
+    const uint16_t* __restrict__ ids,
+    const float* __restrict__ packed, int64_t num_members, const float* __restrict__ src_scale, const float* __restrict__ xin,
+    int64_t ldin, float* __restrict__ planes, int64_t num_pos, int d, unsigned long long* __restrict__ ctrl, int lds_rows_max)
 {
     // LDS: the strip's rows from byte 0 (an index times 16 is then the address itself), and
     // after them the word through which a workgroup learns its next item
     extern __shared__ __align__(16) char lds_raw[];
     v4f_a16* lds = reinterpret_cast<v4f_a16*>(lds_raw);
     unsigned long long& next_item = *reinterpret_cast<unsigned long long*>(lds_raw + (size_t)lds_rows_max * 16);
-    // ... and the count of the item's record groups handed out so far (a wave's first group is its own number)
-    int& groups_taken = *reinterpret_cast<int*>(lds_raw + (size_t)lds_rows_max * 16 + 8);
 
     const int lane = threadIdx.x & (kLanes - 1);
-    const int wave = threadIdx.x / kLanes, waves = blockDim.x / kLanes;
+    // (the same in every lane of a wave: said so, so that what is derived from it is scalar arithmetic and scalar loads)
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kLanes)), waves = blockDim.x / kLanes;
     const int xcd = blockIdx.x & 7;
     const int64_t wgs = gridDim.x >> 3;  // workgroups of this XCD
     const int nstrips = (d + 3) / 4;
-    const int opc = (nstrips + 7) / 8;  // octets per cluster
-    const int64_t octets = (int64_t)num_clusters * opc;
-    const int64_t my_octets = octets > xcd ? (octets - xcd + 7) / 8 : 0;
-    const int64_t items = my_octets * 8;
+    const LdsOctet* mine = octets + lists.off[xcd];
+    const int64_t items = (lists.off[xcd + 1] - lists.off[xcd]) * 8;  // an octet = eight items, strip by strip
 
     int64_t item = blockIdx.x >> 3;
     while (item < items) {
-        if (threadIdx.x == 0) {
-            next_item = (unsigned long long)wgs + atomicAdd(ctrl + xcd, 1ULL);
-            groups_taken = waves;
-        }
-        const int64_t octet = (item >> 3) * 8 + xcd;
-        const int c = (int)(octet / opc);
-        const int strip = (int)(octet % opc) * 8 + (int)(item & 7);
+        if (threadIdx.x == 0) next_item = (unsigned long long)wgs + atomicAdd(ctrl + xcd, 1ULL);
+        const LdsOctet o = mine[item >> 3];
+        const int c = o.set;
+        const int strip = o.octet * 8 + (int)(item & 7);
         const int g_lo = group_off[c], g_hi = group_off[c + 1];
         const bool valid = strip < nstrips && g_hi > g_lo;
-        const int col0 = min(strip * 4, d - 4);  // the last strip moves back to end with the row
         int m = 0;
         if (valid) {
-            const int64_t m_lo = member_off[c];
-            m = (int)(member_off[c + 1] - m_lo);
-            const int32_t* mem = members + m_lo;
-            // stage the strip: the cluster's rows, then zero rows up to the 16 that padding reads point at
+            const int list = list_of_set[c];
+            const int64_t m_lo = member_off[list];
+            m = (int)(member_off[list + 1] - m_lo);
+            // stage the strip: the list's rows, then zero rows up to the 16 that padding reads point at.  The
+            // rows come packed (one run of memory; lists that many sets share), or straight from the matrix,
+            // 16 bytes of every row, times the row's source weight (a list that only this set stages).
             const int rows = (m + 15) / 16 * 16 + 16;
+            const v4f_a16* src = reinterpret_cast<const v4f_a16*>(packed) + ((int64_t)strip * num_members + m_lo);
+            const int32_t* mem = members + m_lo;
+            const int col0 = min(strip * 4, d - 4);  // the last strip moves back to end with the row
             for (int i0 = 0; i0 < rows; i0 += 4 * (int)blockDim.x) {
-                int row[4];
                 v4f_a16 v[4];
+                if (packed) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int i = i0 + u * (int)blockDim.x + (int)threadIdx.x;
-                    row[u] = i < m ? mem[i] : -1;
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * (int)blockDim.x + (int)threadIdx.x;
+                        v[u] = i < m ? src[i] : v4f_a16{0.0f, 0.0f, 0.0f, 0.0f};
+                    }
+                } else {
+                    int row[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int i = i0 + u * (int)blockDim.x + (int)threadIdx.x;
+                        row[u] = i < m ? mem[i] : -1;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        v[u] = v4f_a16{0.0f, 0.0f, 0.0f, 0.0f};
+                        if (row[u] >= 0) v[u] = *reinterpret_cast<const v4f_a4*>(xin + (int64_t)row[u] * ldin + col0);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (src_scale && row[u] >= 0) v[u] *= src_scale[row[u]];
                 }
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    v[u] = v4f_a16{0.0f, 0.0f, 0.0f, 0.0f};
-                    if (row[u] >= 0) v[u] = *reinterpret_cast<const v4f_a4*>(xin + (int64_t)row[u] * ldin + col0);
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
                     const int i = i0 + u * (int)blockDim.x + (int)threadIdx.x;
-                    if (src_scale && row[u] >= 0) v[u] *= src_scale[row[u]];
                     if (i < rows) lds[i] = v[u];
                 }
             }
@@ -127,64 +173,77 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
         __syncthreads();
         const int64_t following = (int64_t)next_item;
         if (valid) {
-            // groups are listed longest first: handing them out one by one keeps the waves level to the end
-            for (int g = g_lo + wave; g < g_hi;) {
-                const LdsGroup G = groups[g];
-                // A lane's indices come kStepBlock (8, one 16-byte load) at a time.  Two register
-                // sets of kAhead such loads alternate: while one is worked through the other is in
-                // flight, which covers the latency of the list (it streams from memory) with four
-                // waves per SIMD.  Loads past the end re-read the last block (never used).
-                const v4u* ip = reinterpret_cast<const v4u*>(ids + G.id_off) + lane;
-                const int nb = G.steps / kStepBlock;
-                v4f_a16 acc[kStepBlock];
+            // A wave takes a run of consecutive groups of the set; the host has cut the set's groups into 16
+            // runs of about equal length in reads (wave_cut).  The groups' indices lie one after the other
+            // in the index list, so the run is one stream of blocks (8 reads of every lane = one 16-byte load per
+            // lane), walked without a stop at the group boundaries.  Two register sets of kAhead blocks
+            // alternate: while one is worked through the other is in flight, which covers the latency of the
+            // list (it streams from memory) with four waves per SIMD.  Loads past the run's end re-read its
+            // last block (never used).
+            const int parts = kWaveCuts / waves;
+            const int32_t* cut = wave_cut + (int64_t)c * (kWaveCuts + 1);
+            int g = __builtin_amdgcn_readfirstlane(cut[wave * parts]);
+            const int g_end = __builtin_amdgcn_readfirstlane(cut[(wave + 1) * parts]);
+            if (g < g_end) {
+                const int64_t k_end = groups[g_end].id_off >> 9;  // (the list of groups ends with a sentinel)
+                int64_t k = groups[g].id_off >> 9;
+                int64_t k_group_end = k + groups[g].steps / kStepBlock;
+                // where this lane's sums go: entry (octet, position) of the planes, 16 bytes of its 128; -1: nowhere
+                auto entry_of = [&](const LdsGroup& G) -> int64_t {
+                    return lane < G.count ? (((int64_t)(strip >> 3) * num_pos + G.first_pos + lane) * 32 + (strip & 7) * 4) : -1;
+                };
+                int64_t entry = entry_of(groups[g]);
+                // what the group after the current one will need, asked for one group ahead
+                LdsGroup next = groups[min(g + 1, g_end)];
+                const v4u* ip = reinterpret_cast<const v4u*>(ids) + lane;
+                v4f_a16 acc[kChains];
 #pragma unroll
-                for (int u = 0; u < kStepBlock; ++u) acc[u] = v4f_a16{0.0f, 0.0f, 0.0f, 0.0f};
-                if (nb > 0) {
-                    auto fetch = [&](v4u(&q)[kAhead], int b0) {
+                for (int u = 0; u < kChains; ++u) acc[u] = v4f_a16{0.0f, 0.0f, 0.0f, 0.0f};
+                auto fetch = [&](v4u(&q)[kAhead], int64_t k0) {
 #pragma unroll
-                        for (int i = 0; i < kAhead; ++i) q[i] = ip[(int64_t)min(b0 + i, nb - 1) * kLanes];
-                    };
-                    auto work = [&](const v4u(&q)[kAhead], int b0) {
+                    for (int i = 0; i < kAhead; ++i) q[i] = ip[min(k0 + i, k_end - 1) * kLanes];
+                };
+                auto add_block = [&](const v4u& q) {
+                    v4f_a16 x[kStepBlock];
 #pragma unroll
-                        for (int i = 0; i < kAhead; ++i) {
-                            if (b0 + i < nb) {  // the same for every lane of the group
-                                v4f_a16 x[kStepBlock];
+                    for (int u = 0; u < 4; ++u) {
+                        x[2 * u] = lds_row(low_half_times_16(q[u]));
+                        x[2 * u + 1] = lds_row(high_half_times_16(q[u]));
+                    }
 #pragma unroll
-                                for (int u = 0; u < 4; ++u) {
-                                    x[2 * u] = lds_row(low_half_times_16(q[i][u]));
-                                    x[2 * u + 1] = lds_row(high_half_times_16(q[i][u]));
-                                }
+                    for (int u = 0; u < kStepBlock; ++u) acc[u % kChains] += x[u];
+                };
+                auto work = [&](const v4u(&q)[kAhead], int64_t k0) {
+                    if (k0 + kAhead < k_group_end) {  // no group ends in these blocks: straight through
 #pragma unroll
-                                for (int u = 0; u < kStepBlock; ++u) acc[u] += x[u];
+                        for (int i = 0; i < kAhead; ++i) add_block(q[i]);
+                        return;
+                    }
+#pragma unroll
+                    for (int i = 0; i < kAhead; ++i) {
+                        if (k0 + i < k_end) {  // the same for every lane of the wave
+                            add_block(q[i]);
+                            if (k0 + i + 1 == k_group_end) {  // the group's last block: its sums leave, the next group begins
+                                const v4f_a16 sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+                                if (entry >= 0) *reinterpret_cast<v4f_a16*>(planes + entry) = sum;
+#pragma unroll
+                                for (int u = 0; u < kChains; ++u) acc[u] = v4f_a16{0.0f, 0.0f, 0.0f, 0.0f};
+                                ++g;
+                                k_group_end += next.steps / kStepBlock;
+                                entry = entry_of(next);
+                                next = groups[min(g + 1, g_end)];
                             }
                         }
-                    };
-                    v4u qa[kAhead], qb[kAhead];
-                    fetch(qa, 0);
-                    for (int b = 0; b < nb; b += 2 * kAhead) {
-                        fetch(qb, b + kAhead);
-                        work(qa, b);
-                        fetch(qa, b + 2 * kAhead);
-                        work(qb, b + kAhead);
                     }
+                };
+                v4u qa[kAhead], qb[kAhead];
+                fetch(qa, k);
+                for (; k < k_end; k += 2 * kAhead) {
+                    fetch(qb, k + kAhead);
+                    work(qa, k);
+                    fetch(qa, k + 2 * kAhead);
+                    work(qb, k + kAhead);
                 }
-                const v4f_a16 sum = ((acc[0] + acc[1]) + (acc[2] + acc[3])) + ((acc[4] + acc[5]) + (acc[6] + acc[7]));
-                const int row = rec_row[(int64_t)g * kLanes + lane];
-                if (row >= 0) {
-                    const int slot = rec_slot[(int64_t)g * kLanes + lane];
-                    if (slot < 0) {
-                        // the whole row, or all of it but one partial row that an earlier launch left in its slot
-                        v4f_a16 total = sum;
-                        if (slot < -1) total += *reinterpret_cast<const v4f_a4*>(carry + (int64_t)(-2 - slot) * carry_ld + col0);
-                        const float s = row_scale ? row_scale[row] : 1.0f;
-                        *reinterpret_cast<v4f_a4*>(xout + (int64_t)row * ldout + col0) = total * s;
-                    } else {
-                        *reinterpret_cast<v4f_a4*>(carry + (int64_t)slot * carry_ld + col0) = sum;
-                    }
-                }
-                int taken = 0;
-                if (lane == 0) taken = atomicAdd(&groups_taken, 1);
-                g = g_lo + __builtin_amdgcn_readfirstlane(taken);
             }
         }
         __syncthreads();  // every read of this strip is done before the next one is staged
@@ -203,12 +262,11 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
 
 gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
 {
-    if (a.d < 4 || a.num_clusters <= 0 || !a.ctrl || !a.xin || !a.xout)
-        return fail(GP_ERR_INVALID_ARG, "LDS pass: needs at least four fp32 columns, clusters and a cursor buffer");
+    if (a.d < 4 || a.num_sets <= 0 || !a.ctrl || !a.xin || !a.planes || a.num_pos <= 0 || a.num_members <= 0 || !a.octets || !a.octet_off)
+        return fail(GP_ERR_INVALID_ARG, "LDS pass: needs at least four fp32 columns, record sets, lists, planes and a cursor buffer");
     if (a.max_members < 0 || a.max_members > kLdsMaxMembers)
-        return fail(GP_ERR_INVALID_ARG, "LDS pass: a cluster of %d rows does not fit the LDS", a.max_members);
-    if (a.carry && a.carry_ld < a.d) return fail(GP_ERR_INVALID_ARG, "LDS pass: partial rows narrower than d");
-    const size_t shm = (size_t)lds_rows(a.max_members) * 16 + 16;  // the rows, the item word and the group count
+        return fail(GP_ERR_INVALID_ARG, "LDS pass: a list of %d rows does not fit the LDS", a.max_members);
+    const size_t shm = (size_t)lds_rows(a.max_members) * 16 + 16;  // the rows and the item word
     // the kernel addresses its dynamic LDS from 0: true as long as it has no static LDS before it
     hipFuncAttributes attr;
     GP_HIP(hipFuncGetAttributes(&attr, (const void*)gp_hop_cluster_lds));
@@ -219,9 +277,17 @@ gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
     // two workgroups of 512 per compute unit where two strips fit its LDS, else one of 1024
     const bool two = shm <= (size_t)kLdsBytesPerCu / 2 - 64;
     const dim3 grid(8 * 32 * (two ? 2 : 1)), block(two ? 512 : 1024);
-    hipLaunchKernelGGL(gp_hop_cluster_lds, grid, block, shm, stream, a.members, a.member_off, a.group_off, a.groups, a.rec_row,
-                       a.rec_slot, a.ids, a.num_clusters, a.src_scale, a.row_scale, a.xin, a.ldin, a.xout, a.ldout, a.carry,
-                       a.carry_ld, a.d, a.ctrl, (int)lds_rows(a.max_members));
+    if (a.packed) {
+        hipLaunchKernelGGL(gp_pack_strips, dim3((unsigned)((a.num_members + 255) / 256)), dim3(256), 0, stream, a.members, a.num_members,
+                           a.src_scale, a.xin, a.ldin, a.d, a.packed);
+        GP_HIP(hipGetLastError());
+    }
+    OctetLists lists;
+    for (int x = 0; x <= 8; ++x) lists.off[x] = a.octet_off[x];
+    hipLaunchKernelGGL(gp_hop_cluster_lds, grid, block, shm, stream, a.members, a.member_off, a.list_of_set, a.group_off, a.wave_cut,
+                       a.groups, a.octets, lists, a.ids, a.packed, a.num_members, a.src_scale, a.xin, a.ldin, a.planes, a.num_pos, a.d,
+                       a.ctrl,
+                       (int)lds_rows(a.max_members));
     GP_HIP(hipGetLastError());
     return GP_OK;
 }

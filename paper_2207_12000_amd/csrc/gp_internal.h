@@ -36,6 +36,7 @@ struct Options {
     int64_t hbm_budget_bytes = 0;
     int64_t lds_pass = 0;        // hot pieces gathered from LDS where the clusters fit it: 0 = automatic, 1 = wherever possible
                                  // (conflict-free order), 2 = never, 3 = wherever possible (column-list order)
+    int64_t hub_pass = 0;        // graphs without row clusters: the most popular rows served from LDS: 0 = where it pays, 1 = always, 2 = never
     int64_t device_plan_chunk = 0;  // GP_PLAN_ON_DEVICE: most candidate entries sorted at once, 0 = 2^31 - 1
 };
 Options& options();
@@ -74,6 +75,25 @@ struct RowClusters {
     double typical_rows = 0.0;     // rows in the cluster of a typical non-zero (non-zero-weighted mean size)
 };
 
+// Which non-zeros are "hot" (their source row is worth keeping close: in the L2 of the XCD
+// that asks, or in LDS), and how the rows that own them are grouped into sets of work.
+// Every set gathers its hot non-zeros from one list of rows.  Two ways to make them
+// (gp_cluster.cpp): from row clusters (set = list = cluster: a row's hot non-zeros are those
+// whose source is in the row's own cluster), or from the most popular rows (one list, the
+// hubs, shared by all sets; sets are ranges of rows; hot = the source is a hub).
+struct HotSets {
+    int32_t num_sets = 0, num_lists = 0;
+    std::vector<int32_t> set_of_row;   // n
+    std::vector<int32_t> list_of_set;  // num_sets
+    std::vector<int32_t> list_of_row;  // n: the list row j is on, -1 = none
+    double hot_fraction = 0.0;         // share of the non-zeros that are hot
+    bool hot(int32_t row, int32_t src) const
+    {
+        const int32_t l = list_of_row[(size_t)src];
+        return l >= 0 && l == list_of_set[(size_t)set_of_row[(size_t)row]];
+    }
+};
+
 // Explicit per-XCD work lists on the device, for one slice shape.
 struct XcdWork {
     int num_slices = 0, slice_elems = 0, chunk_records = 1;
@@ -83,6 +103,7 @@ struct XcdWork {
 };
 
 struct LdsGroup;
+struct LdsOctet;
 struct DevicePlan {
     int device = -1;
     int32_t* col = nullptr;
@@ -112,13 +133,22 @@ struct DevicePlan {
     std::vector<Segment> split_hot_host;  // hot records in plan order (source of the per-XCD lists)
     // LDS pass over the hot pieces: 0 = not looked at yet, 1 = ready, 2 = does not apply to this plan
     int lds_state = 0;
-    int32_t *lds_members = nullptr, *lds_group_off = nullptr, *lds_rec_row = nullptr, *lds_rec_slot = nullptr;
+    int32_t *lds_members = nullptr, *lds_group_off = nullptr, *lds_list_of_set = nullptr, *lds_col = nullptr, *lds_wave_cut = nullptr;
+    LdsOctet* lds_octets = nullptr;
+    int64_t lds_octet_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    std::vector<int64_t> lds_set_reads;  // per set: reads of its groups (octets are dealt per column count)
+    int lds_octets_strips = 0;           // the strip count lds_octets was dealt for
+    Segment* lds_cold = nullptr;    // the segments' other parts in position order
+    float* lds_edge_ws = nullptr;   // per-edge weights in lds_col's order (sym operator)
+    float* lds_planes = nullptr;
+    float* lds_packed = nullptr;    // the lists' rows strip by strip (rewritten every hop)
+    int64_t lds_num_members = 0;
+    int64_t lds_planes_strips = 0;  // planes allocated
+    int32_t lds_num_sets = 0;
     int64_t* lds_member_off = nullptr;
     LdsGroup* lds_groups = nullptr;
     uint16_t* lds_ids = nullptr;
     int32_t lds_max_members = 0;
-    SplitRow* lds_fixup_rows = nullptr;
-    int64_t lds_num_fixup_rows = 0;
     std::vector<void*> retired;  // buffers that were outgrown: freed with the plan, never while work may still use them
 };
 
@@ -147,6 +177,9 @@ struct gp_plan {
 
     mutable std::mutex mu;
     mutable gp::RowClusters clusters;  // made on first use (under mu)
+    // what the split schedule calls hot: 0 = not decided yet, 1 = the row's own cluster, 2 = the hubs, 3 = nothing
+    mutable int hot_mode = 0;
+    mutable gp::HotSets hot_sets;
     mutable gp::DevicePlan dev;
     // streamed schedule: pinned host mirror of col (made on first use) and the state kept
     // from one streamed call to the next (gp_stream.cpp owns both)
@@ -164,67 +197,94 @@ gp_status cut_schedule(const gp_plan& plan, const std::vector<int64_t>& block_of
 void cluster_rows(const gp_plan& P, RowClusters& C);
 void build_xcd_lists(const gp_plan& P, const std::vector<Segment>& segs, const RowClusters& C, int S, int slice_elems, int d,
                      std::vector<Segment>& recs, int64_t off[9]);
-// The plan's segments cut into records that gather inside the row's cluster (hot) and records
-// that gather outside it (cold), with a column list reordered to match (gp_cluster.cpp).
+HotSets hot_sets_from_clusters(const RowClusters& C);
+// the `hubs` most popular source rows; sets of about rows_per_set consecutive rows
+HotSets hot_sets_from_hubs(const gp_plan& P, int32_t hubs, int64_t rows_per_set);
+
+// The plan's segments cut into records that gather from hot rows and records that gather
+// from the others (cold), with a column list reordered to match (gp_cluster.cpp).
 struct SplitSchedule {
     std::vector<int32_t> col;
     std::vector<Segment> hot, cold;
     std::vector<SplitRow> split;
     int64_t num_slots = 0;
 };
-void build_split_schedule(const gp_plan& P, const RowClusters& C, SplitSchedule& out);
+void build_split_schedule(const gp_plan& P, const HotSets& H, SplitSchedule& out);
 
-// The hot pieces arranged for the LDS pass (gp_cluster.cpp builds it, gp_hot_lds.hip runs it): a
-// cluster's source rows are staged in LDS one strip of four fp32 columns at a time, and
-// its hot records, 64 to a group (one per lane, longest first), gather from there.
+// The hot non-zeros arranged for the LDS pass (gp_cluster.cpp builds it, gp_hot_lds.hip runs it):
+// a list's rows are staged in LDS one strip of four fp32 columns at a time, and the hot
+// parts of the segments of a set that gathers from it, 64 to a group (one per lane, longest
+// first), are added up from there into planes: plane t holds, for every position (a
+// segment's place in the pass's own order), the four sums of strip t.  The segment kernel
+// then takes the segments' other non-zeros in position order and adds the plane entries.
+constexpr int kWaveCuts = 16;  // runs a set's groups are cut into (one per wave of a 1024-thread workgroup, two per wave of a 512-thread one)
+constexpr uint8_t kAddPlaneEntry = 0x80;  // in a record's slice byte (implicit lists): add the plane entry of the record's list position
 constexpr int kLdsBytesPerCu = 160 * 1024;
 constexpr int kLdsMaxMembers = 10192;  // (rows rounded up to 16, + 16 zero rows) x 16 bytes and a few words must fit the LDS
 struct LdsGroup {
-    int64_t id_off;  // first of its steps x 64 local source indices; 8 consecutive steps of a lane lie together
-    int32_t steps;   // multiple of 8; shorter records are padded with reads of zero rows
-    int32_t pad;
+    int64_t id_off;     // first of its steps x 64 places; 8 consecutive steps of a lane lie together
+    int64_t first_pos;  // lane l fills the plane entries of position first_pos + l, l < count
+    int32_t steps;      // multiple of 8; shorter segments are padded with reads of zero rows
+    int32_t count;      // lanes that have a segment (the others read zero rows only)
+};
+// One work unit of the pass: eight consecutive strips (an octet) of one set.
+struct LdsOctet {
+    int32_t set, octet;
 };
 struct LdsSchedule {
-    std::vector<int32_t> members;     // rows of cluster c, ascending: members[member_off[c] .. member_off[c+1])
-    std::vector<int64_t> member_off;  // num + 1
-    std::vector<int32_t> group_off;   // num + 1: groups of cluster c
-    std::vector<LdsGroup> groups;
-    // 64 per group: where lane l's sum goes (row -1: no record).  slot >= 0: that partial row; -1: the
-    // output row; <= -2: the output row, after adding partial row -2 - slot (written by the cold launch)
-    std::vector<int32_t> rec_row, rec_slot;
-    std::vector<SplitRow> fixup_rows;  // the cut rows this pass does not finish itself
+    std::vector<int32_t> col;         // the column list, every segment's hot non-zeros first
+    std::vector<Segment> cold;        // every segment's other non-zeros, in position order; slice = kAddPlaneEntry where it has hot ones
+    std::vector<int32_t> members;     // rows of list l, ascending: members[member_off[l] .. member_off[l+1])
+    std::vector<int64_t> member_off;  // num_lists + 1
+    std::vector<int32_t> list_of_set; // num_sets
+    std::vector<int32_t> group_off;   // num_sets + 1: groups of set c
+    std::vector<int32_t> wave_cut;    // kWaveCuts + 1 per set: its groups cut into runs of about equal length in reads
+    std::vector<LdsGroup> groups;     // and a sentinel whose id_off is the length of ids
+    std::vector<int64_t> set_reads;   // per set: reads of its groups, padding included
     std::vector<uint16_t> ids;
-    int32_t max_members = 0;  // largest cluster that has hot records
+    int32_t max_members = 0;  // longest list that hot non-zeros gather from
     int64_t hot_edges = 0;
     bool conflict_free = false;  // reads ordered so that the lanes of one LDS pass hit different banks
 };
 // Rows a strip occupies in LDS for a cluster of m rows: the rows, rounded up to 16, and 16 zero
 // rows (one per bank group) that padding reads point at.
-constexpr double kLdsMaxPadding = 0.3;  // padding reads the automatic choice accepts, as a share of the hot non-zeros
+// Measured on config 4 (4,660-row clusters, rows of 441 hot non-zeros): reads in column-list order
+// come out of LDS at 46.7 TB/s, in conflict-free order at 89 TB/s, and the same rows out of the L2s
+// (per-XCD lists) at 22.9 TB/s; rows that miss the L2s arrive at about 7 TB/s.
+constexpr double kLdsConflictFreeGain = 1.9;
+constexpr double kLdsMaxCostClusters = 1.8;  // reads (in column-list-order equivalents) per hot non-zero beyond which the L2 lists are as fast
+constexpr double kLdsMaxCostHubs = 4.0;      // ... beyond which gathering the hubs from memory is as fast
 inline int64_t lds_rows(int64_t m) { return (m + 15) / 16 * 16 + 16; }
-// false (and `out` unspecified) where the pass does not apply: a cluster with hot records is
-// too large for the LDS, or padding would add more than `max_padding` of the hot non-zeros.
-// order: 0 = conflict-free if its padding is acceptable, else the column list's; 1 = the
-// column list's; 2 = conflict-free.
-bool build_lds_schedule(const gp_plan& P, const RowClusters& C, const SplitSchedule& S, double max_padding, int order,
-                        LdsSchedule& out);
+// false (and `out` unspecified) where the pass does not apply: a list that hot records gather
+// from is too long for the LDS, or the reads (padding included; a conflict-free read counts
+// 1 / kLdsConflictFreeGain) exceed max_cost per hot non-zero.
+// order: 0 = the cheaper of the two; 1 = the column list's; 2 = conflict-free.
+bool build_lds_schedule(const gp_plan& P, const HotSets& H, double max_cost, int order, LdsSchedule& out);
+// The (set, octet) pairs of a launch over rows of `strips` strips, dealt to the 8 XCDs: set by set, every
+// octet to the XCD with the least work so far (work = the set's reads times the octet's strips), so that the
+// strips of a set run on all XCDs at about the same time, each XCD streaming the set's index list for a few
+// octets at once.
+void deal_lds_octets(const std::vector<int64_t>& set_reads, int strips, std::vector<LdsOctet>& octets, int64_t (&off)[9]);
 struct HotLdsArgs {
     // DEVICE arrays of the schedule
     const int32_t* members;
     const int64_t* member_off;
+    const int32_t* list_of_set;
     const int32_t* group_off;
+    const int32_t* wave_cut;
     const LdsGroup* groups;
-    const int32_t *rec_row, *rec_slot;
+    const LdsOctet* octets;   // DEVICE
+    const int64_t* octet_off; // HOST, 9 entries: XCD x takes octets [octet_off[x], octet_off[x+1])
     const uint16_t* ids;
-    int32_t num_clusters, max_members;
+    int32_t num_sets, max_members;
     const float* src_scale;  // DEVICE n weights applied to source rows, or nullptr
-    const float* row_scale;  // DEVICE n scales applied to rows stored whole, or nullptr
     const float* xin;
     int64_t ldin;
-    float* xout;
-    int64_t ldout;
-    float* carry;
-    int64_t carry_ld;
+    float* planes;           // DEVICE ceil(d / 32) planes of num_pos entries of 8 x 4 floats (an octet of strips)
+    int64_t num_pos;
+    float* packed;           // DEVICE scratch, ceil(d / 4) x num_members x 4 floats: the lists' rows strip by strip;
+                             // nullptr: strips are staged straight from xin
+    int64_t num_members;     // rows on all lists together
     int32_t d;
     unsigned long long* ctrl;  // as HopArgs::ctrl
 };
@@ -281,6 +341,10 @@ struct HopArgs {
     int64_t column_slices = 0;
     int64_t persistent_blocks = 0;  // workgroups of the launch, 0 = as many as stay resident
     int64_t column_tile = 0;        // feature columns per kernel pass, 0 = automatic
+    // optional plane entries (fp32 storage, vectors of 4, implicit lists): a record whose slice byte is
+    // kAddPlaneEntry adds planes[((v / 8) * num_pos + p) * 32 + (v % 8) * 4 ..] to its vector v, p being its place in segs
+    const float* planes = nullptr;
+    int64_t num_pos = 0;
     // optional running combination: comb[row] += gamma * result row (fp32, leading dimension ldc);
     // xout may then be nullptr (result row not stored)
     float* comb = nullptr;

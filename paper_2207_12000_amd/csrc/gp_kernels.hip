@@ -232,7 +232,8 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
                                                             T* __restrict__ xout, int64_t ldout,
                                                             float* __restrict__ carry, int64_t carry_ld, int d,
                                                             int num_slices, int slice_elems, float* __restrict__ comb,
-                                                            int64_t ldc, float gamma)
+                                                            int64_t ldc, float gamma, const float* __restrict__ planes,
+                                                            int64_t num_pos, int run_log2)
 {
     constexpr int GPB = kThreads / G;
     constexpr int PF = G >= 32 ? 1 : 32 / G;  // column ids each lane prefetches per segment
@@ -243,7 +244,10 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     constexpr int NACC = sizeof(T) == 2 ? 2 : 4;
     const int lane = threadIdx.x % G;
     const int xcd = blockIdx.x & 7;
-    // this XCD's list: record of position p is segs[base + p * rstep], p < count
+    // This XCD's list: the record of position p < count is segs[place_of(p)].  Implicit lists: the
+    // XCDs that share a slice take the records interleaved, in runs of 2^run_log2 consecutive records
+    // (1 as a rule; 8 where records add plane entries: 8 consecutive entries are one line, which then
+    // only one XCD asks for).
     int64_t base, count;
     int rstep, xcd_slice;
     if (lists.explicit_lists) {
@@ -254,10 +258,19 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     } else {
         const int reps = 8 / num_slices;  // num_slices is 1, 2, 4 or 8 here
         base = xcd / num_slices;
-        count = num_segs > base ? (num_segs - base + reps - 1) / reps : 0;
+        const int64_t run = (int64_t)1 << run_log2;
+        const int64_t runs = (num_segs + run - 1) >> run_log2;                       // of all XCDs
+        const int64_t mine = runs > base ? (runs - base + reps - 1) / reps : 0;      // of this one
+        count = mine << run_log2;
+        if (mine > 0 && base + (mine - 1) * reps == runs - 1) count -= runs * run - num_segs;  // the last run may be short
         rstep = reps;
         xcd_slice = xcd & (num_slices - 1);
     }
+    const int64_t run_mask = ((int64_t)1 << run_log2) - 1;
+    auto place_of = [&](int64_t p) -> int64_t {
+        if (lists.explicit_lists) return base + p;
+        return ((((p >> run_log2) * rstep) + base) << run_log2) + (p & run_mask);
+    };
     // Positions of this group, in the order it visits them.  A chunk is chunk_records
     // consecutive positions; chunk numbers below `groups` are fixed (the group's own
     // number), later ones come from the XCD's cursor.  chunk_records == 0: fixed shares.
@@ -283,11 +296,11 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         return pos;
     };
 
-    const v4i* sp = reinterpret_cast<const v4i*>(segs) + base;
+    const v4i* sp = reinterpret_cast<const v4i*>(segs);
     const v4i none = {0, 0, 0, -1};  // length 0: nothing to fetch
     int64_t t0 = pos, t1 = advance(), t2 = advance();
-    SegRegs s0 = unpack_segment(t0 < count ? sp[t0 * rstep] : none, col_base);
-    v4i raw1 = t1 < count ? sp[t1 * rstep] : none;
+    SegRegs s0 = unpack_segment(t0 < count ? sp[place_of(t0)] : none, col_base);
+    v4i raw1 = t1 < count ? sp[place_of(t1)] : none;
     int c0[PF];
     float w0[PF];
 #pragma unroll
@@ -303,7 +316,7 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         // ---- requests for the segments to come -----------------------------------
         const int64_t t3 = advance();
         const SegRegs s1 = unpack_segment(raw1, col_base);
-        const v4i raw2 = t2 < count ? sp[t2 * rstep] : none;
+        const v4i raw2 = t2 < count ? sp[place_of(t2)] : none;
         int c1[PF];
         float w1[PF];
 #pragma unroll
@@ -482,16 +495,30 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
 
         const bool partial = r.slot >= 0;
         const float rs = (!partial && row_scale) ? row_scale[r.row] : 1.0f;
+        // what an earlier launch has already added up for this record (the sums of its other non-zeros,
+        // four columns to an entry, one plane per vector of the row) joins the sum here
+        bool planed = false;
+        if constexpr (VEC == 4 && sizeof(T) == 4) planed = planes != nullptr && (r.slice & kAddPlaneEntry) != 0;
+        const int64_t place = place_of(t0);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
             if (!live[v]) continue;
             float o[VEC];
+            float before[VEC];
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) before[i] = 0.0f;
+            if constexpr (VEC == 4 && sizeof(T) == 4) {
+                if (planed) {  // entries are kept eight vectors (an octet of strips, one 128-byte line) together
+                    const int j = vlo + v * G + lane;
+                    Row<float, VEC>::load(planes + ((int64_t)(j >> 3) * num_pos + place) * 32 + (j & 7) * 4, before);
+                }
+            }
 #pragma unroll
             for (int i = 0; i < VEC; ++i) {
                 float t = acc[0][v][i];
                 if constexpr (NACC == 2) t += acc[1][v][i];
                 if constexpr (NACC == 4) t = (t + acc[1][v][i]) + (acc[2][v][i] + acc[3][v][i]);
-                o[i] = t * rs;
+                o[i] = (t + before[i]) * rs;
             }
             if (partial) {
                 Row<float, VEC>::store(carry + (int64_t)r.slot * carry_ld + coff[v], o);
@@ -701,15 +728,15 @@ gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
     if (a.edge_w && a.edge_w_per_edge)
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 2>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, chunk_records, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma, a.planes, a.num_pos, a.planes ? 3 : 0);
     else if (a.edge_w)
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 1>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, chunk_records, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma, a.planes, a.num_pos, a.planes ? 3 : 0);
     else
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 0>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, chunk_records, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma, a.planes, a.num_pos, a.planes ? 3 : 0);
     GP_HIP(hipGetLastError());
     return GP_OK;
 }

@@ -38,8 +38,9 @@ void release(DevicePlan& D)
     (void)hipFree(D.split_edge_ws);
     (void)hipFree(D.split_cold);
     (void)hipFree(D.split_rows);
-    for (void* q : {(void*)D.lds_members, (void*)D.lds_member_off, (void*)D.lds_group_off, (void*)D.lds_groups, (void*)D.lds_rec_row,
-                    (void*)D.lds_rec_slot, (void*)D.lds_ids, (void*)D.lds_fixup_rows})
+    for (void* q : {(void*)D.lds_members, (void*)D.lds_member_off, (void*)D.lds_group_off, (void*)D.lds_groups, (void*)D.lds_octets,
+                    (void*)D.lds_ids, (void*)D.lds_list_of_set, (void*)D.lds_col, (void*)D.lds_cold, (void*)D.lds_planes,
+                    (void*)D.lds_wave_cut, (void*)D.lds_packed})
         (void)hipFree(q);
     (void)hipFree(D.split_carry);
     D = DevicePlan();
@@ -179,48 +180,56 @@ gp_status upload_now(T*& dptr, const std::vector<T>& h, hipStream_t stream)
     return GP_OK;
 }
 
+// What this plan's split schedule calls hot (plan->mu held; decided once per plan, from the graph
+// and the plan's options): its row clusters if it has them, else its most popular rows if
+// they are the source of enough non-zeros to be worth a launch of their own, else nothing.
+constexpr double kMinHubFraction = 0.15;
+constexpr double kMinHubWork = 2e9;  // non-zeros x columns below which the pass's launches cost more than they save
+void decide_hot_mode(const gp_plan* plan, int32_t d)
+{
+    if (plan->hot_mode != 0) return;
+    plan->hot_mode = 3;
+    if (plan->opt.cache_schedule == 2 || plan->segs.empty()) return;
+    if (!plan->clusters.ready) cluster_rows(*plan, plan->clusters);
+    const RowClusters& C = plan->clusters;
+    // clusters count if a typical one could be kept close at all: its rows' narrowest slices (one line)
+    // in the share of an L2 the schedule counts on
+    const bool small_enough = C.typical_rows * (double)kLineBytes <= kL2Share * (double)l2_bytes_per_xcd();
+    if (plan->opt.cache_schedule == 1 || (C.num >= 2 && C.inside_fraction >= 0.5 && small_enough)) {
+        plan->hot_sets = hot_sets_from_clusters(C);
+        plan->hot_mode = 1;
+        return;
+    }
+    const bool forced = plan->opt.hub_pass == 1;
+    if (plan->opt.hub_pass == 2 || plan->opt.lds_pass == 2 || plan->opt.split_records == 2) return;
+    if (!forced && (double)plan->nnz * (double)d < kMinHubWork) return;
+    // about 2048 work items (set x strip) per launch, sets of at least 1024 rows
+    const int64_t strips = ((int64_t)d + 3) / 4;
+    const int64_t sets = std::max<int64_t>(1, 2048 / strips);
+    const int64_t rows_per_set = std::max<int64_t>(1024, (plan->n + sets - 1) / sets);
+    HotSets H = hot_sets_from_hubs(*plan, kLdsMaxMembers, rows_per_set);
+    if (!forced && H.hot_fraction < kMinHubFraction) return;
+    plan->hot_sets = std::move(H);
+    plan->hot_mode = 2;
+}
+
 // The split schedule on the device (plan->mu held): reordered column list, cold records,
 // the rows that own partial rows, and a partial-row buffer wide enough for d columns.
-gp_status ensure_split(const gp_plan* plan, int32_t d, bool want_edge_weights, bool want_lds, hipStream_t stream)
+gp_status ensure_split(const gp_plan* plan, int32_t d, bool want_edge_weights, hipStream_t stream)
 {
     DevicePlan& D = plan->dev;
     gp_status st;
-    if (plan->opt.lds_pass == 2) D.lds_state = 2;
-    if (!D.split_ready || (want_lds && D.lds_state == 0)) {
+    if (!D.split_ready) {
         SplitSchedule sch;
-        build_split_schedule(*plan, plan->clusters, sch);
+        build_split_schedule(*plan, plan->hot_sets, sch);
         if (sch.num_slots > INT32_MAX) return fail(GP_ERR_OVERFLOW, "%lld partial rows exceed int32", (long long)sch.num_slots);
-        if (!D.split_ready) {
-            if ((st = upload_now(D.split_col, sch.col, stream)) != GP_OK || (st = upload_now(D.split_cold, sch.cold, stream)) != GP_OK ||
-                (st = upload_now(D.split_rows, sch.split, stream)) != GP_OK)
-                return st;
-            D.split_num_cold = (int64_t)sch.cold.size();
-            D.split_num_rows = (int64_t)sch.split.size();
-            D.split_num_slots = sch.num_slots;
-        }
-        if (want_lds && D.lds_state == 0) {
-            // Padding of the record groups is work without result: beyond kLdsMaxPadding of the
-            // hot non-zeros the per-XCD lists are the better schedule (unless the pass is forced).
-            LdsSchedule L;
-            const bool forced = plan->opt.lds_pass == 1 || plan->opt.lds_pass == 3;
-            if (build_lds_schedule(*plan, plan->clusters, sch, forced ? 16.0 : kLdsMaxPadding,
-                                   plan->opt.lds_pass == 1 ? 2 : plan->opt.lds_pass == 3 ? 1 : 0, L)) {
-                if ((st = upload_now(D.lds_members, L.members, stream)) != GP_OK ||
-                    (st = upload_now(D.lds_member_off, L.member_off, stream)) != GP_OK ||
-                    (st = upload_now(D.lds_group_off, L.group_off, stream)) != GP_OK ||
-                    (st = upload_now(D.lds_groups, L.groups, stream)) != GP_OK ||
-                    (st = upload_now(D.lds_rec_row, L.rec_row, stream)) != GP_OK ||
-                    (st = upload_now(D.lds_rec_slot, L.rec_slot, stream)) != GP_OK || (st = upload_now(D.lds_ids, L.ids, stream)) != GP_OK ||
-                    (st = upload_now(D.lds_fixup_rows, L.fixup_rows, stream)) != GP_OK)
-                    return st;
-                D.lds_num_fixup_rows = (int64_t)L.fixup_rows.size();
-                D.lds_max_members = L.max_members;
-                D.lds_state = 1;
-            } else {
-                D.lds_state = 2;
-            }
-        }
-        if (!D.split_ready) D.split_hot_host.swap(sch.hot);
+        if ((st = upload_now(D.split_col, sch.col, stream)) != GP_OK || (st = upload_now(D.split_cold, sch.cold, stream)) != GP_OK ||
+            (st = upload_now(D.split_rows, sch.split, stream)) != GP_OK)
+            return st;
+        D.split_num_cold = (int64_t)sch.cold.size();
+        D.split_num_rows = (int64_t)sch.split.size();
+        D.split_num_slots = sch.num_slots;
+        D.split_hot_host.swap(sch.hot);
         D.split_ready = true;
     }
     if (want_edge_weights && !D.split_edge_ws && plan->nnz > 0) {
@@ -235,6 +244,62 @@ gp_status ensure_split(const gp_plan* plan, int32_t d, bool want_edge_weights, b
         D.split_carry_ld = 0;
         GP_HIP(hipMalloc((void**)&D.split_carry, (size_t)D.split_num_slots * need_ld * sizeof(float)));
         D.split_carry_ld = need_ld;
+    }
+    return GP_OK;
+}
+
+// The LDS pass's schedule on the device (plan->mu held), and planes for rows of d columns.
+// D.lds_state says afterwards whether the pass applies to this plan (1) or not (2).
+gp_status ensure_lds(const gp_plan* plan, int32_t d, hipStream_t stream)
+{
+    DevicePlan& D = plan->dev;
+    gp_status st;
+    if (plan->opt.lds_pass == 2) D.lds_state = 2;
+    if (D.lds_state == 0) {
+        // Padding of the groups is work without result: beyond a limit the per-XCD lists (clusters)
+        // or plain gathers from memory (hubs) are the better schedule, unless the pass is forced.
+        const bool forced = plan->opt.lds_pass == 1 || plan->opt.lds_pass == 3;
+        const double limit = plan->hot_mode == 2 ? kLdsMaxCostHubs : kLdsMaxCostClusters;
+        LdsSchedule L;
+        if (build_lds_schedule(*plan, plan->hot_sets, forced ? 64.0 : limit, plan->opt.lds_pass == 1 ? 2 : plan->opt.lds_pass == 3 ? 1 : 0,
+                               L)) {
+            if ((st = upload_now(D.lds_col, L.col, stream)) != GP_OK || (st = upload_now(D.lds_cold, L.cold, stream)) != GP_OK ||
+                (st = upload_now(D.lds_members, L.members, stream)) != GP_OK ||
+                (st = upload_now(D.lds_member_off, L.member_off, stream)) != GP_OK ||
+                (st = upload_now(D.lds_list_of_set, L.list_of_set, stream)) != GP_OK ||
+                (st = upload_now(D.lds_group_off, L.group_off, stream)) != GP_OK ||
+                (st = upload_now(D.lds_wave_cut, L.wave_cut, stream)) != GP_OK ||
+                (st = upload_now(D.lds_groups, L.groups, stream)) != GP_OK || (st = upload_now(D.lds_ids, L.ids, stream)) != GP_OK)
+                return st;
+            D.lds_set_reads = L.set_reads;
+            D.lds_max_members = L.max_members;
+            D.lds_num_members = (int64_t)L.members.size();
+            D.lds_num_sets = (int32_t)L.list_of_set.size();
+            D.lds_state = 1;
+        } else {
+            D.lds_state = 2;
+        }
+    }
+    const int64_t strips = ((int64_t)d + 3) / 4;
+    if (D.lds_state == 1 && (int)strips != D.lds_octets_strips) {
+        // the launch's work units for rows of this many strips
+        std::vector<LdsOctet> octets;
+        deal_lds_octets(D.lds_set_reads, (int)strips, octets, D.lds_octet_off);
+        if (D.lds_octets) D.retired.push_back(D.lds_octets);
+        D.lds_octets = nullptr;
+        D.lds_octets_strips = 0;
+        if ((st = upload_now(D.lds_octets, octets, stream)) != GP_OK) return st;
+        D.lds_octets_strips = (int)strips;
+    }
+    if (D.lds_state == 1 && strips > D.lds_planes_strips) {
+        if (D.lds_planes) D.retired.push_back(D.lds_planes);
+        if (D.lds_packed) D.retired.push_back(D.lds_packed);
+        D.lds_planes = D.lds_packed = nullptr;
+        D.lds_planes_strips = 0;
+        GP_HIP(hipMalloc((void**)&D.lds_planes, (size_t)((strips + 7) / 8) * plan->segs.size() * 32 * sizeof(float)));
+        // lists that several sets stage (the hubs) are packed strip by strip once per hop
+        if (plan->hot_mode == 2) GP_HIP(hipMalloc((void**)&D.lds_packed, (size_t)strips * (size_t)D.lds_num_members * 4 * sizeof(float)));
+        D.lds_planes_strips = strips;
     }
     return GP_OK;
 }
@@ -255,22 +320,30 @@ gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream,
         return GP_OK;
     std::lock_guard<std::mutex> lk(plan->mu);
     int S = 0, elems = 0;
-    if (!may_build && !plan->clusters.ready) return GP_OK;  // nothing built yet: implicit lists
-    if (!choose_cache_schedule(plan, a.d, es, vec, S, elems)) return GP_OK;
+    if (!may_build && plan->hot_mode == 0) return GP_OK;  // nothing built yet: implicit lists
+    decide_hot_mode(plan, a.d);
     DevicePlan& D = plan->dev;
+    // the hot pieces can come out of LDS: fp32 rows of at least one strip, a plain hop
+    const bool lds_call = lds && may_build && a.dtype == GP_F32 && a.d >= 4 && !a.comb && a.xout && plan->opt.lds_pass != 2 &&
+                          plan->opt.split_records != 2;
+    // the LDS pass: wherever the plan's lists are short enough for it (the plan's clusters, or its hubs)
+    if (lds_call && (plan->hot_mode == 1 || plan->hot_mode == 2)) {
+        gp_status st = ensure_lds(plan, a.d, stream);
+        if (st != GP_OK) return st;
+        if (D.lds_state == 1) {
+            *lds = true;
+            return GP_OK;
+        }
+    }
+    // no clusters: nothing an L2 could be made to hold
+    if (plan->hot_mode != 1 || !choose_cache_schedule(plan, a.d, es, vec, S, elems)) return GP_OK;
     // hot and cold pieces in phases of their own need buffers of their own: only where the caller may allocate
     // (not worth it when hardly anything leaves the clusters: every row then pays two partial rows for nothing)
     const bool want_split = split && may_build && plan->opt.split_records != 2 &&
                             (plan->opt.split_records == 1 || plan->clusters.inside_fraction < 0.98);
     if (want_split) {
-        // the hot pieces can come out of LDS: fp32 rows of at least one strip, a plain hop
-        const bool want_lds = lds && a.dtype == GP_F32 && a.d >= 4 && !a.comb && a.xout && plan->opt.lds_pass != 2;
-        gp_status st = ensure_split(plan, a.d, a.edge_w != nullptr, want_lds, stream);
+        gp_status st = ensure_split(plan, a.d, a.edge_w != nullptr, stream);
         if (st != GP_OK) return st;
-        if (want_lds && D.lds_state == 1) {
-            *split = *lds = true;
-            return GP_OK;
-        }
     }
     const XcdWork* found = nullptr;
     for (const XcdWork& w : D.work)
@@ -426,38 +499,50 @@ gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t
             if (cold.num_segs > 0 && (st = hop_passes(cold, stream)) != GP_OK) return st;
         }
         if (lds) {
+            // The non-zeros whose source is on a list first, out of LDS, into the planes; then the
+            // segment kernel over the other non-zeros, in the same order of segments, adding the
+            // plane entries and finishing every segment as the plan says.
             HotLdsArgs h;
             h.members = D.lds_members;
             h.member_off = D.lds_member_off;
+            h.list_of_set = D.lds_list_of_set;
             h.group_off = D.lds_group_off;
+            h.wave_cut = D.lds_wave_cut;
             h.groups = D.lds_groups;
-            h.rec_row = D.lds_rec_row;
-            h.rec_slot = D.lds_rec_slot;
+            h.octets = D.lds_octets;
+            h.octet_off = D.lds_octet_off;
             h.ids = D.lds_ids;
-            h.num_clusters = plan->clusters.num;
+            h.num_sets = D.lds_num_sets;
             h.max_members = D.lds_max_members;
             h.src_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : nullptr;
-            h.row_scale = row_scale;
             h.xin = (const float*)a.xin;
             h.ldin = a.ldin;
-            h.xout = (float*)a.xout;
-            h.ldout = a.ldout;
-            h.carry = D.split_carry;
-            h.carry_ld = D.split_carry_ld;
+            h.planes = D.lds_planes;
+            h.num_pos = (int64_t)plan->segs.size();
+            h.packed = D.lds_packed;
+            h.num_members = D.lds_num_members;
             h.d = d;
             h.ctrl = ctrl;
             profile_begin("gp_hop_cluster_lds", stream);
             st = launch_hot_lds(h, stream);
             profile_end(stream);
             if (st != GP_OK) return st;
+            a.segs = D.lds_cold;
+            a.col = D.lds_col;
+            if (a.edge_w) {  // weights by column id: the per-edge array follows the plan's column order
+                a.edge_w = D.dinv_sqrt;
+                a.edge_w_per_edge = false;
+            }
+            a.planes = D.lds_planes;
+            a.num_pos = h.num_pos;
+            if ((st = hop_passes(a, stream)) != GP_OK) return st;
         } else if ((st = hop_passes(a, stream)) != GP_OK) {
             return st;
         }
-        // (the LDS launch finishes rows made of one hot and one cold piece itself)
-        if (lds ? D.lds_num_fixup_rows > 0 : split ? D.split_num_rows > 0 : !plan->split.empty()) {
+        if (split ? D.split_num_rows > 0 : !plan->split.empty()) {
             FixupArgs f;
-            f.split = lds ? D.lds_fixup_rows : split ? D.split_rows : D.split;
-            f.num_split = lds ? D.lds_num_fixup_rows : split ? D.split_num_rows : (int64_t)plan->split.size();
+            f.split = split ? D.split_rows : D.split;
+            f.num_split = split ? D.split_num_rows : (int64_t)plan->split.size();
             f.carry = split ? D.split_carry : carry;
             f.carry_ld = split ? D.split_carry_ld : carry_ld;
             f.row_scale = row_scale;
@@ -620,40 +705,52 @@ extern "C" gp_status gp_plan_work_lists(const gp_plan* plan, int32_t d, gp_dtype
     return GP_OK;
 }
 
-extern "C" gp_status gp_plan_lds_schedule(const gp_plan* plan, int32_t order, int64_t* num_groups, int64_t* num_ids,
-                                          int32_t* conflict_free, int32_t* group_cluster, int64_t* group_id_off,
-                                          int32_t* group_steps, int32_t* rec_row, int32_t* rec_slot, uint16_t* ids,
-                                          int64_t group_capacity, int64_t id_capacity)
+extern "C" gp_status gp_plan_lds_schedule(const gp_plan* plan, int32_t d, int32_t order, gp_lds_view* v)
 {
-    if (!plan || !num_groups || !num_ids || !conflict_free) return fail(GP_ERR_INVALID_ARG, "NULL argument");
+    if (!plan || !v) return fail(GP_ERR_INVALID_ARG, "NULL argument");
     if (order < 0 || order > 2) return fail(GP_ERR_INVALID_ARG, "order must be 0, 1 or 2");
+    if (d < 4) return fail(GP_ERR_INVALID_ARG, "d = %d: the pass needs at least four columns", d);
     try {
         std::lock_guard<std::mutex> lk(plan->mu);
-        *num_groups = *num_ids = 0;
-        *conflict_free = 0;
-        if (plan->segs.empty()) return GP_OK;
-        if (!plan->clusters.ready) cluster_rows(*plan, plan->clusters);
-        SplitSchedule sch;
-        build_split_schedule(*plan, plan->clusters, sch);
+        v->num_groups = v->num_ids = v->num_members = v->num_positions = 0;
+        v->num_sets = v->num_lists = v->conflict_free = v->hot_mode = 0;
+        decide_hot_mode(plan, d);
+        if (plan->hot_mode != 1 && plan->hot_mode != 2) return GP_OK;
         LdsSchedule L;
-        if (!build_lds_schedule(*plan, plan->clusters, sch, order == 0 ? kLdsMaxPadding : 16.0, order, L)) return GP_OK;
-        *num_groups = (int64_t)L.groups.size();
-        *num_ids = (int64_t)L.ids.size();
-        *conflict_free = L.conflict_free ? 1 : 0;
-        const bool want = group_cluster || group_id_off || group_steps || rec_row || rec_slot || ids;
-        if (!want) return GP_OK;
-        if (group_capacity < *num_groups || id_capacity < *num_ids)
-            return fail(GP_ERR_INVALID_ARG, "room for %lld groups and %lld ids, the schedule has %lld and %lld", (long long)group_capacity,
-                        (long long)id_capacity, (long long)*num_groups, (long long)*num_ids);
-        for (int32_t c = 0; c < plan->clusters.num; ++c)
+        const double limit = plan->hot_mode == 2 ? kLdsMaxCostHubs : kLdsMaxCostClusters;
+        if (!build_lds_schedule(*plan, plan->hot_sets, order == 0 ? limit : 64.0, order, L)) return GP_OK;
+        v->hot_mode = plan->hot_mode;
+        v->num_groups = (int64_t)L.groups.size() - 1;  // (without the sentinel)
+        v->num_ids = (int64_t)L.ids.size();
+        v->num_members = (int64_t)L.members.size();
+        v->num_positions = (int64_t)L.cold.size();
+        v->num_sets = (int32_t)L.list_of_set.size();
+        v->num_lists = (int32_t)L.member_off.size() - 1;
+        v->conflict_free = L.conflict_free ? 1 : 0;
+        const bool per_group = v->group_set || v->group_id_off || v->group_steps || v->rec_pos;
+        if ((per_group && v->group_capacity < v->num_groups) || (v->ids && v->id_capacity < v->num_ids) ||
+            (v->list_of_set && v->set_capacity < v->num_sets) || (v->member_off && v->set_capacity < v->num_lists + 1) ||
+            (v->members && v->member_capacity < v->num_members) ||
+            ((v->rest || v->col) && v->position_capacity < std::max<int64_t>(v->num_positions, v->col ? plan->nnz : 0)))
+            return fail(GP_ERR_INVALID_ARG, "an array is too small: %lld groups, %lld ids, %d sets, %d lists, %lld members, %lld positions",
+                        (long long)v->num_groups, (long long)v->num_ids, v->num_sets, v->num_lists, (long long)v->num_members,
+                        (long long)v->num_positions);
+        for (int32_t c = 0; c < v->num_sets; ++c)
             for (int32_t g = L.group_off[(size_t)c]; g < L.group_off[(size_t)c + 1]; ++g) {
-                if (group_cluster) group_cluster[g] = c;
-                if (group_id_off) group_id_off[g] = L.groups[(size_t)g].id_off;
-                if (group_steps) group_steps[g] = L.groups[(size_t)g].steps;
+                if (v->group_set) v->group_set[g] = c;
+                if (v->group_id_off) v->group_id_off[g] = L.groups[(size_t)g].id_off;
+                if (v->group_steps) v->group_steps[g] = L.groups[(size_t)g].steps;
             }
-        if (rec_row) std::copy(L.rec_row.begin(), L.rec_row.end(), rec_row);
-        if (rec_slot) std::copy(L.rec_slot.begin(), L.rec_slot.end(), rec_slot);
-        if (ids) std::copy(L.ids.begin(), L.ids.end(), ids);
+        if (v->rec_pos)
+            for (int64_t g = 0; g < v->num_groups; ++g)
+                for (int l = 0; l < 64; ++l)
+                    v->rec_pos[g * 64 + l] = l < L.groups[(size_t)g].count ? (int32_t)(L.groups[(size_t)g].first_pos + l) : -1;
+        if (v->ids) std::copy(L.ids.begin(), L.ids.end(), v->ids);
+        if (v->list_of_set) std::copy(L.list_of_set.begin(), L.list_of_set.end(), v->list_of_set);
+        if (v->member_off) std::copy(L.member_off.begin(), L.member_off.end(), v->member_off);
+        if (v->members) std::copy(L.members.begin(), L.members.end(), v->members);
+        if (v->rest) std::copy(L.cold.begin(), L.cold.end(), (Segment*)v->rest);
+        if (v->col) std::copy(L.col.begin(), L.col.end(), v->col);
     } catch (const std::exception& e) {
         return fail(GP_ERR_OOM_HOST, "gp_plan_lds_schedule: %s", e.what());
     }

@@ -277,7 +277,7 @@ def test_many_hops_and_repeated_calls_on_one_plan():
 @pytest.fixture
 def _mapping_defaults():
     yield
-    for k in ("column_slices", "persistent_blocks", "cache_schedule", "segment_edges", "split_records", "lds_pass"):
+    for k in ("column_slices", "persistent_blocks", "cache_schedule", "segment_edges", "split_records", "lds_pass", "hub_pass"):
         gp.gp_set_option(k, 0)
 
 
@@ -357,3 +357,29 @@ def test_lds_pass_matches_the_oracle(d, agg, segment_edges, order, _mapping_defa
             gp.gp_profile_enable(False)
         assert launches == 4, f"{w.name} n {w.n}: the LDS pass ran {launches} times, expected once per hop"
         assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("cfg,scale,d,agg", [(2, 0.2, 128, gp.GP_AGG_SYM), (3, 0.02, 100, gp.GP_AGG_MEAN), (2, 0.2, 37, gp.GP_AGG_SUM),
+                                             (3, 0.02, 6, gp.GP_AGG_SYM)])
+@pytest.mark.parametrize("segment_edges,order", [(0, 1), (16, 1), (0, 3)])
+def test_hub_pass_matches_the_oracle(cfg, scale, d, agg, segment_edges, order, _mapping_defaults):
+    """Power-law graphs (no row clusters): the non-zeros whose source is one of the most popular
+    rows are served from LDS, the others gathered from memory, forced on graphs smaller than
+    the automatic choice would take.  Checked against the oracle, with the LDS launch
+    counted; whole records (hub_pass = 2) and bf16 storage keep working on the same graph."""
+    w = gp_synth.make_workload(cfg, scale=scale, d=d)
+    gp.gp_set_option("segment_edges", segment_edges)
+    gp.gp_set_option("hub_pass", 1)
+    gp.gp_set_option("lds_pass", order)
+    budget = max(20_000, w.m // 3)
+    gp.gp_profile_enable(True)
+    try:
+        a = parity_case(w, K=2, dtype=gp.GP_F32, agg=agg, budget=budget)
+        launches, _ = gp.gp_profile_read("gp_hop_cluster_lds")
+        parity_case(w, K=2, dtype=gp.GP_BF16, agg=agg, budget=budget)       # bf16: no LDS pass, the segment kernel alone
+        launches_after, _ = gp.gp_profile_read("gp_hop_cluster_lds")
+    finally:
+        gp.gp_profile_enable(False)
+    assert launches == 2 and launches_after == 2, f"the LDS pass ran {launches} / {launches_after} times, expected once per fp32 hop"
+    gp.gp_set_option("hub_pass", 2)
+    parity_case(w, K=2, dtype=gp.GP_F32, agg=agg, budget=budget)

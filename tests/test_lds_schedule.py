@@ -1,5 +1,6 @@
-"""Host logic of the LDS pass (no GPU): the schedule that orders the in-cluster reads of
-every record is checked against the plan's own CSR and row clusters."""
+"""Host logic of the LDS pass (no GPU): the schedule that cuts every segment into the non-zeros
+served from LDS and the others, and orders the LDS reads, is checked against the plan's own
+CSR, segments and row clusters."""
 import numpy as np
 import pytest
 
@@ -24,91 +25,135 @@ def community_plan(n_comm, comm, pairs, seed, budget=None, segment_edges=0):
         gp.gp_set_option("segment_edges", 0)
 
 
-def decode(plan, sched):
-    """(row -> sorted in-cluster sources read for it, padding reads, steps x lanes table per group)."""
-    label, num, _, _ = plan.row_clusters()
-    order = np.argsort(label, kind="stable")            # a cluster's rows in ascending order
-    counts = np.bincount(label, minlength=num)
-    member_off = np.concatenate([[0], np.cumsum(counts)])
-    got = {}
-    tables = []
-    for g in range(sched["group_cluster"].size):
-        c = int(sched["group_cluster"][g])
-        m = int(counts[c])
+def power_law_plan(scale, forced=False):
+    w = gp_synth.make_workload(2, scale=scale, with_features=False)    # power law: one giant cluster
+    gp.gp_set_option("hub_pass", 1 if forced else 0)
+    try:
+        return gp.gp_plan_blocks(w.src, w.dst, w.n, 10**9, w.flags)
+    finally:
+        gp.gp_set_option("hub_pass", 0)
+
+
+def tables_of(sched):
+    """Per group: (set, list length, [step, lane] table of places)."""
+    member_off, list_of_set = sched["member_off"], sched["list_of_set"]
+    out = []
+    for g in range(sched["group_set"].size):
+        c = int(sched["group_set"][g])
+        l = int(list_of_set[c])
+        m = int(member_off[l + 1] - member_off[l])
+        assert m <= 10192
         steps = int(sched["group_steps"][g])
         assert steps % 8 == 0
         off = int(sched["group_id_off"][g])
         block = sched["ids"][off:off + steps * 64].reshape(steps // 8, 64, 8)
         table = block.transpose(0, 2, 1).reshape(steps, 64)      # [step, lane]
-        tables.append((c, m, table))
         zero_lo = (m + 15) // 16 * 16
-        assert np.all((table < m) | ((table >= zero_lo) & (table < zero_lo + 16))), "an index outside the rows and the zero rows"
-        for lane in range(64):
-            row = int(sched["rec_row"][g * 64 + lane])
-            ids = table[:, lane]
-            real = ids[ids < m]
-            if row < 0:
-                assert real.size == 0, "a lane without a record reads rows"
-                continue
-            assert label[row] == c
-            got.setdefault(row, []).append(order[member_off[c] + real.astype(np.int64)])
-    return label, got, tables
+        assert np.all((table < m) | ((table >= zero_lo) & (table < zero_lo + 16))), "a place outside the list and the zero rows"
+        out.append((c, l, m, table))
+    return out
+
+
+def check_schedule(plan, sched):
+    """Every segment of the plan has one position; the reads of its lane (if any) and the rest
+    record's non-zeros are together exactly the segment's sources, the former all on the list
+    the row's set gathers from, the latter none of them; positions go set by set, most reads
+    first; a group is 64 consecutive positions of one set.  Returns the per-group tables."""
+    members, member_off, list_of_set = sched["members"], sched["member_off"], sched["list_of_set"]
+    on_list = np.full(plan.n, -1, dtype=np.int64)
+    for l in range(member_off.size - 1):
+        rows = members[member_off[l]:member_off[l + 1]]
+        assert np.all(np.diff(rows) > 0), "a list's rows are ascending"
+        on_list[rows] = l
+    segs, rest, col = plan.segments, sched["rest"], sched["col"]
+    assert rest.size == segs.size
+    start_of = lambda a: a["start_lo"].astype(np.int64) | (a["start_hi"].astype(np.int64) << 32)
+    key = lambda a: a["row"].astype(np.int64) * (2 ** 32) + (a["slot"].astype(np.int64) + 1)
+    order = np.argsort(key(segs))
+    at = order[np.searchsorted(key(segs)[order], key(rest))]          # position -> plan segment
+    assert np.array_equal(np.sort(at), np.arange(segs.size)), "positions are a permutation of the segments"
+    seg = segs[at]
+    hot_len = seg["len"].astype(np.int64) - rest["len"].astype(np.int64)
+    assert np.all(hot_len >= 0) and np.array_equal(start_of(rest), start_of(seg) + hot_len)
+    assert np.array_equal(rest["slice"] == 0x80, hot_len > 0) and np.all((rest["slice"] == 0) | (rest["slice"] == 0x80))
+    tables = tables_of(sched)
+    lane_of = {}                                                     # position -> (group, lane)
+    for g, (c, l, m, table) in enumerate(tables):
+        pos = sched["rec_pos"][g * 64:(g + 1) * 64]
+        has = pos >= 0
+        assert has[0], "a group starts with a segment that has reads"
+        assert np.array_equal(pos[has] - pos[0], np.flatnonzero(has)), "a group is 64 consecutive positions"
+        assert np.all(table[:, ~has] >= m), "a lane without a segment reads only zero rows"
+        for lane in np.flatnonzero(has):
+            assert int(pos[lane]) not in lane_of
+            lane_of[int(pos[lane])] = (g, int(lane))
+    assert sorted(lane_of) == list(np.flatnonzero(hot_len > 0)), "exactly the segments with reads have a lane"
+    plan_col = plan.col
+    set_of_pos = np.full(rest.size, -1, dtype=np.int64)
+    for p in range(rest.size):
+        row = int(rest["row"][p])
+        s0 = int(start_of(seg)[p])
+        want = np.sort(plan_col[s0:s0 + int(seg["len"][p])])
+        cold = col[int(start_of(rest)[p]):int(start_of(rest)[p]) + int(rest["len"][p])]
+        if p in lane_of:
+            g, lane = lane_of[p]
+            c, l, m, table = tables[g]
+            places = table[:, lane]
+            hot = members[member_off[l] + places[places < m].astype(np.int64)]
+            set_of_pos[p] = c
+            assert np.all(on_list[cold] != l), f"position {p}: a source on the list was left to the segment kernel"
+        else:
+            hot = np.empty(0, np.int32)
+        assert hot.size == hot_len[p]
+        assert np.array_equal(np.sort(np.concatenate([hot, cold])), want), f"position {p} (row {row})"
+        assert np.array_equal(col[s0:s0 + hot.size], col[s0:s0 + hot.size]) and np.all(np.diff(cold) > 0)   # the rest keeps its order
+    # set by set, most reads first
+    known = set_of_pos >= 0
+    assert np.all(np.diff(set_of_pos[known]) >= 0)
+    for c in np.unique(set_of_pos[known]):
+        idx = np.flatnonzero(set_of_pos == c)
+        assert np.all(np.diff(hot_len[idx]) <= 0)
+    return tables, on_list, hot_len
 
 
 @pytest.mark.parametrize("order", [1, 2])
 @pytest.mark.parametrize("segment_edges,budget", [(0, None), (16, 30_000)])
-def test_every_in_cluster_source_is_read_exactly_once(order, segment_edges, budget):
+def test_every_source_is_taken_exactly_once_clusters(order, segment_edges, budget):
     with community_plan(6, 300, 40_000, 5, budget, segment_edges) as plan:
         sched = plan.lds_schedule(order)
-        assert sched is not None and sched["conflict_free"] == (order == 2)
-        label, got, _ = decode(plan, sched)
-        rowptr, col = plan.rowptr, plan.col
-        for i in range(plan.n):
-            src = col[rowptr[i]:rowptr[i + 1]]
-            want = np.sort(src[label[src] == label[i]])
-            have = np.sort(np.concatenate(got.get(i, [np.empty(0, np.int64)])))
-            assert np.array_equal(want, have), f"row {i}"
-        # a row finished by the pass itself (slot <= -2: "add that partial row, store the row") is one record
-        # here, and the partial row it adds is none of the slots this pass writes
-        slot, row = sched["rec_slot"], sched["rec_row"]
-        joined = row[slot <= -2]
-        assert joined.size == np.unique(joined).size and (joined.size > 0 or segment_edges)   # short segments: hardly a row is two pieces
-        assert all(len(got[int(i)]) == 1 for i in joined)
-        assert not np.intersect1d(-2 - slot[slot <= -2], slot[slot >= 0]).size
+        assert sched is not None and sched["conflict_free"] == (order == 2) and sched["hot_mode"] == 1
+        label, num, _, _ = plan.row_clusters()
+        assert sched["list_of_set"].size == num and np.array_equal(sched["list_of_set"], np.arange(num))
+        assert np.array_equal(sched["members"], np.argsort(label, kind="stable"))     # sets = lists = clusters
+        check_schedule(plan, sched)
 
 
 def test_conflict_free_order_never_puts_two_lanes_of_a_pass_on_one_bank():
     # rows of ~330 non-zeros kept whole (the default would cut them into 64s and the reads of 16 short
-    # records spread less evenly over the 16 bank groups: more padding, checked below)
+    # segments spread less evenly over the 16 bank groups: more padding, checked below)
     with community_plan(6, 1500, 1_500_000, 9, segment_edges=1024) as plan:
         sched = plan.lds_schedule(2)
         assert sched is not None and sched["conflict_free"]
-        _, _, tables = decode(plan, sched)
-        for c, m, table in tables:
+        tables = tables_of(sched)
+        for c, l, m, table in tables:
             for lanes in pass_groups():
                 res = np.sort(table[:, lanes] & 15, axis=1)
                 assert np.all(res == np.arange(16)), "two lanes of one pass share a bank group"
-        # and it costs little on a dense community graph: the automatic choice takes it
         auto = plan.lds_schedule(0)
         assert auto is not None and auto["conflict_free"]
-        hot = sum(int((t < m).sum()) for _, m, t in tables)
+        hot = sum(int((t < m).sum()) for _, _, m, t in tables)
         assert sched["ids"].size <= 1.3 * hot
-    with community_plan(5, 700, 120_000, 9) as plan:      # ~60 reads per record: the padding is too much, column-list order it is
-        auto = plan.lds_schedule(0)
-        assert auto is not None and not auto["conflict_free"]
-        assert plan.lds_schedule(2)["ids"].size > 1.3 * hot_reads(plan, auto)
+    with community_plan(5, 700, 120_000, 9) as plan:      # ~60 reads per segment: more padding (47 % against 14 %) and still the cheaper order
+        auto, plain, free = plan.lds_schedule(0), plan.lds_schedule(1), plan.lds_schedule(2)
+        assert auto is not None and auto["conflict_free"]
+        hot = sum(int((t < m).sum()) for _, _, m, t in tables_of(plain))
+        assert free["ids"].size > 1.3 * hot and free["ids"].size < 1.9 * plain["ids"].size
 
 
-def hot_reads(plan, sched):
-    _, _, tables = decode(plan, sched)
-    return sum(int((t < m).sum()) for _, m, t in tables)
-
-
-def test_conflict_free_order_on_short_records_too():
+def test_conflict_free_order_on_short_segments_too():
     with community_plan(5, 700, 120_000, 9, 30_000, 16) as plan:
         sched = plan.lds_schedule(2)
-        _, _, tables = decode(plan, sched)
-        for c, m, table in tables:
+        for c, l, m, table in tables_of(sched):
             for lanes in pass_groups():
                 assert np.all(np.sort(table[:, lanes] & 15, axis=1) == np.arange(16))
 
@@ -116,27 +161,46 @@ def test_conflict_free_order_on_short_records_too():
 def test_column_list_order_is_kept_by_order_1():
     with community_plan(4, 200, 10_000, 3) as plan:
         sched = plan.lds_schedule(1)
-        label, _, tables = decode(plan, sched)
-        order = np.argsort(label, kind="stable")
-        member_off = np.concatenate([[0], np.cumsum(np.bincount(label))])
-        rowptr, col = plan.rowptr, plan.col
-        for g, (c, m, table) in enumerate(tables):
+        tables, on_list, hot_len = check_schedule(plan, sched)
+        members, member_off, col = sched["members"], sched["member_off"], sched["col"]
+        rest = sched["rest"]
+        start = rest["start_lo"].astype(np.int64) | (rest["start_hi"].astype(np.int64) << 32)
+        for g, (c, l, m, table) in enumerate(tables):
             for lane in range(64):
-                row = int(sched["rec_row"][g * 64 + lane])
-                if row < 0:
+                p = int(sched["rec_pos"][g * 64 + lane])
+                if p < 0:
                     continue
-                ids = table[:, lane]
-                real = order[member_off[c] + ids[ids < m].astype(np.int64)]
-                src = col[rowptr[row]:rowptr[row + 1]]
-                want = src[label[src] == label[row]]
-                if want.size == real.size:               # the row is one record
-                    assert np.array_equal(real, want)
-                    assert np.all(ids[real.size:] >= m), "padding comes after the reads"
+                places = table[:, lane]
+                h = int(hot_len[p])
+                assert np.all(places[:h] < m) and np.all(places[h:] >= m), "padding comes after the reads"
+                # the hot part sits in front of the rest in the reordered column list, in the same order
+                assert np.array_equal(members[member_off[l] + places[:h].astype(np.int64)], col[start[p] - h:start[p]])
 
 
-def test_no_schedule_without_small_clusters():
-    w = gp_synth.make_workload(2, scale=0.05, with_features=False)    # power law: one giant cluster
-    with gp.gp_plan_blocks(w.src, w.dst, w.n, 10**9, w.flags) as plan:
-        label, num, _, _ = plan.row_clusters()
-        if np.bincount(label).max() > 10192:
-            assert plan.lds_schedule(0) is None and plan.lds_schedule(2) is None
+@pytest.mark.parametrize("order", [1, 2])
+def test_hubs_are_the_list_of_a_graph_without_clusters(order):
+    with power_law_plan(0.2, forced=True) as plan:    # (the graph is too small for the automatic choice)
+        sched = plan.lds_schedule(order, d=100)
+        assert sched is not None and sched["hot_mode"] == 2
+        assert sched["member_off"].size == 2 and np.all(sched["list_of_set"] == 0)
+        hubs = sched["members"]
+        assert hubs.size == min(10192, plan.n)
+        # they are the most popular sources, ties to the smaller id
+        uses = np.bincount(plan.col, minlength=plan.n)
+        order_by_use = np.lexsort((np.arange(plan.n), -uses))
+        assert np.array_equal(np.sort(order_by_use[:hubs.size]), hubs)
+        check_schedule(plan, sched)
+        # sets are ranges of consecutive rows
+        rest = sched["rest"]
+        flagged = rest["slice"] == 0x80
+        sets = np.repeat(sched["group_set"], 64)[sched["rec_pos"] >= 0]
+        rows = rest["row"][sched["rec_pos"][sched["rec_pos"] >= 0]]
+        for c in np.unique(sets)[:-1]:
+            assert rows[sets == c].max() < rows[sets == c + 1].min()
+        assert flagged.sum() == (sched["rec_pos"] >= 0).sum()
+
+
+def test_no_schedule_by_itself_for_a_small_power_law_graph():
+    """One giant cluster of more rows than an L2 share holds, and too little work for hubs to be tried."""
+    with power_law_plan(0.2) as plan:
+        assert plan.nnz * 128 < 2e9 and plan.lds_schedule(0) is None and plan.lds_schedule(2) is None
