@@ -254,13 +254,14 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
     b1.record()
     torch.cuda.synchronize()
     bracketed_ms = b0.elapsed_time(b1) / args.steps if memory == "device" else (time.perf_counter() - t0) * 1e3 / args.steps
-    # a hop is one launch of the segment kernel, or two where the plan's cache schedule cuts every record into a
-    # piece that gathers inside the row's cluster and one that gathers outside it (the inside pieces then go
-    # through a second launch of the segment kernel, or through the LDS kernel); the roofline figures below are
-    # per launch, the mean over all of a hop's launches
+    # a hop is one launch of the segment kernel, or several where the plan's cache schedule cuts every segment
+    # into the non-zeros whose source row can be kept close and the others (the former then go through a second
+    # launch of the segment kernel, or through the LDS kernel, which for shared lists has a packing launch before
+    # it); the roofline figures below are per launch, the mean over all of a hop's launches
     seg_launches, seg_ms = gp.gp_profile_read("gp_hop_segments")
     lds_launches, lds_ms = gp.gp_profile_read("gp_hop_cluster_lds")
-    launches, hop_ms = seg_launches + lds_launches, seg_ms + lds_ms
+    pack_launches, pack_ms = gp.gp_profile_read("gp_pack_strips")
+    launches, hop_ms = seg_launches + lds_launches + pack_launches, seg_ms + lds_ms + pack_ms
     fix_launches, fix_ms = gp.gp_profile_read("gp_fixup_rows")
     _, copy_ms = gp.gp_profile_read("gp_copy_rows")
     gp.gp_profile_enable(False)
@@ -270,18 +271,21 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
     launches_per_hop = max(1, round(launches / max(args.steps * K, 1)))
     bytes_per_launch = algorithmic_bytes_per_hop(n, nnz, d, elem) // launches_per_hop
     achieved = bytes_per_launch / avg_launch_s / 1e9
-    options = {k: gp.gp_get_option(k) for k in ("segment_edges", "column_tile", "column_slices", "cache_schedule", "split_records", "lds_pass")}
+    options = {k: gp.gp_get_option(k) for k in ("segment_edges", "column_tile", "column_slices", "cache_schedule", "split_records", "lds_pass", "hub_pass")}
     traffic = recorded_traffic(workload, options) if (args.scale == 1.0 and memory == "device" and not args.contiguous_ids) else None
     flops_per_launch = 2 * nnz * d // launches_per_hop          # one multiply-add per non-zero and column
     gathered_per_launch = nnz * d * elem // launches_per_hop    # bytes the lanes read if every row comes from cache
     S, slice_elems, _, _ = plan.work_lists(d, w.dtype, max(1, min(16 // elem, d)))
     if lds_launches:
-        work_lists = "in-cluster pieces from LDS (strips of 4 columns), the others as implicit lists"
+        sched = plan.lds_schedule(0, d)
+        kind = {1: "in-cluster non-zeros", 2: "non-zeros whose source is one of the 10192 most popular rows"}[sched["hot_mode"]]
+        work_lists = (f"{kind} from LDS (strips of 4 columns, {sched['ids'].size} reads for {int((sched['rest']['slice'] != 0).sum())} "
+                      f"segments, {'conflict-free' if sched['conflict_free'] else 'column-list'} order), the others as implicit lists")
     elif S:
         work_lists = "explicit per XCD, %d column slices of %d" % (S, slice_elems)
     else:
         work_lists = "implicit"
-    hop_kernel = "gp_hop_segments + gp_hop_cluster_lds" if lds_launches else "gp_hop_segments"
+    hop_kernel = "gp_hop_segments" + (" + gp_hop_cluster_lds" if lds_launches else "") + (" + gp_pack_strips" if pack_launches else "")
 
     rec = {
         "metric": "edge-feature updates/s (GEFU/s) for K-hop A^k X precompute",
@@ -310,7 +314,8 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
                      "traffic_frac": round(traffic / avg_launch_s / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
                      "kernel": hop_kernel, "launches": launches, "launches_per_hop": launches_per_hop,
                      "per_kernel": {"gp_hop_segments": {"launches": seg_launches, "avg_launch_us": round(seg_ms * 1e3 / max(seg_launches, 1), 3)},
-                                    "gp_hop_cluster_lds": {"launches": lds_launches, "avg_launch_us": round(lds_ms * 1e3 / max(lds_launches, 1), 3)}},
+                                    "gp_hop_cluster_lds": {"launches": lds_launches, "avg_launch_us": round(lds_ms * 1e3 / max(lds_launches, 1), 3)},
+                                    "gp_pack_strips": {"launches": pack_launches, "avg_launch_us": round(pack_ms * 1e3 / max(pack_launches, 1), 3)}},
                      "avg_launch_us": round(avg_launch_s * 1e6, 3), "algorithmic_bytes_per_launch": bytes_per_launch,
                      "kernel_times_from": f"event-bracketed pass, {bracketed_ms:.5f} ms per step",
                      # the other ceilings of the same launch: plain fp32 vector arithmetic, and the rate at

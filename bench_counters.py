@@ -36,7 +36,7 @@ OUT = os.path.join(os.environ.get("TMPDIR", "/tmp"), "gp_counters")   # raw rocp
 PROFILES = os.path.join(ROOT, "profiles")
 NAMES = {1: "config1_tiny", 2: "config2_chunglu_arxiv_like", 3: "config3_chunglu_mean_d100", 4: "config4_sbm_sum_d602"}
 PMC_SETS = ["FETCH_SIZE", "WRITE_SIZE", "TCC_HIT_sum TCC_MISS_sum", "MeanOccupancyPerCU"]
-HOP_KERNELS = ("gp_hop_segments", "gp_hop_cluster_lds")   # a hop's launches: the figures below are means over all of them
+HOP_KERNELS = ("gp_hop_segments", "gp_hop_cluster_lds", "gp_pack_strips")   # a hop's launches: the figures below are means over all of them
 
 
 def run(cmd, log, limit):

@@ -241,7 +241,8 @@ gp_status gp_plan_work_lists(const gp_plan *plan, int32_t d, gp_dtype dtype, int
  * overlap in time (they share that scratch); different plans are independent.
  * Results are deterministic: the same inputs and options give the same bits on every
  * call (how a row's partial sums are grouped depends on the schedule, so the streamed and
- * the resident schedule, or two settings of "split_records", may differ in the last bits).
+ * the resident schedule, or two settings of "split_records", "lds_pass" or "hub_pass", may differ
+ * in the last bits).
  * Errors: INVALID_ARG, OOM_DEVICE, DEVICE, UNSUPPORTED.
  */
 gp_status gp_propagate(const gp_plan *plan, const void *X, int64_t ldx, int32_t d, gp_dtype dtype,
@@ -268,7 +269,7 @@ gp_status gp_plan_streamed_shape(const gp_plan *plan, int64_t *edge_blocks, int6
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments and same kernels as gp_propagate on device-resident operands, and the same
  * bits in out_stack whenever that call works on whole records (option "split_records"
- * = 2, or a graph without row clusters; with cut records its partial sums are grouped
+ * = 2, or a graph without row clusters or popular rows worth a pass; with cut records its partial sums are grouped
  * differently and the two agree to rounding), but the call makes no allocation of any kind: the scratch
  * the kernels need (work cursors, partial rows of rows that were cut) is a fixed array
  * in device memory of 64 MiB + 256 bytes that each GPU the library is used on holds

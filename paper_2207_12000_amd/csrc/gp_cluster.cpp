@@ -14,10 +14,16 @@
 //      deterministic, independent of the thread count);
 //   2. per column-slice count S, one explicit work list per XCD: records are the
 //      plan's segments, cluster by cluster, each (cluster chunk, slice) pair given to
-//      the XCD with the least work so far.
+//      the XCD with the least work so far;
+//   3. every segment cut into its hot non-zeros (the source is in the row's cluster, or,
+//      in a graph without clusters, one of its most popular rows) and the others: as two
+//      record lists for the L2s, or as the schedule of the LDS pass, which keeps a list
+//      of at most 10,192 rows in a compute unit's LDS one 16-byte strip at a time and
+//      orders every lane's reads so that the lanes the LDS serves together never meet
+//      on a bank.
 //
-// Graphs without such structure (one giant cluster, or clusters whose sources do
-// not fit an L2 at any useful slice width) keep the implicit lists.
+// Graphs without such structure (one giant cluster and no popular rows worth a pass)
+// keep the implicit lists.
 #include <algorithm>
 #include <atomic>
 #include <numeric>

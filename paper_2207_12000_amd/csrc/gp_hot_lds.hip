@@ -260,6 +260,16 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
 
 }  // namespace
 
+gp_status launch_pack_strips(const HotLdsArgs& a, hipStream_t stream)
+{
+    if (a.d < 4 || !a.xin || !a.packed || !a.members || a.num_members <= 0)
+        return fail(GP_ERR_INVALID_ARG, "packing strips: needs at least four fp32 columns, lists and a buffer");
+    hipLaunchKernelGGL(gp_pack_strips, dim3((unsigned)((a.num_members + 255) / 256)), dim3(256), 0, stream, a.members, a.num_members,
+                       a.src_scale, a.xin, a.ldin, a.d, a.packed);
+    GP_HIP(hipGetLastError());
+    return GP_OK;
+}
+
 gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
 {
     if (a.d < 4 || a.num_sets <= 0 || !a.ctrl || !a.xin || !a.planes || a.num_pos <= 0 || a.num_members <= 0 || !a.octets || !a.octet_off)
@@ -277,11 +287,6 @@ gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
     // two workgroups of 512 per compute unit where two strips fit its LDS, else one of 1024
     const bool two = shm <= (size_t)kLdsBytesPerCu / 2 - 64;
     const dim3 grid(8 * 32 * (two ? 2 : 1)), block(two ? 512 : 1024);
-    if (a.packed) {
-        hipLaunchKernelGGL(gp_pack_strips, dim3((unsigned)((a.num_members + 255) / 256)), dim3(256), 0, stream, a.members, a.num_members,
-                           a.src_scale, a.xin, a.ldin, a.d, a.packed);
-        GP_HIP(hipGetLastError());
-    }
     OctetLists lists;
     for (int x = 0; x <= 8; ++x) lists.off[x] = a.octet_off[x];
     hipLaunchKernelGGL(gp_hop_cluster_lds, grid, block, shm, stream, a.members, a.member_off, a.list_of_set, a.group_off, a.wave_cut,

@@ -288,6 +288,7 @@ struct HotLdsArgs {
     int32_t d;
     unsigned long long* ctrl;  // as HopArgs::ctrl
 };
+gp_status launch_pack_strips(const HotLdsArgs& a, hipStream_t stream);  // fills a.packed (where the lists are shared)
 gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream);
 // Slice shape of the explicit work lists for rows of d elements in vectors of `vec`
 // (element size es), or false if this plan keeps the implicit lists.

@@ -523,6 +523,12 @@ gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t
             h.num_members = D.lds_num_members;
             h.d = d;
             h.ctrl = ctrl;
+            if (h.packed) {
+                profile_begin("gp_pack_strips", stream);
+                st = launch_pack_strips(h, stream);
+                profile_end(stream);
+                if (st != GP_OK) return st;
+            }
             profile_begin("gp_hop_cluster_lds", stream);
             st = launch_hot_lds(h, stream);
             profile_end(stream);
