@@ -260,6 +260,20 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
 
 }  // namespace
 
+gp_status prepare_hot_lds(int32_t max_members)
+{
+    if (max_members < 0 || max_members > kLdsMaxMembers) return fail(GP_ERR_INVALID_ARG, "LDS pass: a list of %d rows does not fit the LDS", max_members);
+    // the kernel addresses its dynamic LDS from 0: true as long as it has no static LDS before it
+    hipFuncAttributes attr;
+    GP_HIP(hipFuncGetAttributes(&attr, (const void*)gp_hop_cluster_lds));
+    if (attr.sharedSizeBytes != 0)
+        return fail(GP_ERR_UNSUPPORTED, "LDS pass: the kernel was built with %zu bytes of static LDS", (size_t)attr.sharedSizeBytes);
+    // beyond 64 KB of dynamic LDS a kernel has to be cleared for the size (a host-side setting, per device)
+    const size_t shm = (size_t)lds_rows(max_members) * 16 + 16;
+    GP_HIP(hipFuncSetAttribute((const void*)gp_hop_cluster_lds, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm));
+    return GP_OK;
+}
+
 gp_status launch_pack_strips(const HotLdsArgs& a, hipStream_t stream)
 {
     if (a.d < 4 || !a.xin || !a.packed || !a.members || a.num_members <= 0)
@@ -277,13 +291,6 @@ gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
     if (a.max_members < 0 || a.max_members > kLdsMaxMembers)
         return fail(GP_ERR_INVALID_ARG, "LDS pass: a list of %d rows does not fit the LDS", a.max_members);
     const size_t shm = (size_t)lds_rows(a.max_members) * 16 + 16;  // the rows and the item word
-    // the kernel addresses its dynamic LDS from 0: true as long as it has no static LDS before it
-    hipFuncAttributes attr;
-    GP_HIP(hipFuncGetAttributes(&attr, (const void*)gp_hop_cluster_lds));
-    if (attr.sharedSizeBytes != 0)
-        return fail(GP_ERR_UNSUPPORTED, "LDS pass: the kernel was built with %zu bytes of static LDS", (size_t)attr.sharedSizeBytes);
-    // beyond 64 KB of dynamic LDS a kernel has to be cleared for the size (a host-side setting, per device)
-    GP_HIP(hipFuncSetAttribute((const void*)gp_hop_cluster_lds, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm));
     // two workgroups of 512 per compute unit where two strips fit its LDS, else one of 1024
     const bool two = shm <= (size_t)kLdsBytesPerCu / 2 - 64;
     const dim3 grid(8 * 32 * (two ? 2 : 1)), block(two ? 512 : 1024);

@@ -288,6 +288,9 @@ struct HotLdsArgs {
     int32_t d;
     unsigned long long* ctrl;  // as HopArgs::ctrl
 };
+// Once per device and list length, before the first launch_hot_lds (not a stream operation: kept out of the
+// launch so that a launch can be captured in a graph): clears the kernel for the LDS it will ask for.
+gp_status prepare_hot_lds(int32_t max_members);
 gp_status launch_pack_strips(const HotLdsArgs& a, hipStream_t stream);  // fills a.packed (where the lists are shared)
 gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream);
 // Slice shape of the explicit work lists for rows of d elements in vectors of `vec`

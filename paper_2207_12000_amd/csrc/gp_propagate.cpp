@@ -272,6 +272,7 @@ gp_status ensure_lds(const gp_plan* plan, int32_t d, hipStream_t stream)
                 (st = upload_now(D.lds_groups, L.groups, stream)) != GP_OK || (st = upload_now(D.lds_ids, L.ids, stream)) != GP_OK)
                 return st;
             D.lds_set_reads = L.set_reads;
+            if ((st = prepare_hot_lds(L.max_members)) != GP_OK) return st;
             D.lds_max_members = L.max_members;
             D.lds_num_members = (int64_t)L.members.size();
             D.lds_num_sets = (int32_t)L.list_of_set.size();
