@@ -177,7 +177,8 @@ int64_t gp_plan_segment_edges(const gp_plan *plan);           /* the segment len
  * i.e. never collide on a bank; order 1 keeps the column list's order.  With order 0 the
  * pass applies only where the reads of the chosen order (in column-list-order equivalents)
  * stay below 1.8 per hot non-zero for clusters and 4 for hubs: beyond that the same rows
- * are as fast out of the L2s, or memory.  d (>= 4) is the column count the sets of
+ * are as fast out of the L2s, or memory, and where a set has at least 100000 reads on
+ * average (staging a strip costs the same whatever is read from it).  d (>= 4) is the column count the sets of
  * hot_mode 2 are sized for.
  * The call fills the counts of *view (num_groups = 0: the pass does not apply to this
  * plan) and every array of *view that is not NULL (HOST memory; capacities in elements,

@@ -619,6 +619,13 @@ bool build_lds_schedule(const gp_plan& P, const HotSets& C, double max_cost, int
     out.conflict_free = order == 2 || (order == 0 && cost_free <= cost_plain);
     const std::vector<int32_t>& steps = out.conflict_free ? steps_free : steps_plain;
     if ((out.conflict_free ? cost_free : cost_plain) > max_cost * (double)out.hot_edges) return false;
+    // Staging a strip costs a workgroup some microseconds whatever the set has to read from it: sets
+    // with little to read (many tiny clusters) are better served by the L2s.
+    if (max_cost < kLdsForcedCost) {
+        int64_t busy_sets = 0;
+        for (int32_t c = 0; c < num; ++c) busy_sets += out.group_off[(size_t)c + 1] > out.group_off[(size_t)c];
+        if ((out.conflict_free ? total_free : total_plain) < kLdsMinReadsPerSet * busy_sets) return false;
+    }
     out.groups.resize((size_t)ngroups);
     int64_t id_total = 0;
     for (int64_t g = 0; g < ngroups; ++g) {

@@ -254,6 +254,8 @@ struct LdsSchedule {
 constexpr double kLdsConflictFreeGain = 1.9;
 constexpr double kLdsMaxCostClusters = 1.8;  // reads (in column-list-order equivalents) per hot non-zero beyond which the L2 lists are as fast
 constexpr double kLdsMaxCostHubs = 4.0;      // ... beyond which gathering the hubs from memory is as fast
+constexpr double kLdsForcedCost = 64.0;      // the limit when the pass is forced: whatever the padding
+constexpr int64_t kLdsMinReadsPerSet = 100000;  // reads a set must have on average for a strip's staging (~9 us per work item) to pay
 inline int64_t lds_rows(int64_t m) { return (m + 15) / 16 * 16 + 16; }
 // false (and `out` unspecified) where the pass does not apply: a list that hot records gather
 // from is too long for the LDS, or the reads (padding included; a conflict-free read counts

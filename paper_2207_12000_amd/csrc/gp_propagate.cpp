@@ -205,10 +205,17 @@ void decide_hot_mode(const gp_plan* plan, int32_t d)
     if (!forced && (double)plan->nnz * (double)d < kMinHubWork) return;
     // about 2048 work items (set x strip) per launch, sets of at least 1024 rows
     const int64_t strips = ((int64_t)d + 3) / 4;
-    const int64_t sets = std::max<int64_t>(1, 2048 / strips);
-    const int64_t rows_per_set = std::max<int64_t>(1024, (plan->n + sets - 1) / sets);
+    int64_t sets = std::max<int64_t>(1, 2048 / strips);
+    int64_t rows_per_set = std::max<int64_t>(1024, (plan->n + sets - 1) / sets);
     HotSets H = hot_sets_from_hubs(*plan, kLdsMaxMembers, rows_per_set);
     if (!forced && H.hot_fraction < kMinHubFraction) return;
+    // ... but no more sets than have enough to read each (the hubs do not depend on the sets: same list)
+    const int64_t reads = (int64_t)(1.5 * H.hot_fraction * (double)plan->nnz);
+    if (reads / kLdsMinReadsPerSet < H.num_sets) {
+        sets = std::max<int64_t>(1, reads / (2 * kLdsMinReadsPerSet));
+        rows_per_set = std::max<int64_t>(1024, (plan->n + sets - 1) / sets);
+        H = hot_sets_from_hubs(*plan, kLdsMaxMembers, rows_per_set);
+    }
     plan->hot_sets = std::move(H);
     plan->hot_mode = 2;
 }
@@ -261,7 +268,7 @@ gp_status ensure_lds(const gp_plan* plan, int32_t d, hipStream_t stream)
         const bool forced = plan->opt.lds_pass == 1 || plan->opt.lds_pass == 3;
         const double limit = plan->hot_mode == 2 ? kLdsMaxCostHubs : kLdsMaxCostClusters;
         LdsSchedule L;
-        if (build_lds_schedule(*plan, plan->hot_sets, forced ? 64.0 : limit, plan->opt.lds_pass == 1 ? 2 : plan->opt.lds_pass == 3 ? 1 : 0,
+        if (build_lds_schedule(*plan, plan->hot_sets, forced ? kLdsForcedCost : limit, plan->opt.lds_pass == 1 ? 2 : plan->opt.lds_pass == 3 ? 1 : 0,
                                L)) {
             if ((st = upload_now(D.lds_col, L.col, stream)) != GP_OK || (st = upload_now(D.lds_cold, L.cold, stream)) != GP_OK ||
                 (st = upload_now(D.lds_members, L.members, stream)) != GP_OK ||
@@ -725,7 +732,7 @@ extern "C" gp_status gp_plan_lds_schedule(const gp_plan* plan, int32_t d, int32_
         if (plan->hot_mode != 1 && plan->hot_mode != 2) return GP_OK;
         LdsSchedule L;
         const double limit = plan->hot_mode == 2 ? kLdsMaxCostHubs : kLdsMaxCostClusters;
-        if (!build_lds_schedule(*plan, plan->hot_sets, order == 0 ? limit : 64.0, order, L)) return GP_OK;
+        if (!build_lds_schedule(*plan, plan->hot_sets, order == 0 ? limit : kLdsForcedCost, order, L)) return GP_OK;
         v->hot_mode = plan->hot_mode;
         v->num_groups = (int64_t)L.groups.size() - 1;  // (without the sentinel)
         v->num_ids = (int64_t)L.ids.size();

@@ -103,6 +103,16 @@ struct StreamSchedule {
     }
 };
 
+// a large host-to-host copy on several threads (one thread moves 3 - 5 GB/s, the memory system several times that)
+void copy_on_threads(void* dst, const void* src, size_t n)
+{
+    const int nt = n < ((size_t)4 << 20) ? 1 : std::min(8, host_threads());
+    parallel_run(nt, [&](int t, int k) {
+        const size_t lo = n * (size_t)t / (size_t)k, hi = n * (size_t)(t + 1) / (size_t)k;
+        std::memcpy((char*)dst + lo, (const char*)src + lo, hi - lo);
+    });
+}
+
 // Ordinary (pageable) host memory cannot be the end of an asynchronous copy, and left to
 // the runtime its copies are staged one after the other with the enqueuing thread waiting.
 // The stager moves such operands through a ring of pinned buffers instead: on the way in,
@@ -197,14 +207,7 @@ private:
         char* dst;
         size_t bytes;
     };
-    static void copy_parallel(void* dst, const void* src, size_t n)
-    {
-        const int nt = n < ((size_t)4 << 20) ? 1 : std::min(8, host_threads());
-        parallel_run(nt, [&](int t, int k) {
-            const size_t lo = n * (size_t)t / (size_t)k, hi = n * (size_t)(t + 1) / (size_t)k;
-            std::memcpy((char*)dst + lo, (const char*)src + lo, hi - lo);
-        });
-    }
+    static void copy_parallel(void* dst, const void* src, size_t n) { copy_on_threads(dst, src, n); }
     void drain()
     {
         (void)hipSetDevice(device_);
@@ -348,7 +351,7 @@ gp_status ensure_pinned_col(const gp_plan* plan)
         void* p = nullptr;
         hipError_t e = hipHostMalloc(&p, plan->col.size() * sizeof(int32_t), hipHostMallocDefault);
         if (e != hipSuccess) return fail(GP_ERR_OOM_HOST, "pinned copy of the column list: %s", hipGetErrorString(e));
-        std::memcpy(p, plan->col.data(), plan->col.size() * sizeof(int32_t));
+        copy_on_threads(p, plan->col.data(), plan->col.size() * sizeof(int32_t));
         plan->pinned_col = (int32_t*)p;
     }
     return GP_OK;
@@ -525,7 +528,7 @@ gp_status propagate_streamed(const gp_plan* plan, const void* X, int64_t ldx, in
             void* p = nullptr;
             hipError_t e = hipHostMalloc(&p, C.segs->size() * sizeof(Segment), hipHostMallocDefault);
             if (e != hipSuccess) return fail_clean(fail(GP_ERR_OOM_HOST, "pinned copy of the segment list: %s", hipGetErrorString(e)));
-            std::memcpy(p, C.segs->data(), C.segs->size() * sizeof(Segment));
+            copy_on_threads(p, C.segs->data(), C.segs->size() * sizeof(Segment));
             C.pinned_segs = (Segment*)p;
         }
         if ((st = S->init_streams((int)nbuf)) != GP_OK) return fail_clean(st);

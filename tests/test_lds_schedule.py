@@ -143,11 +143,15 @@ def test_conflict_free_order_never_puts_two_lanes_of_a_pass_on_one_bank():
         assert auto is not None and auto["conflict_free"]
         hot = sum(int((t < m).sum()) for _, _, m, t in tables)
         assert sched["ids"].size <= 1.3 * hot
-    with community_plan(5, 700, 120_000, 9) as plan:      # ~60 reads per segment: more padding (47 % against 14 %) and still the cheaper order
+    with community_plan(5, 700, 120_000, 9) as plan:      # ~60 reads per segment: more padding (47 % against 14 %), still the cheaper order ...
         auto, plain, free = plan.lds_schedule(0), plan.lds_schedule(1), plan.lds_schedule(2)
-        assert auto is not None and auto["conflict_free"]
         hot = sum(int((t < m).sum()) for _, _, m, t in tables_of(plain))
         assert free["ids"].size > 1.3 * hot and free["ids"].size < 1.9 * plain["ids"].size
+        # ... but five sets of ~60,000 reads each are too little work per staged strip: left to the L2s
+        assert free["ids"].size < 5 * 100_000 and auto is None
+    with community_plan(4, 1500, 800_000, 11) as plan:    # ~60 reads per segment, 500,000 per set: taken, conflict-free
+        auto = plan.lds_schedule(0)
+        assert auto is not None and auto["conflict_free"] and auto["ids"].size >= 4 * 100_000
 
 
 def test_conflict_free_order_on_short_segments_too():
