@@ -144,9 +144,9 @@ int64_t gp_plan_segment_edges(const gp_plan *plan);           /* the segment len
  * HOST, room for `capacity` 16-byte records, or NULL to get the counts only.
  * Errors: INVALID_ARG, OOM_HOST. */
 /* gp_plan_lds_schedule: the schedule of the LDS pass (library's own; exposed so host logic
- * can be checked without a GPU).  fp32 hops take the non-zeros whose source row is on a
- * short list of rows (the hot ones) from the compute units' LDS: a workgroup stages four
- * feature columns (16 bytes) of the list's rows, scaled by the operator's source weight,
+ * can be checked without a GPU).  Hops over fp32 rows, and over bf16 rows of a multiple of
+ * four columns, take the non-zeros whose source row is on a short list of rows (the hot
+ * ones) from the compute units' LDS: a workgroup stages four feature columns (as fp32, 16 bytes) of the list's rows, scaled by the operator's source weight,
  * and one lane per segment adds up the segment's hot sources from there, leaving the four
  * sums in a plane entry; the segment kernel then gathers the segments' other non-zeros from
  * memory, adds the plane entries and finishes every segment as the plan says (output row,
@@ -424,7 +424,7 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
  *                     whose source lies in the row's cluster and the others; the others are
  *                     gathered first, whole rows wide, in a launch of their own, and the two
  *                     partial rows are joined by the fix-up; 2 = whole records.
- *   "lds_pass"        fp32 hops with cut records: 0 = the in-cluster pieces are gathered from LDS
+ *   "lds_pass"        0 = the non-zeros whose source is on a short list of rows are gathered from LDS
  *                     where gp_plan_lds_schedule has a schedule for the plan; 1 = the same, with
  *                     the conflict-free order whatever padding it costs; 3 = the same, with the
  *                     column list's order; 2 = never (per-XCD work lists through the L2s).

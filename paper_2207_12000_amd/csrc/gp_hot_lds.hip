@@ -32,6 +32,19 @@ typedef float v4f_a16 __attribute__((ext_vector_type(4)));
 typedef float v4f_a4 __attribute__((ext_vector_type(4), aligned(4)));  // 16-byte access from a dword boundary
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
+typedef unsigned short v4h_a2 __attribute__((ext_vector_type(4), aligned(2)));  // four bf16 from an element boundary
+
+// four consecutive columns of a stored row as fp32: fp32 storage, or bf16 storage widened
+__device__ inline v4f_a16 load_strip(const float* p) { return *reinterpret_cast<const v4f_a4*>(p); }
+__device__ inline v4f_a16 load_strip(const uint16_t* p)
+{
+    const v4h_a2 h = *reinterpret_cast<const v4h_a2*>(p);
+    v4f_a16 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = __uint_as_float((unsigned)h[i] << 16);
+    return v;
+}
+
 constexpr int kLanes = 64;
 constexpr int kStepBlock = 8;  // steps of a lane that lie together in the id list
 constexpr int kAhead = 4;      // index loads in flight per lane
@@ -69,22 +82,23 @@ __device__ inline v4f_a16 lds_row(unsigned byte_offset) { return *reinterpret_ca
 // at a time (a line serves eight consecutive steps out of the caches) and a wavefront stores
 // 64 consecutive entries, so that staging a strip later reads its 16 bytes per row once, not a
 // line per row.
+template <typename T>
 __global__ __launch_bounds__(256) void gp_pack_strips(const int32_t* __restrict__ members, int64_t num_members,
-                                                      const float* __restrict__ src_scale, const float* __restrict__ xin,
+                                                      const float* __restrict__ src_scale, const T* __restrict__ xin,
                                                       int64_t ldin, int d, float* __restrict__ packed)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= num_members) return;
     const int row = members[i];
     const float w = src_scale ? src_scale[row] : 1.0f;
-    const float* src = xin + (int64_t)row * ldin;
+    const T* src = xin + (int64_t)row * ldin;
     const int nstrips = (d + 3) / 4;
     for (int t0 = 0; t0 < nstrips; t0 += 8) {
         v4f_a16 v[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int t = min(t0 + u, nstrips - 1);
-            v[u] = *reinterpret_cast<const v4f_a4*>(src + min(t * 4, d - 4));
+            v[u] = load_strip(src + min(t * 4, d - 4));
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u)
@@ -96,12 +110,13 @@ struct OctetLists {
     int64_t off[9];
 };
 
+template <typename T>
 __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
     const int32_t* __restrict__ members, const int64_t* __restrict__ member_off, const int32_t* __restrict__ list_of_set,
     const int32_t* __restrict__ group_off, const int32_t* __restrict__ wave_cut,
     const LdsGroup* __restrict__ groups, const LdsOctet* __restrict__ octets, const OctetLists lists,
     const uint16_t* __restrict__ ids,
-    const float* __restrict__ packed, int64_t num_members, const float* __restrict__ src_scale, const float* __restrict__ xin,
+    const float* __restrict__ packed, int64_t num_members, const float* __restrict__ src_scale, const T* __restrict__ xin,
     int64_t ldin, float* __restrict__ planes, int64_t num_pos, int d, unsigned long long* __restrict__ ctrl, int lds_rows_max)
 {
     // LDS: the strip's rows from byte 0 (an index times 16 is then the address itself), and
@@ -157,7 +172,7 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         v[u] = v4f_a16{0.0f, 0.0f, 0.0f, 0.0f};
-                        if (row[u] >= 0) v[u] = *reinterpret_cast<const v4f_a4*>(xin + (int64_t)row[u] * ldin + col0);
+                        if (row[u] >= 0) v[u] = load_strip(xin + (int64_t)row[u] * ldin + col0);
                     }
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
@@ -263,23 +278,30 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
 gp_status prepare_hot_lds(int32_t max_members)
 {
     if (max_members < 0 || max_members > kLdsMaxMembers) return fail(GP_ERR_INVALID_ARG, "LDS pass: a list of %d rows does not fit the LDS", max_members);
-    // the kernel addresses its dynamic LDS from 0: true as long as it has no static LDS before it
-    hipFuncAttributes attr;
-    GP_HIP(hipFuncGetAttributes(&attr, (const void*)gp_hop_cluster_lds));
-    if (attr.sharedSizeBytes != 0)
-        return fail(GP_ERR_UNSUPPORTED, "LDS pass: the kernel was built with %zu bytes of static LDS", (size_t)attr.sharedSizeBytes);
-    // beyond 64 KB of dynamic LDS a kernel has to be cleared for the size (a host-side setting, per device)
     const size_t shm = (size_t)lds_rows(max_members) * 16 + 16;
-    GP_HIP(hipFuncSetAttribute((const void*)gp_hop_cluster_lds, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm));
+    for (const void* kernel : {(const void*)gp_hop_cluster_lds<float>, (const void*)gp_hop_cluster_lds<uint16_t>}) {
+        // the kernel addresses its dynamic LDS from 0: true as long as it has no static LDS before it
+        hipFuncAttributes attr;
+        GP_HIP(hipFuncGetAttributes(&attr, kernel));
+        if (attr.sharedSizeBytes != 0)
+            return fail(GP_ERR_UNSUPPORTED, "LDS pass: the kernel was built with %zu bytes of static LDS", (size_t)attr.sharedSizeBytes);
+        // beyond 64 KB of dynamic LDS a kernel has to be cleared for the size (a host-side setting, per device)
+        GP_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm));
+    }
     return GP_OK;
 }
 
 gp_status launch_pack_strips(const HotLdsArgs& a, hipStream_t stream)
 {
     if (a.d < 4 || !a.xin || !a.packed || !a.members || a.num_members <= 0)
-        return fail(GP_ERR_INVALID_ARG, "packing strips: needs at least four fp32 columns, lists and a buffer");
-    hipLaunchKernelGGL(gp_pack_strips, dim3((unsigned)((a.num_members + 255) / 256)), dim3(256), 0, stream, a.members, a.num_members,
-                       a.src_scale, a.xin, a.ldin, a.d, a.packed);
+        return fail(GP_ERR_INVALID_ARG, "packing strips: needs at least four columns, lists and a buffer");
+    const dim3 grid((unsigned)((a.num_members + 255) / 256)), block(256);
+    if (a.dtype == GP_F32)
+        hipLaunchKernelGGL(gp_pack_strips<float>, grid, block, 0, stream, a.members, a.num_members, a.src_scale, (const float*)a.xin, a.ldin,
+                           a.d, a.packed);
+    else
+        hipLaunchKernelGGL(gp_pack_strips<uint16_t>, grid, block, 0, stream, a.members, a.num_members, a.src_scale, (const uint16_t*)a.xin,
+                           a.ldin, a.d, a.packed);
     GP_HIP(hipGetLastError());
     return GP_OK;
 }
@@ -287,7 +309,8 @@ gp_status launch_pack_strips(const HotLdsArgs& a, hipStream_t stream)
 gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
 {
     if (a.d < 4 || a.num_sets <= 0 || !a.ctrl || !a.xin || !a.planes || a.num_pos <= 0 || a.num_members <= 0 || !a.octets || !a.octet_off)
-        return fail(GP_ERR_INVALID_ARG, "LDS pass: needs at least four fp32 columns, record sets, lists, planes and a cursor buffer");
+        return fail(GP_ERR_INVALID_ARG, "LDS pass: needs at least four columns, record sets, lists, planes and a cursor buffer");
+    if (a.dtype == GP_BF16 && a.d % 4 != 0) return fail(GP_ERR_INVALID_ARG, "LDS pass: bf16 rows need a multiple of four columns");
     if (a.max_members < 0 || a.max_members > kLdsMaxMembers)
         return fail(GP_ERR_INVALID_ARG, "LDS pass: a list of %d rows does not fit the LDS", a.max_members);
     const size_t shm = (size_t)lds_rows(a.max_members) * 16 + 16;  // the rows and the item word
@@ -296,10 +319,14 @@ gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
     const dim3 grid(8 * 32 * (two ? 2 : 1)), block(two ? 512 : 1024);
     OctetLists lists;
     for (int x = 0; x <= 8; ++x) lists.off[x] = a.octet_off[x];
-    hipLaunchKernelGGL(gp_hop_cluster_lds, grid, block, shm, stream, a.members, a.member_off, a.list_of_set, a.group_off, a.wave_cut,
-                       a.groups, a.octets, lists, a.ids, a.packed, a.num_members, a.src_scale, a.xin, a.ldin, a.planes, a.num_pos, a.d,
-                       a.ctrl,
-                       (int)lds_rows(a.max_members));
+    if (a.dtype == GP_F32)
+        hipLaunchKernelGGL(gp_hop_cluster_lds<float>, grid, block, shm, stream, a.members, a.member_off, a.list_of_set, a.group_off,
+                           a.wave_cut, a.groups, a.octets, lists, a.ids, a.packed, a.num_members, a.src_scale, (const float*)a.xin, a.ldin,
+                           a.planes, a.num_pos, a.d, a.ctrl, (int)lds_rows(a.max_members));
+    else
+        hipLaunchKernelGGL(gp_hop_cluster_lds<uint16_t>, grid, block, shm, stream, a.members, a.member_off, a.list_of_set, a.group_off,
+                           a.wave_cut, a.groups, a.octets, lists, a.ids, a.packed, a.num_members, a.src_scale, (const uint16_t*)a.xin,
+                           a.ldin, a.planes, a.num_pos, a.d, a.ctrl, (int)lds_rows(a.max_members));
     GP_HIP(hipGetLastError());
     return GP_OK;
 }

@@ -280,7 +280,8 @@ struct HotLdsArgs {
     const uint16_t* ids;
     int32_t num_sets, max_members;
     const float* src_scale;  // DEVICE n weights applied to source rows, or nullptr
-    const float* xin;
+    const void* xin;         // DEVICE rows of `dtype` (bf16 rows: d a multiple of 4)
+    gp_dtype dtype;
     int64_t ldin;
     float* planes;           // DEVICE ceil(d / 32) planes of num_pos entries of 8 x 4 floats (an octet of strips)
     int64_t num_pos;
@@ -347,8 +348,9 @@ struct HopArgs {
     int64_t column_slices = 0;
     int64_t persistent_blocks = 0;  // workgroups of the launch, 0 = as many as stay resident
     int64_t column_tile = 0;        // feature columns per kernel pass, 0 = automatic
-    // optional plane entries (fp32 storage, vectors of 4, implicit lists): a record whose slice byte is
-    // kAddPlaneEntry adds planes[((v / 8) * num_pos + p) * 32 + (v % 8) * 4 ..] to its vector v, p being its place in segs
+    // optional plane entries (vectors of 4 columns, or of 8 bf16 columns with d a multiple of 4; implicit lists): a
+    // record whose slice byte is kAddPlaneEntry adds, to the four columns of strip t, planes[((t / 8) * num_pos + p) * 32
+    // + (t % 8) * 4 ..], p being its place in segs
     const float* planes = nullptr;
     int64_t num_pos = 0;
     // optional running combination: comb[row] += gamma * result row (fp32, leading dimension ldc);

@@ -497,8 +497,9 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
         const float rs = (!partial && row_scale) ? row_scale[r.row] : 1.0f;
         // what an earlier launch has already added up for this record (the sums of its other non-zeros,
         // four columns to an entry, one plane per vector of the row) joins the sum here
+        constexpr bool kCanAddPlanes = VEC == 4 || (VEC == 8 && sizeof(T) == 2);  // whole strips of four columns per vector
         bool planed = false;
-        if constexpr (VEC == 4 && sizeof(T) == 4) planed = planes != nullptr && (r.slice & kAddPlaneEntry) != 0;
+        if constexpr (kCanAddPlanes) planed = planes != nullptr && (r.slice & kAddPlaneEntry) != 0;
         const int64_t place = place_of(t0);
 #pragma unroll
         for (int v = 0; v < VPL; ++v) {
@@ -507,10 +508,17 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
             float before[VEC];
 #pragma unroll
             for (int i = 0; i < VEC; ++i) before[i] = 0.0f;
-            if constexpr (VEC == 4 && sizeof(T) == 4) {
-                if (planed) {  // entries are kept eight vectors (an octet of strips, one 128-byte line) together
-                    const int j = vlo + v * G + lane;
-                    Row<float, VEC>::load(planes + ((int64_t)(j >> 3) * num_pos + place) * 32 + (j & 7) * 4, before);
+            if constexpr (kCanAddPlanes) {
+                if (planed) {  // entries are kept eight strips (an octet, one 128-byte line) together
+                    // strip of the vector's first column (a last vector moved back ends with the row, as the last strip does)
+                    const int t = (coff[v] + 3) >> 2;
+#pragma unroll
+                    for (int h = 0; h < VEC / 4; ++h) {  // (a vector of eight columns: two strips, maybe of two octets)
+                        float part[4];
+                        Row<float, 4>::load(planes + ((int64_t)((t + h) >> 3) * num_pos + place) * 32 + ((t + h) & 7) * 4, part);
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) before[h * 4 + i] = part[i];
+                    }
                 }
             }
 #pragma unroll

@@ -332,8 +332,10 @@ gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream,
     decide_hot_mode(plan, a.d);
     DevicePlan& D = plan->dev;
     // the hot pieces can come out of LDS: fp32 rows of at least one strip, a plain hop
-    const bool lds_call = lds && may_build && a.dtype == GP_F32 && a.d >= 4 && !a.comb && a.xout && plan->opt.lds_pass != 2 &&
-                          plan->opt.split_records != 2;
+    // (whole strips of four columns per vector of the segment kernel: fp32 rows, or bf16 rows of a multiple of four columns
+    // in vectors of 4 or 8)
+    const bool lds_call = lds && may_build && a.d >= 4 && !a.comb && a.xout && plan->opt.lds_pass != 2 && plan->opt.split_records != 2 &&
+                          (a.dtype == GP_F32 ? vec == 4 : (a.d % 4 == 0 && (vec == 4 || vec == 8)));
     // the LDS pass: wherever the plan's lists are short enough for it (the plan's clusters, or its hubs)
     if (lds_call && (plan->hot_mode == 1 || plan->hot_mode == 2)) {
         gp_status st = ensure_lds(plan, a.d, stream);
@@ -523,7 +525,8 @@ gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t
             h.num_sets = D.lds_num_sets;
             h.max_members = D.lds_max_members;
             h.src_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : nullptr;
-            h.xin = (const float*)a.xin;
+            h.xin = a.xin;
+            h.dtype = dtype;
             h.ldin = a.ldin;
             h.planes = D.lds_planes;
             h.num_pos = (int64_t)plan->segs.size();

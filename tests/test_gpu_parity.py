@@ -329,15 +329,18 @@ def community_workload(n_comm, comm, pairs, d, seed):
                              gp_synth.SYMMETRISE | gp_synth.ADD_SELF_LOOPS, None, 4, src, dst, X)
 
 
-@pytest.mark.parametrize("d,agg", [(602, gp.GP_AGG_SUM), (100, gp.GP_AGG_MEAN), (37, gp.GP_AGG_SYM), (4, gp.GP_AGG_SYM),
-                                   (7, gp.GP_AGG_SUM)])
+@pytest.mark.parametrize("dtype,d,agg", [(gp.GP_F32, 602, gp.GP_AGG_SUM), (gp.GP_F32, 100, gp.GP_AGG_MEAN), (gp.GP_F32, 37, gp.GP_AGG_SYM),
+                                         (gp.GP_F32, 4, gp.GP_AGG_SYM), (gp.GP_F32, 7, gp.GP_AGG_SUM),
+                                         (gp.GP_BF16, 128, gp.GP_AGG_SYM), (gp.GP_BF16, 36, gp.GP_AGG_SUM), (gp.GP_BF16, 100, gp.GP_AGG_MEAN)])
 @pytest.mark.parametrize("segment_edges,order", [(0, 1), (16, 1), (0, 3)])
-def test_lds_pass_matches_the_oracle(d, agg, segment_edges, order, _mapping_defaults):
+def test_lds_pass_matches_the_oracle(dtype, d, agg, segment_edges, order, _mapping_defaults):
     """The hot pieces gathered from LDS, reads in conflict-free order (1) and in the column
     list's (3), forced (with rows cut into short segments the automatic choice would decline
     the padding): community graphs whose clusters take one
     strip in half of a compute unit's LDS and more than half of it, column counts that
-    end in a partial strip, rows with and without partial-row slots, every operator.
+    end in a partial strip, rows with and without partial-row slots, every operator, fp32
+    storage and bf16 storage (rows of a multiple of four columns: vectors of eight columns
+    that span two strips, the last one moved back).
     A second call on the same plan's twin repeats the first bit for bit."""
     cases = [gp_synth.make_workload(4, scale=0.004, d=d), gp_synth.make_workload(4, scale=0.04, d=d)]
     if d <= 37:
@@ -350,8 +353,8 @@ def test_lds_pass_matches_the_oracle(d, agg, segment_edges, order, _mapping_defa
         budget = max(20_000, w.m // 3)
         gp.gp_profile_enable(True)
         try:
-            a = parity_case(w, K=2, dtype=gp.GP_F32, agg=agg, budget=budget)
-            b = parity_case(w, K=2, dtype=gp.GP_F32, agg=agg, budget=budget)
+            a = parity_case(w, K=2, dtype=dtype, agg=agg, budget=budget)
+            b = parity_case(w, K=2, dtype=dtype, agg=agg, budget=budget)
             launches, _ = gp.gp_profile_read("gp_hop_cluster_lds")
         finally:
             gp.gp_profile_enable(False)
@@ -366,7 +369,8 @@ def test_hub_pass_matches_the_oracle(cfg, scale, d, agg, segment_edges, order, _
     """Power-law graphs (no row clusters): the non-zeros whose source is one of the most popular
     rows are served from LDS, the others gathered from memory, forced on graphs smaller than
     the automatic choice would take.  Checked against the oracle, with the LDS launch
-    counted; whole records (hub_pass = 2) and bf16 storage keep working on the same graph."""
+    counted; bf16 storage goes the same way where the rows are whole strips, and whole
+    records (hub_pass = 2) keep working on the same graph."""
     w = gp_synth.make_workload(cfg, scale=scale, d=d)
     gp.gp_set_option("segment_edges", segment_edges)
     gp.gp_set_option("hub_pass", 1)
@@ -376,10 +380,11 @@ def test_hub_pass_matches_the_oracle(cfg, scale, d, agg, segment_edges, order, _
     try:
         a = parity_case(w, K=2, dtype=gp.GP_F32, agg=agg, budget=budget)
         launches, _ = gp.gp_profile_read("gp_hop_cluster_lds")
-        parity_case(w, K=2, dtype=gp.GP_BF16, agg=agg, budget=budget)       # bf16: no LDS pass, the segment kernel alone
+        parity_case(w, K=2, dtype=gp.GP_BF16, agg=agg, budget=budget)       # bf16 rows: the pass needs a multiple of four columns
         launches_after, _ = gp.gp_profile_read("gp_hop_cluster_lds")
     finally:
         gp.gp_profile_enable(False)
-    assert launches == 2 and launches_after == 2, f"the LDS pass ran {launches} / {launches_after} times, expected once per fp32 hop"
+    want_after = 4 if d % 4 == 0 else 2
+    assert launches == 2 and launches_after == want_after, f"the LDS pass ran {launches} / {launches_after} times"
     gp.gp_set_option("hub_pass", 2)
     parity_case(w, K=2, dtype=gp.GP_F32, agg=agg, budget=budget)
