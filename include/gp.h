@@ -269,17 +269,20 @@ gp_status gp_plan_streamed_shape(const gp_plan *plan, int64_t *edge_blocks, int6
  * gp_propagate_noalloc -- gp_propagate for callers that cannot allocate: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments and same kernels as gp_propagate on device-resident operands, and the same
- * bits in out_stack whenever that call works on whole records (option "split_records"
- * = 2, or a graph without row clusters or popular rows worth a pass; with cut records its partial sums are grouped
- * differently and the two agree to rounding), but the call makes no allocation of any kind: the scratch
+ * bits in out_stack whenever both calls take the same schedule -- whole records (option
+ * "split_records" = 2, or a graph without row clusters or popular rows worth a pass), or the
+ * LDS pass with what an earlier gp_propagate on the plan has built for it; else a row's
+ * partial sums are grouped differently and the two agree to rounding -- but the call makes
+ * no allocation of any kind: the scratch
  * the kernels need (work cursors, partial rows of rows that were cut) is a fixed array
  * in device memory of 64 MiB + 256 bytes that each GPU the library is used on holds
  * until the process ends.
  *
  *  plan   must already be on the current device (the first gp_propagate on a plan
  *         uploads it); else GP_ERR_INVALID_ARG.  What earlier calls built is used (work
- *         lists, per-edge weights); what they did not build is done without (implicit
- *         lists, weights gathered by column id -- the same numbers).
+ *         lists, per-edge weights, the LDS pass's schedule and planes for rows of as many
+ *         columns); what they did not build is done without (implicit lists, weights
+ *         gathered by column id -- the same numbers).
  *  X, out_stack  DEVICE only (pinned-host operands: GP_ERR_INVALID_ARG).
  *
  * Limit: plan partial rows x round_up(d, 4) x 4 bytes <= gp_noalloc_partial_row_bytes()

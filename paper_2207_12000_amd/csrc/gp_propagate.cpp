@@ -331,14 +331,16 @@ gp_status attach_work_lists(const gp_plan* plan, HopArgs& a, hipStream_t stream,
     if (!may_build && plan->hot_mode == 0) return GP_OK;  // nothing built yet: implicit lists
     decide_hot_mode(plan, a.d);
     DevicePlan& D = plan->dev;
-    // the hot pieces can come out of LDS: fp32 rows of at least one strip, a plain hop
-    // (whole strips of four columns per vector of the segment kernel: fp32 rows, or bf16 rows of a multiple of four columns
-    // in vectors of 4 or 8)
-    const bool lds_call = lds && may_build && a.d >= 4 && !a.comb && a.xout && plan->opt.lds_pass != 2 && plan->opt.split_records != 2 &&
+    // the hot non-zeros can come out of LDS where the segment kernel's vectors are whole strips of four columns:
+    // fp32 rows, or bf16 rows of a multiple of four columns in vectors of 4 or 8; a caller that may not allocate
+    // gets the pass if an earlier call has left everything it needs
+    const int64_t strips = ((int64_t)a.d + 3) / 4;
+    const bool all_there = D.lds_state == 1 && D.lds_octets_strips == (int)strips && D.lds_planes_strips >= strips;  // nothing to build
+    const bool lds_call = lds && (may_build || all_there) && a.d >= 4 && plan->opt.lds_pass != 2 && plan->opt.split_records != 2 &&
                           (a.dtype == GP_F32 ? vec == 4 : (a.d % 4 == 0 && (vec == 4 || vec == 8)));
     // the LDS pass: wherever the plan's lists are short enough for it (the plan's clusters, or its hubs)
     if (lds_call && (plan->hot_mode == 1 || plan->hot_mode == 2)) {
-        gp_status st = ensure_lds(plan, a.d, stream);
+        gp_status st = all_there ? GP_OK : ensure_lds(plan, a.d, stream);
         if (st != GP_OK) return st;
         if (D.lds_state == 1) {
             *lds = true;
@@ -441,6 +443,57 @@ gp_status propagate_resident(const gp_plan* plan, const void* X, int64_t ldx, in
     return resident_hops(plan, X, ldx, d, dtype, agg, K, out, ldo, stream, D.carry, D.carry_ld, D.ctrl, true);
 }
 
+// One hop with the LDS pass: the non-zeros whose source is on a list first, out of LDS, into the
+// planes; then the segment kernel over the other non-zeros, in the same order of segments, adding
+// the plane entries and finishing every segment as the plan says (a = the hop's launch as it would
+// be on implicit lists; its record list, column list and weights are replaced here).
+gp_status lds_hop(const gp_plan* plan, HopArgs& a, gp_agg agg, hipStream_t stream)
+{
+    const DevicePlan& D = plan->dev;
+    gp_status st;
+    HotLdsArgs h;
+    h.members = D.lds_members;
+    h.member_off = D.lds_member_off;
+    h.list_of_set = D.lds_list_of_set;
+    h.group_off = D.lds_group_off;
+    h.wave_cut = D.lds_wave_cut;
+    h.groups = D.lds_groups;
+    h.octets = D.lds_octets;
+    h.octet_off = D.lds_octet_off;
+    h.ids = D.lds_ids;
+    h.num_sets = D.lds_num_sets;
+    h.max_members = D.lds_max_members;
+    h.src_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : nullptr;
+    h.xin = a.xin;
+    h.dtype = a.dtype;
+    h.ldin = a.ldin;
+    h.planes = D.lds_planes;
+    h.num_pos = (int64_t)plan->segs.size();
+    h.packed = D.lds_packed;
+    h.num_members = D.lds_num_members;
+    h.d = a.d;
+    h.ctrl = a.ctrl;
+    if (h.packed) {
+        profile_begin("gp_pack_strips", stream);
+        st = launch_pack_strips(h, stream);
+        profile_end(stream);
+        if (st != GP_OK) return st;
+    }
+    profile_begin("gp_hop_cluster_lds", stream);
+    st = launch_hot_lds(h, stream);
+    profile_end(stream);
+    if (st != GP_OK) return st;
+    a.segs = D.lds_cold;
+    a.col = D.lds_col;
+    if (a.edge_w) {  // weights by column id: the per-edge array follows the plan's column order
+        a.edge_w = D.dinv_sqrt;
+        a.edge_w_per_edge = false;
+    }
+    a.planes = D.lds_planes;
+    a.num_pos = h.num_pos;
+    return hop_passes(a, stream);
+}
+
 // The hop loop on a plan that is already on the device.  may_allocate = false: only what
 // exists is used (work lists that have been built, else the implicit ones; for the sym
 // operator the per-edge weight array if it exists, else the weights gathered by column id,
@@ -509,50 +562,7 @@ gp_status resident_hops(const gp_plan* plan, const void* X, int64_t ldx, int32_t
             if (cold.num_segs > 0 && (st = hop_passes(cold, stream)) != GP_OK) return st;
         }
         if (lds) {
-            // The non-zeros whose source is on a list first, out of LDS, into the planes; then the
-            // segment kernel over the other non-zeros, in the same order of segments, adding the
-            // plane entries and finishing every segment as the plan says.
-            HotLdsArgs h;
-            h.members = D.lds_members;
-            h.member_off = D.lds_member_off;
-            h.list_of_set = D.lds_list_of_set;
-            h.group_off = D.lds_group_off;
-            h.wave_cut = D.lds_wave_cut;
-            h.groups = D.lds_groups;
-            h.octets = D.lds_octets;
-            h.octet_off = D.lds_octet_off;
-            h.ids = D.lds_ids;
-            h.num_sets = D.lds_num_sets;
-            h.max_members = D.lds_max_members;
-            h.src_scale = agg == GP_AGG_SYM ? D.dinv_sqrt : nullptr;
-            h.xin = a.xin;
-            h.dtype = dtype;
-            h.ldin = a.ldin;
-            h.planes = D.lds_planes;
-            h.num_pos = (int64_t)plan->segs.size();
-            h.packed = D.lds_packed;
-            h.num_members = D.lds_num_members;
-            h.d = d;
-            h.ctrl = ctrl;
-            if (h.packed) {
-                profile_begin("gp_pack_strips", stream);
-                st = launch_pack_strips(h, stream);
-                profile_end(stream);
-                if (st != GP_OK) return st;
-            }
-            profile_begin("gp_hop_cluster_lds", stream);
-            st = launch_hot_lds(h, stream);
-            profile_end(stream);
-            if (st != GP_OK) return st;
-            a.segs = D.lds_cold;
-            a.col = D.lds_col;
-            if (a.edge_w) {  // weights by column id: the per-edge array follows the plan's column order
-                a.edge_w = D.dinv_sqrt;
-                a.edge_w_per_edge = false;
-            }
-            a.planes = D.lds_planes;
-            a.num_pos = h.num_pos;
-            if ((st = hop_passes(a, stream)) != GP_OK) return st;
+            if ((st = lds_hop(plan, a, agg, stream)) != GP_OK) return st;
         } else if ((st = hop_passes(a, stream)) != GP_OK) {
             return st;
         }
@@ -642,8 +652,13 @@ gp_status propagate_combine(const gp_plan* plan, const void* X, int64_t ldx, int
         a.comb = comb;
         a.ldc = ldc;
         a.gamma = coeff[k];
-        if ((st = attach_work_lists(plan, a, stream)) != GP_OK) return st;
-        if ((st = hop_passes(a, stream)) != GP_OK) return st;
+        bool lds = false;
+        if ((st = attach_work_lists(plan, a, stream, true, nullptr, &lds)) != GP_OK) return st;
+        if (lds) {
+            if ((st = lds_hop(plan, a, agg, stream)) != GP_OK) return st;
+        } else if ((st = hop_passes(a, stream)) != GP_OK) {
+            return st;
+        }
         if (!plan->split.empty()) {
             FixupArgs f;
             f.split = D.split;

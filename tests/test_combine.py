@@ -76,6 +76,47 @@ def test_gpu_combine_matches_oracle(gpu_or_skip, dtype, agg, K, d, ld_pad):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("dtype,d,agg,hubs", [(gp.GP_F32, 52, AGG_SYM, False), (gp.GP_BF16, 36, AGG_SYM, False), (gp.GP_F32, 37, 1, True)])
+def test_gpu_combine_with_the_lds_pass(gpu_or_skip, dtype, d, agg, hubs):
+    """The filter sum where the hops take their hot non-zeros from LDS (a community graph's clusters, a
+    power-law graph's hubs; forced on these small graphs): the epilogue that adds gamma_k times the hop's rows
+    sits in the segment kernel, after the plane entries have joined the sums."""
+    import torch
+    K = 3
+    w = gp_synth.make_workload(2, scale=0.2, d=d) if hubs else gp_synth.make_workload(4, scale=0.01, d=d)
+    X = w.X if dtype == gp.GP_F32 else gp_synth.f32_to_bf16_bits(w.X)
+    Xw = (w.X if dtype == gp.GP_F32 else gp_synth.bf16_bits_to_f32(X)).astype(np.float64)
+    coeff = np.random.default_rng(d).uniform(-1, 1, K + 1).tolist()
+    tdt = torch.float32 if dtype == gp.GP_F32 else torch.bfloat16
+    xt = torch.from_numpy(X) if dtype == gp.GP_F32 else torch.from_numpy(X.view(np.int16)).view(torch.bfloat16)
+    xd = xt.cuda()
+    out = torch.full((w.n, d), float("nan"), dtype=tdt, device="cuda:0")
+    budget = max(20_000, w.m // 3)
+    op = oracle.plan_blocks(w.src, w.dst, w.n, budget, w.flags)
+    gp.gp_set_option("segment_edges", 16)
+    gp.gp_set_option("hub_pass" if hubs else "lds_pass", 1)
+    gp.gp_profile_enable(True)
+    try:
+        with gp.gp_plan_blocks(w.src, w.dst, w.n, budget, w.flags) as lp:
+            stream = torch.cuda.current_stream().cuda_stream
+            gp.gp_propagate_combine(lp, xd.data_ptr(), d, d, dtype, agg, K, coeff, out.data_ptr(), d, stream)
+            torch.cuda.synchronize()
+        launches, _ = gp.gp_profile_read("gp_hop_cluster_lds")
+    finally:
+        gp.gp_profile_enable(False)
+        gp.gp_set_option("segment_edges", 0)
+        gp.gp_set_option("lds_pass", 0)
+        gp.gp_set_option("hub_pass", 0)
+    assert launches == K
+    got = out.float().cpu().numpy().astype(np.float64)
+    c32 = np.asarray(coeff, dtype=np.float32).astype(np.float64)
+    want, bound = oracle.combine(op, Xw, agg, c32, threads=4)
+    tol = 1e-5 if dtype == gp.GP_F32 else 1e-2
+    err = np.abs(got - want)
+    assert np.all(err <= tol * bound + 1e-30), f"worst ratio {np.max(err / (bound + 1e-300)):.3g}"
+
+
+@pytest.mark.gpu
 def test_gpu_combine_rejects_bad_arguments(gpu_or_skip):
     import torch
     x = torch.zeros((8, 4), device="cuda:0")

@@ -88,3 +88,23 @@ def test_limit_and_unprepared_plan_are_errors():
         gp.gp_propagate_noalloc(plan, Xn.data_ptr(), 32, 32, gp.GP_F32, w.agg, 1, b.data_ptr(), 32, None)
         torch.cuda.synchronize()
         assert torch.equal(a, b)
+
+
+def test_the_lds_pass_is_taken_over_from_an_allocating_call():
+    """What an allocating call has built for the LDS pass (schedule, planes) serves the allocation-free call too:
+    the same launches, the same bits."""
+    import torch
+    gp.gp_set_option("split_records", 0)
+    gp.gp_set_option("lds_pass", 1)
+    try:
+        w = gp_synth.make_workload(4, scale=0.01, d=52)
+        gp.gp_set_option("segment_edges", 16)
+        gp.gp_profile_enable(True)
+        want, got = both_ways(w, gp.GP_F32, gp.GP_AGG_SYM, 2, max(20_000, w.m // 3))
+        launches, _ = gp.gp_profile_read("gp_hop_cluster_lds")
+        assert launches == 4, f"{launches} LDS launches, expected two per call"
+        assert torch.equal(want.view(torch.int32), got.view(torch.int32))
+    finally:
+        gp.gp_profile_enable(False)
+        gp.gp_set_option("lds_pass", 0)
+        gp.gp_set_option("split_records", 2)
