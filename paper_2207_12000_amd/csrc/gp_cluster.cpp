@@ -258,7 +258,13 @@ HotSets hot_sets_from_hubs(const gp_plan& P, int32_t hubs, int64_t rows_per_set)
     HotSets H;
     const int64_t n = P.n;
     std::vector<int32_t> uses((size_t)n, 0);
-    for (int32_t j : P.col) ++uses[(size_t)j];
+    {
+        const int64_t nnz = (int64_t)P.col.size();
+        const int nt = nnz < (1 << 20) ? 1 : host_threads();
+        parallel_run(nt, [&](int t, int k) {
+            for (int64_t e = nnz * t / k; e < nnz * (t + 1) / k; ++e) __atomic_fetch_add(&uses[(size_t)P.col[(size_t)e]], 1, __ATOMIC_RELAXED);
+        });
+    }
     hubs = (int32_t)std::min<int64_t>(hubs, n);
     std::vector<int32_t> order((size_t)n);
     std::iota(order.begin(), order.end(), 0);
