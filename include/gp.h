@@ -157,7 +157,7 @@ int64_t gp_plan_segment_edges(const gp_plan *plan);           /* the segment len
  * rows that are most often a source account for at least 15 % of the non-zeros (and non-zeros
  * times d is at least 2e9: below that the pass's launches cost more than they save): they are
  * the one list, every set (a range of consecutive
- * rows) gathers from it.
+ * rows; about 2048 / strips of them) gathers from it.
  * The pass takes the plan's segments in an order of its own: set by set, inside a set most
  * hot non-zeros first.  A segment's place in that order is its position p; rest[p] is the
  * segment's record (gp_plan_segments' format) reduced to its other non-zeros, which are
@@ -434,6 +434,8 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
  *   "hub_pass"        plans without row clusters: 0 = the most popular rows are served from LDS
  *                     where they are the source of enough non-zeros (gp_plan_lds_schedule,
  *                     hot_mode 2), 1 = whenever the LDS pass applies, 2 = never.
+ *   "hub_sets"        hot_mode 2: number of row sets the rows are cut into (1 .. 65536; 0 = about
+ *                     2048 / strips, fewer where a set would have less than 100000 reads).
  *   "device_plan_chunk"  GP_PLAN_ON_DEVICE: most candidate entries sorted at once
  *                     (1 .. 2^31 - 1; 0 = 2^31 - 1).  Read by gp_plan_blocks.
  *   "cache_schedule"  0 = explicit per-XCD work lists where the plan's row clusters

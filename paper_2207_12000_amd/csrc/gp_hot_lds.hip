@@ -202,14 +202,31 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
             if (g < g_end) {
                 const int64_t k_end = groups[g_end].id_off >> 9;  // (the list of groups ends with a sentinel)
                 int64_t k = groups[g].id_off >> 9;
-                int64_t k_group_end = k + groups[g].steps / kStepBlock;
-                // where this lane's sums go: entry (octet, position) of the planes, 16 bytes of its 128; -1: nowhere
-                auto entry_of = [&](const LdsGroup& G) -> int64_t {
-                    return lane < G.count ? (((int64_t)(strip >> 3) * num_pos + G.first_pos + lane) * 32 + (strip & 7) * 4) : -1;
+                // The descriptors of the run's groups are read 64 at a time, one per lane, and handed out with
+                // v_readlane: a scalar load per group would share its counter with the LDS reads, and every wait
+                // for those would then also wait for a descriptor on its way from memory.
+                int batch = g;  // group of lane 0's descriptor
+                int d_steps = 0, d_count = 0;
+                long long d_pos = 0;
+                auto read_batch = [&](int g0) {
+                    const LdsGroup G = groups[min(g0 + lane, g_end)];
+                    d_steps = G.steps;
+                    d_count = G.count;
+                    d_pos = G.first_pos;
+                    batch = g0;
                 };
-                int64_t entry = entry_of(groups[g]);
-                // what the group after the current one will need, asked for one group ahead
-                LdsGroup next = groups[min(g + 1, g_end)];
+                auto blocks_of = [&](int gg) { return __builtin_amdgcn_readlane(d_steps, gg - batch) / kStepBlock; };
+                // where this lane's sums of group gg go: entry (octet, position) of the planes, 16 bytes of its 128; -1: nowhere
+                auto entry_of = [&](int gg) -> int64_t {
+                    const int count = __builtin_amdgcn_readlane(d_count, gg - batch);
+                    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)d_pos, gg - batch);
+                    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)((unsigned long long)d_pos >> 32), gg - batch);
+                    const int64_t first = (int64_t)(((unsigned long long)hi << 32) | lo);
+                    return lane < count ? (((int64_t)(strip >> 3) * num_pos + first + lane) * 32 + (strip & 7) * 4) : -1;
+                };
+                read_batch(g);
+                int64_t k_group_end = k + blocks_of(g);
+                int64_t entry = entry_of(g);
                 const v4u* ip = reinterpret_cast<const v4u*>(ids) + lane;
                 v4f_a16 acc[kChains];
 #pragma unroll
@@ -234,19 +251,35 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
                         for (int i = 0; i < kAhead; ++i) add_block(q[i]);
                         return;
                     }
+                    // a group ends somewhere in these blocks (short segments: most of the time).  Two blocks of one
+                    // group are still taken in one go, so that their sixteen reads overlap.
+                    auto leave = [&]() {  // the group's last block is done: its sums leave, the next group begins
+                        const v4f_a16 sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+                        if (entry >= 0) *reinterpret_cast<v4f_a16*>(planes + entry) = sum;
 #pragma unroll
-                    for (int i = 0; i < kAhead; ++i) {
-                        if (k0 + i < k_end) {  // the same for every lane of the wave
+                        for (int u = 0; u < kChains; ++u) acc[u] = v4f_a16{0.0f, 0.0f, 0.0f, 0.0f};
+                        ++g;
+                        if (g < g_end) {
+                            if (g - batch == kLanes) read_batch(g);
+                            k_group_end += blocks_of(g);
+                            entry = entry_of(g);
+                        }
+                    };
+#pragma unroll
+                    for (int i = 0; i < kAhead; i += 2) {
+                        const bool has0 = k0 + i < k_end, has1 = k0 + i + 1 < k_end;  // the same for every lane of the wave
+                        if (has1 && k0 + i + 1 != k_group_end) {  // both blocks belong to one group
                             add_block(q[i]);
-                            if (k0 + i + 1 == k_group_end) {  // the group's last block: its sums leave, the next group begins
-                                const v4f_a16 sum = (acc[0] + acc[1]) + (acc[2] + acc[3]);
-                                if (entry >= 0) *reinterpret_cast<v4f_a16*>(planes + entry) = sum;
-#pragma unroll
-                                for (int u = 0; u < kChains; ++u) acc[u] = v4f_a16{0.0f, 0.0f, 0.0f, 0.0f};
-                                ++g;
-                                k_group_end += next.steps / kStepBlock;
-                                entry = entry_of(next);
-                                next = groups[min(g + 1, g_end)];
+                            add_block(q[i + 1]);
+                            if (k0 + i + 2 == k_group_end) leave();
+                        } else {
+                            if (has0) {
+                                add_block(q[i]);
+                                if (k0 + i + 1 == k_group_end) leave();
+                            }
+                            if (has1) {
+                                add_block(q[i + 1]);
+                                if (k0 + i + 2 == k_group_end) leave();
                             }
                         }
                     }

@@ -37,6 +37,7 @@ struct Options {
     int64_t lds_pass = 0;        // hot pieces gathered from LDS where the clusters fit it: 0 = automatic, 1 = wherever possible
                                  // (conflict-free order), 2 = never, 3 = wherever possible (column-list order)
     int64_t hub_pass = 0;        // graphs without row clusters: the most popular rows served from LDS: 0 = where it pays, 1 = always, 2 = never
+    int64_t hub_sets = 0;        // hub pass: row sets the rows are cut into, 0 = automatic
     int64_t device_plan_chunk = 0;  // GP_PLAN_ON_DEVICE: most candidate entries sorted at once, 0 = 2^31 - 1
 };
 Options& options();

@@ -203,15 +203,17 @@ void decide_hot_mode(const gp_plan* plan, int32_t d)
     const bool forced = plan->opt.hub_pass == 1;
     if (plan->opt.hub_pass == 2 || plan->opt.lds_pass == 2 || plan->opt.split_records == 2) return;
     if (!forced && (double)plan->nnz * (double)d < kMinHubWork) return;
-    // about 2048 work items (set x strip) per launch, sets of at least 1024 rows
+    // about 2048 work items (set x strip) per launch, sets of at least 1024 rows (measured on config 3: 10 / 20 / 40 /
+    // 81 / 160 sets of its 25 strips give an LDS launch of 1.28 / 1.08 / 1.07 / 0.80 / 0.77 ms and a segment launch
+    // of 6.66 / 6.75 / 6.77 / 6.83 / 6.86 - 7.03 ms: larger sets order more rows by their number of hot non-zeros)
     const int64_t strips = ((int64_t)d + 3) / 4;
-    int64_t sets = std::max<int64_t>(1, 2048 / strips);
-    int64_t rows_per_set = std::max<int64_t>(1024, (plan->n + sets - 1) / sets);
+    int64_t sets = plan->opt.hub_sets > 0 ? plan->opt.hub_sets : std::max<int64_t>(1, 2048 / strips);
+    int64_t rows_per_set = std::max<int64_t>(plan->opt.hub_sets > 0 ? 64 : 1024, (plan->n + sets - 1) / sets);
     HotSets H = hot_sets_from_hubs(*plan, kLdsMaxMembers, rows_per_set);
     if (!forced && H.hot_fraction < kMinHubFraction) return;
     // ... but no more sets than have enough to read each (the hubs do not depend on the sets: same list)
     const int64_t reads = (int64_t)(1.5 * H.hot_fraction * (double)plan->nnz);
-    if (reads / kLdsMinReadsPerSet < H.num_sets) {
+    if (plan->opt.hub_sets == 0 && reads / kLdsMinReadsPerSet < H.num_sets) {
         sets = std::max<int64_t>(1, reads / (2 * kLdsMinReadsPerSet));
         rows_per_set = std::max<int64_t>(1024, (plan->n + sets - 1) / sets);
         H = hot_sets_from_hubs(*plan, kLdsMaxMembers, rows_per_set);
