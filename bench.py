@@ -30,6 +30,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 FP32_VECTOR_PEAK_TFLOPS = 157.3
+LDS_PEAK_GBS = 256 * 256 * 2.4   # 256 compute units x 256 bytes per clock (ds_read_b128, measured: 146 TB/s sequential) x 2.4 GHz
 HEADLINE_WORKLOAD = 4            # the largest workload that is resident in HBM
 IN_HBM_WORKLOADS = (1, 2, 3, 4)
 
@@ -276,6 +277,7 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
     flops_per_launch = 2 * nnz * d // launches_per_hop          # one multiply-add per non-zero and column
     gathered_per_launch = nnz * d * elem // launches_per_hop    # bytes the lanes read if every row comes from cache
     S, slice_elems, _, _ = plan.work_lists(d, w.dtype, max(1, min(16 // elem, d)))
+    sched = None
     if lds_launches:
         sched = plan.lds_schedule(0, d)
         kind = {1: "in-cluster non-zeros", 2: "non-zeros whose source is one of the 10192 most popular rows"}[sched["hot_mode"]]
@@ -326,6 +328,14 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
                          "gathered_rows": {"achieved": round(gathered_per_launch / avg_launch_s / 1e9, 1), "unit": "GB/s",
                                            "note": "nnz * d * element size per launch over its duration; rows served by the "
                                                    "XCDs' L2 arrive at 20 - 27 TB/s on this machine, rows that miss it at about 7"}}},
+        # the launch that serves the hot non-zeros from LDS: reads of 16 bytes (padding included) over its own duration
+        "lds_launch": None if not sched else {
+            "bound": "lds", "unit": "GB/s", "peak": LDS_PEAK_GBS,
+            "achieved": round(int(sched["ids"].size) * ((d + 3) // 4) * 16 / (lds_ms * 1e-3 / lds_launches) / 1e9, 1),
+            "frac": round(int(sched["ids"].size) * ((d + 3) // 4) * 16 / (lds_ms * 1e-3 / lds_launches) / 1e9 / LDS_PEAK_GBS, 4),
+            "reads_per_strip": int(sched["ids"].size), "strips": (d + 3) // 4, "avg_launch_us": round(lds_ms * 1e3 / lds_launches, 3),
+            "note": "random 16-byte reads come out of LDS at 52 - 57 TB/s on this machine, conflict-free ones (this schedule's) at "
+                    "about 100 with the index arithmetic of a read, sequential ones at 146; 5.6 vector instructions per read allow 112"},
         "other_kernels_ms_per_step": {"gp_fixup_rows": round(fix_ms / args.steps, 5),
                                       "gp_copy_rows": round(copy_ms / args.steps, 5)},
         "host_s": {"generate": round(t_gen, 2), "gp_plan_blocks": round(t_plan, 3),
