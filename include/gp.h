@@ -169,13 +169,15 @@ int64_t gp_plan_segment_edges(const gp_plan *plan);           /* the segment len
  * multiple of 8) reads; read t of lane l is ids[group_id_off[g] + (t / 8) * 512 + l * 8 +
  * t % 8]: the place of the source row on the set's list (list l = members[member_off[l] ..
  * member_off[l+1]), ascending), or, for padding, one of 16 zero rows that follow the list
- * from the next multiple of 16.  order 2 (and order 0 where it costs less: a conflict-free
- * read is served about 1.9 times faster, so where its reads, padding included, number less
- * than 1.9 times the other order's) arranges a group's reads so that the 16 lanes the LDS
- * serves together -- lanes {0-3, 12-15, 20-27} and {4-11, 16-19, 28-31} of each half of a
- * wavefront on gfx950 -- read 16 different residues of the place mod 16 at every step,
- * i.e. never collide on a bank; order 1 keeps the column list's order.  With order 0 the
- * pass applies only where the reads of the chosen order (in column-list-order equivalents)
+ * from the next multiple of 16.  Every group walks as many steps as its longest segment
+ * has reads, rounded up to 8.  order 2 (and order 0) arranges a group's reads inside those
+ * steps so that the 16 lanes the LDS serves together -- lanes {0-3, 12-15, 20-27} and
+ * {4-11, 16-19, 28-31} of each half of a wavefront on gfx950 -- read 16 different residues
+ * of the place mod 16 at every step, i.e. do not collide on a bank, as far as that can be:
+ * where a residue has more reads among the 16 segments than there are steps, the surplus
+ * takes padding slots of its own segments and meets one other read there.  order 1 keeps
+ * the column list's order (about 2.5 collisions per step).  With order 0 the pass applies
+ * only where the reads (padding included; a read of order 2 counting 1 / 1.9)
  * stay below 1.8 per hot non-zero for clusters and 4 for hubs: beyond that the same rows
  * are as fast out of the L2s, or memory, and where a set has at least 100000 reads on
  * average (staging a strip costs the same whatever is read from it).  d (>= 4) is the column count the sets of

@@ -368,16 +368,19 @@ inline int lds_pass_of_lane(int l)
     return ((l >> 5) << 1) | (first ? 0 : 1);
 }
 
-// The reads of the 16 records of one pass group, ordered so that every step asks for 16
-// different bank groups (row index mod 16).  Records and bank groups form a bipartite
-// multigraph (one edge per non-zero); padded with reads of zero rows until every record
-// and every bank group has `steps` edges it is regular, and a regular bipartite multigraph
-// is a sum of perfect matchings (Hall): each matching is one conflict-free step.
+// The reads of the 16 records of one pass group, ordered so that a step asks for 16
+// different bank groups (row index mod 16) wherever that can be.  Records and bank groups
+// form a bipartite multigraph (one edge per non-zero); with no bank group having more than
+// `steps` edges, and padded with reads of zero rows until every record and every bank
+// group has `steps` edges, it is regular, and a regular bipartite multigraph is a sum of
+// perfect matchings (Hall): each matching is one conflict-free step.
 struct PassGroup {
     int32_t count[16][16];               // real reads of record j in bank group r still to place
     std::vector<uint16_t> bucket[16];    // record j's local indices, sorted by bank group, column-list order inside one
     int32_t next[16][16];                // position in bucket[j] of the next unplaced read of bank group r
     int32_t len[16];
+    std::vector<uint16_t> table;         // schedule(): the placement, step by step
+    std::vector<uint16_t> doubled;       // schedule(): per step, the bank groups that two lanes read
 
     void load(int j, const int32_t* col, int32_t n, const int32_t* local)
     {
@@ -401,33 +404,35 @@ struct PassGroup {
         bucket[j].clear();
         for (int r = 0; r < 16; ++r) count[j][r] = next[j][r] = 0;
     }
-    // fewest steps a conflict-free order needs
-    int32_t degree() const
-    {
-        int32_t m = 0;
-        for (int j = 0; j < 16; ++j) m = std::max(m, len[j]);
-        for (int r = 0; r < 16; ++r) {
-            int32_t c = 0;
-            for (int j = 0; j < 16; ++j) c += count[j][r];
-            m = std::max(m, c);
-        }
-        return m;
-    }
-    // emit(j, step, local index) for all 16 records and `steps` >= degree() steps
-    // (false if no matching was found: cannot happen for steps >= degree(), checked all the same)
+    // emit(j, step, local index) for all 16 records and `steps` >= the longest record.  Where a bank group has
+    // more reads than there are steps, the surplus is set aside and afterwards takes the place of padding
+    // reads of its own record: it then meets another lane's read of the same bank group (a two-way conflict:
+    // one more pass for these 16 lanes at that step), which is cheaper than one more step for all 64.
+    // (false if no matching was found: cannot happen, checked all the same)
     template <class Emit>
     bool schedule(int32_t steps, uint16_t zero_base, Emit emit)
     {
-        int32_t w[16][16];  // reads of record j in bank group r still to place, padding included
+        int32_t w[16][16];     // reads of record j in bank group r still to place, padding included
+        int32_t real[16][16];  // ... of which real ones that take part in the conflict-free placement
         int32_t row_need[16], col_need[16];
-        for (int r = 0; r < 16; ++r) col_need[r] = steps;
         for (int j = 0; j < 16; ++j) {
+            if (len[j] > steps) return false;
             row_need[j] = steps - len[j];
-            for (int r = 0; r < 16; ++r) {
-                w[j][r] = count[j][r];
-                col_need[r] -= count[j][r];
-            }
+            for (int r = 0; r < 16; ++r) real[j][r] = count[j][r];
         }
+        for (int r = 0; r < 16; ++r) {
+            int32_t sum = 0;
+            for (int j = 0; j < 16; ++j) sum += count[j][r];
+            for (int j = 0; sum > steps; j = (j + 1) & 15)  // the surplus, taken from the records in turn
+                if (real[j][r] > 0) {
+                    --real[j][r];
+                    ++row_need[j];
+                    --sum;
+                }
+            col_need[r] = steps - sum;
+        }
+        for (int j = 0; j < 16; ++j)
+            for (int r = 0; r < 16; ++r) w[j][r] = real[j][r];
         for (int j = 0, r = 0; j < 16 && r < 16;) {  // padding: any matrix with these margins will do
             const int32_t c = std::min(row_need[j], col_need[r]);
             w[j][r] += c;
@@ -436,6 +441,7 @@ struct PassGroup {
             if (row_need[j] == 0) ++j;
             else ++r;
         }
+        table.assign((size_t)steps * 16, 0);
         int rec_of[16], grp_of[16];  // the current matching
         for (int i = 0; i < 16; ++i) rec_of[i] = grp_of[i] = -1;
         for (int32_t done = 0; done < steps;) {
@@ -450,11 +456,12 @@ struct PassGroup {
                 const int r = grp_of[j];
                 for (int32_t t = 0; t < c; ++t) {
                     uint16_t id = (uint16_t)(zero_base + r);
-                    if (count[j][r] > 0) {
+                    if (real[j][r] > 0) {
                         id = bucket[j][(size_t)next[j][r]++];
+                        --real[j][r];
                         --count[j][r];
                     }
-                    emit(j, done + t, id);
+                    table[(size_t)(done + t) * 16 + j] = id;
                 }
                 w[j][r] -= c;
                 if (w[j][r] == 0) {
@@ -464,6 +471,27 @@ struct PassGroup {
             }
             done += c;
         }
+        // the surplus reads, into padding slots of their own records: a step where the bank group has not
+        // been doubled yet if there is one
+        doubled.assign((size_t)steps, 0);
+        for (int j = 0; j < 16; ++j)
+            for (int r = 0; r < 16; ++r)
+                for (; count[j][r] > 0; --count[j][r]) {
+                    int32_t at = -1;
+                    for (int32_t t = 0; t < steps; ++t)
+                        if (table[(size_t)t * 16 + j] >= zero_base) {
+                            if (at < 0) at = t;
+                            if (!(doubled[(size_t)t] >> r & 1)) {
+                                at = t;
+                                break;
+                            }
+                        }
+                    if (at < 0) return false;
+                    table[(size_t)at * 16 + j] = bucket[j][(size_t)next[j][r]++];
+                    doubled[(size_t)at] |= (uint16_t)(1u << r);
+                }
+        for (int32_t t = 0; t < steps; ++t)
+            for (int j = 0; j < 16; ++j) emit(j, t, table[(size_t)t * 16 + j]);
         return true;
     }
 
@@ -602,17 +630,9 @@ bool build_lds_schedule(const gp_plan& P, const HotSets& C, double max_cost, int
     // steps per group in either order
     std::vector<int32_t> steps_plain((size_t)ngroups), steps_free((size_t)ngroups, 0);
     parallel_run(nt, [&](int t, int k) {
-        PassGroup pg;
-        int lanes[16];
         for (int64_t g = ngroups * t / k; g < ngroups * (t + 1) / k; ++g) {
             steps_plain[(size_t)g] = (hot_len[(size_t)segment_of(g, 0)] + 7) / 8 * 8;
-            if (order == 1) continue;
-            int32_t need = 0;
-            for (int pass = 0; pass < 4; ++pass) {
-                load_pass(pg, g, pass, lanes);
-                need = std::max(need, pg.degree());
-            }
-            steps_free[(size_t)g] = (need + 7) / 8 * 8;
+            steps_free[(size_t)g] = steps_plain[(size_t)g];  // (the order with as few conflicts as these steps allow)
         }
     });
     int64_t total_plain = 0, total_free = 0;

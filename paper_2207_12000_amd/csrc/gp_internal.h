@@ -259,9 +259,9 @@ constexpr double kLdsForcedCost = 64.0;      // the limit when the pass is force
 constexpr int64_t kLdsMinReadsPerSet = 100000;  // reads a set must have on average for a strip's staging (~9 us per work item) to pay
 inline int64_t lds_rows(int64_t m) { return (m + 15) / 16 * 16 + 16; }
 // false (and `out` unspecified) where the pass does not apply: a list that hot records gather
-// from is too long for the LDS, or the reads (padding included; a conflict-free read counts
-// 1 / kLdsConflictFreeGain) exceed max_cost per hot non-zero.
-// order: 0 = the cheaper of the two; 1 = the column list's; 2 = conflict-free.
+// from is too long for the LDS, or the reads (padding included; a read of the conflict-free
+// order counts 1 / kLdsConflictFreeGain) exceed max_cost per hot non-zero.
+// order: 1 = the column list's; 0 / 2 = conflict-free as far as the same number of steps allows.
 bool build_lds_schedule(const gp_plan& P, const HotSets& H, double max_cost, int order, LdsSchedule& out);
 // The (set, octet) pairs of a launch over rows of `strips` strips, dealt to the 8 XCDs: set by set, every
 // octet to the XCD with the least work so far (work = the set's reads times the octet's strips), so that the
