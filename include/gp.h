@@ -438,6 +438,13 @@ gp_status gp_set_hbm_budget_bytes(int64_t bytes);
  *                     hot_mode 2), 1 = whenever the LDS pass applies, 2 = never.
  *   "hub_sets"        hot_mode 2: number of row sets the rows are cut into (1 .. 65536; 0 = about
  *                     2048 / strips, fewer where a set would have less than 100000 reads).
+ *   "plane_strips"    LDS pass: how many strips' sums of one segment lie together in the buffer
+ *                     the two launches of a hop share (1, 2, 4 or 8; 8 = one 128-byte line per
+ *                     segment and eight strips: fewest lines touched by the launch that reads
+ *                     them; 1 = a strip's sums of consecutive segments lie together: whole lines
+ *                     for the launch that writes them).  0 = 8 with row clusters (long segments,
+ *                     few stores), 4 with hubs (short segments: the stores weigh as much as the
+ *                     reads).  The results do not depend on it.
  *   "device_plan_chunk"  GP_PLAN_ON_DEVICE: most candidate entries sorted at once
  *                     (1 .. 2^31 - 1; 0 = 2^31 - 1).  Read by gp_plan_blocks.
  *   "cache_schedule"  0 = explicit per-XCD work lists where the plan's row clusters

@@ -156,6 +156,12 @@ gp_status gp_set_option(const char* name, int64_t value)
         options().hub_sets = value;
         return GP_OK;
     }
+    if (!strcmp(name, "plane_strips")) {
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8)
+            return fail(GP_ERR_INVALID_ARG, "plane_strips must be 0 (automatic), 1, 2, 4 or 8");
+        options().plane_strips = value;
+        return GP_OK;
+    }
     if (!strcmp(name, "device_plan_chunk")) {
         if (value < 0 || value > (INT64_C(1) << 31) - 1) return fail(GP_ERR_INVALID_ARG, "device_plan_chunk must be 0 .. 2^31 - 1");
         options().device_plan_chunk = value;
@@ -187,6 +193,7 @@ int64_t gp_get_option(const char* name)
     if (!strcmp(name, "lds_pass")) return options().lds_pass;
     if (!strcmp(name, "hub_pass")) return options().hub_pass;
     if (!strcmp(name, "hub_sets")) return options().hub_sets;
+    if (!strcmp(name, "plane_strips")) return options().plane_strips;
     if (!strcmp(name, "lc_tile_rows")) return options().lc_tile_rows;
     if (!strcmp(name, "hbm_budget_bytes")) return options().hbm_budget_bytes;
     return -1;

@@ -117,7 +117,7 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
     const LdsGroup* __restrict__ groups, const LdsOctet* __restrict__ octets, const OctetLists lists,
     const uint16_t* __restrict__ ids,
     const float* __restrict__ packed, int64_t num_members, const float* __restrict__ src_scale, const T* __restrict__ xin,
-    int64_t ldin, float* __restrict__ planes, int64_t num_pos, int d, unsigned long long* __restrict__ ctrl, int lds_rows_max)
+    int64_t ldin, float* __restrict__ planes, int64_t num_pos, int d, unsigned long long* __restrict__ ctrl, int lds_rows_max, int plane_log2)
 {
     // LDS: the strip's rows from byte 0 (an index times 16 is then the address itself), and
     // after them the word through which a workgroup learns its next item
@@ -222,7 +222,9 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
                     const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)d_pos, gg - batch);
                     const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)((unsigned long long)d_pos >> 32), gg - batch);
                     const int64_t first = (int64_t)(((unsigned long long)hi << 32) | lo);
-                    return lane < count ? (((int64_t)(strip >> 3) * num_pos + first + lane) * 32 + (strip & 7) * 4) : -1;
+                    return lane < count ? ((((int64_t)(strip >> plane_log2) * num_pos + first + lane) << (2 + plane_log2)) +
+                                           ((strip & ((1 << plane_log2) - 1)) << 2))
+                                        : -1;
                 };
                 read_batch(g);
                 int64_t k_group_end = k + blocks_of(g);
@@ -343,6 +345,7 @@ gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
 {
     if (a.d < 4 || a.num_sets <= 0 || !a.ctrl || !a.xin || !a.planes || a.num_pos <= 0 || a.num_members <= 0 || !a.octets || !a.octet_off)
         return fail(GP_ERR_INVALID_ARG, "LDS pass: needs at least four columns, record sets, lists, planes and a cursor buffer");
+    if (a.plane_log2 < 0 || a.plane_log2 > 3) return fail(GP_ERR_INVALID_ARG, "LDS pass: 1, 2, 4 or 8 strips of a position lie together");
     if (a.dtype == GP_BF16 && a.d % 4 != 0) return fail(GP_ERR_INVALID_ARG, "LDS pass: bf16 rows need a multiple of four columns");
     if (a.max_members < 0 || a.max_members > kLdsMaxMembers)
         return fail(GP_ERR_INVALID_ARG, "LDS pass: a list of %d rows does not fit the LDS", a.max_members);
@@ -355,11 +358,11 @@ gp_status launch_hot_lds(const HotLdsArgs& a, hipStream_t stream)
     if (a.dtype == GP_F32)
         hipLaunchKernelGGL(gp_hop_cluster_lds<float>, grid, block, shm, stream, a.members, a.member_off, a.list_of_set, a.group_off,
                            a.wave_cut, a.groups, a.octets, lists, a.ids, a.packed, a.num_members, a.src_scale, (const float*)a.xin, a.ldin,
-                           a.planes, a.num_pos, a.d, a.ctrl, (int)lds_rows(a.max_members));
+                           a.planes, a.num_pos, a.d, a.ctrl, (int)lds_rows(a.max_members), a.plane_log2);
     else
         hipLaunchKernelGGL(gp_hop_cluster_lds<uint16_t>, grid, block, shm, stream, a.members, a.member_off, a.list_of_set, a.group_off,
                            a.wave_cut, a.groups, a.octets, lists, a.ids, a.packed, a.num_members, a.src_scale, (const uint16_t*)a.xin,
-                           a.ldin, a.planes, a.num_pos, a.d, a.ctrl, (int)lds_rows(a.max_members));
+                           a.ldin, a.planes, a.num_pos, a.d, a.ctrl, (int)lds_rows(a.max_members), a.plane_log2);
     GP_HIP(hipGetLastError());
     return GP_OK;
 }

@@ -38,6 +38,7 @@ struct Options {
                                  // (conflict-free order), 2 = never, 3 = wherever possible (column-list order)
     int64_t hub_pass = 0;        // graphs without row clusters: the most popular rows served from LDS: 0 = where it pays, 1 = always, 2 = never
     int64_t hub_sets = 0;        // hub pass: row sets the rows are cut into, 0 = automatic
+    int64_t plane_strips = 0;    // LDS pass: strips of one position that lie together in the planes (1, 2, 4, 8), 0 = automatic
     int64_t device_plan_chunk = 0;  // GP_PLAN_ON_DEVICE: most candidate entries sorted at once, 0 = 2^31 - 1
 };
 Options& options();
@@ -284,8 +285,10 @@ struct HotLdsArgs {
     const void* xin;         // DEVICE rows of `dtype` (bf16 rows: d a multiple of 4)
     gp_dtype dtype;
     int64_t ldin;
-    float* planes;           // DEVICE ceil(d / 32) planes of num_pos entries of 8 x 4 floats (an octet of strips)
+    float* planes;           // DEVICE ceil(d / 32) x num_pos x 32 floats; the four sums of strip t at position p lie at
+                             // ((t >> plane_log2) * num_pos + p) * (4 << plane_log2) + (t & ((1 << plane_log2) - 1)) * 4
     int64_t num_pos;
+    int plane_log2 = 3;      // 0 .. 3: 2^plane_log2 strips of a position lie together
     float* packed;           // DEVICE scratch, ceil(d / 4) x num_members x 4 floats: the lists' rows strip by strip;
                              // nullptr: strips are staged straight from xin
     int64_t num_members;     // rows on all lists together
@@ -350,10 +353,11 @@ struct HopArgs {
     int64_t persistent_blocks = 0;  // workgroups of the launch, 0 = as many as stay resident
     int64_t column_tile = 0;        // feature columns per kernel pass, 0 = automatic
     // optional plane entries (vectors of 4 columns, or of 8 bf16 columns with d a multiple of 4; implicit lists): a
-    // record whose slice byte is kAddPlaneEntry adds, to the four columns of strip t, planes[((t / 8) * num_pos + p) * 32
-    // + (t % 8) * 4 ..], p being its place in segs
+    // record whose slice byte is kAddPlaneEntry adds, to the four columns of strip t, planes[((t >> plane_log2) * num_pos + p)
+    // * (4 << plane_log2) + (t & ((1 << plane_log2) - 1)) * 4 ..], p being its place in segs
     const float* planes = nullptr;
     int64_t num_pos = 0;
+    int plane_log2 = 3;
     // optional running combination: comb[row] += gamma * result row (fp32, leading dimension ldc);
     // xout may then be nullptr (result row not stored)
     float* comb = nullptr;

@@ -233,7 +233,7 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
                                                             float* __restrict__ carry, int64_t carry_ld, int d,
                                                             int num_slices, int slice_elems, float* __restrict__ comb,
                                                             int64_t ldc, float gamma, const float* __restrict__ planes,
-                                                            int64_t num_pos, int run_log2)
+                                                            int64_t num_pos, int run_log2, int plane_log2)
 {
     constexpr int GPB = kThreads / G;
     constexpr int PF = G >= 32 ? 1 : 32 / G;  // column ids each lane prefetches per segment
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
     const int xcd = blockIdx.x & 7;
     // This XCD's list: the record of position p < count is segs[place_of(p)].  Implicit lists: the
     // XCDs that share a slice take the records interleaved, in runs of 2^run_log2 consecutive records
-    // (1 as a rule; 8 where records add plane entries: 8 consecutive entries are one line, which then
+    // (1 as a rule; 8 where records add plane entries: the entries of 8 consecutive records share their lines, which then
     // only one XCD asks for).
     int64_t base, count;
     int rstep, xcd_slice;
@@ -509,13 +509,15 @@ __global__ __launch_bounds__(kThreads) void gp_hop_segments(const Segment* __res
 #pragma unroll
             for (int i = 0; i < VEC; ++i) before[i] = 0.0f;
             if constexpr (kCanAddPlanes) {
-                if (planed) {  // entries are kept eight strips (an octet, one 128-byte line) together
+                if (planed) {  // 2^plane_log2 strips of a record lie together (eight: an octet, one 128-byte line)
                     // strip of the vector's first column (a last vector moved back ends with the row, as the last strip does)
                     const int t = (coff[v] + 3) >> 2;
 #pragma unroll
                     for (int h = 0; h < VEC / 4; ++h) {  // (a vector of eight columns: two strips, maybe of two octets)
                         float part[4];
-                        Row<float, 4>::load(planes + ((int64_t)((t + h) >> 3) * num_pos + place) * 32 + ((t + h) & 7) * 4, part);
+                        Row<float, 4>::load(planes + ((((int64_t)((t + h) >> plane_log2) * num_pos + place) << (2 + plane_log2)) +
+                                                      (((t + h) & ((1 << plane_log2) - 1)) << 2)),
+                                            part);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) before[h * 4 + i] = part[i];
                     }
@@ -736,15 +738,15 @@ gp_status launch_hop_t(const HopArgs& a, hipStream_t stream)
     if (a.edge_w && a.edge_w_per_edge)
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 2>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, chunk_records, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma, a.planes, a.num_pos, a.planes ? 3 : 0);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma, a.planes, a.num_pos, a.planes ? 3 : 0, a.plane_log2);
     else if (a.edge_w)
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 1>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, chunk_records, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma, a.planes, a.num_pos, a.planes ? 3 : 0);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma, a.planes, a.num_pos, a.planes ? 3 : 0, a.plane_log2);
     else
         hipLaunchKernelGGL((gp_hop_segments<T, VEC, G, VPL, 0>), grid, block, 0, stream, a.segs, a.num_segs, lists, a.ctrl, chunk_records, a.col,
                            a.col_base, a.edge_w, a.row_scale, (const T*)a.xin, a.ldin, (T*)a.xout, a.ldout, a.carry,
-                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma, a.planes, a.num_pos, a.planes ? 3 : 0);
+                           a.carry_ld, a.d, a.num_slices, a.slice_elems, a.comb, a.ldc, a.gamma, a.planes, a.num_pos, a.planes ? 3 : 0, a.plane_log2);
     GP_HIP(hipGetLastError());
     return GP_OK;
 }
@@ -839,6 +841,8 @@ gp_status launch_hop(const HopArgs& a_in, hipStream_t stream)
         a.num_slices = implicit_slices(a, vec);
         a.slice_elems = (nvec + a.num_slices - 1) / a.num_slices * vec;
     }
+    if (a.planes && (a.plane_log2 < 0 || a.plane_log2 > 3))
+        return fail(GP_ERR_INVALID_ARG, "plane entries: 1, 2, 4 or 8 strips of a record lie together");
     int G, vpl;
     group_shape(a.slice_elems, vec, G, vpl);
     if (vpl > max_vpl(vec)) return fail(GP_ERR_UNSUPPORTED, "d = %d needs column tiling (vec = %d)", a.d, vec);

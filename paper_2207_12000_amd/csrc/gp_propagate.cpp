@@ -471,6 +471,12 @@ gp_status lds_hop(const gp_plan* plan, HopArgs& a, gp_agg agg, hipStream_t strea
     h.ldin = a.ldin;
     h.planes = D.lds_planes;
     h.num_pos = (int64_t)plan->segs.size();
+    // Strips of a position that lie together in the planes, P.  Both launches pay per line they touch: the
+    // LDS kernel's store of a strip's sums of 64 positions touches 8 P lines, the segment kernel's record
+    // strips / P.  With long segments (clusters) stores are rare and P = 8 serves the reader; with short
+    // ones (hubs) the stores are what the LDS kernel waits for, and P = 2 .. 4 is the least in sum.
+    const int64_t together = plan->opt.plane_strips > 0 ? plan->opt.plane_strips : plan->hot_mode == 2 ? 4 : 8;
+    h.plane_log2 = together == 1 ? 0 : together == 2 ? 1 : together == 4 ? 2 : 3;
     h.packed = D.lds_packed;
     h.num_members = D.lds_num_members;
     h.d = a.d;
@@ -493,6 +499,7 @@ gp_status lds_hop(const gp_plan* plan, HopArgs& a, gp_agg agg, hipStream_t strea
     }
     a.planes = D.lds_planes;
     a.num_pos = h.num_pos;
+    a.plane_log2 = h.plane_log2;
     return hop_passes(a, stream);
 }
 

@@ -277,7 +277,7 @@ def test_many_hops_and_repeated_calls_on_one_plan():
 @pytest.fixture
 def _mapping_defaults():
     yield
-    for k in ("column_slices", "persistent_blocks", "cache_schedule", "segment_edges", "split_records", "lds_pass", "hub_pass"):
+    for k in ("column_slices", "persistent_blocks", "cache_schedule", "segment_edges", "split_records", "lds_pass", "hub_pass", "plane_strips"):
         gp.gp_set_option(k, 0)
 
 
@@ -388,3 +388,23 @@ def test_hub_pass_matches_the_oracle(cfg, scale, d, agg, segment_edges, order, _
     assert launches == 2 and launches_after == want_after, f"the LDS pass ran {launches} / {launches_after} times"
     gp.gp_set_option("hub_pass", 2)
     parity_case(w, K=2, dtype=gp.GP_F32, agg=agg, budget=budget)
+
+
+@pytest.mark.parametrize("dtype,d", [(gp.GP_F32, 100), (gp.GP_F32, 37), (gp.GP_BF16, 72)])
+def test_plane_layouts_give_the_same_bits(dtype, d, _mapping_defaults):
+    """The buffer through which the LDS launch hands its sums to the segment launch can keep 1, 2,
+    4 or 8 strips of a segment together: the layout changes who touches which line, not what is
+    added, so every layout gives the bits of the default, with row clusters and with hubs, fp32
+    rows (whole strips and a last strip moved back) and bf16 rows (vectors of two strips)."""
+    for cfg, scale, option in ((4, 0.004, "lds_pass"), (3, 0.02, "hub_pass")):
+        w = gp_synth.make_workload(cfg, scale=scale, d=d)
+        gp.gp_set_option(option, 1)
+        budget = max(20_000, w.m // 3)
+        ref = parity_case(w, K=2, dtype=dtype, agg=gp.GP_AGG_SYM, budget=budget)
+        for together in (1, 2, 4, 8):
+            gp.gp_set_option("plane_strips", together)
+            got = parity_case(w, K=2, dtype=dtype, agg=gp.GP_AGG_SYM, budget=budget)
+            assert np.array_equal(ref, got), f"config {cfg}, {together} strips together"
+        gp.gp_set_option("plane_strips", 0)
+        gp.gp_set_option(option, 0)
+

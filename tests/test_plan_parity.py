@@ -171,5 +171,10 @@ def test_options_and_status_strings():
         gp.gp_set_option("no_such_option", 1)
     assert gp.gp_get_option("no_such_option") == -1
     with pytest.raises(gp.GpError):
+        gp.gp_set_option("plane_strips", 3)
+    gp.gp_set_option("plane_strips", 2)
+    assert gp.gp_get_option("plane_strips") == 2
+    gp.gp_set_option("plane_strips", 0)
+    with pytest.raises(gp.GpError):
         gp.gp_set_hbm_budget_bytes(-1)
     gp.gp_set_hbm_budget_bytes(0)
