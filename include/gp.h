@@ -157,13 +157,15 @@ int64_t gp_plan_segment_edges(const gp_plan *plan);           /* the segment len
  * rows that are most often a source account for at least 15 % of the non-zeros (and non-zeros
  * times d is at least 2e9: below that the pass's launches cost more than they save): they are
  * the one list, every set (a range of consecutive
- * rows; about 2048 / strips of them) gathers from it.
+ * rows; about 2048 / strips of them) gathers from it; a segment with fewer than three
+ * sources on the list keeps them among its other non-zeros (handing a segment's sums from
+ * one launch to the other costs about two gathers).
  * The pass takes the plan's segments in an order of its own: set by set, inside a set most
  * hot non-zeros first.  A segment's place in that order is its position p; rest[p] is the
  * segment's record (gp_plan_segments' format) reduced to its other non-zeros, which are
  * col[start .. start + len) of a column list that has every segment's hot non-zeros moved
  * to the front of the segment (both parts keep their order); its slice byte is 0x80 where
- * the segment has hot non-zeros.  64 consecutive positions of a set form a group; lane l of
+ * the segment has hot non-zeros that the pass takes.  64 consecutive positions of a set form a group; lane l of
  * group g fills the plane entries of position rec_pos[64 g + l] (-1: none: past the set's
  * end, or a segment without hot non-zeros).  Every lane of a group walks group_steps[g] (a
  * multiple of 8) reads; read t of lane l is ids[group_id_off[g] + (t / 8) * 512 + l * 8 +

@@ -278,6 +278,7 @@ HotSets hot_sets_from_hubs(const gp_plan& P, int32_t hubs, int64_t rows_per_set)
     }
     H.hot_fraction = P.nnz > 0 ? (double)hot / (double)P.nnz : 0.0;
     H.num_lists = 1;
+    H.min_hot = kHubMinHot;
     rows_per_set = std::max<int64_t>(rows_per_set, 64);
     H.num_sets = (int32_t)std::max<int64_t>(1, (n + rows_per_set - 1) / rows_per_set);
     H.list_of_set.assign((size_t)H.num_sets, 0);
@@ -532,6 +533,8 @@ bool build_lds_schedule(const gp_plan& P, const HotSets& C, double max_cost, int
     if (num <= 0 || C.num_lists <= 0 || nsegs == 0) return false;
     std::vector<int32_t> hot_len;
     hot_first(P, C, out.col, hot_len);
+    for (int32_t& h : hot_len)
+        if (h < C.min_hot) h = 0;  // (the columns stay reordered: the segment kernel then takes them all)
     // the lists' rows, ascending, and every row's place on its list
     out.member_off.assign((size_t)C.num_lists + 1, 0);
     for (int64_t i = 0; i < n; ++i)

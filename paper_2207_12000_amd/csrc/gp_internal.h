@@ -89,6 +89,10 @@ struct HotSets {
     std::vector<int32_t> list_of_set;  // num_sets
     std::vector<int32_t> list_of_row;  // n: the list row j is on, -1 = none
     double hot_fraction = 0.0;         // share of the non-zeros that are hot
+    // LDS pass: a segment with fewer hot non-zeros than this keeps them with its others.  A segment's sums
+    // cross from one launch to the other through memory, a row's bytes written and read: about what two
+    // gathers of popular rows cost the segment kernel.
+    int32_t min_hot = 1;
     bool hot(int32_t row, int32_t src) const
     {
         const int32_t l = list_of_row[(size_t)src];
@@ -257,6 +261,7 @@ constexpr double kLdsConflictFreeGain = 1.9;
 constexpr double kLdsMaxCostClusters = 1.8;  // reads (in column-list-order equivalents) per hot non-zero beyond which the L2 lists are as fast
 constexpr double kLdsMaxCostHubs = 4.0;      // ... beyond which gathering the hubs from memory is as fast
 constexpr double kLdsForcedCost = 64.0;      // the limit when the pass is forced: whatever the padding
+constexpr int32_t kHubMinHot = 3;  // hubs: non-zeros on the list a segment needs for them to go through LDS (measured on config 3: 3 .. 5 is best)
 constexpr int64_t kLdsMinReadsPerSet = 100000;  // reads a set must have on average for a strip's staging (~9 us per work item) to pay
 inline int64_t lds_rows(int64_t m) { return (m + 15) / 16 * 16 + 16; }
 // false (and `out` unspecified) where the pass does not apply: a list that hot records gather

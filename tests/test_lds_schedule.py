@@ -57,7 +57,8 @@ def tables_of(sched):
 def check_schedule(plan, sched):
     """Every segment of the plan has one position; the reads of its lane (if any) and the rest
     record's non-zeros are together exactly the segment's sources, the former all on the list
-    the row's set gathers from, the latter none of them; positions go set by set, most reads
+    the row's set gathers from, the latter none of them (with hubs: a segment with fewer than
+    three sources on the list has no reads and keeps them); positions go set by set, most reads
     first; a group is 64 consecutive positions of one set.  Returns the per-group tables."""
     members, member_off, list_of_set = sched["members"], sched["member_off"], sched["list_of_set"]
     on_list = np.full(plan.n, -1, dtype=np.int64)
@@ -106,7 +107,13 @@ def check_schedule(plan, sched):
             hot = np.empty(0, np.int32)
         assert hot.size == hot_len[p]
         assert np.array_equal(np.sort(np.concatenate([hot, cold])), want), f"position {p} (row {row})"
-        assert np.array_equal(col[s0:s0 + hot.size], col[s0:s0 + hot.size]) and np.all(np.diff(cold) > 0)   # the rest keeps its order
+        if p in lane_of or sched["hot_mode"] != 2:
+            assert np.all(np.diff(cold) > 0)                          # the rest keeps its order
+        else:
+            # hubs: a segment with fewer than three sources on the list keeps them, ahead of its others
+            mine = on_list[cold] == 0
+            k = int(mine.sum())
+            assert k < 3 and np.all(mine[:k]) and np.all(np.diff(cold[:k]) > 0) and np.all(np.diff(cold[k:]) > 0)
     # set by set, most reads first
     known = set_of_pos >= 0
     assert np.all(np.diff(set_of_pos[known]) >= 0)
