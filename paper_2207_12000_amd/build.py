@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libgp.so")
 
-SOURCES = ["gp_api.cpp", "gp_plan.cpp", "gp_schedule.cpp", "gp_cluster.cpp", "gp_propagate.cpp", "gp_stream.cpp", "gp_solve.cpp", "gp_kernels.hip", "gp_noalloc.hip", "gp_hot_lds.hip", "gp_plan_device.hip", "gp_lc.hip"]
+SOURCES = ["gp_api.cpp", "gp_plan.cpp", "gp_schedule.cpp", "gp_cluster.cpp", "gp_propagate.cpp", "gp_stream.cpp", "gp_solve.cpp", "gp_kernels.hip", "gp_noalloc.hip", "gp_hot_lds.hip", "gp_device_sort.hip", "gp_plan_device.hip", "gp_lc.hip"]
 
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -268,6 +268,17 @@ inline int64_t lds_rows(int64_t m) { return (m + 15) / 16 * 16 + 16; }
 // from is too long for the LDS, or the reads (padding included; a read of the conflict-free
 // order counts 1 / kLdsConflictFreeGain) exceed max_cost per hot non-zero.
 // order: 1 = the column list's; 0 / 2 = conflict-free as far as the same number of steps allows.
+// gp_device_sort.hip: device-wide radix sort (ascending) and duplicate removal of at most 2^31 - 1 64-bit keys.
+// low_bits / high_bits: how many bits of the key's low and high word can differ between keys (the others are
+// equal in all keys, or zero).  `other` is a second buffer of `count` keys; *sorted comes back as the one of the
+// two that holds the result.  scratch: device_sort_scratch_words(count) 32-bit words on the device.
+// device_unique_keys writes the distinct keys of a sorted list to `out` (not the list itself) and leaves their
+// number in a word of the scratch, *total (DEVICE).
+size_t device_sort_scratch_words(int64_t count);
+gp_status device_sort_keys(uint64_t* keys, uint64_t* other, int64_t count, int low_bits, int high_bits, uint32_t* scratch,
+                           hipStream_t stream, uint64_t** sorted);
+gp_status device_unique_keys(const uint64_t* sorted, uint64_t* out, int64_t count, uint32_t* scratch, hipStream_t stream,
+                             const uint32_t** total);
 bool build_lds_schedule(const gp_plan& P, const HotSets& H, double max_cost, int order, LdsSchedule& out);
 // The (set, octet) pairs of a launch over rows of `strips` strips, dealt to the 8 XCDs: set by set, every
 // octet to the XCD with the least work so far (work = the set's reads times the octet's strips), so that the

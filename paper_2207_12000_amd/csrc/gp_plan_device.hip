@@ -9,15 +9,11 @@
 // find every row's first entry by binary search; then degrees, 1/sqrt(deg) and 1/deg
 // (in fp64, narrowed once: the host planner's recipe) and the rows at the block
 // boundaries.  Integers and correctly rounded operations only, so the result is the host
-// planner's bit for bit.  The sort and the duplicate removal are rocPRIM's device-wide
-// primitives; every other kernel is this file's.  The column list and the two norm
-// vectors stay on the device for gp_propagate.
+// planner's bit for bit.  The sort and the duplicate removal are gp_device_sort.hip's.
+// The column list and the two norm vectors stay on the device for gp_propagate.
 #include <hip/hip_runtime.h>
 
 #include <cstring>
-
-#include <rocprim/device/device_radix_sort.hpp>
-#include <rocprim/device/device_select.hpp>
 
 #include "gp_internal.h"
 
@@ -52,22 +48,40 @@ __global__ __launch_bounds__(kThreads) void gp_fill_words(unsigned long long* __
 }
 
 // keys of the candidates whose row lies in [r0, r1), in any order (the sort follows):
-// every candidate takes the next free slot from one cursor
+// a wavefront takes the slots for all its keys from the one cursor with a single atomic
 __global__ __launch_bounds__(kThreads) void gp_emit_keys_range(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
                                                                int64_t m, int sym, int loops, int64_t r0, int64_t r1,
                                                                uint64_t* __restrict__ keys, unsigned long long* __restrict__ cursor)
 {
     const int64_t span = m + (loops ? r1 - r0 : 0);
-    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < span; e += (int64_t)gridDim.x * kThreads) {
-        if (e >= m) {  // the self-loop of row r0 + (e - m)
-            const uint64_t i = (uint64_t)(r0 + (e - m));
-            keys[atomicAdd(cursor, 1ULL)] = (i << 32) | i;
-            continue;
+    const int lane = threadIdx.x & 63;
+    for (int64_t e0 = (int64_t)blockIdx.x * kThreads; e0 < span; e0 += (int64_t)gridDim.x * kThreads) {  // (whole workgroups)
+        const int64_t e = e0 + threadIdx.x;
+        uint64_t k0 = 0, k1 = 0;  // up to two keys
+        bool has0 = false, has1 = false;
+        if (e < span) {
+            if (e >= m) {  // the self-loop of row r0 + (e - m)
+                const uint64_t i = (uint64_t)(r0 + (e - m));
+                k0 = (i << 32) | i;
+                has0 = true;
+            } else {
+                const uint32_t s = (uint32_t)src[e], t = (uint32_t)dst[e];
+                if (s != t) {
+                    has0 = (int64_t)t >= r0 && (int64_t)t < r1;
+                    k0 = ((uint64_t)t << 32) | s;
+                    has1 = sym && (int64_t)s >= r0 && (int64_t)s < r1;
+                    k1 = ((uint64_t)s << 32) | t;
+                }
+            }
         }
-        const uint32_t s = (uint32_t)src[e], t = (uint32_t)dst[e];
-        if (s == t) continue;
-        if ((int64_t)t >= r0 && (int64_t)t < r1) keys[atomicAdd(cursor, 1ULL)] = ((uint64_t)t << 32) | s;
-        if (sym && (int64_t)s >= r0 && (int64_t)s < r1) keys[atomicAdd(cursor, 1ULL)] = ((uint64_t)s << 32) | t;
+        const unsigned long long b0 = __ballot(has0), b1 = __ballot(has1), below = (1ull << lane) - 1ull;
+        const int total = __popcll(b0) + __popcll(b1);
+        unsigned long long first = 0;
+        if (lane == 0 && total > 0) first = atomicAdd(cursor, (unsigned long long)total);
+        first = ((unsigned long long)(unsigned)__shfl((int)(first >> 32), 0, 64) << 32) | (unsigned)__shfl((int)(unsigned)first, 0, 64);
+        const unsigned long long mine = first + (unsigned long long)(__popcll(b0 & below) + __popcll(b1 & below));
+        if (has0) keys[mine] = k0;
+        if (has1) keys[mine + (has0 ? 1 : 0)] = k1;
     }
 }
 
@@ -159,11 +173,10 @@ gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64
     int32_t *d_src, *d_dst;
     unsigned long long *d_cnt, *d_cursor;
     int64_t* d_rowptr;
-    size_t* d_count;
     gp_status st;
     if ((st = B.alloc(d_src, (size_t)m)) != GP_OK || (st = B.alloc(d_dst, (size_t)m)) != GP_OK ||
         (st = B.alloc(d_cnt, (size_t)n)) != GP_OK || (st = B.alloc(d_cursor, 1)) != GP_OK ||
-        (st = B.alloc(d_count, 1)) != GP_OK || (st = B.alloc(d_rowptr, (size_t)n + 1)) != GP_OK)
+        (st = B.alloc(d_rowptr, (size_t)n + 1)) != GP_OK)
         return st;
     // ---- candidates per row, and row ranges whose candidates fit one sort ------------
     hipLaunchKernelGGL(gp_fill_words, dim3(grid_for(n)), dim3(kThreads), 0, stream, d_cnt, n, loops ? 1ULL : 0ULL);
@@ -216,38 +229,40 @@ gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64
             }
         }
     } col_guard{d_col};
-    char* d_tmp = nullptr;
-    size_t tmp_cap = 0;
+    uint32_t* d_scratch;  // the sort's digit tables, the duplicate removal's tile counts
+    if ((st = B.alloc(d_scratch, device_sort_scratch_words(largest))) != GP_OK) return st;
+    // bits in which keys can differ: a column is below n, a row of the range below its end
+    auto bits_of = [](int64_t values) {
+        int b = 0;
+        while (b < 32 && (INT64_C(1) << b) < values) ++b;
+        return b;
+    };
 
     int64_t nnz = 0;
     for (size_t k = 0; k < range_cnt.size(); ++k) {
         const int64_t r0 = range_lo[k], r1 = range_lo[k + 1], cand = range_cnt[k];
         int64_t uniq = 0;
+        uint64_t* d_distinct = d_keys;  // (no candidates: nothing is read from it)
         if (cand > 0) {
             hipLaunchKernelGGL(gp_fill_words, dim3(1), dim3(kThreads), 0, stream, d_cursor, (int64_t)1, 0ULL);
             hipLaunchKernelGGL(gp_emit_keys_range, dim3(grid_for(m + (loops ? r1 - r0 : 0))), dim3(kThreads), 0, stream, d_src, d_dst,
                                m, sym ? 1 : 0, loops ? 1 : 0, r0, r1, d_keys, d_cursor);
             GP_HIP(hipGetLastError());
-            size_t need = 0, need2 = 0;
-            GP_HIP(rocprim::radix_sort_keys(nullptr, need, d_keys, d_sorted, (size_t)cand, 0u, 64u, stream));
-            GP_HIP(rocprim::unique(nullptr, need2, d_sorted, d_keys, d_count, (size_t)cand, rocprim::equal_to<uint64_t>(), stream));
-            need = std::max(need, need2);
-            if (need > tmp_cap) {
-                if ((st = B.alloc(d_tmp, need)) != GP_OK) return st;
-                tmp_cap = need;
-            }
-            GP_HIP(rocprim::radix_sort_keys(d_tmp, need, d_keys, d_sorted, (size_t)cand, 0u, 64u, stream));
-            // the unsorted keys are no longer needed: the distinct ones go back into their buffer
-            GP_HIP(rocprim::unique(d_tmp, need, d_sorted, d_keys, d_count, (size_t)cand, rocprim::equal_to<uint64_t>(), stream));
-            size_t count = 0;
-            GP_HIP(hipMemcpyAsync(&count, d_count, sizeof(size_t), hipMemcpyDeviceToHost, stream));
+            uint64_t* sorted = nullptr;
+            if ((st = device_sort_keys(d_keys, d_sorted, cand, bits_of(n), bits_of(r1), d_scratch, stream, &sorted)) != GP_OK) return st;
+            // the distinct keys go into the buffer the sorted ones are not in
+            d_distinct = sorted == d_keys ? d_sorted : d_keys;
+            const uint32_t* d_total = nullptr;
+            if ((st = device_unique_keys(sorted, d_distinct, cand, d_scratch, stream, &d_total)) != GP_OK) return st;
+            uint32_t count = 0;
+            GP_HIP(hipMemcpyAsync(&count, d_total, sizeof(uint32_t), hipMemcpyDeviceToHost, stream));
             GP_HIP(hipStreamSynchronize(stream));
             uniq = (int64_t)count;
-            hipLaunchKernelGGL(gp_keys_to_columns, dim3(grid_for(uniq)), dim3(kThreads), 0, stream, d_keys, uniq, d_col + nnz);
+            hipLaunchKernelGGL(gp_keys_to_columns, dim3(grid_for(uniq)), dim3(kThreads), 0, stream, d_distinct, uniq, d_col + nnz);
             GP_HIP(hipGetLastError());
         }
         // first entries of rows r0 .. r1 (row r1's start is written again, identically, by the next range)
-        hipLaunchKernelGGL(gp_row_starts_range, dim3(grid_for(r1 - r0 + 1)), dim3(kThreads), 0, stream, d_keys, uniq, r0, r1, nnz,
+        hipLaunchKernelGGL(gp_row_starts_range, dim3(grid_for(r1 - r0 + 1)), dim3(kThreads), 0, stream, d_distinct, uniq, r0, r1, nnz,
                            d_rowptr);
         GP_HIP(hipGetLastError());
         GP_HIP(hipStreamSynchronize(stream));  // d_keys is refilled by the next range

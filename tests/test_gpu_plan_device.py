@@ -1,5 +1,6 @@
-"""gp_plan_blocks with GP_PLAN_ON_DEVICE (sort / unique / row pointers on the
-GPU) against the oracle's planner, bit for bit, and against the host planner."""
+"""gp_plan_blocks with GP_PLAN_ON_DEVICE (the library's own radix sort, duplicate
+removal and row pointers on the GPU) against the oracle's planner, bit for bit, and
+against the host planner."""
 import time
 
 import numpy as np
@@ -94,3 +95,29 @@ def test_row_range_chunks_give_the_same_plan(chunk):
             same(lp, op)
     finally:
         gp.gp_set_option("device_plan_chunk", 0)
+
+
+
+@pytest.mark.parametrize("n", [2, 255, 256, 257, 65_535, 65_537, 300_000])
+@pytest.mark.parametrize("m", [4_095, 4_096, 4_097, 16_383, 16_384, 16_385, 70_001])
+def test_sort_and_duplicate_removal_at_their_boundaries(n, m):
+    """The device sort works on tiles of 16384 keys, 256 at a time, one 8-bit digit per pass over
+    the bits a row or column number can occupy; the duplicate removal on tiles of 4096.  Key
+    counts on either side of those tile sizes, node counts on either side of a digit boundary,
+    and edge lists made mostly of repeats (every pair drawn from a small pool), so that whole
+    tiles collapse to a few keys."""
+    rng = np.random.default_rng(n * 131 + m)
+    pool = max(2, min(n, 8 + int((m / 8) ** 0.5)))      # few distinct endpoints: many equal keys
+    ids = rng.choice(n, size=pool, replace=False)
+    a = rng.integers(0, pool, m)
+    b = (a + 1 + rng.integers(0, pool - 1, m)) % pool    # never a itself: every edge is one candidate key
+    src, dst = ids[a], ids[b]
+    op = oracle.plan_blocks(src, dst, n, 5_000, 0)
+    with gp.gp_plan_blocks(src, dst, n, 5_000, gp.GP_PLAN_ON_DEVICE) as lp:
+        same(lp, op)
+    # and spread over all rows, symmetrised with self-loops
+    src2, dst2 = rng.integers(0, n, m), rng.integers(0, n, m)
+    op = oracle.plan_blocks(src2, dst2, n, 5_000, 3)
+    with gp.gp_plan_blocks(src2, dst2, n, 5_000, 3 | gp.GP_PLAN_ON_DEVICE) as lp:
+        same(lp, op)
+
