@@ -12,17 +12,21 @@
 // 47 TB/s over the chip, conflict-free ones at about 90, against 23 TB/s out of the L2s.
 //
 // Work item = (set, strip).  Eight consecutive strips (one 128-byte line of a source row)
-// form an octet; octet o belongs to XCD o % 8, so that the lines a strip fill pulls in
-// serve the other strips of the octet from the same L2.  The workgroups of an XCD take
-// items from that XCD's cursor (ctrl[0..8)); ctrl[8] counts finished workgroups and the
-// last one zeroes all nine words, as in the segment kernel.
+// form an octet, and the host deals every (set, octet) pair to one XCD (a list per XCD, set
+// by set, each pair to the XCD with the least work so far), so that the lines a strip fill
+// pulls in serve the other strips of the octet from the same L2 and all XCDs stream the same
+// set's index list at about the same time.  The workgroups of an XCD take items from that
+// XCD's cursor (ctrl[0..8)); ctrl[8] counts finished workgroups and the last one zeroes all
+// nine words, as in the segment kernel.
 //
-// Results: plane t holds, for every position (a segment's place in the order this pass
-// takes them: 64 consecutive positions to a group, one per lane), the four sums of
-// strip t; a wavefront stores 64 consecutive entries, 1 KB.  The segment kernel, which
-// takes the segments' other non-zeros in the same order, adds them in.  Summation order
-// per segment is fixed by the schedule (four interleaved chains), so runs repeat bit for
-// bit.
+// Results: for every position (a segment's place in the order this pass takes them: 64
+// consecutive positions to a group, one per lane) and every strip, four sums -- a plane
+// entry.  2^plane_log2 strips of a position lie together (eight: one 128-byte line per
+// position and octet, which suits the segment kernel that reads them; fewer: a wavefront's
+// store of 64 positions touches fewer lines, which suits this kernel where segments are
+// short).  The segment kernel, which takes the segments' other non-zeros in the same
+// order, adds them in.  Summation order per segment is fixed by the schedule (four
+// interleaved chains), so runs repeat bit for bit.
 #include "gp_internal.h"
 
 namespace gp {
@@ -216,7 +220,7 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
                     batch = g0;
                 };
                 auto blocks_of = [&](int gg) { return __builtin_amdgcn_readlane(d_steps, gg - batch) / kStepBlock; };
-                // where this lane's sums of group gg go: entry (octet, position) of the planes, 16 bytes of its 128; -1: nowhere
+                // where this lane's sums of group gg go: the plane entry of (strip, position), 16 bytes; -1: nowhere
                 auto entry_of = [&](int gg) -> int64_t {
                     const int count = __builtin_amdgcn_readlane(d_count, gg - batch);
                     const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)d_pos, gg - batch);
