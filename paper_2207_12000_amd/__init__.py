@@ -92,6 +92,14 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2207_12000_amd.build`")
+        # PyTorch brings a HIP runtime of its own and loads it for the whole process.  Loaded after this
+        # library's, the process holds two runtimes that each open the GPU, and calls through the second
+        # fail ("no ROCm-capable device is detected"); loaded before, this library's calls resolve to the
+        # runtime that is already there.  So PyTorch goes first wherever it is installed.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         l = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in _SIGNATURES.items():
             fn = getattr(l, name)
