@@ -49,7 +49,7 @@ def recorded_traffic(workload: int, options: dict):
         return None
     if not rec or rec.get("options") != options:
         return None
-    return rec.get("bytes_per_launch")
+    return rec
 
 WORKLOAD_NAMES = {
     1: "config1: G(n,M) 10k nodes / 210k nnz, d=128 fp32, sym, K=2, 4 edge blocks",
@@ -273,7 +273,19 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
     bytes_per_launch = algorithmic_bytes_per_hop(n, nnz, d, elem) // launches_per_hop
     achieved = bytes_per_launch / avg_launch_s / 1e9
     options = {k: gp.gp_get_option(k) for k in ("segment_edges", "column_tile", "column_slices", "cache_schedule", "split_records", "lds_pass", "hub_pass")}
-    traffic = recorded_traffic(workload, options) if (args.scale == 1.0 and memory == "device" and not args.contiguous_ids) else None
+    recorded = recorded_traffic(workload, options) if (args.scale == 1.0 and memory == "device" and not args.contiguous_ids) else None
+    traffic = recorded.get("bytes_per_launch") if recorded else None
+
+    def kernel_record(name, count, ms):
+        # launches and mean duration of one of the hop's kernels in this run; with the recorded counters, the bytes
+        # one launch of it moved (fetch + write) and the rate that makes against the HBM peak
+        out = {"launches": count, "avg_launch_us": round(ms * 1e3 / max(count, 1), 3)}
+        moved = (recorded or {}).get("per_kernel", {}).get(name)
+        if moved and count:
+            b = moved["fetch_bytes"] + moved["write_bytes"]
+            out["traffic"] = b
+            out["traffic_frac"] = round(b / (ms * 1e-3 / count) / 1e9 / HBM_PEAK_GBS, 4)
+        return out
     flops_per_launch = 2 * nnz * d // launches_per_hop          # one multiply-add per non-zero and column
     gathered_per_launch = nnz * d * elem // launches_per_hop    # bytes the lanes read if every row comes from cache
     S, slice_elems, _, _ = plan.work_lists(d, w.dtype, max(1, min(16 // elem, d)))
@@ -315,9 +327,9 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
                      # the same launch on the bytes the counters saw (fetch + write, per launch): how busy the memory system was
                      "traffic_frac": round(traffic / avg_launch_s / 1e9 / HBM_PEAK_GBS, 4) if traffic else None,
                      "kernel": hop_kernel, "launches": launches, "launches_per_hop": launches_per_hop,
-                     "per_kernel": {"gp_hop_segments": {"launches": seg_launches, "avg_launch_us": round(seg_ms * 1e3 / max(seg_launches, 1), 3)},
-                                    "gp_hop_cluster_lds": {"launches": lds_launches, "avg_launch_us": round(lds_ms * 1e3 / max(lds_launches, 1), 3)},
-                                    "gp_pack_strips": {"launches": pack_launches, "avg_launch_us": round(pack_ms * 1e3 / max(pack_launches, 1), 3)}},
+                     "per_kernel": {"gp_hop_segments": kernel_record("gp_hop_segments", seg_launches, seg_ms),
+                                    "gp_hop_cluster_lds": kernel_record("gp_hop_cluster_lds", lds_launches, lds_ms),
+                                    "gp_pack_strips": kernel_record("gp_pack_strips", pack_launches, pack_ms)},
                      "avg_launch_us": round(avg_launch_s * 1e6, 3), "algorithmic_bytes_per_launch": bytes_per_launch,
                      "kernel_times_from": f"event-bracketed pass, {bracketed_ms:.5f} ms per step",
                      # the other ceilings of the same launch: plain fp32 vector arithmetic, and the rate at

@@ -173,11 +173,15 @@ def main() -> int:
                       f"per launch: {alg / 1e9:.4f} GB; measured / algorithmic = {total / alg:.2f}.  All rows gathered: "
                       f"{rec['config']['nnz'] * dd * 4 / 1e9:.3f} GB per hop.  L2 hit rate over all requests (rows, ids, weights, "
                       f"stores): {100 * hit / max(hit + miss, 1):.1f} %.", ""]
-        with open(os.path.join(PROFILES, f"gp_hop_segments_{tag}.md"), "w") as f:
-            f.write("\n".join(lines))
-        traffic[str(wl)] = {"bytes_per_launch": int(total), "fetch_bytes": int(fetch_b), "write_bytes": int(write_b),
+        per_kernel = {k: {"fetch_bytes": int(means[k].get("FETCH_SIZE", 0.0) * f_fetch * 1024),
+                          "write_bytes": int(means[k].get("WRITE_SIZE", 0.0) * f_write * 1024)} for k in HOP_KERNELS if k in means}
+        lines += ["Per hop kernel, scaled the same way: " + "; ".join(
+            f"{k} fetch {v['fetch_bytes'] / 1e9:.3f} GB + write {v['write_bytes'] / 1e9:.3f} GB" for k, v in per_kernel.items()) + ".", ""]
+        traffic[str(wl)] = {"bytes_per_launch": int(total), "fetch_bytes": int(fetch_b), "write_bytes": int(write_b), "per_kernel": per_kernel,
                             "l2_hit_rate": round(hit / max(hit + miss, 1), 4), "options": rec["config"]["options"],
                             "work_lists": rec["config"]["work_lists"], "summary": f"profiles/gp_hop_segments_{tag}.md"}
+        with open(os.path.join(PROFILES, f"gp_hop_segments_{tag}.md"), "w") as f:
+            f.write("\n".join(lines))
         with open(traffic_path, "w") as f:
             json.dump(traffic, f, indent=1, sort_keys=True)
         print(f"workload {wl}: hop {hop_avg_ns / 1e3:.1f} us, {total / 1e9:.3f} GB per launch, L2 hit {100 * hit / max(hit + miss, 1):.1f} %", flush=True)
