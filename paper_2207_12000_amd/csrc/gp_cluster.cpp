@@ -667,15 +667,20 @@ bool build_lds_schedule(const gp_plan& P, const HotSets& C, double max_cost, int
     out.set_reads.assign((size_t)num, 0);
     for (int32_t c = 0; c < num; ++c)
         out.set_reads[(size_t)c] = out.groups[(size_t)out.group_off[(size_t)c + 1]].id_off - out.groups[(size_t)out.group_off[(size_t)c]].id_off;
-    // a set's groups in kWaveCuts runs of about equal length in reads (a run per wave, or two)
+    // a set's groups in kWaveCuts runs of about equal cost (a run per wave, or two)
     out.wave_cut.assign((size_t)num * (kWaveCuts + 1), 0);
     for (int32_t c = 0; c < num; ++c) {
         const int32_t g0 = out.group_off[(size_t)c], g1 = out.group_off[(size_t)c + 1];
-        const int64_t lo = out.groups[(size_t)g0].id_off, hi = out.groups[(size_t)g1].id_off;
+        // what the groups before g cost a wave: their reads, and per group (its sums stored, the next one's
+        // descriptor taken up) about as much as kLdsGroupCostSteps steps
+        auto cost_to = [&](int32_t g) {
+            return (out.groups[(size_t)g].id_off - out.groups[(size_t)g0].id_off) + 64 * (int64_t)kLdsGroupCostSteps * (int64_t)(g - g0);
+        };
+        const int64_t all = cost_to(g1);
         int32_t g = g0;
         for (int w = 0; w <= kWaveCuts; ++w) {
-            const int64_t target = lo + (hi - lo) * w / kWaveCuts;
-            while (g < g1 && out.groups[(size_t)g].id_off < target) ++g;
+            const int64_t target = all * w / kWaveCuts;
+            while (g < g1 && cost_to(g) < target) ++g;
             out.wave_cut[(size_t)c * (kWaveCuts + 1) + w] = w == kWaveCuts ? g1 : g;
         }
     }

@@ -193,7 +193,7 @@ __global__ __launch_bounds__(1024) void gp_hop_cluster_lds(
         const int64_t following = (int64_t)next_item;
         if (valid) {
             // A wave takes a run of consecutive groups of the set; the host has cut the set's groups into 16
-            // runs of about equal length in reads (wave_cut).  The groups' indices lie one after the other
+            // runs of about equal cost (wave_cut: reads, and a fixed cost per group).  The groups' indices lie one after the other
             // in the index list, so the run is one stream of blocks (8 reads of every lane = one 16-byte load per
             // lane), walked without a stop at the group boundaries.  Two register sets of kAhead blocks
             // alternate: while one is worked through the other is in flight, which covers the latency of the

@@ -223,6 +223,7 @@ void build_split_schedule(const gp_plan& P, const HotSets& H, SplitSchedule& out
 // first), are added up from there into planes: plane t holds, for every position (a
 // segment's place in the pass's own order), the four sums of strip t.  The segment kernel
 // then takes the segments' other non-zeros in position order and adds the plane entries.
+constexpr int kLdsGroupCostSteps = 12;  // a group's end costs a wave about as much as this many steps (config 3, hubs: 487 -> 447 us with 8 .. 32)
 constexpr int kWaveCuts = 16;  // runs a set's groups are cut into (one per wave of a 1024-thread workgroup, two per wave of a 512-thread one)
 constexpr uint8_t kAddPlaneEntry = 0x80;  // in a record's slice byte (implicit lists): add the plane entry of the record's list position
 constexpr int kLdsBytesPerCu = 160 * 1024;
@@ -244,7 +245,7 @@ struct LdsSchedule {
     std::vector<int64_t> member_off;  // num_lists + 1
     std::vector<int32_t> list_of_set; // num_sets
     std::vector<int32_t> group_off;   // num_sets + 1: groups of set c
-    std::vector<int32_t> wave_cut;    // kWaveCuts + 1 per set: its groups cut into runs of about equal length in reads
+    std::vector<int32_t> wave_cut;    // kWaveCuts + 1 per set: its groups cut into runs of about equal cost (reads plus kLdsGroupCostSteps steps per group)
     std::vector<LdsGroup> groups;     // and a sentinel whose id_off is the length of ids
     std::vector<int64_t> set_reads;   // per set: reads of its groups, padding included
     std::vector<uint16_t> ids;
