@@ -178,6 +178,18 @@ def run_config5(scale, capsys, memory="pinned"):
         t0 = time.time()
         with gp.gp_plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags) as lp:
             print(f"planned in {time.time() - t0:.0f} s: nnz {lp.nnz}, {lp.num_blocks} blocks")
+            if scale >= 1.0:
+                # the planner on the GPU at this size: more candidate entries than one sort takes (2^31 - 1), so
+                # it works through two row ranges; every array must be the host planner's
+                t0 = time.time()
+                with gp.gp_plan_blocks(w.src, w.dst, w.n, w.block_budget_edges, w.flags | gp.GP_PLAN_ON_DEVICE) as dp:
+                    print(f"planned on the GPU in {time.time() - t0:.0f} s")
+                    assert dp.nnz == lp.nnz
+                    for name in ("block_off", "block_row_lo", "block_row_hi", "rowptr", "col", "deg", "segments"):
+                        assert np.array_equal(getattr(dp, name), getattr(lp, name)), f"device plan: {name}"
+                    assert np.array_equal(dp.dinv_sqrt.view(np.uint32), lp.dinv_sqrt.view(np.uint32))
+                    assert np.array_equal(dp.dinv.view(np.uint32), lp.dinv.view(np.uint32))
+                print("the GPU planner's arrays equal the host planner's")
             if full_oracle:
                 same_plan(lp, op)
                 # a budget that forces two column slabs and streams every edge block per hop and slab
@@ -231,7 +243,7 @@ def test_config5_streamed_full_size(capsys):
     Pinned, it would need 119.9 GiB (1159 B per node) where the box grants 65.5 GiB, so the hop
     stack (105.9 GiB, X living in slab 0) is ordinary host memory, whose copies the runtime
     stages; the column and segment lists are pinned as always.  Same kernels, same schedule,
-    every hop checked on sampled rows.  Needs about 180 GB of host memory."""
+    every hop checked on sampled rows; the plan is also made on the GPU and compared.  Needs about 200 GB of host memory."""
     if float(os.environ.get("GP_TEST_CONFIG5_FULL", "1")) == 0:
         pytest.skip("GP_TEST_CONFIG5_FULL=0")
     run_config5(1.0, capsys, memory="pageable")
