@@ -168,7 +168,7 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
     if budget is None:
         budget = -(-gp_synth.stored_nonzeros_upper_bound(w.n, w.m, w.flags) // w.n_blocks)
     t0 = time.time()
-    plan = gp.gp_plan_blocks(w.src, w.dst, w.n, budget, w.flags)
+    plan = gp.gp_plan_blocks(w.src, w.dst, w.n, budget, w.flags | (gp.GP_PLAN_ON_DEVICE if args.plan_on_device else 0))
     t_plan = time.time() - t0
     n, nnz, d, K = w.n, plan.nnz, w.d, w.K
     elem = 4 if w.dtype == gp.GP_F32 else 2
@@ -358,7 +358,7 @@ def time_workload(args, gp, torch, workload: int, cpu_baseline: bool):
                     "about 100 with the index arithmetic of a read, sequential ones at 146; 5.6 vector instructions per read allow 112"},
         "other_kernels_ms_per_step": {"gp_fixup_rows": round(fix_ms / args.steps, 5),
                                       "gp_copy_rows": round(copy_ms / args.steps, 5)},
-        "host_s": {"generate": round(t_gen, 2), "gp_plan_blocks": round(t_plan, 3),
+        "host_s": {"generate": round(t_gen, 2), "gp_plan_blocks": round(t_plan, 3), "planned_on": "gpu" if args.plan_on_device else "host",
                    "first_call_with_plan_upload": round(t_first, 4), "timed_wall": round(wall, 3)},
     }
 
@@ -427,6 +427,9 @@ def main() -> int:
     ap.add_argument("--lc", action="store_true",
                     help="time the LC-version forward pass (gp_lc_forward) over the hop stack instead of the precompute")
     ap.add_argument("--lc-batch", type=int, default=4096, help="--lc: mini-batch rows per call (0 = all rows in one call)")
+    ap.add_argument("--plan-on-device", action="store_true",
+                    help="gp_plan_blocks with GP_PLAN_ON_DEVICE: the non-zero set sorted and de-duplicated on the GPU "
+                         "(the plan is the same; host_s.gp_plan_blocks shows the time)")
     ap.add_argument("--contiguous-ids", action="store_true",
                     help="workload 4 only: community-contiguous node ids (locality given) instead of permuted ids")
     args = ap.parse_args()
