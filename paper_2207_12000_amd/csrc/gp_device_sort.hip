@@ -24,41 +24,19 @@
 #include <algorithm>
 #include <utility>
 
+#include "gp_block_scan.h"
 #include "gp_internal.h"
 
 namespace gp {
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kWaves = kThreads / 64;
+constexpr int kThreads = kScanThreads;
+constexpr int kWaves = kScanWaves;
 constexpr int kSortItems = 64;                       // keys per thread of a sort tile
 constexpr int64_t kSortTile = kThreads * kSortItems; // 16384
 constexpr int kScanItems = 16;                       // entries per thread of a scan chunk / keys per thread of a unique tile
 constexpr int64_t kScanChunk = kThreads * kScanItems;  // 4096
-
-// exclusive prefix of v over the workgroup's threads, in thread order; *total = the sum
-__device__ inline uint32_t block_exclusive(uint32_t v, uint32_t* wave_sums /* LDS, kWaves + 1 words */, uint32_t* total)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint32_t incl = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t up = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += up;
-    }
-    __syncthreads();  // (wave_sums may still be read from the call before)
-    if (lane == 63) wave_sums[wave] = incl;
-    __syncthreads();
-    uint32_t before = 0, all = 0;
-#pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-        if (w < wave) before += wave_sums[w];
-        all += wave_sums[w];
-    }
-    *total = all;
-    return before + incl - v;
-}
 
 // ---- exclusive scan of a[0 .. N) in place --------------------------------------------------
 
@@ -108,7 +86,11 @@ __global__ __launch_bounds__(kThreads) void gp_scan_chunks(uint32_t* __restrict_
     }
 }
 
-gp_status exclusive_scan(uint32_t* a, int64_t N, uint32_t* sums, hipStream_t stream)
+}  // namespace
+
+size_t device_scan_scratch_words(int64_t N) { return (size_t)((std::max<int64_t>(N, 1) + kScanChunk - 1) / kScanChunk + 1); }
+
+gp_status device_exclusive_scan(uint32_t* a, int64_t N, uint32_t* sums, hipStream_t stream)
 {
     if (N <= 0) return GP_OK;
     const int64_t P = (N + kScanChunk - 1) / kScanChunk;
@@ -118,6 +100,8 @@ gp_status exclusive_scan(uint32_t* a, int64_t N, uint32_t* sums, hipStream_t str
     GP_HIP(hipGetLastError());
     return GP_OK;
 }
+
+namespace {
 
 // ---- one radix pass ---------------------------------------------------------------------
 
@@ -252,7 +236,7 @@ gp_status device_sort_keys(uint64_t* keys, uint64_t* other, int64_t count, int l
             const int shift = half * 32 + p * 8;
             hipLaunchKernelGGL(gp_radix_count, dim3((unsigned)tiles), dim3(kThreads), 0, stream, from, count, shift, table);
             GP_HIP(hipGetLastError());
-            gp_status st = exclusive_scan(table, table_len, sums, stream);
+            gp_status st = device_exclusive_scan(table, table_len, sums, stream);
             if (st != GP_OK) return st;
             hipLaunchKernelGGL(gp_radix_scatter, dim3((unsigned)tiles), dim3(kThreads), 0, stream, from, to, count, shift, table);
             GP_HIP(hipGetLastError());
@@ -272,7 +256,7 @@ gp_status device_unique_keys(const uint64_t* sorted, uint64_t* out, int64_t coun
     uint32_t* sums = scratch + tiles + 1;
     hipLaunchKernelGGL(gp_unique_count, dim3((unsigned)tiles), dim3(kThreads), 0, stream, sorted, count, tile_count, tiles);
     GP_HIP(hipGetLastError());
-    gp_status st = exclusive_scan(tile_count, tiles + 1, sums, stream);
+    gp_status st = device_exclusive_scan(tile_count, tiles + 1, sums, stream);
     if (st != GP_OK) return st;
     hipLaunchKernelGGL(gp_unique_write, dim3((unsigned)tiles), dim3(kThreads), 0, stream, sorted, count, tile_count, out);
     GP_HIP(hipGetLastError());

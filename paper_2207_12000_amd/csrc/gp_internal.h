@@ -276,6 +276,9 @@ inline int64_t lds_rows(int64_t m) { return (m + 15) / 16 * 16 + 16; }
 // device_unique_keys writes the distinct keys of a sorted list to `out` (not the list itself) and leaves their
 // number in a word of the scratch, *total (DEVICE).
 size_t device_sort_scratch_words(int64_t count);
+// exclusive prefix sums of a[0 .. N) in place (32-bit, DEVICE); sums: device_scan_scratch_words(N) words of scratch
+size_t device_scan_scratch_words(int64_t N);
+gp_status device_exclusive_scan(uint32_t* a, int64_t N, uint32_t* sums, hipStream_t stream);
 gp_status device_sort_keys(uint64_t* keys, uint64_t* other, int64_t count, int low_bits, int high_bits, uint32_t* scratch,
                            hipStream_t stream, uint64_t** sorted);
 gp_status device_unique_keys(const uint64_t* sorted, uint64_t* out, int64_t count, uint32_t* scratch, hipStream_t stream,

@@ -15,6 +15,7 @@
 
 #include <cstring>
 
+#include "gp_block_scan.h"
 #include "gp_internal.h"
 
 namespace gp {
@@ -47,41 +48,65 @@ __global__ __launch_bounds__(kThreads) void gp_fill_words(unsigned long long* __
     for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += (int64_t)gridDim.x * kThreads) p[i] = v;
 }
 
-// keys of the candidates whose row lies in [r0, r1), in any order (the sort follows):
-// a wavefront takes the slots for all its keys from the one cursor with a single atomic
+// Keys of the candidates whose row lies in [r0, r1).  Entry e of the edge list (e < m), or the self-loop of
+// row r0 + (e - m), gives up to two keys.  Two passes over the entries, in tiles of kEmitTile consecutive ones:
+// the first counts every tile's keys, an exclusive scan of the counts gives each tile its first slot, and the
+// second writes the keys in entry order -- no cursor, no atomics, and the same order on every run.
+constexpr int kEmitItems = 16;
+constexpr int64_t kEmitTile = (int64_t)kThreads * kEmitItems;
+
+__device__ inline int keys_of_entry(const int32_t* __restrict__ src, const int32_t* __restrict__ dst, int64_t m, int64_t span,
+                                    int sym, int64_t r0, int64_t r1, int64_t e, uint64_t (&key)[2])
+{
+    if (e >= span) return 0;
+    if (e >= m) {  // the self-loop of row r0 + (e - m)
+        const uint64_t i = (uint64_t)(r0 + (e - m));
+        key[0] = (i << 32) | i;
+        return 1;
+    }
+    const uint32_t s = (uint32_t)src[e], t = (uint32_t)dst[e];
+    if (s == t) return 0;
+    int k = 0;
+    if ((int64_t)t >= r0 && (int64_t)t < r1) key[k++] = ((uint64_t)t << 32) | s;
+    if (sym && (int64_t)s >= r0 && (int64_t)s < r1) key[k++] = ((uint64_t)s << 32) | t;
+    return k;
+}
+
+__global__ __launch_bounds__(kThreads) void gp_count_keys_range(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
+                                                                int64_t m, int sym, int loops, int64_t r0, int64_t r1,
+                                                                uint32_t* __restrict__ tile_count, int64_t tiles)
+{
+    __shared__ uint32_t ws[kScanWaves + 1];
+    const int64_t span = m + (loops ? r1 - r0 : 0);
+    const int64_t t0 = (int64_t)blockIdx.x * kEmitTile;
+    uint32_t c = 0;
+    uint64_t key[2];
+    for (int j = 0; j < kEmitItems; ++j) c += (uint32_t)keys_of_entry(src, dst, m, span, sym, r0, r1, t0 + (int64_t)j * kThreads + threadIdx.x, key);
+    uint32_t total;
+    block_exclusive(c, ws, &total);
+    if (threadIdx.x == 0) {
+        tile_count[blockIdx.x] = total;
+        if (blockIdx.x == 0) tile_count[tiles] = 0;  // the scan leaves the number of keys here
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void gp_emit_keys_range(const int32_t* __restrict__ src, const int32_t* __restrict__ dst,
                                                                int64_t m, int sym, int loops, int64_t r0, int64_t r1,
-                                                               uint64_t* __restrict__ keys, unsigned long long* __restrict__ cursor)
+                                                               const uint32_t* __restrict__ tile_first, uint64_t* __restrict__ keys,
+                                                               int64_t capacity)
 {
+    __shared__ uint32_t ws[kScanWaves + 1];
     const int64_t span = m + (loops ? r1 - r0 : 0);
-    const int lane = threadIdx.x & 63;
-    for (int64_t e0 = (int64_t)blockIdx.x * kThreads; e0 < span; e0 += (int64_t)gridDim.x * kThreads) {  // (whole workgroups)
-        const int64_t e = e0 + threadIdx.x;
-        uint64_t k0 = 0, k1 = 0;  // up to two keys
-        bool has0 = false, has1 = false;
-        if (e < span) {
-            if (e >= m) {  // the self-loop of row r0 + (e - m)
-                const uint64_t i = (uint64_t)(r0 + (e - m));
-                k0 = (i << 32) | i;
-                has0 = true;
-            } else {
-                const uint32_t s = (uint32_t)src[e], t = (uint32_t)dst[e];
-                if (s != t) {
-                    has0 = (int64_t)t >= r0 && (int64_t)t < r1;
-                    k0 = ((uint64_t)t << 32) | s;
-                    has1 = sym && (int64_t)s >= r0 && (int64_t)s < r1;
-                    k1 = ((uint64_t)s << 32) | t;
-                }
-            }
-        }
-        const unsigned long long b0 = __ballot(has0), b1 = __ballot(has1), below = (1ull << lane) - 1ull;
-        const int total = __popcll(b0) + __popcll(b1);
-        unsigned long long first = 0;
-        if (lane == 0 && total > 0) first = atomicAdd(cursor, (unsigned long long)total);
-        first = ((unsigned long long)(unsigned)__shfl((int)(first >> 32), 0, 64) << 32) | (unsigned)__shfl((int)(unsigned)first, 0, 64);
-        const unsigned long long mine = first + (unsigned long long)(__popcll(b0 & below) + __popcll(b1 & below));
-        if (has0) keys[mine] = k0;
-        if (has1) keys[mine + (has0 ? 1 : 0)] = k1;
+    const int64_t t0 = (int64_t)blockIdx.x * kEmitTile;
+    uint32_t run = tile_first[blockIdx.x];
+    for (int j = 0; j < kEmitItems; ++j) {  // 256 consecutive entries per step, in order
+        uint64_t key[2];
+        const int c = keys_of_entry(src, dst, m, span, sym, r0, r1, t0 + (int64_t)j * kThreads + threadIdx.x, key);
+        uint32_t total;
+        const uint32_t at = run + block_exclusive((uint32_t)c, ws, &total);
+        for (int k = 0; k < c; ++k)
+            if ((int64_t)at + k < capacity) keys[at + k] = key[k];  // (the bound always holds: the buffer has one slot per candidate)
+        run += total;
     }
 }
 
@@ -171,11 +196,11 @@ gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64
     hipStream_t stream = nullptr;
     DeviceBuffers B;
     int32_t *d_src, *d_dst;
-    unsigned long long *d_cnt, *d_cursor;
+    unsigned long long* d_cnt;
     int64_t* d_rowptr;
     gp_status st;
     if ((st = B.alloc(d_src, (size_t)m)) != GP_OK || (st = B.alloc(d_dst, (size_t)m)) != GP_OK ||
-        (st = B.alloc(d_cnt, (size_t)n)) != GP_OK || (st = B.alloc(d_cursor, 1)) != GP_OK ||
+        (st = B.alloc(d_cnt, (size_t)n)) != GP_OK ||
         (st = B.alloc(d_rowptr, (size_t)n + 1)) != GP_OK)
         return st;
     // ---- candidates per row, and row ranges whose candidates fit one sort ------------
@@ -229,8 +254,12 @@ gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64
             }
         }
     } col_guard{d_col};
-    uint32_t* d_scratch;  // the sort's digit tables, the duplicate removal's tile counts
+    uint32_t *d_scratch, *d_emit;  // the sort's digit tables and the duplicate removal's tile counts; the key emission's tile counts
     if ((st = B.alloc(d_scratch, device_sort_scratch_words(largest))) != GP_OK) return st;
+    {
+        const int64_t most_tiles = (m + n + kEmitTile - 1) / kEmitTile + 1;  // (+ 1: the total)
+        if ((st = B.alloc(d_emit, (size_t)most_tiles + device_scan_scratch_words(most_tiles))) != GP_OK) return st;
+    }
     // bits in which keys can differ: a column is below n, a row of the range below its end
     auto bits_of = [](int64_t values) {
         int b = 0;
@@ -244,9 +273,13 @@ gp_status csr_on_device(const int32_t* src, const int32_t* dst, int64_t m, int64
         int64_t uniq = 0;
         uint64_t* d_distinct = d_keys;  // (no candidates: nothing is read from it)
         if (cand > 0) {
-            hipLaunchKernelGGL(gp_fill_words, dim3(1), dim3(kThreads), 0, stream, d_cursor, (int64_t)1, 0ULL);
-            hipLaunchKernelGGL(gp_emit_keys_range, dim3(grid_for(m + (loops ? r1 - r0 : 0))), dim3(kThreads), 0, stream, d_src, d_dst,
-                               m, sym ? 1 : 0, loops ? 1 : 0, r0, r1, d_keys, d_cursor);
+            const int64_t span = m + (loops ? r1 - r0 : 0), emit_tiles = (span + kEmitTile - 1) / kEmitTile;
+            hipLaunchKernelGGL(gp_count_keys_range, dim3((unsigned)emit_tiles), dim3(kThreads), 0, stream, d_src, d_dst, m, sym ? 1 : 0,
+                               loops ? 1 : 0, r0, r1, d_emit, emit_tiles);
+            GP_HIP(hipGetLastError());
+            if ((st = device_exclusive_scan(d_emit, emit_tiles + 1, d_emit + emit_tiles + 1, stream)) != GP_OK) return st;
+            hipLaunchKernelGGL(gp_emit_keys_range, dim3((unsigned)emit_tiles), dim3(kThreads), 0, stream, d_src, d_dst, m, sym ? 1 : 0,
+                               loops ? 1 : 0, r0, r1, d_emit, d_keys, cand);
             GP_HIP(hipGetLastError());
             uint64_t* sorted = nullptr;
             if ((st = device_sort_keys(d_keys, d_sorted, cand, bits_of(n), bits_of(r1), d_scratch, stream, &sorted)) != GP_OK) return st;
