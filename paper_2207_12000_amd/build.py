@@ -39,7 +39,7 @@ def _stale(target: str, deps) -> bool:
 
 def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    headers = [os.path.join(CSRC, "gp_internal.h"), os.path.join(ROOT, "include", "gp.h")]
+    headers = [os.path.join(CSRC, "gp_internal.h"), os.path.join(CSRC, "gp_block_scan.h"), os.path.join(ROOT, "include", "gp.h")]
     hipcc = _hipcc()
 
     def compile_one(name: str) -> str:
